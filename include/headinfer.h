@@ -1,0 +1,169 @@
+/*
+ * headinfer.h - C ABI of the head-wise offloaded attention library for AMD MI355X (gfx950).
+ *
+ * The library computes exact causal grouped-query attention ONE KV HEAD AT A TIME, with that head's K/V
+ * history streamed between a pinned host-DRAM cache and a small HBM staging ring (HeadInfer, arXiv 2502.12574:
+ * Section 3.2 "Head-wise Offload", Section 4, Algorithm 1).  Every pointer below is either "host" or "device"
+ * as stated; no framework types cross this boundary.  All functions return an hi_status (0 = success,
+ * negative = error), never throw, never abort and never print.
+ *
+ * Notation (the paper's): L layers, H KV heads per layer, G query heads per KV head (grouped-query sharing),
+ * D_h head dimension, S context length, C chunk length, P past length (rows already cached when a call starts).
+ * Element type is bf16 (2 bytes); one token of one KV head is 2 * D_h * 2 = 512 bytes of K plus V.
+ */
+#ifndef HEADINFER_H
+#define HEADINFER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t hi_status;
+enum {
+  HI_OK = 0,
+  HI_ERR_ARG = -1,         /* null pointer, negative size, layer/head out of range, misaligned pointer      */
+  HI_ERR_UNSUPPORTED = -2, /* head_dim != 128, dtype_bytes != 2, gqa_group not in {1,2,4,8}, batch != 1      */
+  HI_ERR_HBM_BUDGET = -3,  /* the staging ring does not fit the HBM KV budget (fewer than 2 slices)          */
+  HI_ERR_HOST_MEM = -4,    /* the host cache would exceed hi_problem.host_mem_limit_bytes                    */
+  HI_ERR_RANGE = -5,       /* past_len + len > max_context, or chunk_len > chunk                             */
+  HI_ERR_NOT_PINNED = -6,  /* the cache pointer is not pinned host memory (offload) / device memory (resident)*/
+  HI_ERR_HIP = -7          /* a HIP call failed; hi_last_error() has the text                                */
+};
+
+enum { HI_MODE_OFFLOAD = 0, HI_MODE_RESIDENT = 1 };
+enum { HI_REGIME_COMPUTE = 0, HI_REGIME_LINK = 1, HI_REGIME_HBM = 2 };
+/* debug/measurement switches for hi_ctx_set_flags: skip the attention kernels (transfer-only timing) or
+ * skip the H2D/D2H copies (compute-only timing on stale staging contents). Results are meaningless then. */
+enum { HI_FLAG_SKIP_KERNELS = 1, HI_FLAG_SKIP_COPIES = 2, HI_FLAG_TIME_KERNELS = 4 };
+
+/* The paper's statement of the problem (Algorithm 1 "Require": L layers, H heads, sequence length S). */
+typedef struct hi_problem {
+  int32_t n_layers;            /* L */
+  int32_t n_kv_heads;          /* H: KV heads per layer */
+  int32_t gqa_group;           /* G: query heads sharing one KV head; 1, 2, 4 or 8 */
+  int32_t head_dim;            /* D_h; 128 */
+  int64_t max_context;         /* S_max: rows pre-allocated per head in the cache */
+  int32_t chunk;               /* C: largest number of rows one hi_prefill_head call may carry */
+  int32_t gpu_kv_budget_heads; /* HBM KV budget, in whole-head equivalents of S_max rows (>= 1) */
+  int32_t dtype_bytes;         /* 2 (bf16) */
+  int32_t out_fp32;            /* 0: outputs are bf16, 1: outputs are fp32 */
+  int32_t n_compute_units;     /* 0 = 256 (MI355X) */
+  int32_t reserved0;
+  int64_t host_mem_limit_bytes;/* 0 = no check */
+  double link_GBps;            /* host link peak used by the regime prediction; 0 = 64 (PCIe Gen5 x16) */
+  double hbm_GBps;             /* 0 = 8000 */
+  double mfma_TFLOPs;          /* 0 = 2500 (dense bf16) */
+} hi_problem;
+
+/* Output of hi_offload_plan.  Sizes in bytes. */
+typedef struct hi_plan {
+  int32_t heads_per_group;       /* KV heads moved and computed per launch; 1 in this build (finest granularity) */
+  int32_t n_groups;              /* = n_kv_heads / heads_per_group */
+  int32_t paper_heads_per_group; /* what the paper's context-length rule would pick (Section 4, adaptive
+                                    head-wise offloading: 8 up to 500K, 4 to 1M, 2 to 2M, 1 beyond); informational */
+  int32_t n_slices_ring;         /* staging ring: number of slots */
+  int64_t slice_tokens;          /* rows per slot (K part then V part, each slice_tokens * D_h * 2 bytes) */
+  int32_t n_split_decode;        /* workgroups (KV partitions) of one decode launch */
+  int32_t prefill_rows_per_wg;   /* query positions one prefill workgroup covers */
+  int64_t host_bytes_per_head;   /* Eq. 11: 2 * S_max * D_h * sizeof */
+  int64_t host_bytes_total;      /* Eq. 4:  L * H * host_bytes_per_head */
+  int64_t hbm_staging_bytes;     /* n_slices_ring * slice_tokens * 2 * D_h * sizeof  (<= budget * host_bytes_per_head) */
+  int64_t hbm_pingpong_paper_bytes; /* the paper's two-whole-heads ping-pong buffer, for comparison (Appendix A.3) */
+  int64_t workspace_bytes;       /* fp32 (m, l, O) carry of a prefill unit + split-KV partials of a decode unit */
+  int64_t ws_partials_offset;    /* byte offset of the decode partials inside the workspace */
+  double alpha;                  /* Eq. 10: budget / (L * H) */
+  double flop_prefill_unit;      /* useful (causal) flops of one (chunk, head) unit at P = S_max - C */
+  double bytes_link_prefill_unit;/* H2D + D2H bytes of that unit */
+  double bytes_link_decode_unit; /* H2D + D2H bytes of one (token, head) unit at P = S_max - 1 */
+  double t_comp_prefill_s, t_link_prefill_s, t_hbm_prefill_s; /* Section 5: T ~ max(T_comp, T_mem) */
+  double t_comp_decode_s, t_link_decode_s, t_hbm_decode_s;
+  int32_t regime_prefill, regime_decode;                      /* HI_REGIME_* with offloading */
+} hi_plan;
+
+typedef struct hi_stats {
+  int64_t bytes_h2d, bytes_d2h;      /* enqueued so far */
+  int64_t n_h2d_copies, n_d2h_copies;
+  int64_t n_prefill_kernels, n_decode_kernels, n_combine_kernels;
+  int64_t peak_staging_bytes;        /* largest number of staging bytes holding live K/V at once */
+  double prefill_kernel_ms, decode_kernel_ms; /* HIP-event time of the attention kernels since the last
+                                                 hi_reset_stats; only with HI_FLAG_TIME_KERNELS; hi_get_stats
+                                                 synchronises to read them */
+} hi_stats;
+
+typedef struct hi_ctx hi_ctx;
+
+/*
+ * P0 - planning (Algorithm 1 "Initialization"; Eq. 4-6, 10-11; Section 4 "pre-allocates the CPU's KV cache
+ * memory and the GPU's ping-pong memory"; Section 5 performance model).
+ * Pure host arithmetic: needs no GPU and makes no HIP call.  `problem` and `plan` are host pointers owned by
+ * the caller.  Errors: HI_ERR_ARG, HI_ERR_UNSUPPORTED, HI_ERR_HBM_BUDGET, HI_ERR_HOST_MEM; `plan` is left
+ * untouched on error.
+ */
+hi_status hi_offload_plan(const hi_problem* problem, hi_plan* plan);
+
+/*
+ * Context.  The caller owns every large buffer and keeps it alive until hi_ctx_destroy:
+ *   kv_cache       HI_MODE_OFFLOAD : pinned HOST memory, plan.host_bytes_total bytes, layout
+ *                                    [layer][kv_head][K|V][S_max][D_h] bf16 (each head's K rows contiguous, then
+ *                                    its V rows: the head-wise partition of Eq. 7-8);
+ *                  HI_MODE_RESIDENT: DEVICE memory of the same size and layout (no copies; HBM-roofline runs).
+ *   hbm_staging    DEVICE, plan.hbm_staging_bytes (ignored in resident mode; may be null there).
+ *   hbm_workspace  DEVICE, plan.workspace_bytes.
+ *   stream_*       hipStream_t handles (as void*), all at default priority.  Kernels run on stream_compute,
+ *                  host-to-device prefetches on stream_h2d, write-backs on stream_d2h.
+ * Errors: HI_ERR_ARG, HI_ERR_NOT_PINNED, HI_ERR_HIP.
+ */
+hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* plan, int32_t mode, void* kv_cache,
+                        void* hbm_staging, void* hbm_workspace, void* stream_compute, void* stream_h2d,
+                        void* stream_d2h, hi_ctx** out);
+hi_status hi_ctx_destroy(hi_ctx* ctx);
+hi_status hi_ctx_set_flags(hi_ctx* ctx, int32_t flags);
+
+/*
+ * T1 + K1 + T3 - one prefill unit: one chunk, one KV head, its G query heads (Algorithm 1, prefill phase, the
+ * body of the head loop; Eq. 9).  Appends, then attends:
+ *   - rows [past_len, past_len + chunk_len) of (layer, kv_head) in the cache receive k_new / v_new
+ *     (asynchronous write-back on stream_d2h; a device copy in resident mode);
+ *   - out[g][i][:] = softmax_j<=past_len+i( q[g][i] . K[j] / sqrt(D_h) ) V[j]  over the head's rows 0..past_len+i,
+ *     the past rows streamed from the cache through the staging ring, the chunk's own rows read from k_new/v_new.
+ * q_dev   DEVICE bf16 [G][chunk_len][D_h]; k_new_dev, v_new_dev DEVICE bf16 [chunk_len][D_h];
+ * out_dev DEVICE [G][chunk_len][D_h], bf16 or fp32 per hi_problem.out_fp32.  All 16-byte aligned.
+ * next_* name the unit that will be called next (Algorithm 1 "Async Prefetch next KV cache"): its past rows are
+ * prefetched into free ring slots while this unit computes; next_layer = -1 means none.  The hint must be
+ * honoured by the next call, or that call simply fetches on demand.
+ * Asynchronous: enqueues and returns.  Results and the cache append are valid after hi_sync.  The caller's
+ * buffers are borrowed until then.  1 <= chunk_len <= chunk; past_len >= 0; no alignment is required of either.
+ * Errors (synchronous, nothing enqueued, cache untouched): HI_ERR_ARG, HI_ERR_RANGE; HI_ERR_HIP.
+ */
+hi_status hi_prefill_head(hi_ctx* ctx, int32_t layer, int32_t kv_head, const void* q_dev, const void* k_new_dev,
+                          const void* v_new_dev, int64_t past_len, int32_t chunk_len, void* out_dev,
+                          int32_t next_layer, int32_t next_kv_head, int64_t next_past_len);
+
+/*
+ * T1 + K2 + K3 + T3 - one decode unit: one new token, one KV head, its G query rows (Algorithm 1, decode phase).
+ * Appends the token's K/V row at row past_len, then attends over rows 0..past_len inclusive (the token sees
+ * itself).  Split-KV: each partition of the streamed rows yields a partial (max, sum, weighted V); a combine
+ * kernel merges the partials of all partitions and slices with the new row.
+ * q_dev DEVICE bf16 [G][D_h]; k_new_dev, v_new_dev DEVICE bf16 [D_h]; out_dev DEVICE [G][D_h].
+ * Same asynchrony, ownership, hint and error rules as hi_prefill_head.
+ */
+hi_status hi_decode_head(hi_ctx* ctx, int32_t layer, int32_t kv_head, const void* q_dev, const void* k_new_dev,
+                         const void* v_new_dev, int64_t past_len, void* out_dev, int32_t next_layer,
+                         int32_t next_kv_head, int64_t next_past_len);
+
+/* T4 - drain the three streams; surfaces deferred HIP errors (HI_ERR_HIP). */
+hi_status hi_sync(hi_ctx* ctx);
+
+hi_status hi_get_stats(hi_ctx* ctx, hi_stats* out);
+hi_status hi_reset_stats(hi_ctx* ctx);
+
+/* Static strings; never null. hi_last_error is per calling thread. */
+const char* hi_status_string(hi_status s);
+const char* hi_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HEADINFER_H */

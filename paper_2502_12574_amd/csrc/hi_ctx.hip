@@ -1,0 +1,467 @@
+// Host-side pipeline: T1 prefetch (H2D), T3 write-back (D2H), T4 events, and the per-head entry points.
+//
+// Section 4 / Algorithm 1: while head h computes, the next head's K/V history is prefetched from the pinned host
+// cache and the current head's new rows are written back, on separate streams (full-duplex link).  Here the
+// "ping-pong memory" is a ring of sequence slices that together never exceed the HBM KV budget (one head's worth
+// by default): the kernel consumes slice n while later slices - of this head, then of the next one - land, and the
+// softmax state is carried from slice to slice.  All calls only enqueue work; no host thread blocks.
+#include <hip/hip_runtime.h>
+#include <cstring>
+#include <new>
+#include <vector>
+#include "hi_internal.h"
+
+using namespace hi;
+
+#define HI_HIP(call)                                                                   \
+  do {                                                                                 \
+    hipError_t e_ = (call);                                                            \
+    if (e_ != hipSuccess) {                                                            \
+      set_last_error("%s failed: %s", #call, hipGetErrorString(e_));                   \
+      return HI_ERR_HIP;                                                               \
+    }                                                                                  \
+  } while (0)
+
+#define HI_TRY(call)                  \
+  do {                                \
+    hi_status s_ = (call);            \
+    if (s_ != HI_OK) return s_;       \
+  } while (0)
+
+struct TimedSpan {
+  hipEvent_t start, stop;
+  int kind;   // 0 prefill, 1 decode
+};
+
+struct hi_ctx {
+  hi_problem prob;
+  hi_plan plan;
+  int mode = HI_MODE_OFFLOAD;
+  int flags = 0;
+  char* kv = nullptr;        // host (offload) or device (resident) cache
+  char* staging = nullptr;
+  char* ws = nullptr;
+  hipStream_t sc = nullptr, sh = nullptr, sd = nullptr;
+
+  int n_slots = 0;
+  int64_t slice_tokens = 0;
+  std::vector<hipEvent_t> ev_ready, ev_free;   // per ring slot
+  hipEvent_t ev_entry = nullptr;               // compute-stream position when a call starts
+  std::vector<hipEvent_t> ev_wb;               // per (layer, head): last write-back of that head finished
+  std::vector<char> wb_valid;
+
+  // the ring is a FIFO: slices are consumed in the order they were fetched
+  int64_t seq_issued = 0;     // slices whose H2D has been enqueued
+  int64_t seq_consumed = 0;   // slices whose consuming kernel has been enqueued (or that were dropped)
+
+  struct Unit {
+    bool valid = false;
+    int layer = 0, head = 0;
+    int64_t past = 0;
+    int64_t n_slices = 0;
+    int64_t issued = 0;       // slices of this unit already fetched
+    int64_t first_seq = 0;
+  } pend;                     // the unit whose history is (partly) in the ring
+
+  hi_stats stats;
+  std::vector<TimedSpan> spans;
+  std::vector<TimedSpan> span_pool;
+};
+
+namespace {
+
+inline int64_t plane_offset(const hi_ctx* c, int layer, int head, int which /*0 K, 1 V*/) {
+  const int64_t plane = c->prob.max_context * kRowBytes;
+  return (((int64_t)layer * c->prob.n_kv_heads + head) * 2 + which) * plane;
+}
+
+inline char* slot_k(const hi_ctx* c, int slot) { return c->staging + (int64_t)slot * c->slice_tokens * 2 * kRowBytes; }
+inline char* slot_v(const hi_ctx* c, int slot) { return slot_k(c, slot) + c->slice_tokens * kRowBytes; }
+
+inline int64_t slices_of(const hi_ctx* c, int64_t past) { return ceil_div(past, c->slice_tokens); }
+
+inline bool can_issue(const hi_ctx* c) { return c->seq_issued - c->n_slots < c->seq_consumed; }
+
+void note_peak(hi_ctx* c) {
+  const int64_t live = (c->seq_issued - c->seq_consumed) * c->slice_tokens * 2 * kRowBytes;
+  if (live > c->stats.peak_staging_bytes) c->stats.peak_staging_bytes = live;
+}
+
+// enqueue the H2D of the next not-yet-fetched slice of unit u
+hi_status issue_slice(hi_ctx* c, hi_ctx::Unit& u) {
+  const int64_t i = u.issued;
+  const int64_t seq = c->seq_issued;
+  const int slot = (int)(seq % c->n_slots);
+  const int64_t row0 = i * c->slice_tokens;
+  int64_t rows = u.past - row0;
+  if (rows > c->slice_tokens) rows = c->slice_tokens;
+  if (i == 0) {
+    u.first_seq = seq;
+    const int idx = u.layer * c->prob.n_kv_heads + u.head;
+    if (c->wb_valid[idx]) HI_HIP(hipStreamWaitEvent(c->sh, c->ev_wb[idx], 0));   // rows written by an earlier call
+  }
+  if (seq >= c->n_slots) HI_HIP(hipStreamWaitEvent(c->sh, c->ev_free[slot], 0));  // slot's previous tenant consumed
+  if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
+    const char* hk = c->kv + plane_offset(c, u.layer, u.head, 0) + row0 * kRowBytes;
+    const char* hv = c->kv + plane_offset(c, u.layer, u.head, 1) + row0 * kRowBytes;
+    HI_HIP(hipMemcpyAsync(slot_k(c, slot), hk, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
+    HI_HIP(hipMemcpyAsync(slot_v(c, slot), hv, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
+    c->stats.bytes_h2d += 2 * rows * kRowBytes;
+    c->stats.n_h2d_copies += 2;
+  }
+  HI_HIP(hipEventRecord(c->ev_ready[slot], c->sh));
+  u.issued += 1;
+  c->seq_issued += 1;
+  note_peak(c);
+  return HI_OK;
+}
+
+// fetch as far ahead as free slots allow: first the current unit, then the hinted next one
+hi_status top_up(hi_ctx* c, hi_ctx::Unit& cur, hi_ctx::Unit& next) {
+  while (cur.valid && cur.issued < cur.n_slices && can_issue(c)) HI_TRY(issue_slice(c, cur));
+  if (cur.valid && cur.issued < cur.n_slices) return HI_OK;     // keep FIFO order
+  while (next.valid && next.issued < next.n_slices && can_issue(c)) HI_TRY(issue_slice(c, next));
+  return HI_OK;
+}
+
+// a slice has been handed to a kernel (or dropped): its slot becomes free when the compute stream gets here
+hi_status retire_slice(hi_ctx* c, int slot) {
+  HI_HIP(hipEventRecord(c->ev_free[slot], c->sc));
+  c->seq_consumed += 1;
+  return HI_OK;
+}
+
+hi_status span_begin(hi_ctx* c, int kind, TimedSpan* out) {
+  TimedSpan s;
+  if (!c->span_pool.empty()) {
+    s = c->span_pool.back();
+    c->span_pool.pop_back();
+  } else {
+    HI_HIP(hipEventCreate(&s.start));
+    HI_HIP(hipEventCreate(&s.stop));
+  }
+  s.kind = kind;
+  HI_HIP(hipEventRecord(s.start, c->sc));
+  *out = s;
+  return HI_OK;
+}
+
+hi_status span_end(hi_ctx* c, TimedSpan& s) {
+  HI_HIP(hipEventRecord(s.stop, c->sc));
+  c->spans.push_back(s);
+  return HI_OK;
+}
+
+hi_status collect_spans(hi_ctx* c) {
+  for (auto& s : c->spans) {
+    HI_HIP(hipEventSynchronize(s.stop));
+    float ms = 0.f;
+    HI_HIP(hipEventElapsedTime(&ms, s.start, s.stop));
+    if (s.kind == 0) c->stats.prefill_kernel_ms += ms;
+    else c->stats.decode_kernel_ms += ms;
+    c->span_pool.push_back(s);
+  }
+  c->spans.clear();
+  return HI_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+hi_status check_unit_args(const hi_ctx* c, int layer, int head, const void* q, const void* k, const void* v,
+                          int64_t past, int64_t len, const void* out, int next_layer, int next_head,
+                          int64_t next_past) {
+  if (!c) { set_last_error("ctx is null"); return HI_ERR_ARG; }
+  if (!q || !k || !v || !out) { set_last_error("null buffer"); return HI_ERR_ARG; }
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) { set_last_error("buffers must be 16-byte aligned"); return HI_ERR_ARG; }
+  if (layer < 0 || layer >= c->prob.n_layers || head < 0 || head >= c->prob.n_kv_heads) { set_last_error("layer/head out of range"); return HI_ERR_ARG; }
+  if (past < 0 || len < 1) { set_last_error("negative past_len or empty call"); return HI_ERR_ARG; }
+  if (len > c->prob.chunk || past + len > c->prob.max_context) { set_last_error("past_len %lld + len %lld exceeds the plan", (long long)past, (long long)len); return HI_ERR_RANGE; }
+  if (next_layer >= 0) {
+    if (next_layer >= c->prob.n_layers || next_head < 0 || next_head >= c->prob.n_kv_heads || next_past < 0) { set_last_error("prefetch hint out of range"); return HI_ERR_ARG; }
+    if (next_past > c->prob.max_context) { set_last_error("prefetch hint beyond max_context"); return HI_ERR_RANGE; }
+  }
+  return HI_OK;
+}
+
+// make `pend` describe (layer, head, past); drop a stale prefetch if the hint was not honoured
+hi_status adopt_unit(hi_ctx* c, int layer, int head, int64_t past) {
+  auto& p = c->pend;
+  if (p.valid && (p.layer != layer || p.head != head || p.past != past)) {
+    for (int64_t i = 0; i < p.issued; ++i) HI_TRY(retire_slice(c, (int)((p.first_seq + i) % c->n_slots)));
+    p.valid = false;
+  }
+  if (!p.valid) {
+    p = hi_ctx::Unit();
+    p.valid = true;
+    p.layer = layer; p.head = head; p.past = past;
+    p.n_slices = slices_of(c, past);
+  }
+  return HI_OK;
+}
+
+hi_status write_back(hi_ctx* c, int layer, int head, const void* k_new, const void* v_new, int64_t past, int64_t len) {
+  char* dk = c->kv + plane_offset(c, layer, head, 0) + past * kRowBytes;
+  char* dv = c->kv + plane_offset(c, layer, head, 1) + past * kRowBytes;
+  if (c->mode == HI_MODE_RESIDENT) {
+    HI_HIP(hipMemcpyAsync(dk, k_new, len * kRowBytes, hipMemcpyDeviceToDevice, c->sc));
+    HI_HIP(hipMemcpyAsync(dv, v_new, len * kRowBytes, hipMemcpyDeviceToDevice, c->sc));
+    return HI_OK;
+  }
+  // the new rows were produced by earlier work on the compute stream
+  HI_HIP(hipEventRecord(c->ev_entry, c->sc));
+  HI_HIP(hipStreamWaitEvent(c->sd, c->ev_entry, 0));
+  if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
+    HI_HIP(hipMemcpyAsync(dk, k_new, len * kRowBytes, hipMemcpyDeviceToHost, c->sd));
+    HI_HIP(hipMemcpyAsync(dv, v_new, len * kRowBytes, hipMemcpyDeviceToHost, c->sd));
+    c->stats.bytes_d2h += 2 * len * kRowBytes;
+    c->stats.n_d2h_copies += 2;
+  }
+  const int idx = layer * c->prob.n_kv_heads + head;
+  HI_HIP(hipEventRecord(c->ev_wb[idx], c->sd));
+  c->wb_valid[idx] = 1;
+  return HI_OK;
+}
+
+}  // namespace
+
+extern "C" hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* plan, int32_t mode, void* kv_cache,
+                                   void* hbm_staging, void* hbm_workspace, void* stream_compute, void* stream_h2d,
+                                   void* stream_d2h, hi_ctx** out) {
+  if (!out || !plan) { set_last_error("null argument"); return HI_ERR_ARG; }
+  HI_TRY(validate_problem(problem));
+  if (mode != HI_MODE_OFFLOAD && mode != HI_MODE_RESIDENT) { set_last_error("unknown mode"); return HI_ERR_ARG; }
+  if (!kv_cache || !hbm_workspace || (mode == HI_MODE_OFFLOAD && !hbm_staging)) { set_last_error("null buffer"); return HI_ERR_ARG; }
+  hi_plan ref;
+  HI_TRY(hi_offload_plan(problem, &ref));
+  if (std::memcmp(&ref, plan, sizeof(ref)) != 0) { set_last_error("plan does not belong to this problem"); return HI_ERR_ARG; }
+
+  hipPointerAttribute_t attr;
+  hipError_t e = hipPointerGetAttributes(&attr, kv_cache);
+  if (mode == HI_MODE_OFFLOAD) {
+    if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
+      (void)hipGetLastError();
+      set_last_error("kv_cache is not pinned host memory");
+      return HI_ERR_NOT_PINNED;
+    }
+  } else if (e != hipSuccess || attr.type != hipMemoryTypeDevice) {
+    (void)hipGetLastError();
+    set_last_error("resident kv_cache is not device memory");
+    return HI_ERR_NOT_PINNED;
+  }
+
+  hi_ctx* c = new (std::nothrow) hi_ctx();
+  if (!c) { set_last_error("out of host memory"); return HI_ERR_ARG; }
+  c->prob = *problem;
+  c->plan = *plan;
+  c->mode = mode;
+  c->kv = (char*)kv_cache;
+  c->staging = (char*)hbm_staging;
+  c->ws = (char*)hbm_workspace;
+  c->sc = (hipStream_t)stream_compute;
+  c->sh = (hipStream_t)stream_h2d;
+  c->sd = (hipStream_t)stream_d2h;
+  c->n_slots = plan->n_slices_ring;
+  c->slice_tokens = plan->slice_tokens;
+  std::memset(&c->stats, 0, sizeof(c->stats));
+  auto fail = [&](hipError_t err, const char* what) {
+    set_last_error("%s failed: %s", what, hipGetErrorString(err));
+    hi_ctx_destroy(c);
+    return (hi_status)HI_ERR_HIP;
+  };
+  if (mode == HI_MODE_OFFLOAD) {
+    c->ev_ready.assign(c->n_slots, nullptr);
+    c->ev_free.assign(c->n_slots, nullptr);
+    for (int i = 0; i < c->n_slots; ++i) {
+      if ((e = hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+      if ((e = hipEventCreateWithFlags(&c->ev_free[i], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+    }
+    const int n_heads = problem->n_layers * problem->n_kv_heads;
+    c->ev_wb.assign(n_heads, nullptr);
+    c->wb_valid.assign(n_heads, 0);
+    for (int i = 0; i < n_heads; ++i)
+      if ((e = hipEventCreateWithFlags(&c->ev_wb[i], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+    if ((e = hipEventCreateWithFlags(&c->ev_entry, hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+  }
+  *out = c;
+  return HI_OK;
+}
+
+extern "C" hi_status hi_ctx_destroy(hi_ctx* c) {
+  if (!c) return HI_OK;
+  for (auto ev : c->ev_ready) if (ev) (void)hipEventDestroy(ev);
+  for (auto ev : c->ev_free) if (ev) (void)hipEventDestroy(ev);
+  for (auto ev : c->ev_wb) if (ev) (void)hipEventDestroy(ev);
+  if (c->ev_entry) (void)hipEventDestroy(c->ev_entry);
+  for (auto& s : c->spans) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }
+  for (auto& s : c->span_pool) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }
+  delete c;
+  return HI_OK;
+}
+
+extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
+  if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS))) { set_last_error("bad flags"); return HI_ERR_ARG; }
+  c->flags = flags;
+  return HI_OK;
+}
+
+extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
+                                     const void* k_new_dev, const void* v_new_dev, int64_t past_len,
+                                     int32_t chunk_len, void* out_dev, int32_t next_layer, int32_t next_kv_head,
+                                     int64_t next_past_len) {
+  HI_TRY(check_unit_args(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
+                         next_kv_head, next_past_len));
+  const int G = c->prob.gqa_group;
+  const bool run = !(c->flags & HI_FLAG_SKIP_KERNELS);
+  const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
+  PrefillSegment diag{k_new_dev, v_new_dev, chunk_len, 1};
+
+  if (c->mode == HI_MODE_RESIDENT) {
+    PrefillSegment pastseg{c->kv + plane_offset(c, layer, kv_head, 0), c->kv + plane_offset(c, layer, kv_head, 1), past_len, 0};
+    if (run) {
+      TimedSpan sp;
+      if (timed) HI_TRY(span_begin(c, 0, &sp));
+      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, pastseg, diag, 1, 1, c->ws, out_dev, c->prob.out_fp32));
+      if (timed) HI_TRY(span_end(c, sp));
+      c->stats.n_prefill_kernels += 1;
+    }
+    return write_back(c, layer, kv_head, k_new_dev, v_new_dev, past_len, chunk_len);
+  }
+
+  HI_TRY(adopt_unit(c, layer, kv_head, past_len));
+  HI_TRY(write_back(c, layer, kv_head, k_new_dev, v_new_dev, past_len, chunk_len));
+
+  hi_ctx::Unit next;
+  if (next_layer >= 0) {
+    next.valid = true;
+    next.layer = next_layer; next.head = next_kv_head; next.past = next_past_len;
+    next.n_slices = slices_of(c, next_past_len);
+  }
+  hi_ctx::Unit& cur = c->pend;
+  const int64_t ns = cur.n_slices;
+  if (ns == 0) {
+    if (run) {
+      TimedSpan sp;
+      if (timed) HI_TRY(span_begin(c, 0, &sp));
+      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, PrefillSegment{nullptr, nullptr, 0, 0}, diag, 1, 1, c->ws, out_dev, c->prob.out_fp32));
+      if (timed) HI_TRY(span_end(c, sp));
+      c->stats.n_prefill_kernels += 1;
+    }
+  }
+  for (int64_t i = 0; i < ns; ++i) {
+    HI_TRY(top_up(c, cur, next));          // guarantees slice i has been fetched
+    const int slot = (int)((cur.first_seq + i) % c->n_slots);
+    int64_t rows = past_len - i * c->slice_tokens;
+    if (rows > c->slice_tokens) rows = c->slice_tokens;
+    HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
+    if (run) {
+      const bool is_last = (i == ns - 1);
+      PrefillSegment seg{slot_k(c, slot), slot_v(c, slot), rows, 0};
+      TimedSpan sp;
+      if (timed) HI_TRY(span_begin(c, 0, &sp));
+      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, seg, is_last ? diag : PrefillSegment{nullptr, nullptr, 0, 1},
+                            i == 0, is_last, c->ws, out_dev, c->prob.out_fp32));
+      if (timed) HI_TRY(span_end(c, sp));
+      c->stats.n_prefill_kernels += 1;
+    }
+    HI_TRY(retire_slice(c, slot));
+  }
+  cur.valid = false;
+  hi_ctx::Unit none;
+  HI_TRY(top_up(c, none, next));
+  c->pend = next;
+  return HI_OK;
+}
+
+extern "C" hi_status hi_decode_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
+                                    const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
+                                    int32_t next_layer, int32_t next_kv_head, int64_t next_past_len) {
+  HI_TRY(check_unit_args(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, 1, out_dev, next_layer,
+                         next_kv_head, next_past_len));
+  const int G = c->prob.gqa_group;
+  const bool run = !(c->flags & HI_FLAG_SKIP_KERNELS);
+  const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
+  float* partials = (float*)(c->ws + c->plan.ws_partials_offset);
+  const int n_split = c->plan.n_split_decode;
+  auto splits_for = [&](int64_t rows) {
+    const int64_t need = ceil_div(rows, 64);      // one workgroup covers at least 64 rows
+    return (int)(need < n_split ? need : n_split);
+  };
+
+  if (c->mode == HI_MODE_RESIDENT) {
+    int n_part = 0;
+    if (run) {
+      TimedSpan sp;
+      if (timed) HI_TRY(span_begin(c, 1, &sp));
+      if (past_len > 0) {
+        n_part = splits_for(past_len);
+        HI_TRY(launch_decode_partial(c->sc, q_dev, G, c->kv + plane_offset(c, layer, kv_head, 0),
+                                     c->kv + plane_offset(c, layer, kv_head, 1), past_len, n_part, partials, 0));
+        c->stats.n_decode_kernels += 1;
+      }
+      if (timed) HI_TRY(span_end(c, sp));
+      HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32));
+      c->stats.n_combine_kernels += 1;
+    }
+    return write_back(c, layer, kv_head, k_new_dev, v_new_dev, past_len, 1);
+  }
+
+  HI_TRY(adopt_unit(c, layer, kv_head, past_len));
+  HI_TRY(write_back(c, layer, kv_head, k_new_dev, v_new_dev, past_len, 1));
+  hi_ctx::Unit next;
+  if (next_layer >= 0) {
+    next.valid = true;
+    next.layer = next_layer; next.head = next_kv_head; next.past = next_past_len;
+    next.n_slices = slices_of(c, next_past_len);
+  }
+  hi_ctx::Unit& cur = c->pend;
+  const int64_t ns = cur.n_slices;
+  int n_part = 0;
+  for (int64_t i = 0; i < ns; ++i) {
+    HI_TRY(top_up(c, cur, next));
+    const int slot = (int)((cur.first_seq + i) % c->n_slots);
+    int64_t rows = past_len - i * c->slice_tokens;
+    if (rows > c->slice_tokens) rows = c->slice_tokens;
+    HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
+    if (run) {
+      const int np = splits_for(rows);
+      TimedSpan sp;
+      if (timed) HI_TRY(span_begin(c, 1, &sp));
+      HI_TRY(launch_decode_partial(c->sc, q_dev, G, slot_k(c, slot), slot_v(c, slot), rows, np, partials, n_part));
+      if (timed) HI_TRY(span_end(c, sp));
+      n_part += np;
+      c->stats.n_decode_kernels += 1;
+    }
+    HI_TRY(retire_slice(c, slot));
+  }
+  if (run) {
+    HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32));
+    c->stats.n_combine_kernels += 1;
+  }
+  cur.valid = false;
+  hi_ctx::Unit none;
+  HI_TRY(top_up(c, none, next));
+  c->pend = next;
+  return HI_OK;
+}
+
+extern "C" hi_status hi_sync(hi_ctx* c) {
+  if (!c) { set_last_error("ctx is null"); return HI_ERR_ARG; }
+  HI_HIP(hipStreamSynchronize(c->sh));
+  HI_HIP(hipStreamSynchronize(c->sc));
+  HI_HIP(hipStreamSynchronize(c->sd));
+  return HI_OK;
+}
+
+extern "C" hi_status hi_get_stats(hi_ctx* c, hi_stats* out) {
+  if (!c || !out) { set_last_error("null argument"); return HI_ERR_ARG; }
+  HI_TRY(collect_spans(c));
+  *out = c->stats;
+  return HI_OK;
+}
+
+extern "C" hi_status hi_reset_stats(hi_ctx* c) {
+  if (!c) { set_last_error("ctx is null"); return HI_ERR_ARG; }
+  HI_TRY(collect_spans(c));
+  std::memset(&c->stats, 0, sizeof(c->stats));
+  return HI_OK;
+}

@@ -1,0 +1,267 @@
+// K2 (split-KV decode attention) and K3 (log-sum-exp combine) for gfx950.
+//
+// Algorithm 1, decode phase: one new query row per query head attends over the head's whole K/V history
+// (Eq. 3 / Eq. 9).  The work is bandwidth bound (Section 5: decode intensity is O(1) flop per byte), so the
+// kernel is organised around the memory pipeline: every wavefront streams its own contiguous range of 16-row
+// K/V blocks through a private 4-stage LDS ring filled by direct-to-LDS 128-bit loads (24 KiB in flight per
+// wavefront, nothing staged in VGPRs, no workgroup barriers in the loop).  The G <= 16 query heads ride along
+// as the 16 columns of small MFMA tiles (S^T = K Q^T, O^T += V^T P^T), which keeps the vector ALU nearly idle;
+// the matrix unit runs at a few percent of its rate and is not the bound.
+#include "hi_device.h"
+#include "hi_internal.h"
+
+namespace hi {
+
+constexpr int kDecStages = 4;
+constexpr int kDecBlockRows = 16;
+constexpr int kDecTileBytes = kDecBlockRows * kRowBytes;         // 4 KiB of K (or V)
+constexpr int kDecStageBytes = 2 * kDecTileBytes;                // K tile then V tile
+constexpr int kDecWaveLds = kDecStages * kDecStageBytes;         // 32 KiB per wavefront
+constexpr int kDecLdsBytes = 4 * kDecWaveLds;                    // 128 KiB per workgroup
+
+// issue the 8 loads (4 K + 4 V) of block `blk` into `stage`; rows beyond n-1 re-read row n-1 (masked later)
+__device__ __forceinline__ void dec_issue_block(const char* __restrict__ k, const char* __restrict__ v, int64_t blk,
+                                                int64_t n, lds_char* stage, int lane) {
+  const int r_in = lane >> 4;        // row within the 4-row group of one load instruction
+  const int cpos = lane & 15;        // LDS chunk position within the row
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 4 * i + r_in;
+    int64_t row = blk * kDecBlockRows + r;
+    row = row < n ? row : n - 1;
+    const int ck = cpos ^ (r & 15);          // K swizzle
+    const int cv = cpos ^ ((r & 7) << 1);    // V swizzle
+    g2lds16(k + row * kRowBytes + ck * 16, stage + i * 1024);
+    g2lds16(v + row * kRowBytes + cv * 16, stage + kDecTileBytes + i * 1024);
+  }
+}
+
+__global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __restrict__ q, int G,
+                                                             const char* __restrict__ k, const char* __restrict__ v,
+                                                             int64_t n, float* __restrict__ partials, int part0,
+                                                             float c) {
+  extern __shared__ __attribute__((aligned(1024))) char lds_raw[];
+  lds_char* lds = (lds_char*)lds_raw;
+  const int lane = lane_id();
+  const int wave = wave_id();
+  lds_char* wlds = lds + wave * kDecWaveLds;
+
+  const int head = lane & 15;
+  const int g4 = lane >> 4;
+
+  // Q^T as the B operand of S^T = K Q^T: lane holds q[head][32*kk + 8*g4 .. +7]; heads >= G are zero columns
+  bf16x8 qf[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    uint4 raw = make_uint4(0, 0, 0, 0);
+    if (head < G) raw = *(const uint4*)(q + head * kHeadDim + 32 * kk + 8 * g4);
+    qf[kk] = __builtin_bit_cast(bf16x8, raw);
+  }
+  // make the compiler wait for these loads here, not inside the loop (a vmcnt(0) there would drain the ring)
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(qf[kk]));
+
+  const int64_t n_blocks = (n + kDecBlockRows - 1) / kDecBlockRows;
+  const int64_t n_waves = (int64_t)gridDim.x * 4;
+  const int64_t per_wave = (n_blocks + n_waves - 1) / n_waves;
+  const int64_t wid = (int64_t)blockIdx.x * 4 + wave;
+  int64_t b0 = wid * per_wave;
+  int64_t b1 = b0 + per_wave;
+  if (b1 > n_blocks) b1 = n_blocks;
+  if (b0 > b1) b0 = b1;
+
+  float m = kNegBig, l = 0.f;
+  f32x4 o[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  // prologue: up to three blocks in flight
+  for (int s = 0; s < kDecStages - 1; ++s)
+    if (b0 + s < b1) dec_issue_block(k, v, b0 + s, n, wlds + s * kDecStageBytes, lane);
+
+  // lane-constant LDS offsets of the operand reads
+  const int k_tok = lane & 15;
+  const int v_row = 4 * g4 + ((lane & 15) >> 2);
+  const int v_sub = lane & 3;      // which 8-byte quarter of the 32-byte column group
+
+  for (int64_t b = b0; b < b1; ++b) {
+    const int stage = (int)((b - b0) & (kDecStages - 1));
+    if (b + (kDecStages - 1) < b1) {
+      dec_issue_block(k, v, b + (kDecStages - 1), n,
+                      wlds + (int)((b - b0 + kDecStages - 1) & (kDecStages - 1)) * kDecStageBytes, lane);
+      wait_vmcnt<24>();   // everything but the 3 newest blocks has landed
+    } else {
+      wait_vmcnt<0>();
+    }
+    lds_char* kt = wlds + stage * kDecStageBytes;
+    lds_char* vt = kt + kDecTileBytes;
+
+    f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 a = lds_read16(kt + k_tok * kRowBytes + (((4 * kk + g4) ^ k_tok) << 4));
+      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[kk], s, 0, 0, 0);
+    }
+    // register r of lane (g4, head) is the score of row 16*b + 4*g4 + r
+    if ((b + 1) * kDecBlockRows > n) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (b * kDecBlockRows + 4 * g4 + r >= n) s[r] = kNegBig;
+    }
+    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m, mx);
+    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
+      const float alpha = fast_exp2((m - m_new) * c);
+      l *= alpha;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] *= alpha;
+      m = m_new;
+    }
+    const float mc = m * c;
+    float p[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) p[r] = fast_exp2(__builtin_fmaf(s[r], c, -mc));
+    l += (p[0] + p[1]) + (p[2] + p[3]);
+    bf16x4 pb;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) pb[r] = (__bf16)p[r];
+    const short4v pbs = __builtin_bit_cast(short4v, pb);
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      // V^T operand: lane receives dim 16*db + (lane & 15) of rows 4*g4 .. 4*g4+3
+      const int chunk = (2 * db + (v_sub >> 1)) ^ ((v_row & 7) << 1);
+      bf16x4 a = lds_read_tr8(vt + v_row * kRowBytes + (chunk << 4) + ((v_sub & 1) << 3));
+      o[db] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(short4v, a), pbs, o[db], 0, 0, 0);
+    }
+    asm volatile("" ::: "memory");
+  }
+
+  // per-lane-group partial sums -> per-head sums
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+
+  // merge the four wavefronts through LDS (the ring is idle now)
+  __syncthreads();
+  float* red = (float*)lds_raw;                 // [4 waves][16 heads][130]
+  float* mine = red + wave * 16 * kPartialFloats;
+#pragma unroll
+  for (int db = 0; db < 8; ++db)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) mine[head * kPartialFloats + 16 * db + 4 * g4 + r] = o[db][r];
+  if (g4 == 0) {
+    mine[head * kPartialFloats + kHeadDim] = m;
+    mine[head * kPartialFloats + kHeadDim + 1] = l;
+  }
+  __syncthreads();
+  float* dst = partials + (int64_t)(part0 + blockIdx.x) * G * kPartialFloats;
+  for (int idx = threadIdx.x; idx < G * kHeadDim; idx += blockDim.x) {
+    const int h = idx >> 7, dim = idx & 127;
+    float mw[4], M = kNegBig;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      mw[w] = red[(w * 16 + h) * kPartialFloats + kHeadDim];
+      M = fmaxf(M, mw[w]);
+    }
+    float acc = 0.f, L = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float wgt = fast_exp2((mw[w] - M) * c);
+      acc += wgt * red[(w * 16 + h) * kPartialFloats + dim];
+      L += wgt * red[(w * 16 + h) * kPartialFloats + kHeadDim + 1];
+    }
+    dst[h * kPartialFloats + dim] = acc;
+    if (dim == 0) {
+      dst[h * kPartialFloats + kHeadDim] = M;
+      dst[h * kPartialFloats + kHeadDim + 1] = L;
+    }
+  }
+}
+
+// K3: out[g][:] = (sum_s O_s w_s + p_new v_new) / (sum_s l_s w_s + p_new),  w_s = 2^{(m_s - M) c},
+// p_new = 2^{(q_g . k_new - M) c}, M = max(max_s m_s, q_g . k_new).   grid (G, 4): one query head, 32 dims.
+__global__ __launch_bounds__(256) void decode_combine_kernel(const uint16_t* __restrict__ q, int G,
+                                                             const uint16_t* __restrict__ k_new,
+                                                             const uint16_t* __restrict__ v_new,
+                                                             const float* __restrict__ partials, int n_part,
+                                                             void* __restrict__ out, int out_fp32, float c) {
+  __shared__ float red[256];
+  __shared__ float red_o[8][33];
+  __shared__ float bc[2];
+  const int g = blockIdx.x;
+  const int tid = threadIdx.x;
+
+  // score of the token's own row
+  if (tid < 64) {
+    float d = bf16_bits_to_float(q[g * kHeadDim + tid]) * bf16_bits_to_float(k_new[tid]) +
+              bf16_bits_to_float(q[g * kHeadDim + 64 + tid]) * bf16_bits_to_float(k_new[64 + tid]);
+    for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off);
+    if (tid == 0) bc[0] = d;
+  }
+  float mx = kNegBig;
+  for (int p = tid; p < n_part; p += 256) mx = fmaxf(mx, partials[((int64_t)p * G + g) * kPartialFloats + kHeadDim]);
+  red[tid] = mx;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) red[tid] = fmaxf(red[tid], red[tid + s]);
+    __syncthreads();
+  }
+  const float s_new = bc[0];
+  const float M = fmaxf(red[0], s_new);
+
+  const int pl = tid >> 5;                       // 8 partition lanes
+  const int dim = blockIdx.y * 32 + (tid & 31);
+  float acc = 0.f, L = 0.f;
+  for (int p = pl; p < n_part; p += 8) {
+    const float* src = partials + ((int64_t)p * G + g) * kPartialFloats;
+    const float w = fast_exp2((src[kHeadDim] - M) * c);
+    acc += w * src[dim];
+    L += w * src[kHeadDim + 1];
+  }
+  red_o[pl][tid & 31] = acc;
+  if ((tid & 31) == 0) red_o[pl][32] = L;
+  __syncthreads();
+  if (tid < 32) {
+    float a = 0.f, lsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { a += red_o[i][tid]; lsum += red_o[i][32]; }
+    const float p_new = fast_exp2((s_new - M) * c);
+    a += p_new * bf16_bits_to_float(v_new[dim]);
+    lsum += p_new;
+    const float r = a / lsum;
+    if (out_fp32) ((float*)out)[g * kHeadDim + dim] = r;
+    else ((uint16_t*)out)[g * kHeadDim + dim] = float_to_bf16_bits(r);
+  }
+}
+
+static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   // log2(e) / sqrt(128)
+
+hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
+                                int n_split, void* partials, int part0) {
+  if (n <= 0 || n_split <= 0) { set_last_error("decode partial: empty launch"); return HI_ERR_ARG; }
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)decode_partial_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsBytes);
+    if (e != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(decode_partial_kernel, dim3(n_split), dim3(256), kDecLdsBytes, (hipStream_t)stream,
+                     (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_error("decode_partial launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+  return HI_OK;
+}
+
+hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
+                                const void* partials, int n_part, void* out, int out_fp32) {
+  hipLaunchKernelGGL(decode_combine_kernel, dim3(G, 4), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)q, G,
+                     (const uint16_t*)k_new, (const uint16_t*)v_new, (const float*)partials, n_part, out, out_fp32,
+                     kScaleLog2e);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_error("decode_combine launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+  return HI_OK;
+}
+
+}  // namespace hi

@@ -1,0 +1,46 @@
+// Internal declarations shared by the host-side sources of the library (not part of the ABI).
+#pragma once
+#include <cstdint>
+#include <cstddef>
+#include "headinfer.h"
+
+namespace hi {
+
+constexpr int kHeadDim = 128;
+constexpr int kRowBytes = kHeadDim * 2;          // one K (or V) row of one head, bf16
+constexpr int kWgThreads = 256;                  // 4 wavefronts of 64
+constexpr int kCarryFloatsPerLane = 66;          // 64 O^T accumulators + running max + running sum
+constexpr int kPartialFloats = kHeadDim + 2;     // O[128], m, l of one (partition, query head)
+
+void set_last_error(const char* fmt, ...);
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+// query positions covered by one prefill workgroup, and the grid's second dimension, for a GQA group size
+inline int prefill_strip(int G) { return 32 * (4 / (G < 4 ? G : 4)); }
+inline int prefill_grid_y(int G) { return G > 4 ? G / 4 : 1; }
+
+hi_status validate_problem(const hi_problem* p);
+
+// ---- kernel launchers (defined in the .hip files) ------------------------------------------------------
+struct PrefillSegment {
+  const void* k;      // device, [n][128] bf16
+  const void* v;
+  int64_t n;          // rows
+  int causal;         // 1: rows are the chunk's own (row j visible to query i iff j <= i)
+};
+
+// One launch of the prefill kernel over up to two KV segments.  first: start from an empty softmax state
+// instead of loading the carry; last: normalise and write `out` instead of storing the carry.
+hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& a,
+                         const PrefillSegment& b, int first, int last, void* carry, void* out, int out_fp32);
+
+// Split-KV decode over rows [0, n) of one slice: writes n_split partials starting at partial index part0.
+hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
+                                int n_split, void* partials, int part0);
+// Merge n_part partials with the token's own row and write out[G][128].
+hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
+                                const void* partials, int n_part, void* out, int out_fp32);
+
+}  // namespace hi

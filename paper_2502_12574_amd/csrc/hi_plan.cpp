@@ -1,0 +1,139 @@
+// hi_offload_plan: pure host arithmetic (no HIP calls).
+// Follows Algorithm 1 "Initialization", Eq. 4-6 and 10-11 (cache size, on-GPU fraction), Section 4
+// (pre-allocation; adaptive head-wise offloading thresholds) and the Section 5 performance model.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include "hi_internal.h"
+
+namespace hi {
+
+static thread_local char g_last_error[512] = "";
+
+void set_last_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_last_error, sizeof(g_last_error), fmt, ap);
+  va_end(ap);
+}
+
+hi_status validate_problem(const hi_problem* p) {
+  if (!p) { set_last_error("problem is null"); return HI_ERR_ARG; }
+  if (p->n_layers < 1 || p->n_kv_heads < 1 || p->max_context < 1 || p->chunk < 1 ||
+      p->gpu_kv_budget_heads < 1 || p->n_compute_units < 0 || p->host_mem_limit_bytes < 0 ||
+      p->link_GBps < 0 || p->hbm_GBps < 0 || p->mfma_TFLOPs < 0 || (p->out_fp32 != 0 && p->out_fp32 != 1)) {
+    set_last_error("problem field out of range");
+    return HI_ERR_ARG;
+  }
+  if (p->chunk > p->max_context) { set_last_error("chunk %d exceeds max_context", p->chunk); return HI_ERR_ARG; }
+  if (p->head_dim != kHeadDim) { set_last_error("head_dim %d unsupported (128 only)", p->head_dim); return HI_ERR_UNSUPPORTED; }
+  if (p->dtype_bytes != 2) { set_last_error("dtype_bytes %d unsupported (bf16 only)", p->dtype_bytes); return HI_ERR_UNSUPPORTED; }
+  const int g = p->gqa_group;
+  if (!(g == 1 || g == 2 || g == 4 || g == 8)) { set_last_error("gqa_group %d unsupported", g); return HI_ERR_UNSUPPORTED; }
+  return HI_OK;
+}
+
+}  // namespace hi
+
+using namespace hi;
+
+extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
+  if (!out) { set_last_error("plan is null"); return HI_ERR_ARG; }
+  hi_status st = validate_problem(p);
+  if (st != HI_OK) return st;
+
+  hi_plan pl;
+  std::memset(&pl, 0, sizeof(pl));
+  const int64_t S = p->max_context;
+  const int64_t C = p->chunk;
+  const int G = p->gqa_group;
+  const int64_t row = 2LL * p->head_dim * p->dtype_bytes;  // K row + V row of one head
+
+  // Eq. 11 and Eq. 4
+  pl.host_bytes_per_head = S * row;
+  pl.host_bytes_total = (int64_t)p->n_layers * p->n_kv_heads * pl.host_bytes_per_head;
+  if (p->host_mem_limit_bytes > 0 && pl.host_bytes_total > p->host_mem_limit_bytes) {
+    set_last_error("host cache of %lld bytes exceeds the limit", (long long)pl.host_bytes_total);
+    return HI_ERR_HOST_MEM;
+  }
+  // Eq. 10
+  pl.alpha = (double)p->gpu_kv_budget_heads / ((double)p->n_layers * p->n_kv_heads);
+  pl.hbm_pingpong_paper_bytes = 2 * pl.host_bytes_per_head;
+
+  // finest granularity: one KV head per transfer and launch
+  pl.heads_per_group = 1;
+  pl.n_groups = p->n_kv_heads;
+  {  // Section 4: all heads fused up to 500K, two groups to 1M, four to 2M, eight beyond
+    int groups = S <= 500 * 1024 ? 1 : S <= 1024 * 1024 ? 2 : S <= 2048 * 1024 ? 4 : 8;
+    int hpg = p->n_kv_heads / groups;
+    pl.paper_heads_per_group = hpg < 1 ? 1 : hpg;
+  }
+
+  // staging ring: sequence slices inside the HBM budget, so that a slice can land while another is consumed
+  const int64_t budget_tokens = (int64_t)p->gpu_kv_budget_heads * S;
+  int64_t slice = (budget_tokens / 8) / 64 * 64;
+  if (slice < 64) slice = 64;
+  if (slice > 262144) slice = 262144;
+  if (budget_tokens / slice > 64) slice = round_up(ceil_div(budget_tokens, 64), 64);
+  const int64_t n_slices = budget_tokens / slice;
+  if (n_slices < 2) {
+    set_last_error("HBM KV budget of %lld rows cannot hold two staging slices", (long long)budget_tokens);
+    return HI_ERR_HBM_BUDGET;
+  }
+  pl.slice_tokens = slice;
+  pl.n_slices_ring = (int32_t)n_slices;
+  pl.hbm_staging_bytes = n_slices * slice * row;
+
+  const int n_cu = p->n_compute_units > 0 ? p->n_compute_units : 256;
+  pl.n_split_decode = n_cu;
+  pl.prefill_rows_per_wg = prefill_strip(G);
+
+  const int64_t n_wg = ceil_div(C, pl.prefill_rows_per_wg) * prefill_grid_y(G);
+  const int64_t carry_bytes = n_wg * kWgThreads * kCarryFloatsPerLane * 4;
+  const int64_t max_parts = (ceil_div(S, slice) + 1) * pl.n_split_decode;
+  const int64_t partial_bytes = max_parts * G * kPartialFloats * 4;
+  pl.ws_partials_offset = round_up(carry_bytes, 256);
+  pl.workspace_bytes = pl.ws_partials_offset + round_up(partial_bytes, 256);
+
+  // Section 5: T ~ max(T_comp, T_mem), evaluated for the deepest unit
+  const double link = (p->link_GBps > 0 ? p->link_GBps : 64.0) * 1e9;
+  const double hbm = (p->hbm_GBps > 0 ? p->hbm_GBps : 8000.0) * 1e9;
+  const double mfma = (p->mfma_TFLOPs > 0 ? p->mfma_TFLOPs : 2500.0) * 1e12;
+  const double P = (double)(S - C);
+  const double d = p->head_dim;
+  pl.flop_prefill_unit = 4.0 * d * G * ((double)C * P + 0.5 * (double)C * ((double)C + 1.0));
+  pl.bytes_link_prefill_unit = (double)row * (P + (double)C);
+  pl.bytes_link_decode_unit = (double)row * (double)S;
+  const double qo_bytes = 2.0 * G * (double)C * d * p->dtype_bytes;
+  pl.t_comp_prefill_s = pl.flop_prefill_unit / mfma;
+  pl.t_link_prefill_s = pl.bytes_link_prefill_unit / link;
+  pl.t_hbm_prefill_s = ((double)row * (P + (double)C) + qo_bytes) / hbm;
+  pl.t_comp_decode_s = 4.0 * d * G * (double)S / mfma;
+  pl.t_link_decode_s = pl.bytes_link_decode_unit / link;
+  pl.t_hbm_decode_s = (double)row * (double)S / hbm;
+  auto regime = [](double tc, double tl, double th) {
+    if (tc >= tl && tc >= th) return (int32_t)HI_REGIME_COMPUTE;
+    return tl >= th ? (int32_t)HI_REGIME_LINK : (int32_t)HI_REGIME_HBM;
+  };
+  pl.regime_prefill = regime(pl.t_comp_prefill_s, pl.t_link_prefill_s, pl.t_hbm_prefill_s);
+  pl.regime_decode = regime(pl.t_comp_decode_s, pl.t_link_decode_s, pl.t_hbm_decode_s);
+
+  *out = pl;
+  return HI_OK;
+}
+
+extern "C" const char* hi_status_string(hi_status s) {
+  switch (s) {
+    case HI_OK: return "HI_OK";
+    case HI_ERR_ARG: return "HI_ERR_ARG";
+    case HI_ERR_UNSUPPORTED: return "HI_ERR_UNSUPPORTED";
+    case HI_ERR_HBM_BUDGET: return "HI_ERR_HBM_BUDGET";
+    case HI_ERR_HOST_MEM: return "HI_ERR_HOST_MEM";
+    case HI_ERR_RANGE: return "HI_ERR_RANGE";
+    case HI_ERR_NOT_PINNED: return "HI_ERR_NOT_PINNED";
+    case HI_ERR_HIP: return "HI_ERR_HIP";
+    default: return "HI_ERR_UNKNOWN";
+  }
+}
+
+extern "C" const char* hi_last_error(void) { return hi::g_last_error; }

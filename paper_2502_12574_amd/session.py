@@ -1,0 +1,67 @@
+"""Buffers, streams and a context for one problem: the thin harness the tests and the benchmark share.
+
+PyTorch is used for device / pinned-host memory and streams only; every step of the path runs in the library.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as hb
+
+
+class Session:
+    def __init__(self, n_layers, n_kv_heads, gqa_group, max_context, chunk, mode=hb.HI_MODE_OFFLOAD, out_fp32=1,
+                 device="cuda:0", gpu_kv_budget_heads=1, n_compute_units=0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("a GPU is required: the library has no CPU path")
+        self.device = torch.device(device)
+        self.mode = mode
+        self.G = gqa_group
+        self.problem = hb.make_problem(n_layers, n_kv_heads, gqa_group, max_context, chunk, out_fp32=out_fp32,
+                                       gpu_kv_budget_heads=gpu_kv_budget_heads, n_compute_units=n_compute_units)
+        self.plan = hb.hi_offload_plan(self.problem)
+        nbytes = self.plan.host_bytes_total
+        if mode == hb.HI_MODE_OFFLOAD:
+            self.kv = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+            self.staging = torch.empty(self.plan.hbm_staging_bytes, dtype=torch.uint8, device=self.device)
+        else:
+            self.kv = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            self.staging = None
+        self.workspace = torch.empty(self.plan.workspace_bytes, dtype=torch.uint8, device=self.device)
+        self.s_compute = torch.cuda.Stream(self.device)
+        self.s_h2d = torch.cuda.Stream(self.device)
+        self.s_d2h = torch.cuda.Stream(self.device)
+        self.ctx = hb.hi_ctx_create(self.problem, self.plan, mode, self.kv, self.staging, self.workspace,
+                                    self.s_compute, self.s_h2d, self.s_d2h)
+        self.out_dtype = torch.float32 if out_fp32 else torch.bfloat16
+
+    # [layer][kv_head][K|V][S_max][d] bf16 views of the cache (host or device)
+    def cache_view(self) -> torch.Tensor:
+        p = self.problem
+        return self.kv.view(torch.bfloat16).view(p.n_layers, p.n_kv_heads, 2, p.max_context, p.head_dim)
+
+    def prefill_head(self, layer, head, q, k_new, v_new, past_len, out, nxt=None):
+        nl, nh, npast = nxt if nxt is not None else (-1, 0, 0)
+        return hb.hi_prefill_head(self.ctx, layer, head, q, k_new, v_new, past_len, k_new.shape[0], out, nl, nh, npast)
+
+    def decode_head(self, layer, head, q, k_new, v_new, past_len, out, nxt=None):
+        nl, nh, npast = nxt if nxt is not None else (-1, 0, 0)
+        return hb.hi_decode_head(self.ctx, layer, head, q, k_new, v_new, past_len, out, nl, nh, npast)
+
+    def sync(self):
+        hb.hi_sync(self.ctx)
+
+    def stats(self):
+        return hb.hi_get_stats(self.ctx)
+
+    def close(self):
+        if self.ctx is not None:
+            hb.hi_sync(self.ctx, check=False)
+            hb.hi_ctx_destroy(self.ctx)
+            self.ctx = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()

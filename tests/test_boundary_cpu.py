@@ -1,0 +1,146 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports what the header declares, plans correctly
+(against the memory-model oracle and the values the paper prints) and rejects bad arguments before any GPU call."""
+import ctypes
+import json
+import os
+import re
+import subprocess
+
+import pytest
+
+from oracle import memory_model as mm
+from paper_2502_12574_amd import binding as hb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLD = json.load(open(os.path.join(ROOT, "tests", "golden", "paper_memory_tables.json")))
+
+
+def llama(S, C, **kw):
+    return hb.make_problem(n_layers=32, n_kv_heads=8, gqa_group=4, max_context=S, chunk=C, **kw)
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "headinfer.h")).read()
+    code = re.sub(r"/\*.*?\*/", "", header, flags=re.S)            # declarations only, not the comments
+    declared = set(re.findall(r"\b(hi_[a-z_]+)\s*\(", code))
+    assert declared == set(hb.EXPORTS)
+    raw = ctypes.CDLL(hb.LIB_PATH)
+    for name in declared:
+        assert hasattr(raw, name), name
+    assert hb.status_string(0) == "HI_OK" and hb.status_string(-5) == "HI_ERR_RANGE"
+
+
+def test_struct_layouts_match_the_c_header(tmp_path):
+    # compile the header with the host C compiler and compare sizes and a few offsets with the ctypes mirror
+    src = tmp_path / "sz.c"
+    src.write_text('''#include <stdio.h>
+#include <stddef.h>
+#include "headinfer.h"
+int main(void){ printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(hi_problem), sizeof(hi_plan), sizeof(hi_stats),
+  offsetof(hi_problem, mfma_TFLOPs), offsetof(hi_plan, regime_decode), offsetof(hi_stats, decode_kernel_ms)); return 0; }
+''')
+    exe = tmp_path / "sz"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split()]
+    want = [ctypes.sizeof(hb.hi_problem), ctypes.sizeof(hb.hi_plan), ctypes.sizeof(hb.hi_stats),
+            hb.hi_problem.mfma_TFLOPs.offset, hb.hi_plan.regime_decode.offset, hb.hi_stats.decode_kernel_ms.offset]
+    assert got == want
+
+
+def test_plan_pins_paper_memory_numbers():
+    S = 1 << 20
+    pl = hb.hi_offload_plan(llama(S, 16384))
+    # Eq. 11: one head's K+V at 1M tokens = 512 MiB; Table 10 "1" GB is the two-head ping-pong
+    assert pl.host_bytes_per_head == 512 << 20 == mm.head_bytes(mm.LLAMA3_8B, S)
+    assert pl.hbm_pingpong_paper_bytes == 1 << 30
+    assert pl.hbm_pingpong_paper_bytes / 2 ** 30 == GOLD["table10_1M_context"]["rows"]["headwise"]["kv"]
+    # Eq. 4 / Table 10: 128 GB in total
+    assert pl.host_bytes_total == 128 << 30 == mm.kv_cache_bytes(mm.LLAMA3_8B, S)
+    assert pl.host_bytes_total / 2 ** 30 == GOLD["table10_1M_context"]["rows"]["headwise"]["total_kv"]
+    # Eq. 10
+    assert pl.alpha == GOLD["alpha"]["value"] == mm.alpha_headwise(mm.LLAMA3_8B)
+    # the strict one-head budget: the ring never exceeds one head's bytes
+    assert pl.hbm_staging_bytes <= pl.host_bytes_per_head
+    assert pl.hbm_staging_bytes == pl.n_slices_ring * pl.slice_tokens * 512 and pl.n_slices_ring >= 2
+    assert pl.heads_per_group == 1 and pl.n_groups == 8
+    # Table 11, HeadInfer-4000K row: 3.91 GB on the GPU (two heads), 500 GB in total
+    S4 = 4000 * 1024
+    pl4 = hb.hi_offload_plan(llama(S4, 32768))
+    g = GOLD["table11_max_context"]["rows"]["headwise"]
+    assert round(pl4.hbm_pingpong_paper_bytes / 2 ** 30, 2) == g["kv"]
+    assert round(pl4.host_bytes_total / 2 ** 30) == g["total_kv"]
+
+
+@pytest.mark.parametrize("S,expect", [(100 * 1024, 8), (500 * 1024, 8), (500 * 1024 + 1, 4), (1 << 20, 4),
+                                      ((1 << 20) + 1, 2), (2 << 20, 2), ((2 << 20) + 1, 1), (4 << 20, 1)])
+def test_plan_reports_paper_adaptive_grouping(S, expect):
+    # Section 4: all heads fused up to 500K, two groups to 1M, four to 2M, eight (one head each) beyond
+    assert hb.hi_offload_plan(llama(S, 8192)).paper_heads_per_group == expect
+
+
+def test_plan_flop_and_byte_model_matches_oracle():
+    S, Cc = 1 << 20, 16384
+    pl = hb.hi_offload_plan(llama(S, Cc))
+    assert pl.flop_prefill_unit == mm.causal_flops_unit(4, Cc, S - Cc, 128)
+    assert pl.bytes_link_prefill_unit == 512 * S
+    assert pl.bytes_link_decode_unit == 512 * S
+    # link intensity of a prefill unit is ~ C * G flop per byte (the law behind Table 12's offload columns)
+    assert abs(pl.flop_prefill_unit / (512 * (S - Cc)) / (Cc * 4) - 1.0) < 0.01
+    assert pl.regime_prefill == hb.HI_REGIME_COMPUTE and pl.regime_decode == hb.HI_REGIME_LINK
+    # Table 12: with a 25 GB/s link and 165 TFLOPS, a 1K-context offloaded prefill is link bound, 10K is not
+    for S_k, row in ((1, "memory"), (10, "compute")):
+        p = llama(S_k * 1024, S_k * 1024, link_GBps=25.0, mfma_TFLOPs=165.0, hbm_GBps=1000.0)
+        got = hb.hi_offload_plan(p).regime_prefill
+        # the paper's table counts 4*S^2*d flops against 2*S*d*2*2 KV bytes (non-causal); at chunk = S and P = 0
+        # the causal unit has half those flops, so the 1K case stays link bound and the 10K case compute bound
+        assert (got == hb.HI_REGIME_LINK) == (row == "memory"), (S_k, got)
+
+
+def test_plan_geometry_small_and_large():
+    pl = hb.hi_offload_plan(hb.make_problem(1, 1, 4, 2048 + 16, 512))
+    assert pl.slice_tokens == 256 and pl.n_slices_ring == 8 and pl.prefill_rows_per_wg == 32
+    pl = hb.hi_offload_plan(llama(4 << 20, 32768))
+    assert pl.slice_tokens == 262144 and pl.n_slices_ring == 16
+    assert pl.workspace_bytes >= pl.ws_partials_offset + (17 * 256) * 4 * 130 * 4
+    assert hb.hi_offload_plan(hb.make_problem(1, 1, 1, 4096, 512)).prefill_rows_per_wg == 128
+
+
+def test_plan_rejects_bad_problems():
+    bad = [
+        (dict(head_dim=64), hb.HI_ERR_UNSUPPORTED),
+        (dict(dtype_bytes=4), hb.HI_ERR_UNSUPPORTED),
+        (dict(gqa_group=3), hb.HI_ERR_UNSUPPORTED),
+        (dict(n_layers=0), hb.HI_ERR_ARG),
+        (dict(max_context=0), hb.HI_ERR_ARG),
+        (dict(chunk=0), hb.HI_ERR_ARG),
+        (dict(chunk=5000), hb.HI_ERR_ARG),
+        (dict(gpu_kv_budget_heads=0), hb.HI_ERR_ARG),
+        (dict(max_context=100, chunk=50), hb.HI_ERR_HBM_BUDGET),
+        (dict(host_mem_limit_bytes=1 << 20), hb.HI_ERR_HOST_MEM),
+    ]
+    for kw, code in bad:
+        args = dict(n_layers=2, n_kv_heads=2, gqa_group=4, max_context=4096, chunk=512)
+        args.update(kw)
+        st, plan = hb.hi_offload_plan(hb.make_problem(**args), check=False)
+        assert st == code, (kw, st)
+        assert plan.host_bytes_total == 0          # untouched on error
+    assert hb.lib().hi_offload_plan(None, None) == hb.HI_ERR_ARG
+
+
+def test_entry_points_reject_null_context_without_touching_the_gpu():
+    L = hb.lib()
+    assert L.hi_prefill_head(None, 0, 0, None, None, None, 0, 1, None, -1, 0, 0) == hb.HI_ERR_ARG
+    assert L.hi_decode_head(None, 0, 0, None, None, None, 0, None, -1, 0, 0) == hb.HI_ERR_ARG
+    assert L.hi_sync(None) == hb.HI_ERR_ARG
+    assert L.hi_get_stats(None, None) == hb.HI_ERR_ARG
+    assert L.hi_ctx_destroy(None) == hb.HI_OK
+    prob = hb.make_problem(1, 1, 4, 4096, 512)
+    plan = hb.hi_offload_plan(prob)
+    st, _ = hb.hi_ctx_create(prob, plan, 7, 1, 1, 1, None, None, None, check=False)
+    assert st == hb.HI_ERR_ARG                      # unknown mode
+    st, _ = hb.hi_ctx_create(prob, plan, hb.HI_MODE_OFFLOAD, None, 1, 1, None, None, None, check=False)
+    assert st == hb.HI_ERR_ARG                      # null cache
+    other = hb.hi_offload_plan(hb.make_problem(1, 1, 4, 8192, 512))
+    st, _ = hb.hi_ctx_create(prob, other, hb.HI_MODE_OFFLOAD, 1, 1, 1, None, None, None, check=False)
+    assert st == hb.HI_ERR_ARG and "plan" in hb.last_error()

@@ -1,0 +1,184 @@
+"""GPU parity, element by element, against the fp64 oracle at sizes the oracle finishes in seconds.
+
+Tolerance (bf16 inputs, fp32 accumulation, fp32 output): max-abs <= 1e-2 and relative L2 <= 5e-3 per
+(call, query head); bf16 output must equal the round-to-nearest-even of the fp32 output bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from paper_2502_12574_amd import binding as hb
+from paper_2502_12574_amd import synth
+from paper_2502_12574_amd.session import Session
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2 = 1e-2, 5e-3
+
+
+def check(got: torch.Tensor, ref: np.ndarray, what=""):
+    got = got.detach().to("cpu").to(torch.float64).numpy()
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    assert np.isfinite(got).all(), what
+    err = np.abs(got - ref).max()
+    flat_g, flat_r = got.reshape(got.shape[0], -1), ref.reshape(ref.shape[0], -1)
+    rel = np.sqrt(((flat_g - flat_r) ** 2).sum(axis=1) / (flat_r ** 2).sum(axis=1)).max()
+    assert err <= MAX_ABS and rel <= REL_L2, (what, err, rel)
+    return err, rel
+
+
+def run_config1(mode, seed=20250213, S=2048, C=512, G=4, n_decode=16):
+    """Tiny single-layer, single-KV-head case: chunked prefill then decode steps, full tensors returned."""
+    dev = "cuda:0"
+    with Session(1, 1, G, S + n_decode, C, mode=mode, out_fp32=1) as ss:
+        outs, dec = [], []
+        with torch.cuda.stream(ss.s_compute):
+            Q = torch.stack([synth.draw_q(seed, 0, g, 0, S + n_decode, device=dev) for g in range(G)])
+            K = synth.draw_k(seed, 0, 0, 0, S + n_decode, device=dev)
+            V = synth.draw_v(seed, 0, 0, 0, S + n_decode, device=dev)
+            for p in range(0, S, C):
+                q = Q[:, p:p + C].contiguous()
+                out = torch.empty(G, C, 128, dtype=torch.float32, device=dev)
+                nxt = (0, 0, p + C)
+                ss.prefill_head(0, 0, q, K[p:p + C], V[p:p + C], p, out, nxt)
+                outs.append(out)
+            for t in range(n_decode):
+                p = S + t
+                q = Q[:, p].contiguous()
+                out = torch.empty(G, 128, dtype=torch.float32, device=dev)
+                ss.decode_head(0, 0, q, K[p], V[p], p, out, (0, 0, p + 1) if t + 1 < n_decode else None)
+                dec.append(out)
+        ss.sync()
+        cache = ss.cache_view()[0, 0].to("cpu").clone()
+        stats = ss.stats()
+        plan = ss.plan
+    return (torch.cat(outs, dim=1).cpu(), torch.stack(dec).cpu(), cache, Q.cpu(), K.cpu(), V.cpu(), stats, plan)
+
+
+@pytest.fixture(scope="module")
+def cfg1_oracle():
+    seed, S, nd, G = 20250213, 2048, 16, 4
+    Q = np.stack([synth.to_f64(synth.draw_q(seed, 0, g, 0, S + nd)) for g in range(G)])
+    K = synth.to_f64(synth.draw_k(seed, 0, 0, 0, S + nd))
+    V = synth.to_f64(synth.draw_v(seed, 0, 0, 0, S + nd))
+    return oa.attn_head(Q, K, V)          # [G, S+nd, d]; row p is also what a decode step at position p returns
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
+def test_config1_prefill_and_decode_match_oracle(mode, cfg1_oracle):
+    S, nd = 2048, 16
+    pre, dec, cache, Q, K, V, stats, plan = run_config1(mode)
+    # the GPU saw the same bits the oracle regenerated on the CPU
+    assert torch.equal(K, synth.draw_k(20250213, 0, 0, 0, S + nd))
+    for g in range(4):
+        check(pre[g:g + 1], cfg1_oracle[g:g + 1, :S], f"prefill head {g}")
+    for t in range(nd):
+        check(dec[t], cfg1_oracle[:, S + t], f"decode step {t}")
+    # write-back: the cache holds exactly the rows that were appended
+    assert torch.equal(cache[0, :S + nd], K) and torch.equal(cache[1, :S + nd], V)
+    if mode == hb.HI_MODE_OFFLOAD:
+        assert stats.peak_staging_bytes <= plan.host_bytes_per_head          # <= 1 KV head resident in HBM
+        assert stats.bytes_d2h == 512 * (S + nd)
+        assert stats.bytes_h2d == 512 * (sum(range(0, S, 512)) + sum(S + t for t in range(nd)))
+
+
+def test_offloaded_equals_resident_bitwise_for_prefill():
+    a = run_config1(hb.HI_MODE_RESIDENT)
+    b = run_config1(hb.HI_MODE_OFFLOAD)
+    assert torch.equal(a[0], b[0])
+    assert (a[1] - b[1]).abs().max() < 1e-5      # decode partitions differ between the two modes
+
+
+def one_unit(G, P, C, seed, out_fp32=1, mode=hb.HI_MODE_RESIDENT, peaked=False):
+    dev = "cuda:0"
+    with Session(1, 1, G, max(P + C, 128), max(C, 1), mode=mode, out_fp32=out_fp32) as ss:
+        with torch.cuda.stream(ss.s_compute):
+            Q = torch.stack([synth.draw_q(seed, 0, g, P, C, device=dev) for g in range(G)])
+            K = synth.draw_k(seed, 0, 0, 0, P + C, device=dev, peaked=peaked)
+            V = synth.draw_v(seed, 0, 0, 0, P + C, device=dev)
+            cv = ss.cache_view()
+            if P:
+                cv[0, 0, 0, :P].copy_(K[:P])
+                cv[0, 0, 1, :P].copy_(V[:P])
+            torch.cuda.current_stream().synchronize()
+            out = torch.empty(G, C, 128, dtype=ss.out_dtype, device=dev)
+            ss.prefill_head(0, 0, Q, K[P:], V[P:], P, out)
+        ss.sync()
+        return out.cpu(), Q.cpu(), K.cpu(), V.cpu()
+
+
+@pytest.mark.parametrize("G,P,C", [(4, 0, 1), (4, 0, 31), (4, 1, 33), (4, 63, 100), (4, 65, 257), (4, 300, 64),
+                                   (4, 1000, 129), (1, 77, 200), (2, 130, 95), (8, 200, 70), (8, 0, 40)])
+def test_prefill_ragged_shapes(G, P, C):
+    out, Q, K, V = one_unit(G, P, C, seed=900 + P + C)
+    ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
+    for g in range(G):
+        check(out[g:g + 1], ref[g:g + 1], f"G={G} P={P} C={C} head {g}")
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
+def test_prefill_ragged_offload_and_peaked_keys(mode):
+    # keys scaled x4 on one row in ten: logits with sigma ~ 4, peaked softmax rows
+    G, P, C = 4, 1500, 300
+    out, Q, K, V = one_unit(G, P, C, seed=31337, mode=mode, peaked=True)
+    ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
+    for g in range(G):
+        check(out[g:g + 1], ref[g:g + 1], f"peaked head {g}")
+
+
+def test_bf16_output_is_rne_of_fp32_output():
+    a, *_ = one_unit(4, 200, 96, seed=5, out_fp32=1)
+    b, *_ = one_unit(4, 200, 96, seed=5, out_fp32=0)
+    assert b.dtype == torch.bfloat16
+    assert torch.equal(a.to(torch.bfloat16), b)
+
+
+@pytest.mark.parametrize("G,P", [(4, 0), (4, 1), (4, 15), (4, 17), (4, 1000), (4, 5001), (1, 333), (2, 64), (8, 2049)])
+def test_decode_ragged_shapes(G, P):
+    dev = "cuda:0"
+    seed = 4000 + P
+    for mode in (hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD):
+        with Session(1, 2, G, max(P + 1, 128), 64, mode=mode, out_fp32=1) as ss:
+            with torch.cuda.stream(ss.s_compute):
+                q = torch.stack([synth.draw_q(seed, 0, g, P, 1, device=dev)[0] for g in range(G)])
+                K = synth.draw_k(seed, 0, 1, 0, P + 1, device=dev)
+                V = synth.draw_v(seed, 0, 1, 0, P + 1, device=dev)
+                cv = ss.cache_view()
+                if P:
+                    cv[0, 1, 0, :P].copy_(K[:P])
+                    cv[0, 1, 1, :P].copy_(V[:P])
+                torch.cuda.current_stream().synchronize()
+                out = torch.empty(G, 128, dtype=torch.float32, device=dev)
+                ss.decode_head(0, 1, q, K[P], V[P], P, out)
+            ss.sync()
+            ref = oa.attn_rows(synth.to_f64(q), synth.to_f64(K), synth.to_f64(V), np.full(G, P))
+            check(out, ref, f"decode G={G} P={P} mode={mode}")
+            assert torch.equal(ss.cache_view()[0, 1, 0, P].cpu(), K[P].cpu())
+
+
+def test_runtime_argument_errors_leave_cache_untouched():
+    dev = "cuda:0"
+    with Session(1, 1, 4, 1024, 128, mode=hb.HI_MODE_OFFLOAD) as ss:
+        ss.kv.fill_(7)
+        q = torch.zeros(4, 128, 128, dtype=torch.bfloat16, device=dev)
+        k = torch.zeros(128, 128, dtype=torch.bfloat16, device=dev)
+        out = torch.zeros(4, 128, 128, dtype=torch.float32, device=dev)
+        L = hb.lib()
+        f = lambda *a: L.hi_prefill_head(ss.ctx, *a)
+        assert f(0, 0, q.data_ptr(), k.data_ptr(), k.data_ptr(), 1000, 128, out.data_ptr(), -1, 0, 0) == hb.HI_ERR_RANGE
+        assert f(0, 0, q.data_ptr(), k.data_ptr(), k.data_ptr(), 0, 129, out.data_ptr(), -1, 0, 0) == hb.HI_ERR_RANGE
+        assert f(1, 0, q.data_ptr(), k.data_ptr(), k.data_ptr(), 0, 128, out.data_ptr(), -1, 0, 0) == hb.HI_ERR_ARG
+        assert f(0, 0, q.data_ptr() + 2, k.data_ptr(), k.data_ptr(), 0, 128, out.data_ptr(), -1, 0, 0) == hb.HI_ERR_ARG
+        assert f(0, 0, q.data_ptr(), k.data_ptr(), k.data_ptr(), 0, 0, out.data_ptr(), -1, 0, 0) == hb.HI_ERR_ARG
+        assert f(0, 0, q.data_ptr(), k.data_ptr(), k.data_ptr(), -1, 1, out.data_ptr(), -1, 0, 0) == hb.HI_ERR_ARG
+        ss.sync()
+        assert bool((ss.kv == 7).all())
+    # an ordinary (pageable) host buffer is refused
+    prob = hb.make_problem(1, 1, 4, 1024, 128)
+    plan = hb.hi_offload_plan(prob)
+    pageable = torch.empty(plan.host_bytes_total, dtype=torch.uint8)
+    stg = torch.empty(plan.hbm_staging_bytes, dtype=torch.uint8, device=dev)
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=dev)
+    st, _ = hb.hi_ctx_create(prob, plan, hb.HI_MODE_OFFLOAD, pageable, stg, ws, None, None, None, check=False)
+    assert st == hb.HI_ERR_NOT_PINNED
