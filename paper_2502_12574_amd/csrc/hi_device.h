@@ -38,6 +38,16 @@ __device__ __forceinline__ void g2lds16(const char* gsrc, lds_char* lds_uniform)
                : "memory");
 }
 
+// Same, addressed as (64-bit scalar base) + (32-bit per-lane byte offset) + immediate: no vector ALU work per load.
+// The instruction's immediate offset is added to the global address and to the LDS address alike.
+template <int IMM>
+__device__ __forceinline__ void g2lds16_s(const char* sbase, uint32_t voff, uint32_t lds_uniform_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
+               :
+               : "s"(lds_uniform_addr), "v"(voff), "s"(sbase), "n"(IMM)
+               : "memory");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");

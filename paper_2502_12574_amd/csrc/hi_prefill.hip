@@ -18,6 +18,7 @@
 //
 // The softmax state (m, l, O) can be carried across launches (one launch per staging slice) in a register-image
 // workspace, which is how a unit is computed while later slices of its past are still on the host link.
+#include <type_traits>
 #include "hi_device.h"
 #include "hi_internal.h"
 
@@ -42,21 +43,6 @@ struct PrefillArgs {
 __device__ __forceinline__ int swz_k(int row) { return row & 15; }
 __device__ __forceinline__ int swz_v(int row) { return ((row & 3) << 2) | (row & 2); }
 
-// the whole workgroup loads one 64-row K tile and V tile: 8 instructions per wavefront
-__device__ __forceinline__ void pf_issue_tile(const char* __restrict__ k, const char* __restrict__ v, int64_t row0,
-                                              int64_t n, lds_char* stage, int wave, int lane) {
-  const int r_in = lane >> 4;
-  const int cpos = lane & 15;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = (wave * 4 + i) * 4 + r_in;
-    int64_t row = row0 + r;
-    row = row < n ? row : n - 1;
-    g2lds16(k + row * kRowBytes + ((cpos ^ swz_k(r)) << 4), stage + (wave * 4 + i) * 1024);
-    g2lds16(v + row * kRowBytes + ((cpos ^ swz_v(r)) << 4), stage + kPfTileBytes + (wave * 4 + i) * 1024);
-  }
-}
-
 // combine a value with the one held by lane ^ 32 (the other 32 K/V rows of the same query row)
 __device__ __forceinline__ float max_halves(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -67,9 +53,134 @@ __device__ __forceinline__ float sum_halves(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// Per-lane constants of the tile traffic, computed once per kernel.
+struct PfLaneConst {
+  uint32_t gk[4];    // global byte offset inside a 64-row K tile of this lane's 4 load instructions
+  uint32_t gv;       // same for V (instruction i adds i * 1024)
+  uint32_t koff[8];  // LDS byte offset of the K operand read for contraction step kk (sub-block 1 adds 8192)
+  uint32_t voff[4];  // LDS byte offset of the V^T transpose read for dim block db (+2048 next 4 rows of the
+                     // pair, +4096 second 16-row group, +8192 second sub-block)
+};
+
+// One stage's tile loads by the whole workgroup (8 instructions per wavefront).  Full tiles need no vector ALU
+// work at all; the last tile of a segment clamps its row indices (rows past the end re-read the last row and are
+// masked by the caller).
+__device__ __forceinline__ void pf_issue_tile(const char* kt, const char* vt, int rows, uint32_t lds_stage,
+                                              int wave, int lane, const PfLaneConst& lc) {
+  const uint32_t ldk = lds_stage + wave * 4096;
+  const uint32_t ldv = ldk + kPfTileBytes;
+  if (rows >= kPfTileRows) {
+    g2lds16_s<0>(kt, lc.gk[0], ldk);
+    g2lds16_s<0>(kt, lc.gk[1], ldk + 1024);
+    g2lds16_s<0>(kt, lc.gk[2], ldk + 2048);
+    g2lds16_s<0>(kt, lc.gk[3], ldk + 3072);
+    g2lds16_s<0>(vt, lc.gv, ldv);
+    g2lds16_s<1024>(vt, lc.gv, ldv);     // the immediate advances the global AND the LDS address
+    g2lds16_s<2048>(vt, lc.gv, ldv);
+    g2lds16_s<3072>(vt, lc.gv, ldv);
+  } else {
+    const int r_in = lane >> 4;
+    const int cpos = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = (wave * 4 + i) * 4 + r_in;
+      const int rc = r < rows ? r : rows - 1;
+      g2lds16_s<0>(kt, (uint32_t)(rc * kRowBytes + ((cpos ^ swz_k(r)) << 4)), ldk + i * 1024);
+      g2lds16_s<0>(vt, (uint32_t)(rc * kRowBytes + ((cpos ^ swz_v(r)) << 4)), ldv + i * 1024);
+    }
+  }
+}
+
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+struct PfState {
+  f32x16 o[4];
+  float m, l;
+};
+
+// One 64-row tile out of LDS stage STAGE: S^T = K Q^T, online softmax, O^T += V^T P^T.
+// mask_rel: rows of the tile with index > mask_rel are masked for this lane (>= 63 means no masking).
+template <int STAGE>
+__device__ __forceinline__ void pf_compute_tile(lds_char* lds, const PfLaneConst& lc, const bf16x8 (&qf)[8],
+                                                PfState& st, float c, bool masked, int mask_rel, int hl) {
+  lds_char* kt = lds + STAGE * kPfStageBytes;
+  lds_char* vt = kt + kPfTileBytes;
+
+  // S^T: register r of sub-block sb is tile row 32*sb + 8*(r/4) + 4*hl + r%4 (query row = lane % 32)
+  f32x16 s[2];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb) {
+    bf16x8 kf[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) kf[kk] = *(lds_bf16x8*)(kt + lc.koff[kk] + sb * 8192);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[sb][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s[sb], 0, 0, 0);
+  }
+
+  if (masked) {
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
+        if (row > mask_rel) s[sb][r] = kNegBig;
+      }
+  }
+
+  // online softmax: per lane = per query row; the other half-wave holds the other 32 rows of the tile
+  float mx = s[0][0];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
+  mx = max_halves(mx);
+  const float m_new = fmaxf(st.m, mx);
+  if (__builtin_amdgcn_ballot_w64(m_new > st.m) != 0) {
+    const float alpha = fast_exp2((st.m - m_new) * c);
+    st.l *= alpha;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
+    st.m = m_new;
+  }
+  const float mc = st.m * c;
+  float lsum = 0.f;
+  bf16x8 pb[2][2];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float p = fast_exp2(__builtin_fmaf(s[sb][8 * u + j], c, -mc));
+        lsum += p;
+        pb[sb][u][j] = (__bf16)p;
+      }
+  st.l += lsum;
+
+  // O^T += V^T P^T : contraction index 8*hl + j of MFMA (sb,u) is tile row 32*sb + 16*u + 8*(j/4) + 4*hl + j%4
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const bf16x4 v0 = lds_read_tr8(vt + lc.voff[db] + sb * 8192 + u * 4096);
+        const bf16x4 v1 = lds_read_tr8(vt + lc.voff[db] + sb * 8192 + u * 4096 + 2048);
+        const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[sb][u], st.o[db], 0, 0, 0);
+      }
+    }
+}
+
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   __shared__ __attribute__((aligned(1024))) char lds_raw[kPfLdsBytes];
   lds_char* lds = (lds_char*)lds_raw;
+  const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
   const int lane = lane_id();
   const int wave = wave_id();
   const int hl = lane >> 5;            // which half of the wavefront
@@ -85,6 +196,27 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   const int my_i = qi;
   if (qi > a.C - 1) qi = a.C - 1;
 
+  PfLaneConst lc;
+  {
+    const int r_in = lane >> 4, cpos = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = (wave * 4 + i) * 4 + r_in;
+      lc.gk[i] = (uint32_t)(r * kRowBytes + ((cpos ^ swz_k(r)) << 4));
+    }
+    const int r0 = wave * 16 + r_in;                // swz_v depends on r & 3 only, so +4 rows = +1024 bytes
+    lc.gv = (uint32_t)(r0 * kRowBytes + ((cpos ^ swz_v(r0)) << 4));
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) lc.koff[kk] = (uint32_t)(col * kRowBytes + (((2 * kk + hl) ^ swz_k(col)) << 4));
+    const int s16 = lane & 15, q16 = col >> 4;
+    const int row_lo = 4 * hl + (s16 >> 2);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      const int chunk = 4 * db + 2 * q16 + ((s16 & 3) >> 1);
+      lc.voff[db] = (uint32_t)(row_lo * kRowBytes + ((chunk ^ swz_v(row_lo)) << 4) + ((s16 & 1) << 3));
+    }
+  }
+
   // Q^T operand: lane holds q[g][qi][16*kk + 8*hl .. +7]
   bf16x8 qf[8];
   {
@@ -93,152 +225,96 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 16 * kk));
   }
 
-  f32x16 o[4];
-  float m, l;
+  PfState st;
   const int64_t wg_linear = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
   float* carry = a.carry + wg_linear * (kCarryFloatsPerLane * kWgThreads) + threadIdx.x;
   if (a.first) {
-    m = kNegBig;
-    l = 0.f;
+    st.m = kNegBig;
+    st.l = 0.f;
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+      for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
   } else {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[db][r] = carry[(db * 16 + r) * kWgThreads];
-    m = carry[64 * kWgThreads];
-    l = carry[65 * kWgThreads];
+      for (int r = 0; r < 16; ++r) st.o[db][r] = carry[(db * 16 + r) * kWgThreads];
+    st.m = carry[64 * kWgThreads];
+    st.l = carry[65 * kWgThreads];
   }
   // the compiler's own waits for the loads above belong here, not inside the tile loop
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) asm volatile("" : "+v"(qf[kk]));
-  asm volatile("" : "+v"(m), "+v"(l));
+  asm volatile("" : "+v"(st.m), "+v"(st.l));
 #pragma unroll
-  for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(o[db]));
+  for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(st.o[db]));
 
   // tiles: segment A (all of it), then the part of segment B at or below the workgroup's causal boundary
-  const int64_t ta = (a.na + kPfTileRows - 1) / kPfTileRows;
-  int64_t nb_vis = a.nb < (int64_t)i_hi + 1 ? a.nb : (int64_t)i_hi + 1;
-  const int64_t tb = (nb_vis + kPfTileRows - 1) / kPfTileRows;
-  const int64_t T = ta + tb;
+  const int ta = (int)((a.na + kPfTileRows - 1) / kPfTileRows);
+  const int64_t nb_vis = a.nb < (int64_t)i_hi + 1 ? a.nb : (int64_t)i_hi + 1;
+  const int tb = (int)((nb_vis + kPfTileRows - 1) / kPfTileRows);
+  const int T = ta + tb;
 
-  auto issue = [&](int64_t t) {
-    lds_char* stage = lds + (int)(t & (kPfStages - 1)) * kPfStageBytes;
-    if (t < ta) pf_issue_tile(a.ka, a.va, t * kPfTileRows, a.na, stage, wave, lane);
-    else pf_issue_tile(a.kb, a.vb, (t - ta) * kPfTileRows, a.nb, stage, wave, lane);
+  auto issue = [&](int t) {
+    const uint32_t stage = lds_base + (uint32_t)(t & (kPfStages - 1)) * kPfStageBytes;
+    if (t < ta) {
+      const int64_t row0 = (int64_t)t * kPfTileRows;
+      const int64_t left = a.na - row0;
+      pf_issue_tile(a.ka + row0 * kRowBytes, a.va + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
+                    stage, wave, lane, lc);
+    } else {
+      const int64_t row0 = (int64_t)(t - ta) * kPfTileRows;
+      const int64_t left = a.nb - row0;
+      pf_issue_tile(a.kb + row0 * kRowBytes, a.vb + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
+                    stage, wave, lane, lc);
+    }
   };
 
   if (T > 0) issue(0);
 
   const float c = a.c;
-  for (int64_t t = 0; t < T; ++t) {
+  // one tile: wait for it, let everybody see it (and be done with the previous one), refill the freed stage,
+  // compute.  The loop is unrolled by the two LDS stages so every LDS address is an immediate and the
+  // accumulators never meet at a control-flow join inside the loop.
+  auto step = [&](int t, auto stage_tag) {
+    constexpr int STAGE = decltype(stage_tag)::value;
     wait_vmcnt<0>();
     __syncthreads();
     if (t + 1 < T) issue(t + 1);
-
-    lds_char* kt = lds + (int)(t & (kPfStages - 1)) * kPfStageBytes;
-    lds_char* vt = kt + kPfTileBytes;
-
-    // S^T tile: 64 K/V rows x 32 query rows; register r of sub-block sb is row 32*sb + 8*(r/4) + 4*hl + r%4
-    f32x16 s[2];
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[sb][r] = 0.f;
-      const int tok = 32 * sb + col;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        bf16x8 kf = lds_read16(kt + tok * kRowBytes + (((2 * kk + hl) ^ swz_k(tok)) << 4));
-        s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[sb], 0, 0, 0);
-      }
-    }
-
     // masks: rows past the end of the segment, and (chunk's own rows) rows after the query's position
     const bool in_b = t >= ta;
-    const int64_t j0 = (in_b ? (t - ta) : t) * kPfTileRows;
+    const int64_t j0 = (int64_t)(in_b ? (t - ta) : t) * kPfTileRows;
     const int64_t n_seg = in_b ? a.nb : a.na;
-    const bool tail = j0 + kPfTileRows > n_seg;
-    const bool diag = in_b && (j0 + kPfTileRows - 1 > i0);
-    if (tail || diag) {
+    const bool masked = (j0 + kPfTileRows > n_seg) || (in_b && (j0 + kPfTileRows - 1 > i0));
+    int rel = kPfTileRows;
+    if (masked) {
       int64_t lim = n_seg - 1;                       // last visible row index
       if (in_b && (int64_t)my_i < lim) lim = my_i;
-      const int rel = (int)(lim - j0);               // rows with index > rel are masked
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
-          if (row > rel) s[sb][r] = kNegBig;
-        }
+      const int64_t d = lim - j0;
+      rel = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
     }
-
-    // online softmax (per lane = per query row; the other half-wave holds the other 32 rows of the tile)
-    float mx = s[0][0];
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
-    mx = max_halves(mx);
-    const float m_new = fmaxf(m, mx);
-    if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
-      const float alpha = fast_exp2((m - m_new) * c);
-      l *= alpha;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-      m = m_new;
-    }
-    const float mc = m * c;
-    float lsum = 0.f;
-    bf16x8 pb[2][2];
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float p = fast_exp2(__builtin_fmaf(s[sb][8 * u + j], c, -mc));
-          lsum += p;
-          pb[sb][u][j] = (__bf16)p;
-        }
-    l += lsum;
-
-    // O^T += V^T P^T : contraction index 8*hl + j of MFMA (sb,u) is tile row 32*sb + 16*u + 8*(j/4) + 4*hl + j%4
-    const int q16 = col >> 4;
-    const int s16 = lane & 15;
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int row_lo = 32 * sb + 16 * u + 4 * hl + (s16 >> 2);
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const int chunk = 4 * db + 2 * q16 + ((s16 & 3) >> 1);
-          const int sub8 = (s16 & 1) << 3;
-          bf16x4 v0 = lds_read_tr8(vt + row_lo * kRowBytes + ((chunk ^ swz_v(row_lo)) << 4) + sub8);
-          bf16x4 v1 = lds_read_tr8(vt + (row_lo + 8) * kRowBytes + ((chunk ^ swz_v(row_lo + 8)) << 4) + sub8);
-          bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[sb][u], o[db], 0, 0, 0);
-        }
-      }
+    pf_compute_tile<STAGE>(lds, lc, qf, st, c, masked, rel, hl);
+  };
+  int t = 0;
+  for (; t + 1 < T; t += 2) {
+    step(t, std::integral_constant<int, 0>());
+    step(t + 1, std::integral_constant<int, 1>());
   }
+  if (t < T) step(t, std::integral_constant<int, 0>());
 
   if (!a.last) {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) carry[(db * 16 + r) * kWgThreads] = o[db][r];
-    carry[64 * kWgThreads] = m;
-    carry[65 * kWgThreads] = l;
+      for (int r = 0; r < 16; ++r) carry[(db * 16 + r) * kWgThreads] = st.o[db][r];
+    carry[64 * kWgThreads] = st.m;
+    carry[65 * kWgThreads] = st.l;
     return;
   }
 
   // normalise and write out[g][i][:]; register r of block db is dim 32*db + 8*(r/4) + 4*hl + r%4
-  const float l_tot = sum_halves(l);
+  const float l_tot = sum_halves(st.l);
   const float inv = 1.0f / l_tot;
   if (my_i < a.C) {
     const int64_t base = ((int64_t)g * a.C + my_i) * kHeadDim;
@@ -247,8 +323,8 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 #pragma unroll
       for (int rq = 0; rq < 4; ++rq) {
         const int dim = 32 * db + 8 * rq + 4 * hl;
-        const float x0 = o[db][4 * rq] * inv, x1 = o[db][4 * rq + 1] * inv;
-        const float x2 = o[db][4 * rq + 2] * inv, x3 = o[db][4 * rq + 3] * inv;
+        const float x0 = st.o[db][4 * rq] * inv, x1 = st.o[db][4 * rq + 1] * inv;
+        const float x2 = st.o[db][4 * rq + 2] * inv, x3 = st.o[db][4 * rq + 3] * inv;
         if (a.out_fp32) {
           *(float4*)((float*)a.out + base + dim) = make_float4(x0, x1, x2, x3);
         } else {
