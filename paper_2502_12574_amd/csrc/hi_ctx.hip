@@ -165,6 +165,10 @@ hi_status collect_spans(hi_ctx* c) {
   return HI_OK;
 }
 
+int pf_variant(const hi_ctx* c) {
+  return (c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_WIDE) ? 2 : 0;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 hi_status check_unit_args(const hi_ctx* c, int layer, int head, const void* q, const void* k, const void* v,
@@ -299,7 +303,8 @@ extern "C" hi_status hi_ctx_destroy(hi_ctx* c) {
 }
 
 extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
-  if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS))) { set_last_error("bad flags"); return HI_ERR_ARG; }
+  if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS | HI_FLAG_PREFILL_NARROW |
+                      HI_FLAG_PREFILL_WIDE))) { set_last_error("bad flags"); return HI_ERR_ARG; }
   c->flags = flags;
   return HI_OK;
 }
@@ -320,7 +325,7 @@ extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, 
     if (run) {
       TimedSpan sp;
       if (timed) HI_TRY(span_begin(c, 0, &sp));
-      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, pastseg, diag, 1, 1, c->ws, out_dev, c->prob.out_fp32));
+      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, pastseg, diag, 1, 1, c->ws, out_dev, c->prob.out_fp32, pf_variant(c)));
       if (timed) HI_TRY(span_end(c, sp));
       c->stats.n_prefill_kernels += 1;
     }
@@ -342,7 +347,7 @@ extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, 
     if (run) {
       TimedSpan sp;
       if (timed) HI_TRY(span_begin(c, 0, &sp));
-      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, PrefillSegment{nullptr, nullptr, 0, 0}, diag, 1, 1, c->ws, out_dev, c->prob.out_fp32));
+      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, PrefillSegment{nullptr, nullptr, 0, 0}, diag, 1, 1, c->ws, out_dev, c->prob.out_fp32, pf_variant(c)));
       if (timed) HI_TRY(span_end(c, sp));
       c->stats.n_prefill_kernels += 1;
     }
@@ -359,7 +364,7 @@ extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, 
       TimedSpan sp;
       if (timed) HI_TRY(span_begin(c, 0, &sp));
       HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, seg, is_last ? diag : PrefillSegment{nullptr, nullptr, 0, 1},
-                            i == 0, is_last, c->ws, out_dev, c->prob.out_fp32));
+                            i == 0, is_last, c->ws, out_dev, c->prob.out_fp32, pf_variant(c)));
       if (timed) HI_TRY(span_end(c, sp));
       c->stats.n_prefill_kernels += 1;
     }

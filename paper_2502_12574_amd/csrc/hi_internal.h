@@ -33,8 +33,11 @@ struct PrefillSegment {
 
 // One launch of the prefill kernel over up to two KV segments.  first: start from an empty softmax state
 // instead of loading the carry; last: normalise and write `out` instead of storing the carry.
+// variant: 0 or 1 = narrow kernel (32 positions per wave), 2 = wide kernel (64 per wave);
+// every launch of one unit must use the same variant (the carry layouts differ).
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& a,
-                         const PrefillSegment& b, int first, int last, void* carry, void* out, int out_fp32);
+                         const PrefillSegment& b, int first, int last, void* carry, void* out, int out_fp32,
+                         int variant);
 
 // Split-KV decode over rows [0, n) of one slice: writes n_split partials starting at partial index part0.
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,

@@ -90,9 +90,11 @@ def test_offloaded_equals_resident_bitwise_for_prefill():
     assert (a[1] - b[1]).abs().max() < 1e-5      # decode partitions differ between the two modes
 
 
-def one_unit(G, P, C, seed, out_fp32=1, mode=hb.HI_MODE_RESIDENT, peaked=False):
+def one_unit(G, P, C, seed, out_fp32=1, mode=hb.HI_MODE_RESIDENT, peaked=False, flags=0):
     dev = "cuda:0"
     with Session(1, 1, G, max(P + C, 128), max(C, 1), mode=mode, out_fp32=out_fp32) as ss:
+        if flags:
+            hb.hi_ctx_set_flags(ss.ctx, flags)
         with torch.cuda.stream(ss.s_compute):
             Q = torch.stack([synth.draw_q(seed, 0, g, P, C, device=dev) for g in range(G)])
             K = synth.draw_k(seed, 0, 0, 0, P + C, device=dev, peaked=peaked)
@@ -115,6 +117,18 @@ def test_prefill_ragged_shapes(G, P, C):
     ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
     for g in range(G):
         check(out[g:g + 1], ref[g:g + 1], f"G={G} P={P} C={C} head {g}")
+
+
+@pytest.mark.parametrize("G,P,C", [(4, 0, 1), (4, 0, 31), (4, 1, 33), (4, 63, 100), (4, 65, 257), (4, 300, 64),
+                                   (4, 1000, 129), (1, 77, 200), (2, 130, 95), (8, 200, 70), (8, 0, 40),
+                                   (4, 97, 700)])
+@pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
+def test_prefill_wide_kernel_ragged_shapes(G, P, C, mode):
+    # the 64-positions-per-wave kernel is normally picked for long chunks only; force it on small shapes
+    out, Q, K, V = one_unit(G, P, C, seed=700 + P + C, mode=mode, flags=hb.HI_FLAG_PREFILL_WIDE)
+    ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
+    for g in range(G):
+        check(out[g:g + 1], ref[g:g + 1], f"wide G={G} P={P} C={C} head {g}")
 
 
 @pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
