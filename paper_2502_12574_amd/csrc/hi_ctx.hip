@@ -404,8 +404,11 @@ extern "C" hi_status hi_decode_head(hi_ctx* c, int32_t layer, int32_t kv_head, c
         c->stats.n_decode_kernels += 1;
       }
       if (timed) HI_TRY(span_end(c, sp));
-      HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32));
+      HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32,
+                                   c->kv + plane_offset(c, layer, kv_head, 0) + past_len * kRowBytes,
+                                   c->kv + plane_offset(c, layer, kv_head, 1) + past_len * kRowBytes));
       c->stats.n_combine_kernels += 1;
+      return HI_OK;
     }
     return write_back(c, layer, kv_head, k_new_dev, v_new_dev, past_len, 1);
   }
@@ -439,7 +442,8 @@ extern "C" hi_status hi_decode_head(hi_ctx* c, int32_t layer, int32_t kv_head, c
     HI_TRY(retire_slice(c, slot));
   }
   if (run) {
-    HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32));
+    HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32,
+                                 nullptr, nullptr));
     c->stats.n_combine_kernels += 1;
   }
   cur.valid = false;

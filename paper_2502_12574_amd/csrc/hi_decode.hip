@@ -2,7 +2,7 @@
 //
 // Algorithm 1, decode phase: one new query row per query head attends over the head's whole K/V history
 // (Eq. 3 / Eq. 9).  The work is bandwidth bound (Section 5: decode intensity is O(1) flop per byte), so the
-// kernel is organised around the memory pipeline: every wavefront streams its own contiguous range of 16-row
+// kernel is organised around the memory pipeline: every wavefront streams its share of the 16-row
 // K/V blocks through a private 4-stage LDS ring filled by direct-to-LDS 128-bit loads (24 KiB in flight per
 // wavefront, nothing staged in VGPRs, no workgroup barriers in the loop).  The G <= 16 query heads ride along
 // as the 16 columns of small MFMA tiles (S^T = K Q^T, O^T += V^T P^T), which keeps the vector ALU nearly idle;
@@ -61,14 +61,12 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __r
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(qf[kk]));
 
+  // 16-row blocks are dealt round-robin to the wavefronts of the grid, so at any moment the whole chip reads one
+  // compact window of the K and V streams (friendlier to HBM pages and TLBs than one far-apart range per wave)
   const int64_t n_blocks = (n + kDecBlockRows - 1) / kDecBlockRows;
   const int64_t n_waves = (int64_t)gridDim.x * 4;
-  const int64_t per_wave = (n_blocks + n_waves - 1) / n_waves;
   const int64_t wid = (int64_t)blockIdx.x * 4 + wave;
-  int64_t b0 = wid * per_wave;
-  int64_t b1 = b0 + per_wave;
-  if (b1 > n_blocks) b1 = n_blocks;
-  if (b0 > b1) b0 = b1;
+  const int64_t cnt = wid < n_blocks ? (n_blocks - wid + n_waves - 1) / n_waves : 0;   // blocks of this wave
 
   float m = kNegBig, l = 0.f;
   f32x4 o[8];
@@ -77,18 +75,19 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __r
 
   // prologue: up to three blocks in flight
   for (int s = 0; s < kDecStages - 1; ++s)
-    if (b0 + s < b1) dec_issue_block(k, v, b0 + s, n, wlds + s * kDecStageBytes, lane);
+    if (s < cnt) dec_issue_block(k, v, wid + s * n_waves, n, wlds + s * kDecStageBytes, lane);
 
   // lane-constant LDS offsets of the operand reads
   const int k_tok = lane & 15;
   const int v_row = 4 * g4 + ((lane & 15) >> 2);
   const int v_sub = lane & 3;      // which 8-byte quarter of the 32-byte column group
 
-  for (int64_t b = b0; b < b1; ++b) {
-    const int stage = (int)((b - b0) & (kDecStages - 1));
-    if (b + (kDecStages - 1) < b1) {
-      dec_issue_block(k, v, b + (kDecStages - 1), n,
-                      wlds + (int)((b - b0 + kDecStages - 1) & (kDecStages - 1)) * kDecStageBytes, lane);
+  for (int64_t i = 0; i < cnt; ++i) {
+    const int64_t b = wid + i * n_waves;
+    const int stage = (int)(i & (kDecStages - 1));
+    if (i + (kDecStages - 1) < cnt) {
+      dec_issue_block(k, v, b + (kDecStages - 1) * n_waves, n,
+                      wlds + (int)((i + kDecStages - 1) & (kDecStages - 1)) * kDecStageBytes, lane);
       wait_vmcnt<24>();   // everything but the 3 newest blocks has landed
     } else {
       wait_vmcnt<0>();
@@ -180,52 +179,64 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __r
 }
 
 // K3: out[g][:] = (sum_s O_s w_s + p_new v_new) / (sum_s l_s w_s + p_new),  w_s = 2^{(m_s - M) c},
-// p_new = 2^{(q_g . k_new - M) c}, M = max(max_s m_s, q_g . k_new).   grid (G, 4): one query head, 32 dims.
+// p_new = 2^{(q_g . k_new - M) c}, M = max(max_s m_s, q_g . k_new).   grid (G, 8): one query head, 16 dims;
+// thread = (one of 16 partition lanes, one dim), several independent loads in flight per thread.
+constexpr int kCombDims = 16;
+constexpr int kCombLanes = 256 / kCombDims;
+
 __global__ __launch_bounds__(256) void decode_combine_kernel(const uint16_t* __restrict__ q, int G,
                                                              const uint16_t* __restrict__ k_new,
                                                              const uint16_t* __restrict__ v_new,
                                                              const float* __restrict__ partials, int n_part,
-                                                             void* __restrict__ out, int out_fp32, float c) {
-  __shared__ float red[256];
-  __shared__ float red_o[8][33];
-  __shared__ float bc[2];
+                                                             void* __restrict__ out, int out_fp32, float c,
+                                                             uint16_t* __restrict__ k_append,
+                                                             uint16_t* __restrict__ v_append) {
+  __shared__ float red[4];
+  __shared__ float red_o[kCombLanes][kCombDims + 1];
+  __shared__ float bc;
   const int g = blockIdx.x;
   const int tid = threadIdx.x;
+  const float* base = partials + (int64_t)g * kPartialFloats;
+  const int64_t stride = (int64_t)G * kPartialFloats;
 
-  // score of the token's own row
+  // HBM-resident cache: the token's K/V row is appended here instead of by two tiny device copies
+  if (k_append != nullptr && blockIdx.x == 0 && blockIdx.y == 0 && tid < kHeadDim) {
+    k_append[tid] = k_new[tid];
+    v_append[tid] = v_new[tid];
+  }
+
+  // score of the token's own row (first wavefront), and the maximum over all partitions
+  float mx = kNegBig;
+  for (int p = tid; p < n_part; p += 256) mx = fmaxf(mx, base[p * stride + kHeadDim]);
   if (tid < 64) {
     float d = bf16_bits_to_float(q[g * kHeadDim + tid]) * bf16_bits_to_float(k_new[tid]) +
               bf16_bits_to_float(q[g * kHeadDim + 64 + tid]) * bf16_bits_to_float(k_new[64 + tid]);
     for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off);
-    if (tid == 0) bc[0] = d;
+    if (tid == 0) bc = d;
   }
-  float mx = kNegBig;
-  for (int p = tid; p < n_part; p += 256) mx = fmaxf(mx, partials[((int64_t)p * G + g) * kPartialFloats + kHeadDim]);
-  red[tid] = mx;
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  if ((tid & 63) == 0) red[tid >> 6] = mx;
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if (tid < s) red[tid] = fmaxf(red[tid], red[tid + s]);
-    __syncthreads();
-  }
-  const float s_new = bc[0];
-  const float M = fmaxf(red[0], s_new);
+  const float s_new = bc;
+  const float M = fmaxf(fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3])), s_new);
 
-  const int pl = tid >> 5;                       // 8 partition lanes
-  const int dim = blockIdx.y * 32 + (tid & 31);
+  const int pl = tid / kCombDims;
+  const int dim = blockIdx.y * kCombDims + (tid % kCombDims);
   float acc = 0.f, L = 0.f;
-  for (int p = pl; p < n_part; p += 8) {
-    const float* src = partials + ((int64_t)p * G + g) * kPartialFloats;
+#pragma unroll 4
+  for (int p = pl; p < n_part; p += kCombLanes) {
+    const float* src = base + p * stride;
     const float w = fast_exp2((src[kHeadDim] - M) * c);
-    acc += w * src[dim];
-    L += w * src[kHeadDim + 1];
+    acc = __builtin_fmaf(w, src[dim], acc);
+    L = __builtin_fmaf(w, src[kHeadDim + 1], L);
   }
-  red_o[pl][tid & 31] = acc;
-  if ((tid & 31) == 0) red_o[pl][32] = L;
+  red_o[pl][tid % kCombDims] = acc;
+  if ((tid % kCombDims) == 0) red_o[pl][kCombDims] = L;
   __syncthreads();
-  if (tid < 32) {
+  if (tid < kCombDims) {
     float a = 0.f, lsum = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { a += red_o[i][tid]; lsum += red_o[i][32]; }
+    for (int i = 0; i < kCombLanes; ++i) { a += red_o[i][tid]; lsum += red_o[i][kCombDims]; }
     const float p_new = fast_exp2((s_new - M) * c);
     a += p_new * bf16_bits_to_float(v_new[dim]);
     lsum += p_new;
@@ -255,10 +266,11 @@ hi_status launch_decode_partial(void* stream, const void* q, int G, const void* 
 }
 
 hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
-                                const void* partials, int n_part, void* out, int out_fp32) {
-  hipLaunchKernelGGL(decode_combine_kernel, dim3(G, 4), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)q, G,
-                     (const uint16_t*)k_new, (const uint16_t*)v_new, (const float*)partials, n_part, out, out_fp32,
-                     kScaleLog2e);
+                                const void* partials, int n_part, void* out, int out_fp32, void* k_append,
+                                void* v_append) {
+  hipLaunchKernelGGL(decode_combine_kernel, dim3(G, kHeadDim / kCombDims), dim3(256), 0, (hipStream_t)stream,
+                     (const uint16_t*)q, G, (const uint16_t*)k_new, (const uint16_t*)v_new, (const float*)partials,
+                     n_part, out, out_fp32, kScaleLog2e, (uint16_t*)k_append, (uint16_t*)v_append);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("decode_combine launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
   return HI_OK;

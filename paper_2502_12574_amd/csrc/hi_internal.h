@@ -42,8 +42,10 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
 // Split-KV decode over rows [0, n) of one slice: writes n_split partials starting at partial index part0.
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
                                 int n_split, void* partials, int part0);
-// Merge n_part partials with the token's own row and write out[G][128].
+// Merge n_part partials with the token's own row and write out[G][128]; if k_append/v_append are not null the
+// token's K/V row is also copied there (device rows of an HBM-resident cache).
 hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
-                                const void* partials, int n_part, void* out, int out_fp32);
+                                const void* partials, int n_part, void* out, int out_fp32, void* k_append,
+                                void* v_append);
 
 }  // namespace hi
