@@ -32,6 +32,11 @@ HQ, HKV, G, D = 32, 8, 4, 128
 PEAK_MFMA_TFLOPS = 2500.0     # dense bf16
 PEAK_HBM_GBPS = 8000.0
 PEAK_LINK_GBPS = 64.0         # PCIe Gen5 x16, one direction
+# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/*_pmc.md), each scaled by
+# what the same counter read for a 1 GiB copy kernel in the same run: a prefill launch over one 131072-row
+# staging slice with chunk 16384, and the resident decode launch over 1M rows (reads each K/V byte once).
+PREFILL_TRAFFIC_PER_LAUNCH = 1.05 * 2 ** 30 + 16 * 2 ** 20
+DECODE_TRAFFIC_PER_ROW = 512.0
 
 
 def causal_flops_layer(S):
@@ -181,7 +186,8 @@ def main():
         extra["decode_resident"] = {
             "ms_per_token_per_layer": t_res / nr * 1e3,
             "roofline": {"bound": "hbm", "achieved": k2_bytes / (k2_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBPS,
-                         "unit": "GB/s", "frac": k2_bytes / (k2_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, "traffic": None,
+                         "unit": "GB/s", "frac": k2_bytes / (k2_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS,
+                         "traffic": DECODE_TRAFFIC_PER_ROW * (S + (nr - 1) / 2.0),
                          "kernel": "decode_partial_kernel", "avg_launch_ms": k2_ms,
                          "wall_GBps": 512.0 * HKV * S * nr / t_res / 1e9}}
         ss_r.close()
@@ -208,7 +214,9 @@ def main():
         "peak_staging_bytes": peak_staging, "one_head_bytes": ss.plan.host_bytes_per_head,
         "input_generation_s": t_gen,
         "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS, "traffic": None, "kernel": "prefill_kernel",
+                     "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS,
+                     "traffic": PREFILL_TRAFFIC_PER_LAUNCH if (S, C) == (1 << 20, 16384) else None,
+                     "kernel": "prefill_kernel",
                      "launches_per_step": n_pre_k / K, "avg_launch_ms": kern_pre_ms / max(n_pre_k, 1),
                      "flops_per_launch": flops / (n_pre_k / K),
                      "wall_TFLOPs": flops / prefill_s / 1e12},
