@@ -123,6 +123,11 @@ hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* plan, int32_t 
                         void* stream_d2h, hi_ctx** out);
 hi_status hi_ctx_destroy(hi_ctx* ctx);
 hi_status hi_ctx_set_flags(hi_ctx* ctx, int32_t flags);
+/* Bounded run-ahead of the caller: hi_prefill_head / hi_decode_head first wait (on the host) until the unit
+ * `units` calls earlier has finished on stream_compute; the history of the unit being enqueued is already being
+ * prefetched by then, so the link stays busy, and the runtime's queues stay short (with hundreds of cross-stream
+ * waits queued ahead the copy engine leaves gaps between transfers).  Default 2; 0 = never wait; at most 15. */
+hi_status hi_ctx_set_run_ahead(hi_ctx* ctx, int32_t units);
 
 /*
  * T1 + K1 + T3 - one prefill unit: one chunk, one KV head, its G query heads (Algorithm 1, prefill phase, the
@@ -136,7 +141,8 @@ hi_status hi_ctx_set_flags(hi_ctx* ctx, int32_t flags);
  * next_* name the unit that will be called next (Algorithm 1 "Async Prefetch next KV cache"): its past rows are
  * prefetched into free ring slots while this unit computes; next_layer = -1 means none.  The hint must be
  * honoured by the next call, or that call simply fetches on demand.
- * Asynchronous: enqueues and returns.  Results and the cache append are valid after hi_sync.  The caller's
+ * Asynchronous: enqueues and returns (after the bounded run-ahead wait described at hi_ctx_set_run_ahead).  Results
+ * and the cache append are valid after hi_sync.  The caller's
  * buffers are borrowed until then.  1 <= chunk_len <= chunk; past_len >= 0; no alignment is required of either.
  * Errors (synchronous, nothing enqueued, cache untouched): HI_ERR_ARG, HI_ERR_RANGE; HI_ERR_HIP.
  */

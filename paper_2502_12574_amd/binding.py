@@ -18,7 +18,8 @@ HI_REGIME_COMPUTE, HI_REGIME_LINK, HI_REGIME_HBM = 0, 1, 2
 HI_FLAG_SKIP_KERNELS, HI_FLAG_SKIP_COPIES, HI_FLAG_TIME_KERNELS = 1, 2, 4
 HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_WIDE = 8, 16
 
-EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_flags", "hi_prefill_head",
+EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
+           "hi_prefill_head",
            "hi_decode_head", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
 
 
@@ -73,6 +74,7 @@ def lib() -> C.CDLL:
                                     C.POINTER(vp)]
         L.hi_ctx_destroy.argtypes = [vp]
         L.hi_ctx_set_flags.argtypes = [vp, i32]
+        L.hi_ctx_set_run_ahead.argtypes = [vp, i32]
         L.hi_prefill_head.argtypes = [vp, i32, i32, vp, vp, vp, i64, i32, vp, i32, i32, i64]
         L.hi_decode_head.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp, i32, i32, i64]
         L.hi_sync.argtypes = [vp]
@@ -146,6 +148,13 @@ def hi_ctx_set_flags(ctx, flags: int, check: bool = True):
     st = lib().hi_ctx_set_flags(ctx, flags)
     if check and st != HI_OK:
         raise HiError(st, "hi_ctx_set_flags")
+    return st
+
+
+def hi_ctx_set_run_ahead(ctx, units: int, check: bool = True):
+    st = lib().hi_ctx_set_run_ahead(ctx, units)
+    if check and st != HI_OK:
+        raise HiError(st, "hi_ctx_set_run_ahead")
     return st
 
 

@@ -63,6 +63,12 @@ struct hi_ctx {
     int64_t first_seq = 0;
   } pend;                     // the unit whose history is (partly) in the ring
 
+  // bounded run-ahead of the calling thread: a call first waits until the unit `run_ahead` calls earlier has
+  // finished on the compute stream (its successor's history is already being prefetched by then)
+  int run_ahead = 2;
+  std::vector<hipEvent_t> ev_unit;             // ring of "unit finished" events
+  int64_t n_units = 0;
+
   hi_stats stats;
   std::vector<TimedSpan> spans;
   std::vector<TimedSpan> span_pool;
@@ -162,6 +168,22 @@ hi_status collect_spans(hi_ctx* c) {
     c->span_pool.push_back(s);
   }
   c->spans.clear();
+  return HI_OK;
+}
+
+constexpr int kUnitRing = 16;
+
+// Pace the host: with hundreds of cross-stream waits queued far ahead the copy engine sees gaps between
+// consecutive transfers (measured: 45 GB/s free-running against 55 GB/s when at most 1-3 units are queued).
+hi_status pace_begin(hi_ctx* c) {
+  if (c->run_ahead > 0 && c->n_units >= c->run_ahead)
+    HI_HIP(hipEventSynchronize(c->ev_unit[(c->n_units - c->run_ahead) % kUnitRing]));
+  return HI_OK;
+}
+
+hi_status pace_end(hi_ctx* c) {
+  HI_HIP(hipEventRecord(c->ev_unit[c->n_units % kUnitRing], c->sc));
+  c->n_units += 1;
   return HI_OK;
 }
 
@@ -272,6 +294,9 @@ extern "C" hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* pla
     hi_ctx_destroy(c);
     return (hi_status)HI_ERR_HIP;
   };
+  c->ev_unit.assign(kUnitRing, nullptr);
+  for (int i = 0; i < kUnitRing; ++i)
+    if ((e = hipEventCreateWithFlags(&c->ev_unit[i], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
   if (mode == HI_MODE_OFFLOAD) {
     c->ev_ready.assign(c->n_slots, nullptr);
     c->ev_free.assign(c->n_slots, nullptr);
@@ -295,6 +320,7 @@ extern "C" hi_status hi_ctx_destroy(hi_ctx* c) {
   for (auto ev : c->ev_ready) if (ev) (void)hipEventDestroy(ev);
   for (auto ev : c->ev_free) if (ev) (void)hipEventDestroy(ev);
   for (auto ev : c->ev_wb) if (ev) (void)hipEventDestroy(ev);
+  for (auto ev : c->ev_unit) if (ev) (void)hipEventDestroy(ev);
   if (c->ev_entry) (void)hipEventDestroy(c->ev_entry);
   for (auto& s : c->spans) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }
   for (auto& s : c->span_pool) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }
@@ -309,12 +335,16 @@ extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
   return HI_OK;
 }
 
-extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
-                                     const void* k_new_dev, const void* v_new_dev, int64_t past_len,
-                                     int32_t chunk_len, void* out_dev, int32_t next_layer, int32_t next_kv_head,
-                                     int64_t next_past_len) {
-  HI_TRY(check_unit_args(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
-                         next_kv_head, next_past_len));
+extern "C" hi_status hi_ctx_set_run_ahead(hi_ctx* c, int32_t units) {
+  if (!c || units < 0 || units >= kUnitRing) { set_last_error("run-ahead must be in [0, %d)", kUnitRing); return HI_ERR_ARG; }
+  c->run_ahead = units;
+  return HI_OK;
+}
+
+static hi_status prefill_head_impl(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
+                                   const void* k_new_dev, const void* v_new_dev, int64_t past_len,
+                                   int32_t chunk_len, void* out_dev, int32_t next_layer, int32_t next_kv_head,
+                                   int64_t next_past_len) {
   const int G = c->prob.gqa_group;
   const bool run = !(c->flags & HI_FLAG_SKIP_KERNELS);
   const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
@@ -377,11 +407,9 @@ extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, 
   return HI_OK;
 }
 
-extern "C" hi_status hi_decode_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
-                                    const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
-                                    int32_t next_layer, int32_t next_kv_head, int64_t next_past_len) {
-  HI_TRY(check_unit_args(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, 1, out_dev, next_layer,
-                         next_kv_head, next_past_len));
+static hi_status decode_head_impl(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
+                                  const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
+                                  int32_t next_layer, int32_t next_kv_head, int64_t next_past_len) {
   const int G = c->prob.gqa_group;
   const bool run = !(c->flags & HI_FLAG_SKIP_KERNELS);
   const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
@@ -451,6 +479,29 @@ extern "C" hi_status hi_decode_head(hi_ctx* c, int32_t layer, int32_t kv_head, c
   HI_TRY(top_up(c, none, next));
   c->pend = next;
   return HI_OK;
+}
+
+extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
+                                     const void* k_new_dev, const void* v_new_dev, int64_t past_len,
+                                     int32_t chunk_len, void* out_dev, int32_t next_layer, int32_t next_kv_head,
+                                     int64_t next_past_len) {
+  HI_TRY(check_unit_args(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
+                         next_kv_head, next_past_len));
+  HI_TRY(pace_begin(c));
+  HI_TRY(prefill_head_impl(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
+                           next_kv_head, next_past_len));
+  return pace_end(c);
+}
+
+extern "C" hi_status hi_decode_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
+                                    const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
+                                    int32_t next_layer, int32_t next_kv_head, int64_t next_past_len) {
+  HI_TRY(check_unit_args(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, 1, out_dev, next_layer,
+                         next_kv_head, next_past_len));
+  HI_TRY(pace_begin(c));
+  HI_TRY(decode_head_impl(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, out_dev, next_layer,
+                          next_kv_head, next_past_len));
+  return pace_end(c);
 }
 
 extern "C" hi_status hi_sync(hi_ctx* c) {

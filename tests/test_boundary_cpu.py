@@ -133,6 +133,7 @@ def test_entry_points_reject_null_context_without_touching_the_gpu():
     assert L.hi_prefill_head(None, 0, 0, None, None, None, 0, 1, None, -1, 0, 0) == hb.HI_ERR_ARG
     assert L.hi_decode_head(None, 0, 0, None, None, None, 0, None, -1, 0, 0) == hb.HI_ERR_ARG
     assert L.hi_sync(None) == hb.HI_ERR_ARG
+    assert L.hi_ctx_set_run_ahead(None, 2) == hb.HI_ERR_ARG and L.hi_ctx_set_flags(None, 0) == hb.HI_ERR_ARG
     assert L.hi_get_stats(None, None) == hb.HI_ERR_ARG
     assert L.hi_ctx_destroy(None) == hb.HI_OK
     prob = hb.make_problem(1, 1, 4, 4096, 512)
