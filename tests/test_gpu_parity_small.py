@@ -196,3 +196,46 @@ def test_runtime_argument_errors_leave_cache_untouched():
     ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=dev)
     st, _ = hb.hi_ctx_create(prob, plan, hb.HI_MODE_OFFLOAD, pageable, stg, ws, None, None, None, check=False)
     assert st == hb.HI_ERR_NOT_PINNED
+
+
+def test_pipeline_hazards_poisoned_staging_and_unhonoured_hints():
+    """Staging buffer reuse: the ring (here 8 slots of 64 rows) is poisoned with NaN patterns before the run, units
+    of two heads alternate with prefetch hints that are sometimes wrong (the library must drop the stale prefetch
+    and fetch on demand) and sometimes absent; every result must still match the oracle, bit for bit the same as
+    an HBM-resident run, and no NaN may leak from the poison."""
+    dev, seed, G, H, C, n_chunks = "cuda:0", 77, 4, 2, 96, 5
+    S = C * n_chunks
+    results = {}
+    for mode in (hb.HI_MODE_OFFLOAD, hb.HI_MODE_RESIDENT):
+        with Session(1, H, G, S, C, mode=mode, out_fp32=1) as ss:
+            if mode == hb.HI_MODE_OFFLOAD:
+                assert ss.plan.n_slices_ring * ss.plan.slice_tokens <= S and ss.plan.slice_tokens == 64
+                ss.staging.view(torch.int16).fill_(0x7FC1)          # bf16 NaN pattern
+                ss.kv.view(torch.int16).fill_(0x7FC1)
+            outs = {}
+            with torch.cuda.stream(ss.s_compute):
+                for c in range(n_chunks):
+                    p = c * C
+                    for h in range(H):
+                        q = torch.stack([synth.draw_q(seed, 0, h * G + g, p, C, device=dev) for g in range(G)])
+                        k = synth.draw_k(seed, 0, h, p, C, device=dev)
+                        v = synth.draw_v(seed, 0, h, p, C, device=dev)
+                        out = torch.empty(G, C, 128, dtype=torch.float32, device=dev)
+                        good = (0, h + 1, p) if h + 1 < H else (0, 0, p + C)
+                        hint = [good, (0, h, p), None, (0, (h + 1) % H, max(p - C, 0))][(c + h) % 4]   # right, wrong, none, wrong
+                        if hint == good and c == n_chunks - 1 and h == H - 1:
+                            hint = None
+                        ss.prefill_head(0, h, q, k, v, p, out, hint)
+                        outs[(c, h)] = out
+            ss.sync()
+            results[mode] = {k: v.cpu() for k, v in outs.items()}
+    for h in range(H):
+        Q = np.stack([synth.to_f64(synth.draw_q(seed, 0, h * G + g, 0, S)) for g in range(G)])
+        K = synth.to_f64(synth.draw_k(seed, 0, h, 0, S))
+        V = synth.to_f64(synth.draw_v(seed, 0, h, 0, S))
+        ref = oa.attn_head(Q, K, V)
+        for c in range(n_chunks):
+            a, b = results[hb.HI_MODE_OFFLOAD][(c, h)], results[hb.HI_MODE_RESIDENT][(c, h)]
+            assert torch.equal(a, b), (c, h)
+            for g in range(G):
+                check(a[g:g + 1], ref[g:g + 1, c * C:(c + 1) * C], f"hazard test chunk {c} head {h} q {g}")
