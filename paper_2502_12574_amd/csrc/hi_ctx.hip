@@ -4,7 +4,8 @@
 // cache and the current head's new rows are written back, on separate streams (full-duplex link).  Here the
 // "ping-pong memory" is a ring of sequence slices that together never exceed the HBM KV budget (one head's worth
 // by default): the kernel consumes slice n while later slices - of this head, then of the next one - land, and the
-// softmax state is carried from slice to slice.  All calls only enqueue work; no host thread blocks.
+// softmax state is carried from slice to slice.  Calls only enqueue work; the one host-side wait is the bounded
+// run-ahead (a call waits until the unit two calls earlier has finished), which keeps the runtime's queues short.
 #include <hip/hip_runtime.h>
 #include <cstring>
 #include <new>
