@@ -189,7 +189,8 @@ hi_status pace_end(hi_ctx* c) {
 }
 
 int pf_variant(const hi_ctx* c) {
-  return (c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_WIDE) ? 2 : 0;
+  return (c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_WIDE) ? 2 :
+         (c->flags & HI_FLAG_PREFILL_DEEP) ? 3 : 0;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -331,7 +332,7 @@ extern "C" hi_status hi_ctx_destroy(hi_ctx* c) {
 
 extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
   if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS | HI_FLAG_PREFILL_NARROW |
-                      HI_FLAG_PREFILL_WIDE))) { set_last_error("bad flags"); return HI_ERR_ARG; }
+                      HI_FLAG_PREFILL_WIDE | HI_FLAG_PREFILL_DEEP))) { set_last_error("bad flags"); return HI_ERR_ARG; }
   c->flags = flags;
   return HI_OK;
 }

@@ -33,7 +33,8 @@ struct PrefillSegment {
 
 // One launch of the prefill kernel over up to two KV segments.  first: start from an empty softmax state
 // instead of loading the carry; last: normalise and write `out` instead of storing the carry.
-// variant: 0 or 1 = narrow kernel (32 positions per wave), 2 = wide kernel (64 per wave);
+// variant: 0 = pick by chunk length (deep if it fills the chip, else narrow), 1 = narrow kernel (4 waves,
+// 2 LDS stages), 2 = wide kernel (64 positions per wave), 3 = deep kernel (8 waves, 4 LDS stages);
 // every launch of one unit must use the same variant (the carry layouts differ).
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& a,
                          const PrefillSegment& b, int first, int last, void* carry, void* out, int out_fp32,

@@ -62,28 +62,34 @@ struct PfLaneConst {
                      // pair, +4096 second 16-row group, +8192 second sub-block)
 };
 
-// One stage's tile loads by the whole workgroup (8 instructions per wavefront).  Full tiles need no vector ALU
-// work at all; the last tile of a segment clamps its row indices (rows past the end re-read the last row and are
-// masked by the caller).
+// One stage's tile loads by the whole workgroup of NW wavefronts (16 / NW K and as many V instructions per
+// wavefront).  Full tiles need no vector ALU work at all; the last tile of a segment clamps its row indices (rows
+// past the end re-read the last row and are masked by the caller).
+template <int NW>
 __device__ __forceinline__ void pf_issue_tile(const char* kt, const char* vt, int rows, uint32_t lds_stage,
                                               int wave, int lane, const PfLaneConst& lc) {
-  const uint32_t ldk = lds_stage + wave * 4096;
+  constexpr int NI = 16 / NW;
+  const uint32_t ldk = lds_stage + wave * (NI * 1024);
   const uint32_t ldv = ldk + kPfTileBytes;
   if (rows >= kPfTileRows) {
     g2lds16_s<0>(kt, lc.gk[0], ldk);
     g2lds16_s<0>(kt, lc.gk[1], ldk + 1024);
-    g2lds16_s<0>(kt, lc.gk[2], ldk + 2048);
-    g2lds16_s<0>(kt, lc.gk[3], ldk + 3072);
+    if (NI > 2) {
+      g2lds16_s<0>(kt, lc.gk[2], ldk + 2048);
+      g2lds16_s<0>(kt, lc.gk[3], ldk + 3072);
+    }
     g2lds16_s<0>(vt, lc.gv, ldv);
     g2lds16_s<1024>(vt, lc.gv, ldv);     // the immediate advances the global AND the LDS address
-    g2lds16_s<2048>(vt, lc.gv, ldv);
-    g2lds16_s<3072>(vt, lc.gv, ldv);
+    if (NI > 2) {
+      g2lds16_s<2048>(vt, lc.gv, ldv);
+      g2lds16_s<3072>(vt, lc.gv, ldv);
+    }
   } else {
     const int r_in = lane >> 4;
     const int cpos = lane & 15;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = (wave * 4 + i) * 4 + r_in;
+    for (int i = 0; i < NI; ++i) {
+      const int r = (wave * NI + i) * 4 + r_in;
       const int rc = r < rows ? r : rows - 1;
       g2lds16_s<0>(kt, (uint32_t)(rc * kRowBytes + ((cpos ^ swz_k(r)) << 4)), ldk + i * 1024);
       g2lds16_s<0>(vt, (uint32_t)(rc * kRowBytes + ((cpos ^ swz_v(r)) << 4)), ldv + i * 1024);
@@ -99,12 +105,10 @@ struct PfState {
   float m, l;
 };
 
-// One 64-row tile out of LDS stage STAGE: S^T = K Q^T, online softmax, O^T += V^T P^T.
+// One 64-row tile out of the LDS stage starting at kt: S^T = K Q^T, online softmax, O^T += V^T P^T.
 // mask_rel: rows of the tile with index > mask_rel are masked for this lane (>= 63 means no masking).
-template <int STAGE>
-__device__ __forceinline__ void pf_compute_tile(lds_char* lds, const PfLaneConst& lc, const bf16x8 (&qf)[8],
+__device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst& lc, const bf16x8 (&qf)[8],
                                                 PfState& st, float c, bool masked, int mask_rel, int hl) {
-  lds_char* kt = lds + STAGE * kPfStageBytes;
   lds_char* vt = kt + kPfTileBytes;
 
   // S^T: register r of sub-block sb is tile row 32*sb + 8*(r/4) + 4*hl + r%4 (query row = lane % 32)
@@ -261,13 +265,13 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     if (t < ta) {
       const int64_t row0 = (int64_t)t * kPfTileRows;
       const int64_t left = a.na - row0;
-      pf_issue_tile(a.ka + row0 * kRowBytes, a.va + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
-                    stage, wave, lane, lc);
+      pf_issue_tile<4>(a.ka + row0 * kRowBytes, a.va + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
+                       stage, wave, lane, lc);
     } else {
       const int64_t row0 = (int64_t)(t - ta) * kPfTileRows;
       const int64_t left = a.nb - row0;
-      pf_issue_tile(a.kb + row0 * kRowBytes, a.vb + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
-                    stage, wave, lane, lc);
+      pf_issue_tile<4>(a.kb + row0 * kRowBytes, a.vb + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
+                       stage, wave, lane, lc);
     }
   };
 
@@ -294,7 +298,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
       const int64_t d = lim - j0;
       rel = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
     }
-    pf_compute_tile<STAGE>(lds, lc, qf, st, c, masked, rel, hl);
+    pf_compute_tile(lds + STAGE * kPfStageBytes, lc, qf, st, c, masked, rel, hl);
   };
   int t = 0;
   for (; t + 1 < T; t += 2) {
@@ -314,6 +318,167 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   }
 
   // normalise and write out[g][i][:]; register r of block db is dim 32*db + 8*(r/4) + 4*hl + r%4
+  const float l_tot = sum_halves(st.l);
+  const float inv = 1.0f / l_tot;
+  if (my_i < a.C) {
+    const int64_t base = ((int64_t)g * a.C + my_i) * kHeadDim;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int dim = 32 * db + 8 * rq + 4 * hl;
+        const float x0 = st.o[db][4 * rq] * inv, x1 = st.o[db][4 * rq + 1] * inv;
+        const float x2 = st.o[db][4 * rq + 2] * inv, x3 = st.o[db][4 * rq + 3] * inv;
+        if (a.out_fp32) {
+          *(float4*)((float*)a.out + base + dim) = make_float4(x0, x1, x2, x3);
+        } else {
+          uint2 pk;
+          pk.x = (uint32_t)float_to_bf16_bits(x0) | ((uint32_t)float_to_bf16_bits(x1) << 16);
+          pk.y = (uint32_t)float_to_bf16_bits(x2) | ((uint32_t)float_to_bf16_bits(x3) << 16);
+          *(uint2*)((uint16_t*)a.out + base + dim) = pk;
+        }
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Deep variant of the narrow kernel: 8 wavefronts per workgroup (two per SIMD, 32 positions each: the G query
+// heads at 64 positions for G = 4), one workgroup per compute unit, and FOUR LDS stages, so three tiles are in
+// flight while one is consumed (the two-stage kernel has one) and every K/V byte pulled from L2 serves 256 query
+// rows.  Same per-wave arithmetic as the narrow kernel (pf_compute_tile); used for chunks long enough to give
+// every compute unit a workgroup.
+constexpr int kPdWaves = 8;
+constexpr int kPdStages = 4;
+constexpr int kPdLdsBytes = kPdStages * kPfStageBytes;   // 128 KiB
+
+__global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) char lds_dyn[];
+  lds_char* lds = (lds_char*)lds_dyn;
+  const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+  const int lane = lane_id();
+  const int wave = wave_id();
+  const int hl = lane >> 5;
+  const int col = lane & 31;
+
+  const int gl = a.G < 4 ? a.G : 4;
+  const int strip = 32 * (kPdWaves / gl);
+  const int bx = gridDim.x - 1 - blockIdx.x;
+  const int g = blockIdx.y * 4 + (wave % gl);
+  const int i0 = bx * strip + 32 * (wave / gl);
+  const int i_hi = bx * strip + strip - 1;
+  int qi = i0 + col;
+  const int my_i = qi;
+  if (qi > a.C - 1) qi = a.C - 1;
+
+  PfLaneConst lc;
+  {
+    const int r_in = lane >> 4, cpos = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int r = (wave * 2 + i) * 4 + r_in;
+      lc.gk[i] = (uint32_t)(r * kRowBytes + ((cpos ^ swz_k(r)) << 4));
+    }
+    lc.gk[2] = lc.gk[3] = 0;
+    const int r0 = wave * 8 + r_in;
+    lc.gv = (uint32_t)(r0 * kRowBytes + ((cpos ^ swz_v(r0)) << 4));
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) lc.koff[kk] = (uint32_t)(col * kRowBytes + (((2 * kk + hl) ^ swz_k(col)) << 4));
+    const int s16 = lane & 15, q16 = col >> 4;
+    const int row_lo = 4 * hl + (s16 >> 2);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+      const int chunk = 4 * db + 2 * q16 + ((s16 & 3) >> 1);
+      lc.voff[db] = (uint32_t)(row_lo * kRowBytes + ((chunk ^ swz_v(row_lo)) << 4) + ((s16 & 1) << 3));
+    }
+  }
+
+  bf16x8 qf[8];
+  {
+    const uint16_t* qrow = a.q + ((int64_t)g * a.C + qi) * kHeadDim + 8 * hl;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 16 * kk));
+  }
+
+  PfState st;
+  const int64_t wg_linear = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+  float* carry = a.carry + wg_linear * (kCarryFloatsPerLane * kPdWaves * 64) + threadIdx.x;
+  constexpr int kLanes = kPdWaves * 64;
+  if (a.first) {
+    st.m = kNegBig;
+    st.l = 0.f;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
+  } else {
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[db][r] = carry[(db * 16 + r) * kLanes];
+    st.m = carry[64 * kLanes];
+    st.l = carry[65 * kLanes];
+  }
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) asm volatile("" : "+v"(qf[kk]));
+  asm volatile("" : "+v"(st.m), "+v"(st.l));
+#pragma unroll
+  for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(st.o[db]));
+
+  const int ta = (int)((a.na + kPfTileRows - 1) / kPfTileRows);
+  const int64_t nb_vis = a.nb < (int64_t)i_hi + 1 ? a.nb : (int64_t)i_hi + 1;
+  const int tb = (int)((nb_vis + kPfTileRows - 1) / kPfTileRows);
+  const int T = ta + tb;
+
+  auto issue = [&](int t) {
+    const uint32_t stage = lds_base + (uint32_t)(t & (kPdStages - 1)) * kPfStageBytes;
+    if (t < ta) {
+      const int64_t row0 = (int64_t)t * kPfTileRows;
+      const int64_t left = a.na - row0;
+      pf_issue_tile<kPdWaves>(a.ka + row0 * kRowBytes, a.va + row0 * kRowBytes,
+                              left < kPfTileRows ? (int)left : kPfTileRows, stage, wave, lane, lc);
+    } else {
+      const int64_t row0 = (int64_t)(t - ta) * kPfTileRows;
+      const int64_t left = a.nb - row0;
+      pf_issue_tile<kPdWaves>(a.kb + row0 * kRowBytes, a.vb + row0 * kRowBytes,
+                              left < kPfTileRows ? (int)left : kPfTileRows, stage, wave, lane, lc);
+    }
+  };
+
+  // each tile is 4 load instructions per wave; up to three tiles in flight
+  if (T > 0) issue(0);
+  if (T > 1) issue(1);
+  if (T > 2) issue(2);
+  const float c = a.c;
+  for (int t = 0; t < T; ++t) {
+    if (t + 2 < T) wait_vmcnt<8>();          // tile t has landed; t+1 and t+2 may still be in flight
+    else if (t + 1 < T) wait_vmcnt<4>();
+    else wait_vmcnt<0>();
+    __syncthreads();                         // visible to all waves; everyone is done with tile t-1's stage
+    if (t + 3 < T) issue(t + 3);
+    const bool in_b = t >= ta;
+    const int64_t j0 = (int64_t)(in_b ? (t - ta) : t) * kPfTileRows;
+    const int64_t n_seg = in_b ? a.nb : a.na;
+    const bool masked = (j0 + kPfTileRows > n_seg) || (in_b && (j0 + kPfTileRows - 1 > i0));
+    int rel = kPfTileRows;
+    if (masked) {
+      int64_t lim = n_seg - 1;
+      if (in_b && (int64_t)my_i < lim) lim = my_i;
+      const int64_t d = lim - j0;
+      rel = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
+    }
+    pf_compute_tile(lds + (t & (kPdStages - 1)) * kPfStageBytes, lc, qf, st, c, masked, rel, hl);
+  }
+
+  if (!a.last) {
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) carry[(db * 16 + r) * kLanes] = st.o[db][r];
+    carry[64 * kLanes] = st.m;
+    carry[65 * kLanes] = st.l;
+    return;
+  }
+
   const float l_tot = sum_halves(st.l);
   const float inv = 1.0f / l_tot;
   if (my_i < a.C) {
@@ -443,13 +608,13 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel_wide(PrefillArgs a) {
     if (t < ta) {
       const int64_t row0 = (int64_t)t * kPfTileRows;
       const int64_t left = a.na - row0;
-      pf_issue_tile(a.ka + row0 * kRowBytes, a.va + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
-                    stage, wave, lane, lc);
+      pf_issue_tile<4>(a.ka + row0 * kRowBytes, a.va + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
+                       stage, wave, lane, lc);
     } else {
       const int64_t row0 = (int64_t)(t - ta) * kPfTileRows;
       const int64_t left = a.nb - row0;
-      pf_issue_tile(a.kb + row0 * kRowBytes, a.vb + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
-                    stage, wave, lane, lc);
+      pf_issue_tile<4>(a.kb + row0 * kRowBytes, a.vb + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
+                       stage, wave, lane, lc);
     }
   };
 
@@ -609,6 +774,8 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel_wide(PrefillArgs a) {
   }
 }
 
+constexpr int kDeepMinWorkgroups = 192;
+
 static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   // log2(e) / sqrt(128)
 
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& sa,
@@ -628,16 +795,22 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   const int strip = prefill_strip(G);
   const int gy = prefill_grid_y(G);
   const bool wide = variant == 2;
-  if (wide) {
+  // the deep kernel covers 2 * strip positions per workgroup; use it when that still fills the chip
+  const bool deep = variant == 3 || (variant == 0 && ceil_div(chunk_len, 2 * strip) * gy >= kDeepMinWorkgroups);
+  if (wide || deep) {
     static bool attr_set = false;
     if (!attr_set) {
       hipError_t ea = hipFuncSetAttribute((const void*)prefill_kernel_wide, hipFuncAttributeMaxDynamicSharedMemorySize,
                                           kPwLdsBytes);
+      if (ea == hipSuccess)
+        ea = hipFuncSetAttribute((const void*)prefill_kernel_deep, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 kPdLdsBytes);
       if (ea != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(ea)); return HI_ERR_HIP; }
       attr_set = true;
     }
     dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)gy);
-    hipLaunchKernelGGL(prefill_kernel_wide, grid, dim3(kWgThreads), kPwLdsBytes, (hipStream_t)stream, a);
+    if (wide) hipLaunchKernelGGL(prefill_kernel_wide, grid, dim3(kWgThreads), kPwLdsBytes, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
   } else {
     dim3 grid((unsigned)ceil_div(chunk_len, strip), (unsigned)gy);
     hipLaunchKernelGGL(prefill_kernel, grid, dim3(kWgThreads), 0, (hipStream_t)stream, a);

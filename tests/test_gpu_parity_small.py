@@ -123,12 +123,15 @@ def test_prefill_ragged_shapes(G, P, C):
                                    (4, 1000, 129), (1, 77, 200), (2, 130, 95), (8, 200, 70), (8, 0, 40),
                                    (4, 97, 700)])
 @pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
-def test_prefill_wide_kernel_ragged_shapes(G, P, C, mode):
-    # the 64-positions-per-wave kernel is normally picked for long chunks only; force it on small shapes
-    out, Q, K, V = one_unit(G, P, C, seed=700 + P + C, mode=mode, flags=hb.HI_FLAG_PREFILL_WIDE)
+@pytest.mark.parametrize("variant", ["wide", "deep"])
+def test_prefill_other_kernel_variants_ragged_shapes(G, P, C, mode, variant):
+    # the 8-wave / 4-stage kernel is normally picked for long chunks only and the 64-positions-per-wave kernel
+    # only on request; force each of them on small ragged shapes
+    flag = hb.HI_FLAG_PREFILL_WIDE if variant == "wide" else hb.HI_FLAG_PREFILL_DEEP
+    out, Q, K, V = one_unit(G, P, C, seed=700 + P + C, mode=mode, flags=flag)
     ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
     for g in range(G):
-        check(out[g:g + 1], ref[g:g + 1], f"wide G={G} P={P} C={C} head {g}")
+        check(out[g:g + 1], ref[g:g + 1], f"{variant} G={G} P={P} C={C} head {g}")
 
 
 @pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
