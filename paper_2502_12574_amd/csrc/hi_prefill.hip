@@ -112,16 +112,16 @@ __device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst&
   lds_char* vt = kt + kPfTileBytes;
 
   // S^T: register r of sub-block sb is tile row 32*sb + 8*(r/4) + 4*hl + r%4 (query row = lane % 32)
+  // (the two sub-blocks' accumulation chains alternate, so consecutive MFMAs never depend on each other)
   f32x16 s[2];
 #pragma unroll
-  for (int sb = 0; sb < 2; ++sb) {
-    bf16x8 kf[8];
+  for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) kf[kk] = *(lds_bf16x8*)(kt + lc.koff[kk] + sb * 8192);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[sb][r] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s[sb], 0, 0, 0);
+  for (int kk = 0; kk < 8; ++kk) {
+    const bf16x8 k0 = *(lds_bf16x8*)(kt + lc.koff[kk]);
+    const bf16x8 k1 = *(lds_bf16x8*)(kt + lc.koff[kk] + 8192);
+    s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[kk], s[0], 0, 0, 0);
+    s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[kk], s[1], 0, 0, 0);
   }
 
   if (masked) {
