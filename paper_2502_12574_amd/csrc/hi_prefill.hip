@@ -62,15 +62,14 @@ struct PfLaneConst {
                      // pair, +4096 second 16-row group, +8192 second sub-block)
 };
 
-// One stage's tile loads by the whole workgroup of NW wavefronts (16 / NW K and as many V instructions per
-// wavefront).  Full tiles need no vector ALU work at all; the last tile of a segment clamps its row indices (rows
-// past the end re-read the last row and are masked by the caller).
+// One tile's K loads (or V loads) by the whole workgroup of NW wavefronts: 16 / NW instructions per wavefront.
+// Full tiles need no vector ALU work at all; the last tile of a segment clamps its row indices (rows past the
+// end re-read the last row and are masked by the caller).  lds_tile is the LDS byte address of the 16 KiB tile.
 template <int NW>
-__device__ __forceinline__ void pf_issue_tile(const char* kt, const char* vt, int rows, uint32_t lds_stage,
-                                              int wave, int lane, const PfLaneConst& lc) {
+__device__ __forceinline__ void pf_issue_k(const char* kt, int rows, uint32_t lds_tile, int wave, int lane,
+                                           const PfLaneConst& lc) {
   constexpr int NI = 16 / NW;
-  const uint32_t ldk = lds_stage + wave * (NI * 1024);
-  const uint32_t ldv = ldk + kPfTileBytes;
+  const uint32_t ldk = lds_tile + wave * (NI * 1024);
   if (rows >= kPfTileRows) {
     g2lds16_s<0>(kt, lc.gk[0], ldk);
     g2lds16_s<0>(kt, lc.gk[1], ldk + 1024);
@@ -78,6 +77,24 @@ __device__ __forceinline__ void pf_issue_tile(const char* kt, const char* vt, in
       g2lds16_s<0>(kt, lc.gk[2], ldk + 2048);
       g2lds16_s<0>(kt, lc.gk[3], ldk + 3072);
     }
+  } else {
+    const int r_in = lane >> 4;
+    const int cpos = lane & 15;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int r = (wave * NI + i) * 4 + r_in;
+      const int rc = r < rows ? r : rows - 1;
+      g2lds16_s<0>(kt, (uint32_t)(rc * kRowBytes + ((cpos ^ swz_k(r)) << 4)), ldk + i * 1024);
+    }
+  }
+}
+
+template <int NW>
+__device__ __forceinline__ void pf_issue_v(const char* vt, int rows, uint32_t lds_tile, int wave, int lane,
+                                           const PfLaneConst& lc) {
+  constexpr int NI = 16 / NW;
+  const uint32_t ldv = lds_tile + wave * (NI * 1024);
+  if (rows >= kPfTileRows) {
     g2lds16_s<0>(vt, lc.gv, ldv);
     g2lds16_s<1024>(vt, lc.gv, ldv);     // the immediate advances the global AND the LDS address
     if (NI > 2) {
@@ -91,10 +108,17 @@ __device__ __forceinline__ void pf_issue_tile(const char* kt, const char* vt, in
     for (int i = 0; i < NI; ++i) {
       const int r = (wave * NI + i) * 4 + r_in;
       const int rc = r < rows ? r : rows - 1;
-      g2lds16_s<0>(kt, (uint32_t)(rc * kRowBytes + ((cpos ^ swz_k(r)) << 4)), ldk + i * 1024);
       g2lds16_s<0>(vt, (uint32_t)(rc * kRowBytes + ((cpos ^ swz_v(r)) << 4)), ldv + i * 1024);
     }
   }
+}
+
+// One stage's tile loads (K tile, then V tile).
+template <int NW>
+__device__ __forceinline__ void pf_issue_tile(const char* kt, const char* vt, int rows, uint32_t lds_stage,
+                                              int wave, int lane, const PfLaneConst& lc) {
+  pf_issue_k<NW>(kt, rows, lds_stage, wave, lane, lc);
+  pf_issue_v<NW>(vt, rows, lds_stage + kPfTileBytes, wave, lane, lc);
 }
 
 typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
@@ -105,15 +129,11 @@ struct PfState {
   float m, l;
 };
 
-// One 64-row tile out of the LDS stage starting at kt: S^T = K Q^T, online softmax, O^T += V^T P^T.
-// mask_rel: rows of the tile with index > mask_rel are masked for this lane (>= 63 means no masking).
-__device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst& lc, const bf16x8 (&qf)[8],
-                                                PfState& st, float c, bool masked, int mask_rel, int hl) {
-  lds_char* vt = kt + kPfTileBytes;
-
-  // S^T: register r of sub-block sb is tile row 32*sb + 8*(r/4) + 4*hl + r%4 (query row = lane % 32)
-  // (the two sub-blocks' accumulation chains alternate, so consecutive MFMAs never depend on each other)
-  f32x16 s[2];
+// S^T = K Q^T for one 64-row K tile at kt: register r of sub-block sb is tile row 32*sb + 8*(r/4) + 4*hl + r%4
+// (query row = lane % 32).  The two sub-blocks' accumulation chains alternate, so consecutive MFMAs never
+// depend on each other.
+__device__ __forceinline__ void pf_scores(lds_char* kt, const PfLaneConst& lc, const bf16x8 (&qf)[8],
+                                          f32x16 (&s)[2]) {
 #pragma unroll
   for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
 #pragma unroll
@@ -123,7 +143,14 @@ __device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst&
     s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k0, qf[kk], s[0], 0, 0, 0);
     s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k1, qf[kk], s[1], 0, 0, 0);
   }
+}
 
+// Online softmax of one tile's scores: per lane = per query row; the other half-wave holds the other 32 rows of
+// the tile.  Updates (m, l), rescales O when the running maximum moved, and leaves the probabilities rounded to
+// bf16 in pb, laid out as the B operands of the second product.
+// mask_rel: rows of the tile with index > mask_rel are masked for this lane (>= 63 means no masking).
+__device__ __forceinline__ void pf_softmax(f32x16 (&s)[2], PfState& st, float c, bool masked, int mask_rel, int hl,
+                                           bf16x8 (&pb)[2][2]) {
   if (masked) {
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb)
@@ -133,8 +160,6 @@ __device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst&
         if (row > mask_rel) s[sb][r] = kNegBig;
       }
   }
-
-  // online softmax: per lane = per query row; the other half-wave holds the other 32 rows of the tile
   float mx = s[0][0];
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
@@ -153,7 +178,6 @@ __device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst&
   }
   const float mc = st.m * c;
   float lsum = 0.f;
-  bf16x8 pb[2][2];
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -165,8 +189,16 @@ __device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst&
         pb[sb][u][j] = (__bf16)p;
       }
   st.l += lsum;
+  // the conversions belong to this phase (the values are first used after the caller's barrier)
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(pb[sb][u]));
+}
 
-  // O^T += V^T P^T : contraction index 8*hl + j of MFMA (sb,u) is tile row 32*sb + 16*u + 8*(j/4) + 4*hl + j%4
+// O^T += V^T P^T for one 64-row V tile at vt: contraction index 8*hl + j of MFMA (sb,u) is tile row
+// 32*sb + 16*u + 8*(j/4) + 4*hl + j%4.
+__device__ __forceinline__ void pf_pv(lds_char* vt, const PfLaneConst& lc, const bf16x8 (&pb)[2][2], PfState& st) {
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -179,6 +211,71 @@ __device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst&
         st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[sb][u], st.o[db], 0, 0, 0);
       }
     }
+}
+
+// Matrix phase of the alternating schedule: O^T += V^T P^T of the previous tile (V tile at vt, probabilities
+// pb), then S^T = K Q^T of the next (K tile at kt), as ONE software-pipelined sequence of 32 MFMAs whose LDS
+// operand reads run kPfAhead steps ahead of their use: a wavefront that has the matrix pipe to itself must hide
+// the LDS latency on its own.
+constexpr int kPfAhead = 5;
+
+__device__ __forceinline__ bf16x8 pf_matrix_operand(int i, lds_char* vt, lds_char* kt, const PfLaneConst& lc) {
+  if (i < 16) {     // V^T fragment of step (sb, u, db)
+    const int sb = i >> 3, u = (i >> 2) & 1, db = i & 3;
+    const bf16x4 v0 = lds_read_tr8(vt + lc.voff[db] + sb * 8192 + u * 4096);
+    const bf16x4 v1 = lds_read_tr8(vt + lc.voff[db] + sb * 8192 + u * 4096 + 2048);
+    return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+  const int kk = (i - 16) >> 1, sb = (i - 16) & 1;   // K fragment of step (kk, sb)
+  return *(lds_bf16x8*)(kt + lc.koff[kk] + sb * 8192);
+}
+
+// The tile loads a wavefront of the 8-wave kernel issues while it runs a matrix phase: its two K and two V
+// instructions (full tiles only; k / v are null otherwise) ride in the gaps between the first MFMAs, where
+// their scalar set-up and the issue itself cost next to nothing.
+struct PfPhaseLoads {
+  const char* k;      // K tile base (global), null: nothing to issue
+  const char* v;      // V tile base
+  uint32_t ldk, ldv;  // LDS byte address of this wave's first destination row group in the K / V tile
+};
+
+template <bool LOADS_ALWAYS>
+__device__ __forceinline__ void pf_matrix_phase(lds_char* vt, lds_char* kt, const PfLaneConst& lc,
+                                                const bf16x8 (&qf)[8], const bf16x8 (&pb)[2][2], PfState& st,
+                                                f32x16 (&s)[2], const PfPhaseLoads& ld) {
+  bf16x8 op[kPfAhead + 1];
+#pragma unroll
+  for (int i = 0; i < kPfAhead; ++i) op[i] = pf_matrix_operand(i, vt, kt, lc);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    if (i + kPfAhead < 32) op[(i + kPfAhead) % (kPfAhead + 1)] = pf_matrix_operand(i + kPfAhead, vt, kt, lc);
+    const bf16x8 x = op[i % (kPfAhead + 1)];
+    if (i < 16) {
+      const int sb = i >> 3, u = (i >> 2) & 1, db = i & 3;
+      st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, pb[sb][u], st.o[db], 0, 0, 0);
+    } else {
+      const int kk = (i - 16) >> 1, sb = (i - 16) & 1;
+      s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qf[kk], s[sb], 0, 0, 0);
+    }
+    if (i == 1 && (LOADS_ALWAYS || ld.k)) g2lds16_s<0>(ld.k, lc.gk[0], ld.ldk);
+    if (i == 3 && (LOADS_ALWAYS || ld.k)) g2lds16_s<0>(ld.k, lc.gk[1], ld.ldk + 1024);
+    if (i == 5 && (LOADS_ALWAYS || ld.v)) g2lds16_s<0>(ld.v, lc.gv, ld.ldv);
+    if (i == 7 && (LOADS_ALWAYS || ld.v)) g2lds16_s<1024>(ld.v, lc.gv, ld.ldv);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// One 64-row tile out of the LDS stage starting at kt, straight through.
+__device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst& lc, const bf16x8 (&qf)[8],
+                                                PfState& st, float c, bool masked, int mask_rel, int hl) {
+  f32x16 s[2];
+  bf16x8 pb[2][2];
+  pf_scores(kt, lc, qf, s);
+  pf_softmax(s, st, c, masked, mask_rel, hl, pb);
+  pf_pv(kt + kPfTileBytes, lc, pb, st);
 }
 
 __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
@@ -429,32 +526,55 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   const int tb = (int)((nb_vis + kPfTileRows - 1) / kPfTileRows);
   const int T = ta + tb;
 
-  auto issue = [&](int t) {
+  // K tile t (which = 0) or V tile t (which = 1) of the sweep: this wave's share of its loads
+  auto issue = [&](int t, int which) {
+    if (t >= T) return;
+    const bool in_b = t >= ta;
+    const int64_t row0 = (int64_t)(in_b ? t - ta : t) * kPfTileRows;
+    const int64_t left = (in_b ? a.nb : a.na) - row0;
+    const int rows = left < kPfTileRows ? (int)left : kPfTileRows;
     const uint32_t stage = lds_base + (uint32_t)(t & (kPdStages - 1)) * kPfStageBytes;
-    if (t < ta) {
-      const int64_t row0 = (int64_t)t * kPfTileRows;
-      const int64_t left = a.na - row0;
-      pf_issue_tile<kPdWaves>(a.ka + row0 * kRowBytes, a.va + row0 * kRowBytes,
-                              left < kPfTileRows ? (int)left : kPfTileRows, stage, wave, lane, lc);
-    } else {
-      const int64_t row0 = (int64_t)(t - ta) * kPfTileRows;
-      const int64_t left = a.nb - row0;
-      pf_issue_tile<kPdWaves>(a.kb + row0 * kRowBytes, a.vb + row0 * kRowBytes,
-                              left < kPfTileRows ? (int)left : kPfTileRows, stage, wave, lane, lc);
-    }
+    if (which == 0) pf_issue_k<kPdWaves>((in_b ? a.kb : a.ka) + row0 * kRowBytes, rows, stage, wave, lane, lc);
+    else pf_issue_v<kPdWaves>((in_b ? a.vb : a.va) + row0 * kRowBytes, rows, stage + kPfTileBytes, wave, lane, lc);
+  };
+  // Every wave issues, in this order: K0 | K1 V0 | K2 V1 | then, in the matrix phase of tile t, K(t+3) V(t+2)
+  // (2 instructions each).  "K(t+1) and V(t) have landed" therefore means: at most the last two pairs are still
+  // in flight, when both pairs exist in full.
+  auto wait_landed = [&](int t) {
+    if (t + 3 < T) wait_vmcnt<8>();
+    else wait_vmcnt<0>();
+  };
+  auto phase_barrier = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
   };
 
-  // each tile is 4 load instructions per wave; up to three tiles in flight
-  if (T > 0) issue(0);
-  if (T > 1) issue(1);
-  if (T > 2) issue(2);
+  // The two wavefronts of a SIMD alternate: while one runs its matrix phase (O += V P of the previous tile, then
+  // the scores of the next), the other runs its softmax phase on the vector ALU.  Both groups execute the same
+  // program with two barriers per tile; group 1 passes one extra barrier first, so it is always one phase behind
+  // (and group 0 passes one extra at the end: every wave executes the same number of barriers).
+  //   phase index (barriers passed so far):  group 0: matrix(t) = 2t, softmax(t) = 2t + 1;  group 1: one later.
+  //   K(t) is read in phases 2t, 2t+1; V(t) in phases 2t+2, 2t+3.  K(t+3) replaces K(t-1) (last read in phase
+  //   2t-1) and V(t+2) replaces V(t-2) (last read in phase 2t-1): both are issued in matrix(t), phase >= 2t.
+  //   Each wave waits for its share of K(t+1) and V(t) at the end of matrix(t): before the barrier that ends
+  //   phase 2t+1 at the latest, and K(t+1) is first read in phase 2t+2, V(t) in phase 2t+2.
+#ifdef HI_PP_GROUP_LOW
+  const int group = wave & 1;
+#else
+  const int group = wave >> 2;
+#endif
   const float c = a.c;
-  for (int t = 0; t < T; ++t) {
-    if (t + 2 < T) wait_vmcnt<8>();          // tile t has landed; t+1 and t+2 may still be in flight
-    else if (t + 1 < T) wait_vmcnt<4>();
-    else wait_vmcnt<0>();
-    __syncthreads();                         // visible to all waves; everyone is done with tile t-1's stage
-    if (t + 3 < T) issue(t + 3);
+  issue(0, 0);
+  issue(1, 0); issue(0, 1);
+  issue(2, 0); issue(1, 1);
+  wait_landed(-1);                           // K(0)
+  phase_barrier();
+  if (group == 1) phase_barrier();
+
+  f32x16 sc[2];
+  bf16x8 pb[2][2];
+  auto softmax_phase = [&](int t) {
     const bool in_b = t >= ta;
     const int64_t j0 = (int64_t)(in_b ? (t - ta) : t) * kPfTileRows;
     const int64_t n_seg = in_b ? a.nb : a.na;
@@ -466,8 +586,103 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
       const int64_t d = lim - j0;
       rel = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
     }
-    pf_compute_tile(lds + (t & (kPdStages - 1)) * kPfStageBytes, lc, qf, st, c, masked, rel, hl);
+    pf_softmax(sc, st, c, masked, rel, hl, pb);
+  };
+#ifdef HI_TIMERS
+  long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  long long tprev = __builtin_amdgcn_s_memtime();
+  const long long tstart = tprev;
+#define HI_TICK(i) { __builtin_amdgcn_sched_barrier(0); const long long tn_ = __builtin_amdgcn_s_memtime(); tm[i] += tn_ - tprev; tprev = tn_; __builtin_amdgcn_sched_barrier(0); }
+#else
+#define HI_TICK(i)
+#endif
+  // tile 0: nothing to accumulate yet
+  issue(3, 0);
+  issue(2, 1);
+  pf_scores(lds, lc, qf, sc);
+  wait_landed(0);
+  phase_barrier();
+  softmax_phase(0);
+  phase_barrier();
+  // any tile t >= 1
+  auto generic_tile = [&](int t) {
+    // K(t+3) and V(t+2): full tiles are issued from inside the matrix phase, partial ones (row clamping) here
+    PfPhaseLoads ld;
+    ld.k = ld.v = nullptr;
+    const int tk = t + 3, tv = t + 2;
+    const bool kb = tk >= ta, vb = tv >= ta;
+    const int64_t krow0 = (int64_t)(kb ? tk - ta : tk) * kPfTileRows, vrow0 = (int64_t)(vb ? tv - ta : tv) * kPfTileRows;
+    const bool kfull = tk < T && (kb ? a.nb : a.na) - krow0 >= kPfTileRows;
+    const bool vfull = tv < T && (vb ? a.nb : a.na) - vrow0 >= kPfTileRows;
+    if (kfull) ld.k = (kb ? a.kb : a.ka) + krow0 * kRowBytes; else issue(tk, 0);
+    if (vfull) ld.v = (vb ? a.vb : a.va) + vrow0 * kRowBytes; else issue(tv, 1);
+    ld.ldk = lds_base + (uint32_t)(tk & (kPdStages - 1)) * kPfStageBytes + wave * 2048;
+    ld.ldv = lds_base + (uint32_t)(tv & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes + wave * 2048;
+    pf_matrix_phase<false>(lds + ((t - 1) & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes,
+                           lds + (t & (kPdStages - 1)) * kPfStageBytes, lc, qf, pb, st, sc, ld);
+    wait_landed(t);
+    phase_barrier();
+    softmax_phase(t);
+    phase_barrier();
+  };
+  // Steady state: tile t of the past segment with K(t+3), V(t+2) full tiles of the same segment and nothing
+  // masked.  The stage t % 4 is a compile-time constant (every LDS address is an immediate) and the scalar work
+  // per tile is two pointer increments.
+  const char* kp = a.ka;     // K(t+3), V(t+2) of the next fast tile
+  const char* vp = a.va;
+  const uint32_t ld_wave = lds_base + wave * 2048;
+  auto fast_tile = [&](auto stage_tag) {
+    constexpr int S = decltype(stage_tag)::value;
+    PfPhaseLoads ld;
+    ld.k = kp;
+    ld.v = vp;
+    ld.ldk = ld_wave + ((S + 3) & 3) * kPfStageBytes;
+    ld.ldv = ld_wave + ((S + 2) & 3) * kPfStageBytes + kPfTileBytes;
+    HI_TICK(1)
+    pf_matrix_phase<true>(lds + ((S + 3) & 3) * kPfStageBytes + kPfTileBytes, lds + S * kPfStageBytes, lc, qf, pb, st,
+                          sc, ld);
+    HI_TICK(2)
+    wait_vmcnt<8>();
+    HI_TICK(3)
+    phase_barrier();
+    HI_TICK(4)
+    pf_softmax(sc, st, c, false, kPfTileRows, hl, pb);
+    HI_TICK(5)
+    phase_barrier();
+    HI_TICK(6)
+    kp += kPfTileBytes;
+    vp += kPfTileBytes;
+  };
+  const int t_fast = (int)(a.na / kPfTileRows) - 3;     // tiles [1, t_fast) qualify
+  int t = 1;
+  if (t_fast >= 8) {
+    for (; t < 4; ++t) generic_tile(t);
+    kp = a.ka + (int64_t)(t + 3) * kPfTileBytes;
+    vp = a.va + (int64_t)(t + 2) * kPfTileBytes;
+#ifdef HI_TIMERS
+    tprev = __builtin_amdgcn_s_memtime();
+#endif
+    for (; t + 4 <= t_fast; t += 4) {
+      fast_tile(std::integral_constant<int, 0>());
+      fast_tile(std::integral_constant<int, 1>());
+      fast_tile(std::integral_constant<int, 2>());
+      fast_tile(std::integral_constant<int, 3>());
+#ifdef HI_TIMERS
+      tm[7] += 4;
+#endif
+    }
   }
+  for (; t < T; ++t) generic_tile(t);
+#ifdef HI_TIMERS
+  if (lane == 0) {
+    long long* tp = (long long*)a.carry + (wg_linear * 8 + wave) * 8;
+    tp[0] = tprev - tstart;
+    for (int i = 1; i < 7; ++i) tp[i] = tm[i];
+    tp[7] = tm[7];
+  }
+#endif
+  pf_pv(lds + ((T - 1) & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes, lc, pb, st);
+  if (group == 0) phase_barrier();
 
   if (!a.last) {
 #pragma unroll
