@@ -145,10 +145,27 @@ __device__ __forceinline__ void pf_scores(lds_char* kt, const PfLaneConst& lc, c
   }
 }
 
+// Part q (0..15) of a tile's row sum, taken over the bf16-rounded probabilities the second product consumes:
+// l += pb[2q] + pb[2q+1], one dot-product instruction with fp32 accumulation.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+__device__ __forceinline__ void pf_row_sum(const bf16x8 (&pb)[2][2], int q, float& l) {
+  const bf16x8 x = pb[q >> 3][(q >> 2) & 1];
+  const int j = q & 3;
+  bf16x2 pr, one;
+  pr[0] = x[2 * j];
+  pr[1] = x[2 * j + 1];
+  one[0] = (__bf16)1.0f;
+  one[1] = (__bf16)1.0f;
+  l = __builtin_amdgcn_fdot2_f32_bf16(pr, one, l, false);
+}
+
 // Online softmax of one tile's scores: per lane = per query row; the other half-wave holds the other 32 rows of
 // the tile.  Updates (m, l), rescales O when the running maximum moved, and leaves the probabilities rounded to
 // bf16 in pb, laid out as the B operands of the second product.
 // mask_rel: rows of the tile with index > mask_rel are masked for this lane (>= 63 means no masking).
+// SUM: 1 = the row sum accumulates the fp32 probabilities; 2 = it accumulates the bf16-rounded ones (pf_row_sum:
+// half as many instructions); 0 = left to the caller.
+template <int SUM = 1>
 __device__ __forceinline__ void pf_softmax(f32x16 (&s)[2], PfState& st, float c, bool masked, int mask_rel, int hl,
                                            bf16x8 (&pb)[2][2]) {
   if (masked) {
@@ -178,17 +195,24 @@ __device__ __forceinline__ void pf_softmax(f32x16 (&s)[2], PfState& st, float c,
   }
   const float mc = st.m * c;
   float lsum = 0.f;
+  float lq[4] = {0.f, 0.f, 0.f, 0.f};     // SUM == 2: one short accumulation chain per group of 8 probabilities
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < 2; ++u) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const float p = fast_exp2(__builtin_fmaf(s[sb][8 * u + j], c, -mc));
-        lsum += p;
+        if (SUM == 1) lsum += p;
         pb[sb][u][j] = (__bf16)p;
       }
-  st.l += lsum;
+      if (SUM == 2) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) pf_row_sum(pb, 8 * sb + 4 * u + j, lq[2 * sb + u]);
+      }
+    }
+  if (SUM == 1) st.l += lsum;
+  if (SUM == 2) st.l += (lq[0] + lq[1]) + (lq[2] + lq[3]);
   // the conversions belong to this phase (the values are first used after the caller's barrier)
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
@@ -239,13 +263,22 @@ struct PfPhaseLoads {
   uint32_t ldk, ldv;  // LDS byte address of this wave's first destination row group in the K / V tile
 };
 
-template <bool LOADS_ALWAYS>
+// the first kPfAhead operands of a matrix phase (they are V^T fragments), read ahead of the phase
+__device__ __forceinline__ void pf_matrix_preread(lds_char* vt, const PfLaneConst& lc, bf16x8 (&pre)[kPfAhead]) {
+#pragma unroll
+  for (int i = 0; i < kPfAhead; ++i) pre[i] = pf_matrix_operand(i, vt, vt, lc);
+}
+
+// PREREAD: the caller has already read the first kPfAhead operands into pre (during its softmax phase).
+template <bool LOADS_ALWAYS, bool PREREAD>
 __device__ __forceinline__ void pf_matrix_phase(lds_char* vt, lds_char* kt, const PfLaneConst& lc,
                                                 const bf16x8 (&qf)[8], const bf16x8 (&pb)[2][2], PfState& st,
-                                                f32x16 (&s)[2], const PfPhaseLoads& ld) {
+                                                f32x16 (&s)[2], const PfPhaseLoads& ld,
+                                                const bf16x8 (&pre)[kPfAhead]) {
+  static_assert(kPfAhead <= 16, "pre-read operands are V fragments");
   bf16x8 op[kPfAhead + 1];
 #pragma unroll
-  for (int i = 0; i < kPfAhead; ++i) op[i] = pf_matrix_operand(i, vt, kt, lc);
+  for (int i = 0; i < kPfAhead; ++i) op[i] = PREREAD ? pre[i] : pf_matrix_operand(i, vt, kt, lc);
 #pragma unroll
   for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
   __builtin_amdgcn_sched_barrier(0);
@@ -538,10 +571,10 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     else pf_issue_v<kPdWaves>((in_b ? a.vb : a.va) + row0 * kRowBytes, rows, stage + kPfTileBytes, wave, lane, lc);
   };
   // Every wave issues, in this order: K0 | K1 V0 | K2 V1 | then, in the matrix phase of tile t, K(t+3) V(t+2)
-  // (2 instructions each).  "K(t+1) and V(t) have landed" therefore means: at most the last two pairs are still
-  // in flight, when both pairs exist in full.
+  // (2 instructions each).  The one wait per tile is at the end of the softmax phase of tile t: everything up to
+  // V(t+1) has landed when at most K(t+3) V(t+2) are still in flight.
   auto wait_landed = [&](int t) {
-    if (t + 3 < T) wait_vmcnt<8>();
+    if (t + 3 < T) wait_vmcnt<4>();
     else wait_vmcnt<0>();
   };
   auto phase_barrier = [&]() {
@@ -555,20 +588,17 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   // program with two barriers per tile; group 1 passes one extra barrier first, so it is always one phase behind
   // (and group 0 passes one extra at the end: every wave executes the same number of barriers).
   //   phase index (barriers passed so far):  group 0: matrix(t) = 2t, softmax(t) = 2t + 1;  group 1: one later.
-  //   K(t) is read in phases 2t, 2t+1; V(t) in phases 2t+2, 2t+3.  K(t+3) replaces K(t-1) (last read in phase
-  //   2t-1) and V(t+2) replaces V(t-2) (last read in phase 2t-1): both are issued in matrix(t), phase >= 2t.
-  //   Each wave waits for its share of K(t+1) and V(t) at the end of matrix(t): before the barrier that ends
-  //   phase 2t+1 at the latest, and K(t+1) is first read in phase 2t+2, V(t) in phase 2t+2.
-#ifdef HI_PP_GROUP_LOW
-  const int group = wave & 1;
-#else
+  //   Reads: K(t) in phases 2t, 2t+1; V(t) in phases 2t+1 (operands read ahead during softmax(t)) .. 2t+3.
+  //   Writes: K(t+3) replaces K(t-1) (last read in phase 2t-1) and V(t+2) replaces V(t-2) (last read in phase
+  //   2t-1): both are issued in matrix(t), phase >= 2t.
+  //   Landing: each wave waits at the end of softmax(t-1) for its share of everything up to V(t): that is phase
+  //   2t at the latest, and K(t+1) is first read in phase 2t+2, V(t) in phase 2t+1.
   const int group = wave >> 2;
-#endif
   const float c = a.c;
   issue(0, 0);
   issue(1, 0); issue(0, 1);
   issue(2, 0); issue(1, 1);
-  wait_landed(-1);                           // K(0)
+  wait_landed(-1);                           // K(0), K(1), V(0)
   phase_barrier();
   if (group == 1) phase_barrier();
 
@@ -586,7 +616,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
       const int64_t d = lim - j0;
       rel = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
     }
-    pf_softmax(sc, st, c, masked, rel, hl, pb);
+    pf_softmax<2>(sc, st, c, masked, rel, hl, pb);
   };
 #ifdef HI_TIMERS
   long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -600,10 +630,11 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   issue(3, 0);
   issue(2, 1);
   pf_scores(lds, lc, qf, sc);
-  wait_landed(0);
   phase_barrier();
   softmax_phase(0);
+  wait_landed(0);
   phase_barrier();
+  bf16x8 pre[kPfAhead];
   // any tile t >= 1
   auto generic_tile = [&](int t) {
     // K(t+3) and V(t+2): full tiles are issued from inside the matrix phase, partial ones (row clamping) here
@@ -618,11 +649,11 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     if (vfull) ld.v = (vb ? a.vb : a.va) + vrow0 * kRowBytes; else issue(tv, 1);
     ld.ldk = lds_base + (uint32_t)(tk & (kPdStages - 1)) * kPfStageBytes + wave * 2048;
     ld.ldv = lds_base + (uint32_t)(tv & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes + wave * 2048;
-    pf_matrix_phase<false>(lds + ((t - 1) & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes,
-                           lds + (t & (kPdStages - 1)) * kPfStageBytes, lc, qf, pb, st, sc, ld);
-    wait_landed(t);
+    pf_matrix_phase<false, false>(lds + ((t - 1) & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes,
+                                  lds + (t & (kPdStages - 1)) * kPfStageBytes, lc, qf, pb, st, sc, ld, pre);
     phase_barrier();
     softmax_phase(t);
+    wait_landed(t);
     phase_barrier();
   };
   // Steady state: tile t of the past segment with K(t+3), V(t+2) full tiles of the same segment and nothing
@@ -639,15 +670,19 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     ld.ldk = ld_wave + ((S + 3) & 3) * kPfStageBytes;
     ld.ldv = ld_wave + ((S + 2) & 3) * kPfStageBytes + kPfTileBytes;
     HI_TICK(1)
-    pf_matrix_phase<true>(lds + ((S + 3) & 3) * kPfStageBytes + kPfTileBytes, lds + S * kPfStageBytes, lc, qf, pb, st,
-                          sc, ld);
+    __builtin_amdgcn_s_setprio(2);
+    pf_matrix_phase<true, true>(lds + ((S + 3) & 3) * kPfStageBytes + kPfTileBytes, lds + S * kPfStageBytes, lc, qf,
+                                pb, st, sc, ld, pre);
+    __builtin_amdgcn_s_setprio(0);
     HI_TICK(2)
-    wait_vmcnt<8>();
-    HI_TICK(3)
     phase_barrier();
     HI_TICK(4)
-    pf_softmax(sc, st, c, false, kPfTileRows, hl, pb);
+    pf_matrix_preread(lds + S * kPfStageBytes + kPfTileBytes, lc, pre);     // V(t), for the next matrix phase
+    __builtin_amdgcn_sched_barrier(0);
+    pf_softmax<2>(sc, st, c, false, kPfTileRows, hl, pb);
     HI_TICK(5)
+    wait_vmcnt<4>();
+    HI_TICK(3)
     phase_barrier();
     HI_TICK(6)
     kp += kPfTileBytes;
@@ -659,6 +694,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     for (; t < 4; ++t) generic_tile(t);
     kp = a.ka + (int64_t)(t + 3) * kPfTileBytes;
     vp = a.va + (int64_t)(t + 2) * kPfTileBytes;
+    pf_matrix_preread(lds + ((t - 1) & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes, lc, pre);
 #ifdef HI_TIMERS
     tprev = __builtin_amdgcn_s_memtime();
 #endif
