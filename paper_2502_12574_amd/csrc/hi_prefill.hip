@@ -145,27 +145,10 @@ __device__ __forceinline__ void pf_scores(lds_char* kt, const PfLaneConst& lc, c
   }
 }
 
-// Part q (0..15) of a tile's row sum, taken over the bf16-rounded probabilities the second product consumes:
-// l += pb[2q] + pb[2q+1], one dot-product instruction with fp32 accumulation.
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-__device__ __forceinline__ void pf_row_sum(const bf16x8 (&pb)[2][2], int q, float& l) {
-  const bf16x8 x = pb[q >> 3][(q >> 2) & 1];
-  const int j = q & 3;
-  bf16x2 pr, one;
-  pr[0] = x[2 * j];
-  pr[1] = x[2 * j + 1];
-  one[0] = (__bf16)1.0f;
-  one[1] = (__bf16)1.0f;
-  l = __builtin_amdgcn_fdot2_f32_bf16(pr, one, l, false);
-}
-
 // Online softmax of one tile's scores: per lane = per query row; the other half-wave holds the other 32 rows of
 // the tile.  Updates (m, l), rescales O when the running maximum moved, and leaves the probabilities rounded to
 // bf16 in pb, laid out as the B operands of the second product.
 // mask_rel: rows of the tile with index > mask_rel are masked for this lane (>= 63 means no masking).
-// SUM: 1 = the row sum accumulates the fp32 probabilities; 2 = it accumulates the bf16-rounded ones (pf_row_sum:
-// half as many instructions); 0 = left to the caller.
-template <int SUM = 1>
 __device__ __forceinline__ void pf_softmax(f32x16 (&s)[2], PfState& st, float c, bool masked, int mask_rel, int hl,
                                            bf16x8 (&pb)[2][2]) {
   if (masked) {
@@ -195,25 +178,67 @@ __device__ __forceinline__ void pf_softmax(f32x16 (&s)[2], PfState& st, float c,
   }
   const float mc = st.m * c;
   float lsum = 0.f;
-  float lq[4] = {0.f, 0.f, 0.f, 0.f};     // SUM == 2: one short accumulation chain per group of 8 probabilities
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const float p = fast_exp2(__builtin_fmaf(s[sb][8 * u + j], c, -mc));
-        if (SUM == 1) lsum += p;
+        lsum += p;
         pb[sb][u][j] = (__bf16)p;
       }
-      if (SUM == 2) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) pf_row_sum(pb, 8 * sb + 4 * u + j, lq[2 * sb + u]);
-      }
-    }
-  if (SUM == 1) st.l += lsum;
-  if (SUM == 2) st.l += (lq[0] + lq[1]) + (lq[2] + lq[3]);
+  st.l += lsum;
   // the conversions belong to this phase (the values are first used after the caller's barrier)
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(pb[sb][u]));
+}
+
+// Softmax phase of a steady-state tile whose scores left the matrix pipe as s - m (relative to the running
+// reference m of the row: the score accumulators start from negm = -m instead of zero), so p = 2^(c (s - m)) is
+// one multiplication and one exponential.  The reference only moves when a score exceeds it by more than
+// kPfSlack in the exponent (p <= 2^kPfSlack is as harmless as p <= 1 in fp32 and bf16, and it makes the
+// rescaling - O, l, this tile's scores and negm, all in place - a rare event instead of a per-tile one).
+constexpr float kPfSlack = 12.0f;
+
+__device__ __forceinline__ void pf_softmax_fast(f32x16 (&s)[2], PfState& st, float c, f32x16& negm,
+                                                bf16x8 (&pb)[2][2]) {
+  float mx = s[0][0];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
+  mx = max_halves(mx);
+  if (__builtin_amdgcn_ballot_w64(mx * c > kPfSlack) != 0) {
+    const float d = fmaxf(mx, 0.f);       // lanes whose maximum did not move keep their reference
+    const float alpha = fast_exp2(-d * c);
+    st.l *= alpha;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[sb][r] -= d;
+    st.m += d;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[r] = -st.m;
+  }
+  float lq[4] = {0.f, 0.f, 0.f, 0.f};     // four short accumulation chains
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float p = fast_exp2(s[sb][8 * u + j] * c);
+        lq[2 * sb + u] += p;
+        pb[sb][u][j] = (__bf16)p;
+      }
+  st.l += (lq[0] + lq[1]) + (lq[2] + lq[3]);
 #pragma unroll
   for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -237,26 +262,37 @@ __device__ __forceinline__ void pf_pv(lds_char* vt, const PfLaneConst& lc, const
     }
 }
 
-// Matrix phase of the alternating schedule: O^T += V^T P^T of the previous tile (V tile at vt, probabilities
-// pb), then S^T = K Q^T of the next (K tile at kt), as ONE software-pipelined sequence of 32 MFMAs whose LDS
-// operand reads run kPfAhead steps ahead of their use: a wavefront that has the matrix pipe to itself must hide
-// the LDS latency on its own.
-constexpr int kPfAhead = 5;
+// ---- helpers of the 8-wave kernel.  Its LDS holds a ring of K tiles at [0, 64 KiB) and a ring of V tiles at
+// [64 KiB, 128 KiB); the lane constants koff / voff are absolute LDS byte addresses (voff includes the V ring's
+// base), so that with a compile-time ring slot every operand read is "register + immediate" (the immediate of an
+// LDS instruction reaches 64 KiB).
+constexpr int kPdWaves = 8;
+constexpr int kPdStages = 4;
+constexpr uint32_t kPdVRing = 65536;
+constexpr int kPdLdsBytes = 2 * kPdStages * kPfTileBytes;   // 128 KiB
 
-__device__ __forceinline__ bf16x8 pf_matrix_operand(int i, lds_char* vt, lds_char* kt, const PfLaneConst& lc) {
-  if (i < 16) {     // V^T fragment of step (sb, u, db)
+// Matrix phase of the alternating schedule: O^T += V^T P^T of the previous tile (V tile at ring offset v_off,
+// probabilities pb), then S^T = K Q^T of the next (K tile at ring offset k_off), as ONE software-pipelined
+// sequence of 32 MFMAs whose LDS operand reads run kPfAhead steps ahead of their use: a wavefront that has the
+// matrix pipe to itself must hide the LDS latency on its own.  Operand i < 16 is the V^T fragment of step
+// (sb, u, db) = (i / 8, i / 4 % 2, i % 4); operand 16 + j is the K fragment of step (kk, sb) = (j / 2, j % 2).
+constexpr int kPfAhead = 4;
+
+__device__ __forceinline__ bf16x8 pd_operand(int i, uint32_t v_off, uint32_t k_off, const PfLaneConst& lc) {
+  if (i < 16) {
     const int sb = i >> 3, u = (i >> 2) & 1, db = i & 3;
-    const bf16x4 v0 = lds_read_tr8(vt + lc.voff[db] + sb * 8192 + u * 4096);
-    const bf16x4 v1 = lds_read_tr8(vt + lc.voff[db] + sb * 8192 + u * 4096 + 2048);
+    const uint32_t ad = lc.voff[db] + v_off + sb * 8192 + u * 4096;
+    const bf16x4 v0 = lds_read_tr8((lds_char*)(uintptr_t)ad);
+    const bf16x4 v1 = lds_read_tr8((lds_char*)(uintptr_t)(ad + 2048));
     return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
   }
-  const int kk = (i - 16) >> 1, sb = (i - 16) & 1;   // K fragment of step (kk, sb)
-  return *(lds_bf16x8*)(kt + lc.koff[kk] + sb * 8192);
+  const int kk = (i - 16) >> 1, sb = (i - 16) & 1;
+  return *(lds_bf16x8*)(uintptr_t)(lc.koff[kk] + k_off + sb * 8192);
 }
 
-// The tile loads a wavefront of the 8-wave kernel issues while it runs a matrix phase: its two K and two V
-// instructions (full tiles only; k / v are null otherwise) ride in the gaps between the first MFMAs, where
-// their scalar set-up and the issue itself cost next to nothing.
+// The tile loads a wavefront issues while it runs a matrix phase: its two K and two V instructions (full tiles
+// only; k / v are null otherwise) ride in the gaps between the first MFMAs, where their scalar set-up and the
+// issue itself cost next to nothing.
 struct PfPhaseLoads {
   const char* k;      // K tile base (global), null: nothing to issue
   const char* v;      // V tile base
@@ -264,34 +300,38 @@ struct PfPhaseLoads {
 };
 
 // the first kPfAhead operands of a matrix phase (they are V^T fragments), read ahead of the phase
-__device__ __forceinline__ void pf_matrix_preread(lds_char* vt, const PfLaneConst& lc, bf16x8 (&pre)[kPfAhead]) {
+__device__ __forceinline__ void pd_preread(uint32_t v_off, const PfLaneConst& lc, bf16x8 (&pre)[kPfAhead]) {
 #pragma unroll
-  for (int i = 0; i < kPfAhead; ++i) pre[i] = pf_matrix_operand(i, vt, vt, lc);
+  for (int i = 0; i < kPfAhead; ++i) pre[i] = pd_operand(i, v_off, 0, lc);
 }
 
 // PREREAD: the caller has already read the first kPfAhead operands into pre (during its softmax phase).
-template <bool LOADS_ALWAYS, bool PREREAD>
-__device__ __forceinline__ void pf_matrix_phase(lds_char* vt, lds_char* kt, const PfLaneConst& lc,
+// CINIT: the score accumulators start from cinit (minus the row's running reference) instead of zero.
+template <bool LOADS_ALWAYS, bool PREREAD, bool CINIT>
+__device__ __forceinline__ void pd_matrix_phase(uint32_t v_off, uint32_t k_off, const PfLaneConst& lc,
                                                 const bf16x8 (&qf)[8], const bf16x8 (&pb)[2][2], PfState& st,
                                                 f32x16 (&s)[2], const PfPhaseLoads& ld,
-                                                const bf16x8 (&pre)[kPfAhead]) {
+                                                const bf16x8 (&pre)[kPfAhead], const f32x16& cinit) {
   static_assert(kPfAhead <= 16, "pre-read operands are V fragments");
   bf16x8 op[kPfAhead + 1];
 #pragma unroll
-  for (int i = 0; i < kPfAhead; ++i) op[i] = PREREAD ? pre[i] : pf_matrix_operand(i, vt, kt, lc);
+  for (int i = 0; i < kPfAhead; ++i) op[i] = PREREAD ? pre[i] : pd_operand(i, v_off, k_off, lc);
+  if (!CINIT) {
 #pragma unroll
-  for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
+    for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
+  }
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < 32; ++i) {
-    if (i + kPfAhead < 32) op[(i + kPfAhead) % (kPfAhead + 1)] = pf_matrix_operand(i + kPfAhead, vt, kt, lc);
+    if (i + kPfAhead < 32) op[(i + kPfAhead) % (kPfAhead + 1)] = pd_operand(i + kPfAhead, v_off, k_off, lc);
     const bf16x8 x = op[i % (kPfAhead + 1)];
     if (i < 16) {
       const int sb = i >> 3, u = (i >> 2) & 1, db = i & 3;
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, pb[sb][u], st.o[db], 0, 0, 0);
     } else {
       const int kk = (i - 16) >> 1, sb = (i - 16) & 1;
-      s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qf[kk], s[sb], 0, 0, 0);
+      if (CINIT && kk == 0) s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qf[kk], cinit, 0, 0, 0);
+      else s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qf[kk], s[sb], 0, 0, 0);
     }
     if (i == 1 && (LOADS_ALWAYS || ld.k)) g2lds16_s<0>(ld.k, lc.gk[0], ld.ldk);
     if (i == 3 && (LOADS_ALWAYS || ld.k)) g2lds16_s<0>(ld.k, lc.gk[1], ld.ldk + 1024);
@@ -472,15 +512,10 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Deep variant of the narrow kernel: 8 wavefronts per workgroup (two per SIMD, 32 positions each: the G query
-// heads at 64 positions for G = 4), one workgroup per compute unit, and FOUR LDS stages, so three tiles are in
-// flight while one is consumed (the two-stage kernel has one) and every K/V byte pulled from L2 serves 256 query
-// rows.  Same per-wave arithmetic as the narrow kernel (pf_compute_tile); used for chunks long enough to give
-// every compute unit a workgroup.
-constexpr int kPdWaves = 8;
-constexpr int kPdStages = 4;
-constexpr int kPdLdsBytes = kPdStages * kPfStageBytes;   // 128 KiB
-
+// The 8-wave kernel: 8 wavefronts per workgroup (two per SIMD, 32 positions each: the G query heads at 64
+// positions for G = 4), one workgroup per compute unit, four K and four V tiles in LDS, every K/V byte pulled
+// from L2 serves 256 query rows.  The two wavefronts of a SIMD alternate between a matrix phase and a softmax
+// phase (see the schedule below); used for chunks long enough to give every compute unit a workgroup.
 __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char lds_dyn[];
   lds_char* lds = (lds_char*)lds_dyn;
@@ -512,16 +547,19 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     const int r0 = wave * 8 + r_in;
     lc.gv = (uint32_t)(r0 * kRowBytes + ((cpos ^ swz_v(r0)) << 4));
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) lc.koff[kk] = (uint32_t)(col * kRowBytes + (((2 * kk + hl) ^ swz_k(col)) << 4));
+    for (int kk = 0; kk < 8; ++kk)
+      lc.koff[kk] = lds_base + (uint32_t)(col * kRowBytes + (((2 * kk + hl) ^ swz_k(col)) << 4));
     const int s16 = lane & 15, q16 = col >> 4;
     const int row_lo = 4 * hl + (s16 >> 2);
 #pragma unroll
     for (int db = 0; db < 4; ++db) {
       const int chunk = 4 * db + 2 * q16 + ((s16 & 3) >> 1);
-      lc.voff[db] = (uint32_t)(row_lo * kRowBytes + ((chunk ^ swz_v(row_lo)) << 4) + ((s16 & 1) << 3));
+      lc.voff[db] = lds_base + kPdVRing +
+                    (uint32_t)(row_lo * kRowBytes + ((chunk ^ swz_v(row_lo)) << 4) + ((s16 & 1) << 3));
     }
   }
 
+  // Q^T operand: lane holds q[g][qi][16*kk + 8*hl .. +7]
   bf16x8 qf[8];
   {
     const uint16_t* qrow = a.q + ((int64_t)g * a.C + qi) * kHeadDim + 8 * hl;
@@ -560,15 +598,15 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   const int T = ta + tb;
 
   // K tile t (which = 0) or V tile t (which = 1) of the sweep: this wave's share of its loads
-  auto issue = [&](int t, int which) {
+  auto issue = [&](int t, int which) __attribute__((always_inline)) {
     if (t >= T) return;
     const bool in_b = t >= ta;
     const int64_t row0 = (int64_t)(in_b ? t - ta : t) * kPfTileRows;
     const int64_t left = (in_b ? a.nb : a.na) - row0;
     const int rows = left < kPfTileRows ? (int)left : kPfTileRows;
-    const uint32_t stage = lds_base + (uint32_t)(t & (kPdStages - 1)) * kPfStageBytes;
-    if (which == 0) pf_issue_k<kPdWaves>((in_b ? a.kb : a.ka) + row0 * kRowBytes, rows, stage, wave, lane, lc);
-    else pf_issue_v<kPdWaves>((in_b ? a.vb : a.va) + row0 * kRowBytes, rows, stage + kPfTileBytes, wave, lane, lc);
+    const uint32_t slot = lds_base + (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes;
+    if (which == 0) pf_issue_k<kPdWaves>((in_b ? a.kb : a.ka) + row0 * kRowBytes, rows, slot, wave, lane, lc);
+    else pf_issue_v<kPdWaves>((in_b ? a.vb : a.va) + row0 * kRowBytes, rows, slot + kPdVRing, wave, lane, lc);
   };
   // Every wave issues, in this order: K0 | K1 V0 | K2 V1 | then, in the matrix phase of tile t, K(t+3) V(t+2)
   // (2 instructions each).  The one wait per tile is at the end of the softmax phase of tile t: everything up to
@@ -593,7 +631,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   //   2t-1): both are issued in matrix(t), phase >= 2t.
   //   Landing: each wave waits at the end of softmax(t-1) for its share of everything up to V(t): that is phase
   //   2t at the latest, and K(t+1) is first read in phase 2t+2, V(t) in phase 2t+1.
-  const int group = wave >> 2;
+  const int group = wave >> 2;       // waves w and w + 4 share a SIMD
   const float c = a.c;
   issue(0, 0);
   issue(1, 0); issue(0, 1);
@@ -604,7 +642,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
 
   f32x16 sc[2];
   bf16x8 pb[2][2];
-  auto softmax_phase = [&](int t) {
+  auto softmax_phase = [&](int t) __attribute__((always_inline)) {
     const bool in_b = t >= ta;
     const int64_t j0 = (int64_t)(in_b ? (t - ta) : t) * kPfTileRows;
     const int64_t n_seg = in_b ? a.nb : a.na;
@@ -616,27 +654,26 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
       const int64_t d = lim - j0;
       rel = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
     }
-    pf_softmax<2>(sc, st, c, masked, rel, hl, pb);
+    pf_softmax(sc, st, c, masked, rel, hl, pb);
   };
-#ifdef HI_TIMERS
-  long long tm[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  long long tprev = __builtin_amdgcn_s_memtime();
-  const long long tstart = tprev;
-#define HI_TICK(i) { __builtin_amdgcn_sched_barrier(0); const long long tn_ = __builtin_amdgcn_s_memtime(); tm[i] += tn_ - tprev; tprev = tn_; __builtin_amdgcn_sched_barrier(0); }
-#else
-#define HI_TICK(i)
-#endif
   // tile 0: nothing to accumulate yet
   issue(3, 0);
   issue(2, 1);
-  pf_scores(lds, lc, qf, sc);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { sc[0][r] = 0.f; sc[1][r] = 0.f; }
+#pragma unroll
+  for (int i = 16; i < 32; ++i)
+    sc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, 0, 0, lc), qf[(i - 16) >> 1], sc[i & 1], 0, 0, 0);
   phase_barrier();
   softmax_phase(0);
   wait_landed(0);
   phase_barrier();
   bf16x8 pre[kPfAhead];
+  f32x16 negm;       // minus the row's running reference, the start value of the steady-state score accumulators
+#pragma unroll
+  for (int r = 0; r < 16; ++r) negm[r] = 0.f;
   // any tile t >= 1
-  auto generic_tile = [&](int t) {
+  auto generic_tile = [&](int t) __attribute__((always_inline)) {
     // K(t+3) and V(t+2): full tiles are issued from inside the matrix phase, partial ones (row clamping) here
     PfPhaseLoads ld;
     ld.k = ld.v = nullptr;
@@ -647,10 +684,11 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     const bool vfull = tv < T && (vb ? a.nb : a.na) - vrow0 >= kPfTileRows;
     if (kfull) ld.k = (kb ? a.kb : a.ka) + krow0 * kRowBytes; else issue(tk, 0);
     if (vfull) ld.v = (vb ? a.vb : a.va) + vrow0 * kRowBytes; else issue(tv, 1);
-    ld.ldk = lds_base + (uint32_t)(tk & (kPdStages - 1)) * kPfStageBytes + wave * 2048;
-    ld.ldv = lds_base + (uint32_t)(tv & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes + wave * 2048;
-    pf_matrix_phase<false, false>(lds + ((t - 1) & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes,
-                                  lds + (t & (kPdStages - 1)) * kPfStageBytes, lc, qf, pb, st, sc, ld, pre);
+    ld.ldk = lds_base + (uint32_t)(tk & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
+    ld.ldv = lds_base + kPdVRing + (uint32_t)(tv & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
+    pd_matrix_phase<false, false, false>((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes,
+                                         (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes, lc, qf, pb, st, sc, ld, pre,
+                                         negm);
     phase_barrier();
     softmax_phase(t);
     wait_landed(t);
@@ -662,29 +700,23 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   const char* kp = a.ka;     // K(t+3), V(t+2) of the next fast tile
   const char* vp = a.va;
   const uint32_t ld_wave = lds_base + wave * 2048;
-  auto fast_tile = [&](auto stage_tag) {
+  auto fast_tile = [&](auto stage_tag) __attribute__((always_inline)) {
     constexpr int S = decltype(stage_tag)::value;
     PfPhaseLoads ld;
     ld.k = kp;
     ld.v = vp;
-    ld.ldk = ld_wave + ((S + 3) & 3) * kPfStageBytes;
-    ld.ldv = ld_wave + ((S + 2) & 3) * kPfStageBytes + kPfTileBytes;
-    HI_TICK(1)
+    ld.ldk = ld_wave + ((S + 3) & 3) * kPfTileBytes;
+    ld.ldv = ld_wave + kPdVRing + ((S + 2) & 3) * kPfTileBytes;
     __builtin_amdgcn_s_setprio(2);
-    pf_matrix_phase<true, true>(lds + ((S + 3) & 3) * kPfStageBytes + kPfTileBytes, lds + S * kPfStageBytes, lc, qf,
-                                pb, st, sc, ld, pre);
+    pd_matrix_phase<true, true, true>(((S + 3) & 3) * kPfTileBytes, S * kPfTileBytes, lc, qf, pb, st, sc, ld, pre,
+                                      negm);
     __builtin_amdgcn_s_setprio(0);
-    HI_TICK(2)
     phase_barrier();
-    HI_TICK(4)
-    pf_matrix_preread(lds + S * kPfStageBytes + kPfTileBytes, lc, pre);     // V(t), for the next matrix phase
+    pd_preread(S * kPfTileBytes, lc, pre);     // V(t), for the next matrix phase
     __builtin_amdgcn_sched_barrier(0);
-    pf_softmax<2>(sc, st, c, false, kPfTileRows, hl, pb);
-    HI_TICK(5)
+    pf_softmax_fast(sc, st, c, negm, pb);
     wait_vmcnt<4>();
-    HI_TICK(3)
     phase_barrier();
-    HI_TICK(6)
     kp += kPfTileBytes;
     vp += kPfTileBytes;
   };
@@ -694,30 +726,24 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     for (; t < 4; ++t) generic_tile(t);
     kp = a.ka + (int64_t)(t + 3) * kPfTileBytes;
     vp = a.va + (int64_t)(t + 2) * kPfTileBytes;
-    pf_matrix_preread(lds + ((t - 1) & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes, lc, pre);
-#ifdef HI_TIMERS
-    tprev = __builtin_amdgcn_s_memtime();
-#endif
+    pd_preread((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes, lc, pre);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[r] = -st.m;
     for (; t + 4 <= t_fast; t += 4) {
       fast_tile(std::integral_constant<int, 0>());
       fast_tile(std::integral_constant<int, 1>());
       fast_tile(std::integral_constant<int, 2>());
       fast_tile(std::integral_constant<int, 3>());
-#ifdef HI_TIMERS
-      tm[7] += 4;
-#endif
     }
   }
   for (; t < T; ++t) generic_tile(t);
-#ifdef HI_TIMERS
-  if (lane == 0) {
-    long long* tp = (long long*)a.carry + (wg_linear * 8 + wave) * 8;
-    tp[0] = tprev - tstart;
-    for (int i = 1; i < 7; ++i) tp[i] = tm[i];
-    tp[7] = tm[7];
+  {
+    const uint32_t v_off = (uint32_t)((T - 1) & (kPdStages - 1)) * kPfTileBytes;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      st.o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, v_off, 0, lc), pb[i >> 3][(i >> 2) & 1],
+                                                            st.o[i & 3], 0, 0, 0);
   }
-#endif
-  pf_pv(lds + ((T - 1) & (kPdStages - 1)) * kPfStageBytes + kPfTileBytes, lc, pb, st);
   if (group == 0) phase_barrier();
 
   if (!a.last) {
