@@ -35,7 +35,7 @@ PEAK_LINK_GBPS = 64.0         # PCIe Gen5 x16, one direction
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/*_pmc.md), each scaled by
 # what the same counter read for a 1 GiB copy kernel in the same run: a prefill launch over one 131072-row
 # staging slice with chunk 16384, and the resident decode launch over 1M rows (reads each K/V byte once).
-PREFILL_TRAFFIC_PER_LAUNCH = 1.05 * 2 ** 30 + 16 * 2 ** 20
+PREFILL_TRAFFIC_PER_LAUNCH = 591.5 * 2 ** 20 + 16 * 2 ** 20
 DECODE_TRAFFIC_PER_ROW = 512.0
 
 
@@ -216,7 +216,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS,
                      "traffic": PREFILL_TRAFFIC_PER_LAUNCH if (S, C) == (1 << 20, 16384) else None,
-                     "kernel": "prefill_kernel",
+                     "kernel": "prefill_kernel_deep",
                      "launches_per_step": n_pre_k / K, "avg_launch_ms": kern_pre_ms / max(n_pre_k, 1),
                      "flops_per_launch": flops / (n_pre_k / K),
                      "wall_TFLOPs": flops / prefill_s / 1e12},
