@@ -9,12 +9,17 @@
 //     lane holds are already laid out as the B operand of the second product O^T += V^T P^T once rounded to
 //     bf16 - no cross-lane shuffles between the two contractions.
 //   * The V^T operand comes from LDS transpose reads (ds_read_b64_tr_b16) of the row-major V tile.
-//   * K/V tiles of 64 rows go HBM -> LDS by direct-to-LDS 128-bit loads, double buffered, swizzled for
-//     conflict-free operand reads; one workgroup barrier per tile.
-//   * A workgroup is 4 wavefronts = the G query heads at the same 32 positions (for G = 4), so all waves share
-//     the causal boundary and sweep the same K/V tiles: 128 query rows per K/V byte fetched from L2.
+//   * K/V tiles of 64 rows go HBM -> LDS by direct-to-LDS 128-bit loads, swizzled for conflict-free operand
+//     reads.
+//   * The G query heads at the same positions share a workgroup (for G = 4), so all its waves share the causal
+//     boundary and sweep the same K/V tiles.
 //   * Workgroups of a unit sweep the K/V rows in near lock-step, so each tile is pulled from HBM about once per
 //     XCD and served to the other compute units from that XCD's L2.
+//
+// Three kernels share this arithmetic: prefill_kernel (4 waves, 2 LDS stages, two workgroups per compute unit, one
+// barrier per tile: short chunks), prefill_kernel_deep (8 waves, one workgroup per compute unit, the two waves of
+// a SIMD alternating between a matrix phase and a softmax phase: long chunks, the fast one) and
+// prefill_kernel_wide (64 positions per wave; on request only).
 //
 // The softmax state (m, l, O) can be carried across launches (one launch per staging slice) in a register-image
 // workspace, which is how a unit is computed while later slices of its past are still on the host link.
