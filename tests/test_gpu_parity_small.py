@@ -90,7 +90,8 @@ def test_offloaded_equals_resident_bitwise_for_prefill():
     assert (a[1] - b[1]).abs().max() < 1e-5      # decode partitions differ between the two modes
 
 
-def one_unit(G, P, C, seed, out_fp32=1, mode=hb.HI_MODE_RESIDENT, peaked=False, flags=0):
+def one_unit(G, P, C, seed, out_fp32=1, mode=hb.HI_MODE_RESIDENT, peaked=False, flags=0, k_row_scale=None):
+    """k_row_scale: optional fp32 tensor [P + C], key row t is multiplied by k_row_scale[t] (and rounded to bf16)."""
     dev = "cuda:0"
     with Session(1, 1, G, max(P + C, 128), max(C, 1), mode=mode, out_fp32=out_fp32) as ss:
         if flags:
@@ -98,6 +99,8 @@ def one_unit(G, P, C, seed, out_fp32=1, mode=hb.HI_MODE_RESIDENT, peaked=False, 
         with torch.cuda.stream(ss.s_compute):
             Q = torch.stack([synth.draw_q(seed, 0, g, P, C, device=dev) for g in range(G)])
             K = synth.draw_k(seed, 0, 0, 0, P + C, device=dev, peaked=peaked)
+            if k_row_scale is not None:
+                K = (K.float() * k_row_scale.to(dev)[:, None]).to(torch.bfloat16)
             V = synth.draw_v(seed, 0, 0, 0, P + C, device=dev)
             cv = ss.cache_view()
             if P:
@@ -132,6 +135,40 @@ def test_prefill_other_kernel_variants_ragged_shapes(G, P, C, mode, variant):
     ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
     for g in range(G):
         check(out[g:g + 1], ref[g:g + 1], f"{variant} G={G} P={P} C={C} head {g}")
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
+@pytest.mark.parametrize("G,P,C", [(4, 8000, 192), (4, 7003, 70), (2, 6500, 260), (8, 6160, 64)])
+def test_prefill_8wave_kernel_steady_state(G, P, C, mode):
+    # pasts long enough that the 8-wave kernel runs its unrolled steady-state loop (at least 11 full tiles per
+    # launch: in offload mode the staging slices of these shapes hold 768-1024 rows, so it is entered in every
+    # launch and the state crosses launches), with ragged ends on both segments
+    out, Q, K, V = one_unit(G, P, C, seed=4100 + P + C, mode=mode, flags=hb.HI_FLAG_PREFILL_DEEP)
+    ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
+    for g in range(G):
+        check(out[g:g + 1], ref[g:g + 1], f"8-wave G={G} P={P} C={C} head {g}")
+
+
+@pytest.mark.parametrize("shape", ["rising", "falling", "spikes"])
+@pytest.mark.parametrize("variant", ["deep", "narrow"])
+def test_prefill_running_reference_moves(shape, variant):
+    # key magnitudes that keep moving the rows' running maxima: rising along the sequence (the steady-state loop of
+    # the 8-wave kernel must rescale in place again and again), falling (later probabilities underflow against an
+    # early reference), and isolated rows scaled x8 deep inside the past
+    G, P, C = 4, 4096, 128
+    t = torch.arange(P + C, dtype=torch.float32)
+    if shape == "rising":
+        sc = 1.0 + 5.0 * t / (P + C)
+    elif shape == "falling":
+        sc = 6.0 - 5.0 * t / (P + C)
+    else:
+        sc = torch.ones(P + C)
+        sc[torch.tensor([700, 1501, 2302, 3103, 3904])] = 8.0
+    flag = hb.HI_FLAG_PREFILL_DEEP if variant == "deep" else hb.HI_FLAG_PREFILL_NARROW
+    out, Q, K, V = one_unit(G, P, C, seed=5200, flags=flag, k_row_scale=sc)
+    ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
+    for g in range(G):
+        check(out[g:g + 1], ref[g:g + 1], f"{variant} {shape} head {g}")
 
 
 @pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
