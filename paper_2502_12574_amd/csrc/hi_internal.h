@@ -21,6 +21,27 @@ inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
 inline int prefill_strip(int G) { return 32 * (4 / (G < 4 ? G : 4)); }
 inline int prefill_grid_y(int G) { return G > 4 ? G / 4 : 1; }
 
+// The 8-wave prefill kernel covers 2 * strip positions per workgroup.  When a chunk gives it fewer workgroups than
+// would fill the chip, `split` workgroups share each block of positions and divide the K/V rows of every launch
+// between them (their states are merged after the unit's last launch).  The launcher picks that kernel when
+// workgroups * split reaches kPrefillDeepMinWorkgroups, the 4-wave kernel otherwise.
+constexpr int kPrefillFillWorkgroups = 192;
+constexpr int kPrefillDeepMinWorkgroups = 128;
+constexpr int kPrefillMaxSplit = 8;
+inline int prefill_split(int G, int64_t chunk_len) {
+  const int64_t wgs = ceil_div(chunk_len, 2 * prefill_strip(G)) * prefill_grid_y(G);
+  int split = 1;
+  while (wgs * split < kPrefillFillWorkgroups && split < kPrefillMaxSplit) split *= 2;
+  return split;
+}
+// upper bound, in images of a 4-wave workgroup's state (256 lanes x 66 floats), of the carry any prefill launch
+// of chunks up to C rows can need: split * workgroups stays below 2 * kPrefillFillWorkgroups 8-wave images
+inline int64_t prefill_carry_images(int G, int64_t C) {
+  const int64_t narrow = (ceil_div(C, prefill_strip(G)) + 1) * prefill_grid_y(G);
+  const int64_t split_bound = 2 * (2 * kPrefillFillWorkgroups + prefill_grid_y(G));
+  return narrow > split_bound ? narrow : split_bound;
+}
+
 hi_status validate_problem(const hi_problem* p);
 
 // ---- kernel launchers (defined in the .hip files) ------------------------------------------------------
@@ -33,9 +54,9 @@ struct PrefillSegment {
 
 // One launch of the prefill kernel over up to two KV segments.  first: start from an empty softmax state
 // instead of loading the carry; last: normalise and write `out` instead of storing the carry.
-// variant: 0 = pick by chunk length (deep if it fills the chip, else narrow), 1 = narrow kernel (4 waves,
-// 2 LDS stages), 2 = wide kernel (64 positions per wave), 3 = deep kernel (8 waves, 4 LDS stages);
-// every launch of one unit must use the same variant (the carry layouts differ).
+// variant: 0 = pick by chunk length (the 8-wave kernel, split over the rows if need be, when that fills the chip,
+// else the 4-wave one), 1 = 4-wave kernel (2 LDS stages), 2 = wide kernel (64 positions per wave), 3 = 8-wave
+// kernel; every launch of one unit must use the same variant (the carry layouts differ).
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& a,
                          const PrefillSegment& b, int first, int last, void* carry, void* out, int out_fp32,
                          int variant);

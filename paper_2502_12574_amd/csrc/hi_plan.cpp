@@ -88,9 +88,8 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   pl.n_split_decode = n_cu;
   pl.prefill_rows_per_wg = prefill_strip(G);
 
-  // either kernel variant: 32 or 64 positions per wave, the same bytes per position (+1 for rounding)
-  const int64_t n_wg = (ceil_div(C, pl.prefill_rows_per_wg) + 1) * prefill_grid_y(G);
-  const int64_t carry_bytes = n_wg * kWgThreads * kCarryFloatsPerLane * 4;
+  // any kernel variant: the same bytes per position, times the split-KV factor of the 8-wave kernel
+  const int64_t carry_bytes = prefill_carry_images(G, C) * kWgThreads * kCarryFloatsPerLane * 4;
   const int64_t max_parts = (ceil_div(S, slice) + 1) * pl.n_split_decode;
   const int64_t partial_bytes = max_parts * G * kPartialFloats * 4;
   pl.ws_partials_offset = round_up(carry_bytes, 256);

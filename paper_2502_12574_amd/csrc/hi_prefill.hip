@@ -43,6 +43,7 @@ struct PrefillArgs {
   void* out;              // [G][C][128]
   int G, C, first, last, out_fp32;
   float c;                // log2(e) / sqrt(d)
+  int split;              // 8-wave kernel: workgroups along grid z share a block of positions and divide the rows
 };
 
 __device__ __forceinline__ int swz_k(int row) { return row & 15; }
@@ -572,10 +573,35 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 16 * kk));
   }
 
+  // Split-KV: workgroup z of a.split takes the past tiles [ta z / split, ta (z + 1) / split) of this launch, the
+  // last one also the chunk's own rows; each keeps its own state in the carry, merged by prefill_merge_kernel
+  // after the unit's last launch.  A split with nothing to do in this launch leaves (or initialises) its state.
+  if (a.split > 1) {
+    const int64_t ta_all = (a.na + kPfTileRows - 1) / kPfTileRows;
+    const int64_t t0 = ta_all * blockIdx.z / a.split, t1 = ta_all * (blockIdx.z + 1) / a.split;
+    const int64_t r0 = t0 * kPfTileRows;
+    int64_t r1 = t1 * kPfTileRows;
+    if (r1 > a.na) r1 = a.na;
+    a.ka += r0 * kRowBytes;
+    a.va += r0 * kRowBytes;
+    a.na = r1 - r0;
+    if ((int)blockIdx.z != a.split - 1) a.nb = 0;
+    a.last = 0;
+  }
+
   PfState st;
-  const int64_t wg_linear = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-  float* carry = a.carry + wg_linear * (kCarryFloatsPerLane * kPdWaves * 64) + threadIdx.x;
   constexpr int kLanes = kPdWaves * 64;
+  const int64_t wg_linear = ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+  float* carry = a.carry + wg_linear * (kCarryFloatsPerLane * kLanes) + threadIdx.x;
+  if (a.na <= 0 && a.nb <= 0) {      // no tile for this workgroup in this launch
+    if (a.first) {
+#pragma unroll
+      for (int i = 0; i < 64; ++i) carry[i * kLanes] = 0.f;
+      carry[64 * kLanes] = kNegBig;
+      carry[65 * kLanes] = 0.f;
+    }
+    return;
+  }
   if (a.first) {
     st.m = kNegBig;
     st.l = 0.f;
@@ -772,6 +798,59 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
         const int dim = 32 * db + 8 * rq + 4 * hl;
         const float x0 = st.o[db][4 * rq] * inv, x1 = st.o[db][4 * rq + 1] * inv;
         const float x2 = st.o[db][4 * rq + 2] * inv, x3 = st.o[db][4 * rq + 3] * inv;
+        if (a.out_fp32) {
+          *(float4*)((float*)a.out + base + dim) = make_float4(x0, x1, x2, x3);
+        } else {
+          uint2 pk;
+          pk.x = (uint32_t)float_to_bf16_bits(x0) | ((uint32_t)float_to_bf16_bits(x1) << 16);
+          pk.y = (uint32_t)float_to_bf16_bits(x2) | ((uint32_t)float_to_bf16_bits(x3) << 16);
+          *(uint2*)((uint16_t*)a.out + base + dim) = pk;
+        }
+      }
+  }
+}
+
+// Merge of the split-KV states of the 8-wave kernel, run once after a unit's last launch: the same grid (without
+// z) and the same lane layout, so every lane combines its own register images - m = max m_s,
+// O = sum O_s 2^(c (m_s - m)), l likewise - then normalises and writes out[g][i][:].
+__global__ __launch_bounds__(512) void prefill_merge_kernel(PrefillArgs a) {
+  const int lane = lane_id();
+  const int wave = wave_id();
+  const int hl = lane >> 5;
+  const int col = lane & 31;
+  const int gl = a.G < 4 ? a.G : 4;
+  const int strip = 32 * (kPdWaves / gl);
+  const int bx = gridDim.x - 1 - blockIdx.x;
+  const int g = blockIdx.y * 4 + (wave % gl);
+  const int my_i = bx * strip + 32 * (wave / gl) + col;
+  constexpr int kLanes = kPdWaves * 64;
+  const int64_t wg_per_split = (int64_t)gridDim.y * gridDim.x;
+  const int64_t wg_linear = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+
+  float m = kNegBig;
+  for (int z = 0; z < a.split; ++z)
+    m = fmaxf(m, a.carry[(z * wg_per_split + wg_linear) * (kCarryFloatsPerLane * kLanes) + 64 * kLanes + threadIdx.x]);
+  float o[64];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) o[i] = 0.f;
+  float l = 0.f;
+  for (int z = 0; z < a.split; ++z) {
+    const float* cz = a.carry + (z * wg_per_split + wg_linear) * (kCarryFloatsPerLane * kLanes) + threadIdx.x;
+    const float w = fast_exp2((cz[64 * kLanes] - m) * a.c);
+    l += w * cz[65 * kLanes];
+#pragma unroll
+    for (int i = 0; i < 64; ++i) o[i] += w * cz[i * kLanes];
+  }
+  const float inv = 1.0f / sum_halves(l);
+  if (my_i < a.C) {
+    const int64_t base = ((int64_t)g * a.C + my_i) * kHeadDim;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int dim = 32 * db + 8 * rq + 4 * hl;
+        const float x0 = o[db * 16 + 4 * rq] * inv, x1 = o[db * 16 + 4 * rq + 1] * inv;
+        const float x2 = o[db * 16 + 4 * rq + 2] * inv, x3 = o[db * 16 + 4 * rq + 3] * inv;
         if (a.out_fp32) {
           *(float4*)((float*)a.out + base + dim) = make_float4(x0, x1, x2, x3);
         } else {
@@ -1056,8 +1135,6 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel_wide(PrefillArgs a) {
   }
 }
 
-constexpr int kDeepMinWorkgroups = 192;
-
 static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   // log2(e) / sqrt(128)
 
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& sa,
@@ -1077,8 +1154,10 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   const int strip = prefill_strip(G);
   const int gy = prefill_grid_y(G);
   const bool wide = variant == 2;
-  // the deep kernel covers 2 * strip positions per workgroup; use it when that still fills the chip
-  const bool deep = variant == 3 || (variant == 0 && ceil_div(chunk_len, 2 * strip) * gy >= kDeepMinWorkgroups);
+  const int split = prefill_split(G, chunk_len);
+  const int64_t deep_wgs = ceil_div(chunk_len, 2 * strip) * gy;
+  const bool deep = variant == 3 || (variant == 0 && deep_wgs * split >= kPrefillDeepMinWorkgroups);
+  a.split = 1;
   if (wide || deep) {
     static bool attr_set = false;
     if (!attr_set) {
@@ -1090,9 +1169,19 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
       if (ea != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(ea)); return HI_ERR_HIP; }
       attr_set = true;
     }
-    dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)gy);
-    if (wide) hipLaunchKernelGGL(prefill_kernel_wide, grid, dim3(kWgThreads), kPwLdsBytes, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
+    if (wide) {
+      dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)gy);
+      hipLaunchKernelGGL(prefill_kernel_wide, grid, dim3(kWgThreads), kPwLdsBytes, (hipStream_t)stream, a);
+    } else {
+      a.split = split;
+      dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)gy, (unsigned)split);
+      hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
+      if (split > 1 && last) {
+        hipError_t e1 = hipGetLastError();
+        if (e1 != hipSuccess) { set_last_error("prefill launch: %s", hipGetErrorString(e1)); return HI_ERR_HIP; }
+        hipLaunchKernelGGL(prefill_merge_kernel, dim3(grid.x, grid.y), dim3(kPdWaves * 64), 0, (hipStream_t)stream, a);
+      }
+    }
   } else {
     dim3 grid((unsigned)ceil_div(chunk_len, strip), (unsigned)gy);
     hipLaunchKernelGGL(prefill_kernel, grid, dim3(kWgThreads), 0, (hipStream_t)stream, a);
