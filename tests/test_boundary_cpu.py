@@ -99,7 +99,7 @@ def test_plan_flop_and_byte_model_matches_oracle():
 
 def test_plan_geometry_small_and_large():
     pl = hb.hi_offload_plan(hb.make_problem(1, 1, 4, 2048 + 16, 512))
-    assert pl.slice_tokens == 256 and pl.n_slices_ring == 8 and pl.prefill_rows_per_wg == 32
+    assert pl.slice_tokens == 512 and pl.n_slices_ring == 4 and pl.prefill_rows_per_wg == 32
     pl = hb.hi_offload_plan(llama(4 << 20, 32768))
     assert pl.slice_tokens == 262144 and pl.n_slices_ring == 16
     assert pl.workspace_bytes >= pl.ws_partials_offset + (17 * 256) * 4 * 130 * 4

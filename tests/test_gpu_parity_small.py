@@ -239,7 +239,7 @@ def test_runtime_argument_errors_leave_cache_untouched():
 
 
 def test_pipeline_hazards_poisoned_staging_and_unhonoured_hints():
-    """Staging buffer reuse: the ring (here 8 slots of 64 rows) is poisoned with NaN patterns before the run, units
+    """Staging buffer reuse: the ring (here 7 slots of 64 rows) is poisoned with NaN patterns before the run, units
     of two heads alternate with prefetch hints that are sometimes wrong (the library must drop the stale prefetch
     and fetch on demand) and sometimes absent; every result must still match the oracle, bit for bit the same as
     an HBM-resident run, and no NaN may leak from the poison."""
