@@ -573,27 +573,38 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 16 * kk));
   }
 
-  // Split-KV: workgroup z of a.split takes the past tiles [ta z / split, ta (z + 1) / split) of this launch, the
-  // last one also the chunk's own rows; each keeps its own state in the carry, merged by prefill_merge_kernel
-  // after the unit's last launch.  A split with nothing to do in this launch leaves (or initialises) its state.
-  if (a.split > 1) {
+  // This workgroup's tile sequence: the past segment's tiles, then the chunk's own tiles up to its causal boundary.
+  // Split-KV: workgroup z of a.split takes the part [T z / split, T (z + 1) / split) of that sequence, keeps its
+  // own state in the carry, and prefill_merge_kernel merges the states after the unit's last launch.  A split with
+  // nothing to do in this launch leaves (or initialises) its state.
+  int b_t0 = 0;                       // first tile of the chunk's own rows this workgroup takes
+  int tb;                             // and how many
+  {
     const int64_t ta_all = (a.na + kPfTileRows - 1) / kPfTileRows;
-    const int64_t t0 = ta_all * blockIdx.z / a.split, t1 = ta_all * (blockIdx.z + 1) / a.split;
-    const int64_t r0 = t0 * kPfTileRows;
-    int64_t r1 = t1 * kPfTileRows;
-    if (r1 > a.na) r1 = a.na;
-    a.ka += r0 * kRowBytes;
-    a.va += r0 * kRowBytes;
-    a.na = r1 - r0;
-    if ((int)blockIdx.z != a.split - 1) a.nb = 0;
-    a.last = 0;
+    const int64_t nb_vis = a.nb < (int64_t)i_hi + 1 ? a.nb : (int64_t)i_hi + 1;
+    const int64_t tb_all = (nb_vis + kPfTileRows - 1) / kPfTileRows;
+    tb = (int)tb_all;
+    if (a.split > 1) {
+      const int64_t t_all = ta_all + tb_all;
+      const int64_t g0 = t_all * blockIdx.z / a.split, g1 = t_all * (blockIdx.z + 1) / a.split;
+      const int64_t a0 = g0 < ta_all ? g0 : ta_all, a1 = g1 < ta_all ? g1 : ta_all;
+      const int64_t r0 = a0 * kPfTileRows;
+      int64_t r1 = a1 * kPfTileRows;
+      if (r1 > a.na) r1 = a.na;
+      a.ka += r0 * kRowBytes;
+      a.va += r0 * kRowBytes;
+      a.na = r1 - r0;
+      b_t0 = (int)((g0 > ta_all ? g0 : ta_all) - ta_all);
+      tb = (int)((g1 > ta_all ? g1 : ta_all) - ta_all) - b_t0;
+      a.last = 0;
+    }
   }
 
   PfState st;
   constexpr int kLanes = kPdWaves * 64;
   const int64_t wg_linear = ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
   float* carry = a.carry + wg_linear * (kCarryFloatsPerLane * kLanes) + threadIdx.x;
-  if (a.na <= 0 && a.nb <= 0) {      // no tile for this workgroup in this launch
+  if (a.na <= 0 && tb <= 0) {      // no tile for this workgroup in this launch
     if (a.first) {
 #pragma unroll
       for (int i = 0; i < 64; ++i) carry[i * kLanes] = 0.f;
@@ -624,15 +635,14 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(st.o[db]));
 
   const int ta = (int)((a.na + kPfTileRows - 1) / kPfTileRows);
-  const int64_t nb_vis = a.nb < (int64_t)i_hi + 1 ? a.nb : (int64_t)i_hi + 1;
-  const int tb = (int)((nb_vis + kPfTileRows - 1) / kPfTileRows);
   const int T = ta + tb;
+  const int tb_base = b_t0 - ta;      // tile t >= ta of the sweep is tile t + tb_base of the chunk's own rows
 
   // K tile t (which = 0) or V tile t (which = 1) of the sweep: this wave's share of its loads
   auto issue = [&](int t, int which) __attribute__((always_inline)) {
     if (t >= T) return;
     const bool in_b = t >= ta;
-    const int64_t row0 = (int64_t)(in_b ? t - ta : t) * kPfTileRows;
+    const int64_t row0 = (int64_t)(in_b ? t + tb_base : t) * kPfTileRows;
     const int64_t left = (in_b ? a.nb : a.na) - row0;
     const int rows = left < kPfTileRows ? (int)left : kPfTileRows;
     const uint32_t slot = lds_base + (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes;
@@ -675,7 +685,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   bf16x8 pb[2][2];
   auto softmax_phase = [&](int t) __attribute__((always_inline)) {
     const bool in_b = t >= ta;
-    const int64_t j0 = (int64_t)(in_b ? (t - ta) : t) * kPfTileRows;
+    const int64_t j0 = (int64_t)(in_b ? t + tb_base : t) * kPfTileRows;
     const int64_t n_seg = in_b ? a.nb : a.na;
     const bool masked = (j0 + kPfTileRows > n_seg) || (in_b && (j0 + kPfTileRows - 1 > i0));
     int rel = kPfTileRows;
@@ -710,7 +720,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     ld.k = ld.v = nullptr;
     const int tk = t + 3, tv = t + 2;
     const bool kb = tk >= ta, vb = tv >= ta;
-    const int64_t krow0 = (int64_t)(kb ? tk - ta : tk) * kPfTileRows, vrow0 = (int64_t)(vb ? tv - ta : tv) * kPfTileRows;
+    const int64_t krow0 = (int64_t)(kb ? tk + tb_base : tk) * kPfTileRows;
+    const int64_t vrow0 = (int64_t)(vb ? tv + tb_base : tv) * kPfTileRows;
     const bool kfull = tk < T && (kb ? a.nb : a.na) - krow0 >= kPfTileRows;
     const bool vfull = tv < T && (vb ? a.nb : a.na) - vrow0 >= kPfTileRows;
     if (kfull) ld.k = (kb ? a.kb : a.ka) + krow0 * kRowBytes; else issue(tk, 0);
@@ -751,21 +762,35 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     kp += kPfTileBytes;
     vp += kPfTileBytes;
   };
-  const int t_fast = (int)(a.na / kPfTileRows) - 3;     // tiles [1, t_fast) qualify
+  // A run of steady-state tiles [t, t_end) of one segment whose tile 0 is tile `tile0` of the sweep and whose rows
+  // start at kbase / vbase: general tiles up to a multiple of four, then the unrolled loop.
   int t = 1;
-  if (t_fast >= 8) {
-    for (; t < 4; ++t) generic_tile(t);
-    kp = a.ka + (int64_t)(t + 3) * kPfTileBytes;
-    vp = a.va + (int64_t)(t + 2) * kPfTileBytes;
+  auto fast_run = [&](int t_end, const char* kbase, const char* vbase, int tile0) __attribute__((always_inline)) {
+    if (t_end - t < 8) return;
+    while (t & 3) { generic_tile(t); ++t; }
+    kp = kbase + (int64_t)(t + 3 - tile0) * kPfTileBytes;
+    vp = vbase + (int64_t)(t + 2 - tile0) * kPfTileBytes;
     pd_preread((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes, lc, pre);
 #pragma unroll
     for (int r = 0; r < 16; ++r) negm[r] = -st.m;
-    for (; t + 4 <= t_fast; t += 4) {
+    for (; t + 4 <= t_end; t += 4) {
       fast_tile(std::integral_constant<int, 0>());
       fast_tile(std::integral_constant<int, 1>());
       fast_tile(std::integral_constant<int, 2>());
       fast_tile(std::integral_constant<int, 3>());
     }
+  };
+  // past segment: tile t qualifies if K(t+3) and V(t+2) are full tiles of the segment too
+  fast_run((int)(a.na / kPfTileRows) - 3, a.ka, a.va, 0);
+  // the chunk's own rows: tiles that end at or before the first position of the workgroup are not masked for any
+  // of its lanes (own tile j = t + tb_base; its rows are 64 j .. 64 j + 63)
+  while (t < ta && t < T) { generic_tile(t); ++t; }
+  {
+    const int64_t unmasked = ((int64_t)bx * strip + 1) / kPfTileRows;          // own tiles 0 .. unmasked - 1
+    const int64_t loadable = a.nb / kPfTileRows - 3;                           // K(t+3), V(t+2) full
+    const int64_t j_end = unmasked < loadable ? unmasked : loadable;
+    const int64_t t_end = j_end - tb_base < T - 3 ? j_end - tb_base : T - 3;
+    fast_run((int)t_end, a.kb, a.vb, -tb_base);
   }
   for (; t < T; ++t) generic_tile(t);
   {
