@@ -163,6 +163,26 @@ hi_status hi_decode_head(hi_ctx* ctx, int32_t layer, int32_t kv_head, const void
                          const void* v_new_dev, int64_t past_len, void* out_dev, int32_t next_layer,
                          int32_t next_kv_head, int64_t next_past_len);
 
+/*
+ * Head groups (Section 4, "adaptive head-wise offloading": several heads fused per transfer and per launch at
+ * shorter contexts, to amortise the per-head overheads; a group of all heads is layer-wise offload).  The same
+ * two operations over n_heads consecutive KV heads kv_head .. kv_head + n_heads - 1 of one layer, in one call:
+ * one launch per staging slice covers all heads of the group, and a staging slice holds
+ * plan.slice_tokens / n_heads rows (rounded down to a multiple of 64) of each, so the HBM budget is unchanged.
+ * q_dev   DEVICE bf16 [n_heads][G][len][D_h]; k_new_dev, v_new_dev DEVICE bf16 [n_heads][len][D_h];
+ * out_dev DEVICE [n_heads][G][len][D_h]  (len = chunk_len, or 1 with that axis dropped for decode).
+ * The hint names the next group (first head and size).  hi_prefill_head / hi_decode_head are the n_heads = 1
+ * case; results are identical whatever the grouping.  Extra errors: HI_ERR_HBM_BUDGET when a slice cannot hold
+ * 64 rows of every head of the group, HI_ERR_UNSUPPORTED with HI_FLAG_PREFILL_WIDE.
+ */
+hi_status hi_prefill_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n_heads, const void* q_dev,
+                           const void* k_new_dev, const void* v_new_dev, int64_t past_len, int32_t chunk_len,
+                           void* out_dev, int32_t next_layer, int32_t next_kv_head, int32_t next_n_heads,
+                           int64_t next_past_len);
+hi_status hi_decode_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n_heads, const void* q_dev,
+                          const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
+                          int32_t next_layer, int32_t next_kv_head, int32_t next_n_heads, int64_t next_past_len);
+
 /* T4 - drain the three streams; surfaces deferred HIP errors (HI_ERR_HIP). */
 hi_status hi_sync(hi_ctx* ctx);
 

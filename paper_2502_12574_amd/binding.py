@@ -19,8 +19,7 @@ HI_FLAG_SKIP_KERNELS, HI_FLAG_SKIP_COPIES, HI_FLAG_TIME_KERNELS = 1, 2, 4
 HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_WIDE, HI_FLAG_PREFILL_DEEP = 8, 16, 32
 
 EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
-           "hi_prefill_head",
-           "hi_decode_head", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
+           "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
 
 
 class hi_problem(C.Structure):
@@ -77,6 +76,8 @@ def lib() -> C.CDLL:
         L.hi_ctx_set_run_ahead.argtypes = [vp, i32]
         L.hi_prefill_head.argtypes = [vp, i32, i32, vp, vp, vp, i64, i32, vp, i32, i32, i64]
         L.hi_decode_head.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp, i32, i32, i64]
+        L.hi_prefill_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, i32, vp, i32, i32, i32, i64]
+        L.hi_decode_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, vp, i32, i32, i32, i64]
         L.hi_sync.argtypes = [vp]
         L.hi_get_stats.argtypes = [vp, C.POINTER(hi_stats)]
         L.hi_reset_stats.argtypes = [vp]
@@ -173,6 +174,24 @@ def hi_decode_head(ctx, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, o
                               _ptr(out_dev), next_layer, next_kv_head, next_past_len)
     if check and st != HI_OK:
         raise HiError(st, "hi_decode_head")
+    return st
+
+
+def hi_prefill_group(ctx, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev,
+                     next_layer=-1, next_kv_head=0, next_n_heads=1, next_past_len=0, check: bool = True):
+    st = lib().hi_prefill_group(ctx, layer, kv_head, n_heads, _ptr(q_dev), _ptr(k_new_dev), _ptr(v_new_dev), past_len,
+                                chunk_len, _ptr(out_dev), next_layer, next_kv_head, next_n_heads, next_past_len)
+    if check and st != HI_OK:
+        raise HiError(st, "hi_prefill_group")
+    return st
+
+
+def hi_decode_group(ctx, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, out_dev, next_layer=-1,
+                    next_kv_head=0, next_n_heads=1, next_past_len=0, check: bool = True):
+    st = lib().hi_decode_group(ctx, layer, kv_head, n_heads, _ptr(q_dev), _ptr(k_new_dev), _ptr(v_new_dev), past_len,
+                               _ptr(out_dev), next_layer, next_kv_head, next_n_heads, next_past_len)
+    if check and st != HI_OK:
+        raise HiError(st, "hi_decode_group")
     return st
 
 

@@ -57,7 +57,8 @@ struct hi_ctx {
 
   struct Unit {
     bool valid = false;
-    int layer = 0, head = 0;
+    int layer = 0, head = 0;  // first head of the group
+    int nh = 1;               // heads in the group
     int64_t past = 0;
     int64_t n_slices = 0;
     int64_t issued = 0;       // slices of this unit already fetched
@@ -82,10 +83,18 @@ inline int64_t plane_offset(const hi_ctx* c, int layer, int head, int which /*0 
   return (((int64_t)layer * c->prob.n_kv_heads + head) * 2 + which) * plane;
 }
 
+// A ring slot holds one sequence slice of every head of a group: rows_of(nh) rows of K then of V per head, the
+// heads head_pitch(nh) bytes apart (Section 4, adaptive head grouping: more heads per transfer and launch, each
+// with a shorter slice, inside the same HBM budget).
+inline int64_t rows_of(const hi_ctx* c, int nh) {
+  const int64_t r = (c->slice_tokens / nh) / 64 * 64;
+  return r < 64 ? 64 : r;
+}
+inline int64_t head_pitch(const hi_ctx* c, int nh) { return rows_of(c, nh) * 2 * kRowBytes; }
 inline char* slot_k(const hi_ctx* c, int slot) { return c->staging + (int64_t)slot * c->slice_tokens * 2 * kRowBytes; }
-inline char* slot_v(const hi_ctx* c, int slot) { return slot_k(c, slot) + c->slice_tokens * kRowBytes; }
+inline char* slot_v(const hi_ctx* c, int slot, int nh) { return slot_k(c, slot) + rows_of(c, nh) * kRowBytes; }
 
-inline int64_t slices_of(const hi_ctx* c, int64_t past) { return ceil_div(past, c->slice_tokens); }
+inline int64_t slices_of(const hi_ctx* c, int64_t past, int nh) { return ceil_div(past, rows_of(c, nh)); }
 
 inline bool can_issue(const hi_ctx* c) { return c->seq_issued - c->n_slots < c->seq_consumed; }
 
@@ -94,27 +103,33 @@ void note_peak(hi_ctx* c) {
   if (live > c->stats.peak_staging_bytes) c->stats.peak_staging_bytes = live;
 }
 
-// enqueue the H2D of the next not-yet-fetched slice of unit u
+// enqueue the H2D of the next not-yet-fetched slice of unit u (all heads of its group)
 hi_status issue_slice(hi_ctx* c, hi_ctx::Unit& u) {
   const int64_t i = u.issued;
   const int64_t seq = c->seq_issued;
   const int slot = (int)(seq % c->n_slots);
-  const int64_t row0 = i * c->slice_tokens;
+  const int64_t st = rows_of(c, u.nh);
+  const int64_t row0 = i * st;
   int64_t rows = u.past - row0;
-  if (rows > c->slice_tokens) rows = c->slice_tokens;
+  if (rows > st) rows = st;
   if (i == 0) {
     u.first_seq = seq;
-    const int idx = u.layer * c->prob.n_kv_heads + u.head;
-    if (c->wb_valid[idx]) HI_HIP(hipStreamWaitEvent(c->sh, c->ev_wb[idx], 0));   // rows written by an earlier call
+    for (int j = 0; j < u.nh; ++j) {
+      const int idx = u.layer * c->prob.n_kv_heads + u.head + j;
+      if (c->wb_valid[idx]) HI_HIP(hipStreamWaitEvent(c->sh, c->ev_wb[idx], 0));   // rows written by an earlier call
+    }
   }
   if (seq >= c->n_slots) HI_HIP(hipStreamWaitEvent(c->sh, c->ev_free[slot], 0));  // slot's previous tenant consumed
   if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
-    const char* hk = c->kv + plane_offset(c, u.layer, u.head, 0) + row0 * kRowBytes;
-    const char* hv = c->kv + plane_offset(c, u.layer, u.head, 1) + row0 * kRowBytes;
-    HI_HIP(hipMemcpyAsync(slot_k(c, slot), hk, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
-    HI_HIP(hipMemcpyAsync(slot_v(c, slot), hv, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
-    c->stats.bytes_h2d += 2 * rows * kRowBytes;
-    c->stats.n_h2d_copies += 2;
+    for (int j = 0; j < u.nh; ++j) {
+      const char* hk = c->kv + plane_offset(c, u.layer, u.head + j, 0) + row0 * kRowBytes;
+      const char* hv = c->kv + plane_offset(c, u.layer, u.head + j, 1) + row0 * kRowBytes;
+      char* dk = slot_k(c, slot) + j * head_pitch(c, u.nh);
+      HI_HIP(hipMemcpyAsync(dk, hk, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
+      HI_HIP(hipMemcpyAsync(dk + st * kRowBytes, hv, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
+    }
+    c->stats.bytes_h2d += 2 * rows * kRowBytes * u.nh;
+    c->stats.n_h2d_copies += 2 * u.nh;
   }
   HI_HIP(hipEventRecord(c->ev_ready[slot], c->sh));
   u.issued += 1;
@@ -195,58 +210,74 @@ int pf_variant(const hi_ctx* c) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-hi_status check_unit_args(const hi_ctx* c, int layer, int head, const void* q, const void* k, const void* v,
-                          int64_t past, int64_t len, const void* out, int next_layer, int next_head,
+hi_status check_unit_args(const hi_ctx* c, int layer, int head, int nh, const void* q, const void* k, const void* v,
+                          int64_t past, int64_t len, const void* out, int next_layer, int next_head, int next_nh,
                           int64_t next_past) {
   if (!c) { set_last_error("ctx is null"); return HI_ERR_ARG; }
   if (!q || !k || !v || !out) { set_last_error("null buffer"); return HI_ERR_ARG; }
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) { set_last_error("buffers must be 16-byte aligned"); return HI_ERR_ARG; }
-  if (layer < 0 || layer >= c->prob.n_layers || head < 0 || head >= c->prob.n_kv_heads) { set_last_error("layer/head out of range"); return HI_ERR_ARG; }
+  if (layer < 0 || layer >= c->prob.n_layers || head < 0 || nh < 1 || head + nh > c->prob.n_kv_heads) { set_last_error("layer/head out of range"); return HI_ERR_ARG; }
+  if (c->mode == HI_MODE_OFFLOAD && ((int64_t)nh * 64 > c->slice_tokens || (next_layer >= 0 && (int64_t)next_nh * 64 > c->slice_tokens))) {
+    set_last_error("a staging slice of %lld rows cannot hold 64 rows of each head of the group", (long long)c->slice_tokens);
+    return HI_ERR_HBM_BUDGET;
+  }
+  if (nh > 1 && (c->flags & HI_FLAG_PREFILL_WIDE)) { set_last_error("the 64-positions-per-wave kernel takes one head per launch"); return HI_ERR_UNSUPPORTED; }
   if (past < 0 || len < 1) { set_last_error("negative past_len or empty call"); return HI_ERR_ARG; }
   if (len > c->prob.chunk || past + len > c->prob.max_context) { set_last_error("past_len %lld + len %lld exceeds the plan", (long long)past, (long long)len); return HI_ERR_RANGE; }
   if (next_layer >= 0) {
-    if (next_layer >= c->prob.n_layers || next_head < 0 || next_head >= c->prob.n_kv_heads || next_past < 0) { set_last_error("prefetch hint out of range"); return HI_ERR_ARG; }
+    if (next_layer >= c->prob.n_layers || next_head < 0 || next_nh < 1 || next_head + next_nh > c->prob.n_kv_heads || next_past < 0) { set_last_error("prefetch hint out of range"); return HI_ERR_ARG; }
     if (next_past > c->prob.max_context) { set_last_error("prefetch hint beyond max_context"); return HI_ERR_RANGE; }
   }
   return HI_OK;
 }
 
-// make `pend` describe (layer, head, past); drop a stale prefetch if the hint was not honoured
-hi_status adopt_unit(hi_ctx* c, int layer, int head, int64_t past) {
+// make `pend` describe (layer, head group, past); drop a stale prefetch if the hint was not honoured
+hi_status adopt_unit(hi_ctx* c, int layer, int head, int nh, int64_t past) {
   auto& p = c->pend;
-  if (p.valid && (p.layer != layer || p.head != head || p.past != past)) {
+  if (p.valid && (p.layer != layer || p.head != head || p.nh != nh || p.past != past)) {
     for (int64_t i = 0; i < p.issued; ++i) HI_TRY(retire_slice(c, (int)((p.first_seq + i) % c->n_slots)));
     p.valid = false;
   }
   if (!p.valid) {
     p = hi_ctx::Unit();
     p.valid = true;
-    p.layer = layer; p.head = head; p.past = past;
-    p.n_slices = slices_of(c, past);
+    p.layer = layer; p.head = head; p.nh = nh; p.past = past;
+    p.n_slices = slices_of(c, past, nh);
   }
   return HI_OK;
 }
 
-hi_status write_back(hi_ctx* c, int layer, int head, const void* k_new, const void* v_new, int64_t past, int64_t len) {
-  char* dk = c->kv + plane_offset(c, layer, head, 0) + past * kRowBytes;
-  char* dv = c->kv + plane_offset(c, layer, head, 1) + past * kRowBytes;
-  if (c->mode == HI_MODE_RESIDENT) {
-    HI_HIP(hipMemcpyAsync(dk, k_new, len * kRowBytes, hipMemcpyDeviceToDevice, c->sc));
-    HI_HIP(hipMemcpyAsync(dv, v_new, len * kRowBytes, hipMemcpyDeviceToDevice, c->sc));
-    return HI_OK;
+// k_new / v_new: [nh][len][128]
+hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, const void* v_new, int64_t past,
+                     int64_t len) {
+  const bool resident = c->mode == HI_MODE_RESIDENT;
+  if (!resident) {
+    // the new rows were produced by earlier work on the compute stream
+    HI_HIP(hipEventRecord(c->ev_entry, c->sc));
+    HI_HIP(hipStreamWaitEvent(c->sd, c->ev_entry, 0));
   }
-  // the new rows were produced by earlier work on the compute stream
-  HI_HIP(hipEventRecord(c->ev_entry, c->sc));
-  HI_HIP(hipStreamWaitEvent(c->sd, c->ev_entry, 0));
-  if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
-    HI_HIP(hipMemcpyAsync(dk, k_new, len * kRowBytes, hipMemcpyDeviceToHost, c->sd));
-    HI_HIP(hipMemcpyAsync(dv, v_new, len * kRowBytes, hipMemcpyDeviceToHost, c->sd));
-    c->stats.bytes_d2h += 2 * len * kRowBytes;
-    c->stats.n_d2h_copies += 2;
+  for (int j = 0; j < nh; ++j) {
+    char* dk = c->kv + plane_offset(c, layer, head + j, 0) + past * kRowBytes;
+    char* dv = c->kv + plane_offset(c, layer, head + j, 1) + past * kRowBytes;
+    const char* sk = (const char*)k_new + j * len * kRowBytes;
+    const char* sv = (const char*)v_new + j * len * kRowBytes;
+    if (resident) {
+      HI_HIP(hipMemcpyAsync(dk, sk, len * kRowBytes, hipMemcpyDeviceToDevice, c->sc));
+      HI_HIP(hipMemcpyAsync(dv, sv, len * kRowBytes, hipMemcpyDeviceToDevice, c->sc));
+    } else if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
+      HI_HIP(hipMemcpyAsync(dk, sk, len * kRowBytes, hipMemcpyDeviceToHost, c->sd));
+      HI_HIP(hipMemcpyAsync(dv, sv, len * kRowBytes, hipMemcpyDeviceToHost, c->sd));
+      c->stats.bytes_d2h += 2 * len * kRowBytes;
+      c->stats.n_d2h_copies += 2;
+    }
   }
-  const int idx = layer * c->prob.n_kv_heads + head;
-  HI_HIP(hipEventRecord(c->ev_wb[idx], c->sd));
-  c->wb_valid[idx] = 1;
+  if (!resident) {
+    for (int j = 0; j < nh; ++j) {
+      const int idx = layer * c->prob.n_kv_heads + head + j;
+      HI_HIP(hipEventRecord(c->ev_wb[idx], c->sd));
+      c->wb_valid[idx] = 1;
+    }
+  }
   return HI_OK;
 }
 
@@ -343,62 +374,55 @@ extern "C" hi_status hi_ctx_set_run_ahead(hi_ctx* c, int32_t units) {
   return HI_OK;
 }
 
-static hi_status prefill_head_impl(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
-                                   const void* k_new_dev, const void* v_new_dev, int64_t past_len,
-                                   int32_t chunk_len, void* out_dev, int32_t next_layer, int32_t next_kv_head,
-                                   int64_t next_past_len) {
+// One prefill unit: a group of nh KV heads starting at kv_head (nh = 1: the paper's finest granularity).
+static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t nh, const void* q_dev,
+                              const void* k_new_dev, const void* v_new_dev, int64_t past_len, int32_t chunk_len,
+                              void* out_dev, int32_t next_layer, int32_t next_kv_head, int32_t next_nh,
+                              int64_t next_past_len) {
   const int G = c->prob.gqa_group;
   const bool run = !(c->flags & HI_FLAG_SKIP_KERNELS);
   const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
   PrefillSegment diag{k_new_dev, v_new_dev, chunk_len, 1};
+  auto launch = [&](const PrefillSegment& seg, const PrefillSegment& own, int first, int last) -> hi_status {
+    TimedSpan sp;
+    if (timed) HI_TRY(span_begin(c, 0, &sp));
+    HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, seg, own, first, last, c->ws, out_dev, c->prob.out_fp32,
+                          pf_variant(c), nh));
+    if (timed) HI_TRY(span_end(c, sp));
+    c->stats.n_prefill_kernels += 1;
+    return HI_OK;
+  };
 
   if (c->mode == HI_MODE_RESIDENT) {
-    PrefillSegment pastseg{c->kv + plane_offset(c, layer, kv_head, 0), c->kv + plane_offset(c, layer, kv_head, 1), past_len, 0};
-    if (run) {
-      TimedSpan sp;
-      if (timed) HI_TRY(span_begin(c, 0, &sp));
-      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, pastseg, diag, 1, 1, c->ws, out_dev, c->prob.out_fp32, pf_variant(c)));
-      if (timed) HI_TRY(span_end(c, sp));
-      c->stats.n_prefill_kernels += 1;
-    }
-    return write_back(c, layer, kv_head, k_new_dev, v_new_dev, past_len, chunk_len);
+    PrefillSegment pastseg{c->kv + plane_offset(c, layer, kv_head, 0), c->kv + plane_offset(c, layer, kv_head, 1),
+                           past_len, 0, 2 * c->prob.max_context * kRowBytes};
+    if (run) HI_TRY(launch(pastseg, diag, 1, 1));
+    return write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, chunk_len);
   }
 
-  HI_TRY(adopt_unit(c, layer, kv_head, past_len));
-  HI_TRY(write_back(c, layer, kv_head, k_new_dev, v_new_dev, past_len, chunk_len));
+  HI_TRY(adopt_unit(c, layer, kv_head, nh, past_len));
+  HI_TRY(write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, chunk_len));
 
   hi_ctx::Unit next;
   if (next_layer >= 0) {
     next.valid = true;
-    next.layer = next_layer; next.head = next_kv_head; next.past = next_past_len;
-    next.n_slices = slices_of(c, next_past_len);
+    next.layer = next_layer; next.head = next_kv_head; next.nh = next_nh; next.past = next_past_len;
+    next.n_slices = slices_of(c, next_past_len, next_nh);
   }
   hi_ctx::Unit& cur = c->pend;
   const int64_t ns = cur.n_slices;
-  if (ns == 0) {
-    if (run) {
-      TimedSpan sp;
-      if (timed) HI_TRY(span_begin(c, 0, &sp));
-      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, PrefillSegment{nullptr, nullptr, 0, 0}, diag, 1, 1, c->ws, out_dev, c->prob.out_fp32, pf_variant(c)));
-      if (timed) HI_TRY(span_end(c, sp));
-      c->stats.n_prefill_kernels += 1;
-    }
-  }
+  const int64_t st = rows_of(c, nh);
+  if (ns == 0 && run) HI_TRY(launch(PrefillSegment{nullptr, nullptr, 0, 0}, diag, 1, 1));
   for (int64_t i = 0; i < ns; ++i) {
     HI_TRY(top_up(c, cur, next));          // guarantees slice i has been fetched
     const int slot = (int)((cur.first_seq + i) % c->n_slots);
-    int64_t rows = past_len - i * c->slice_tokens;
-    if (rows > c->slice_tokens) rows = c->slice_tokens;
+    int64_t rows = past_len - i * st;
+    if (rows > st) rows = st;
     HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
     if (run) {
       const bool is_last = (i == ns - 1);
-      PrefillSegment seg{slot_k(c, slot), slot_v(c, slot), rows, 0};
-      TimedSpan sp;
-      if (timed) HI_TRY(span_begin(c, 0, &sp));
-      HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, seg, is_last ? diag : PrefillSegment{nullptr, nullptr, 0, 1},
-                            i == 0, is_last, c->ws, out_dev, c->prob.out_fp32, pf_variant(c)));
-      if (timed) HI_TRY(span_end(c, sp));
-      c->stats.n_prefill_kernels += 1;
+      PrefillSegment seg{slot_k(c, slot), slot_v(c, slot, nh), rows, 0, head_pitch(c, nh)};
+      HI_TRY(launch(seg, is_last ? diag : PrefillSegment{nullptr, nullptr, 0, 1}, i == 0, is_last));
     }
     HI_TRY(retire_slice(c, slot));
   }
@@ -409,71 +433,78 @@ static hi_status prefill_head_impl(hi_ctx* c, int32_t layer, int32_t kv_head, co
   return HI_OK;
 }
 
-static hi_status decode_head_impl(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
-                                  const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
-                                  int32_t next_layer, int32_t next_kv_head, int64_t next_past_len) {
+// One decode unit: the token's rows of a group of nh KV heads.
+static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t nh, const void* q_dev,
+                             const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
+                             int32_t next_layer, int32_t next_kv_head, int32_t next_nh, int64_t next_past_len) {
   const int G = c->prob.gqa_group;
   const bool run = !(c->flags & HI_FLAG_SKIP_KERNELS);
   const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
   float* partials = (float*)(c->ws + c->plan.ws_partials_offset);
-  const int n_split = c->plan.n_split_decode;
+  const int64_t part_stride = decode_part_head_stride(c->prob.max_context, c->slice_tokens, c->plan.n_split_decode, G);
+  const int64_t part_cap = part_stride / (G * kPartialFloats);       // partials one head may write
+  const int n_split = c->plan.n_split_decode / nh > 0 ? c->plan.n_split_decode / nh : 1;
   auto splits_for = [&](int64_t rows) {
     const int64_t need = ceil_div(rows, 64);      // one workgroup covers at least 64 rows
     return (int)(need < n_split ? need : n_split);
   };
+  auto partial = [&](const void* k, const void* v, int64_t rows, int np, int part0, int64_t kv_stride) -> hi_status {
+    if (part0 + np > part_cap) { set_last_error("decode: partial workspace exhausted"); return HI_ERR_UNSUPPORTED; }
+    TimedSpan sp;
+    if (timed) HI_TRY(span_begin(c, 1, &sp));
+    HI_TRY(launch_decode_partial(c->sc, q_dev, G, k, v, rows, np, partials, part0, nh, kv_stride, part_stride));
+    if (timed) HI_TRY(span_end(c, sp));
+    c->stats.n_decode_kernels += 1;
+    return HI_OK;
+  };
 
   if (c->mode == HI_MODE_RESIDENT) {
+    const int64_t plane2 = 2 * c->prob.max_context * kRowBytes;
     int n_part = 0;
     if (run) {
-      TimedSpan sp;
-      if (timed) HI_TRY(span_begin(c, 1, &sp));
       if (past_len > 0) {
         n_part = splits_for(past_len);
-        HI_TRY(launch_decode_partial(c->sc, q_dev, G, c->kv + plane_offset(c, layer, kv_head, 0),
-                                     c->kv + plane_offset(c, layer, kv_head, 1), past_len, n_part, partials, 0));
-        c->stats.n_decode_kernels += 1;
+        HI_TRY(partial(c->kv + plane_offset(c, layer, kv_head, 0), c->kv + plane_offset(c, layer, kv_head, 1), past_len,
+                       n_part, 0, plane2));
       }
-      if (timed) HI_TRY(span_end(c, sp));
       HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32,
                                    c->kv + plane_offset(c, layer, kv_head, 0) + past_len * kRowBytes,
-                                   c->kv + plane_offset(c, layer, kv_head, 1) + past_len * kRowBytes));
+                                   c->kv + plane_offset(c, layer, kv_head, 1) + past_len * kRowBytes, nh, part_stride,
+                                   plane2));
       c->stats.n_combine_kernels += 1;
       return HI_OK;
     }
-    return write_back(c, layer, kv_head, k_new_dev, v_new_dev, past_len, 1);
+    return write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, 1);
   }
 
-  HI_TRY(adopt_unit(c, layer, kv_head, past_len));
-  HI_TRY(write_back(c, layer, kv_head, k_new_dev, v_new_dev, past_len, 1));
+  HI_TRY(adopt_unit(c, layer, kv_head, nh, past_len));
+  HI_TRY(write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, 1));
   hi_ctx::Unit next;
   if (next_layer >= 0) {
     next.valid = true;
-    next.layer = next_layer; next.head = next_kv_head; next.past = next_past_len;
-    next.n_slices = slices_of(c, next_past_len);
+    next.layer = next_layer; next.head = next_kv_head; next.nh = next_nh; next.past = next_past_len;
+    next.n_slices = slices_of(c, next_past_len, next_nh);
   }
   hi_ctx::Unit& cur = c->pend;
   const int64_t ns = cur.n_slices;
+  const int64_t st = rows_of(c, nh);
   int n_part = 0;
   for (int64_t i = 0; i < ns; ++i) {
     HI_TRY(top_up(c, cur, next));
     const int slot = (int)((cur.first_seq + i) % c->n_slots);
-    int64_t rows = past_len - i * c->slice_tokens;
-    if (rows > c->slice_tokens) rows = c->slice_tokens;
+    int64_t rows = past_len - i * st;
+    if (rows > st) rows = st;
     HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
     if (run) {
       const int np = splits_for(rows);
-      TimedSpan sp;
-      if (timed) HI_TRY(span_begin(c, 1, &sp));
-      HI_TRY(launch_decode_partial(c->sc, q_dev, G, slot_k(c, slot), slot_v(c, slot), rows, np, partials, n_part));
-      if (timed) HI_TRY(span_end(c, sp));
+      HI_TRY(partial(slot_k(c, slot), slot_v(c, slot, nh), rows, np, n_part, head_pitch(c, nh)));
       n_part += np;
-      c->stats.n_decode_kernels += 1;
     }
     HI_TRY(retire_slice(c, slot));
   }
   if (run) {
     HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32,
-                                 nullptr, nullptr));
+                                 nullptr, nullptr, nh, part_stride, 0));
     c->stats.n_combine_kernels += 1;
   }
   cur.valid = false;
@@ -483,27 +514,43 @@ static hi_status decode_head_impl(hi_ctx* c, int32_t layer, int32_t kv_head, con
   return HI_OK;
 }
 
+extern "C" hi_status hi_prefill_group(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t n_heads, const void* q_dev,
+                                      const void* k_new_dev, const void* v_new_dev, int64_t past_len,
+                                      int32_t chunk_len, void* out_dev, int32_t next_layer, int32_t next_kv_head,
+                                      int32_t next_n_heads, int64_t next_past_len) {
+  HI_TRY(check_unit_args(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev,
+                         next_layer, next_kv_head, next_n_heads, next_past_len));
+  HI_TRY(pace_begin(c));
+  HI_TRY(prefill_impl(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
+                      next_kv_head, next_n_heads, next_past_len));
+  return pace_end(c);
+}
+
+extern "C" hi_status hi_decode_group(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t n_heads, const void* q_dev,
+                                     const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
+                                     int32_t next_layer, int32_t next_kv_head, int32_t next_n_heads,
+                                     int64_t next_past_len) {
+  HI_TRY(check_unit_args(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, 1, out_dev, next_layer,
+                         next_kv_head, next_n_heads, next_past_len));
+  HI_TRY(pace_begin(c));
+  HI_TRY(decode_impl(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, out_dev, next_layer,
+                     next_kv_head, next_n_heads, next_past_len));
+  return pace_end(c);
+}
+
 extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
                                      const void* k_new_dev, const void* v_new_dev, int64_t past_len,
                                      int32_t chunk_len, void* out_dev, int32_t next_layer, int32_t next_kv_head,
                                      int64_t next_past_len) {
-  HI_TRY(check_unit_args(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
-                         next_kv_head, next_past_len));
-  HI_TRY(pace_begin(c));
-  HI_TRY(prefill_head_impl(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
-                           next_kv_head, next_past_len));
-  return pace_end(c);
+  return hi_prefill_group(c, layer, kv_head, 1, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
+                          next_kv_head, 1, next_past_len);
 }
 
 extern "C" hi_status hi_decode_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
                                     const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
                                     int32_t next_layer, int32_t next_kv_head, int64_t next_past_len) {
-  HI_TRY(check_unit_args(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, 1, out_dev, next_layer,
-                         next_kv_head, next_past_len));
-  HI_TRY(pace_begin(c));
-  HI_TRY(decode_head_impl(c, layer, kv_head, q_dev, k_new_dev, v_new_dev, past_len, out_dev, next_layer,
-                          next_kv_head, next_past_len));
-  return pace_end(c);
+  return hi_decode_group(c, layer, kv_head, 1, q_dev, k_new_dev, v_new_dev, past_len, out_dev, next_layer,
+                         next_kv_head, 1, next_past_len);
 }
 
 extern "C" hi_status hi_sync(hi_ctx* c) {

@@ -39,7 +39,13 @@ __device__ __forceinline__ void dec_issue_block(const char* __restrict__ k, cons
 __global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __restrict__ q, int G,
                                                              const char* __restrict__ k, const char* __restrict__ v,
                                                              int64_t n, float* __restrict__ partials, int part0,
-                                                             float c) {
+                                                             float c, int64_t kv_head_stride,
+                                                             int64_t part_head_stride) {
+  // group launches: blockIdx.y is the head
+  q += (int64_t)blockIdx.y * G * kHeadDim;
+  k += blockIdx.y * kv_head_stride;
+  v += blockIdx.y * kv_head_stride;
+  partials += blockIdx.y * part_head_stride;
   extern __shared__ __attribute__((aligned(1024))) char lds_raw[];
   lds_char* lds = (lds_char*)lds_raw;
   const int lane = lane_id();
@@ -190,7 +196,18 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const uint16_t* __r
                                                              const float* __restrict__ partials, int n_part,
                                                              void* __restrict__ out, int out_fp32, float c,
                                                              uint16_t* __restrict__ k_append,
-                                                             uint16_t* __restrict__ v_append) {
+                                                             uint16_t* __restrict__ v_append,
+                                                             int64_t part_head_stride, int64_t append_head_stride) {
+  // group launches: blockIdx.z is the head
+  q += (int64_t)blockIdx.z * G * kHeadDim;
+  k_new += blockIdx.z * kHeadDim;
+  v_new += blockIdx.z * kHeadDim;
+  partials += blockIdx.z * part_head_stride;
+  out = (char*)out + (int64_t)blockIdx.z * G * kHeadDim * (out_fp32 ? 4 : 2);
+  if (k_append != nullptr) {
+    k_append = (uint16_t*)((char*)k_append + blockIdx.z * append_head_stride);
+    v_append = (uint16_t*)((char*)v_append + blockIdx.z * append_head_stride);
+  }
   __shared__ float red[4];
   __shared__ float red_o[kCombLanes][kCombDims + 1];
   __shared__ float bc;
@@ -249,8 +266,9 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const uint16_t* __r
 static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   // log2(e) / sqrt(128)
 
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
-                                int n_split, void* partials, int part0) {
-  if (n <= 0 || n_split <= 0) { set_last_error("decode partial: empty launch"); return HI_ERR_ARG; }
+                                int n_split, void* partials, int part0, int n_heads, int64_t kv_head_stride,
+                                int64_t part_head_stride) {
+  if (n <= 0 || n_split <= 0 || n_heads < 1) { set_last_error("decode partial: empty launch"); return HI_ERR_ARG; }
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)decode_partial_kernel,
@@ -258,8 +276,9 @@ hi_status launch_decode_partial(void* stream, const void* q, int G, const void* 
     if (e != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
     attr_set = true;
   }
-  hipLaunchKernelGGL(decode_partial_kernel, dim3(n_split), dim3(256), kDecLdsBytes, (hipStream_t)stream,
-                     (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e);
+  hipLaunchKernelGGL(decode_partial_kernel, dim3(n_split, n_heads), dim3(256), kDecLdsBytes, (hipStream_t)stream,
+                     (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e,
+                     kv_head_stride, part_head_stride);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("decode_partial launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
   return HI_OK;
@@ -267,10 +286,11 @@ hi_status launch_decode_partial(void* stream, const void* q, int G, const void* 
 
 hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
                                 const void* partials, int n_part, void* out, int out_fp32, void* k_append,
-                                void* v_append) {
-  hipLaunchKernelGGL(decode_combine_kernel, dim3(G, kHeadDim / kCombDims), dim3(256), 0, (hipStream_t)stream,
+                                void* v_append, int n_heads, int64_t part_head_stride, int64_t append_head_stride) {
+  hipLaunchKernelGGL(decode_combine_kernel, dim3(G, kHeadDim / kCombDims, n_heads), dim3(256), 0, (hipStream_t)stream,
                      (const uint16_t*)q, G, (const uint16_t*)k_new, (const uint16_t*)v_new, (const float*)partials,
-                     n_part, out, out_fp32, kScaleLog2e, (uint16_t*)k_append, (uint16_t*)v_append);
+                     n_part, out, out_fp32, kScaleLog2e, (uint16_t*)k_append, (uint16_t*)v_append, part_head_stride,
+                     append_head_stride);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("decode_combine launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
   return HI_OK;

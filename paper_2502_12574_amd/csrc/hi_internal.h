@@ -28,28 +28,37 @@ inline int prefill_grid_y(int G) { return G > 4 ? G / 4 : 1; }
 constexpr int kPrefillFillWorkgroups = 192;
 constexpr int kPrefillDeepMinWorkgroups = 128;
 constexpr int kPrefillMaxSplit = 8;
-inline int prefill_split(int G, int64_t chunk_len) {
-  const int64_t wgs = ceil_div(chunk_len, 2 * prefill_strip(G)) * prefill_grid_y(G);
+inline int prefill_split(int G, int64_t chunk_len, int n_heads = 1) {
+  const int64_t wgs = ceil_div(chunk_len, 2 * prefill_strip(G)) * prefill_grid_y(G) * n_heads;
   int split = 1;
   while (wgs * split < kPrefillFillWorkgroups && split < kPrefillMaxSplit) split *= 2;
   return split;
 }
 // upper bound, in images of a 4-wave workgroup's state (256 lanes x 66 floats), of the carry any prefill launch
-// of chunks up to C rows can need: split * workgroups stays below 2 * kPrefillFillWorkgroups 8-wave images
-inline int64_t prefill_carry_images(int G, int64_t C) {
-  const int64_t narrow = (ceil_div(C, prefill_strip(G)) + 1) * prefill_grid_y(G);
-  const int64_t split_bound = 2 * (2 * kPrefillFillWorkgroups + prefill_grid_y(G));
+// of chunks up to C rows over groups of up to n_heads heads can need: split * workgroups stays below
+// 2 * kPrefillFillWorkgroups 8-wave images
+inline int64_t prefill_carry_images(int G, int64_t C, int n_heads) {
+  const int64_t narrow = (ceil_div(C, prefill_strip(G)) + 1) * prefill_grid_y(G) * n_heads;
+  const int64_t split_bound = 2 * (2 * kPrefillFillWorkgroups + prefill_grid_y(G) * n_heads);
   return narrow > split_bound ? narrow : split_bound;
+}
+
+// floats of decode partials one head can produce (one launch per staging slice, n_split partials each; a head of
+// a group has 1/n of the slice and 1/n of the partitions, up to rounding - hence the factor 2): the distance
+// between the heads' partials in the workspace
+inline int64_t decode_part_head_stride(int64_t max_context, int64_t slice_tokens, int n_split, int G) {
+  return 2 * (ceil_div(max_context, slice_tokens) + 1) * n_split * G * kPartialFloats;
 }
 
 hi_status validate_problem(const hi_problem* p);
 
 // ---- kernel launchers (defined in the .hip files) ------------------------------------------------------
 struct PrefillSegment {
-  const void* k;      // device, [n][128] bf16
+  const void* k;      // device, [n][128] bf16 (first head of a group)
   const void* v;
   int64_t n;          // rows
   int causal;         // 1: rows are the chunk's own (row j visible to query i iff j <= i)
+  int64_t head_stride = 0;   // bytes from one head's K (V) rows to the next head's, for launches over a head group
 };
 
 // One launch of the prefill kernel over up to two KV segments.  first: start from an empty softmax state
@@ -57,17 +66,24 @@ struct PrefillSegment {
 // variant: 0 = pick by chunk length (the 8-wave kernel, split over the rows if need be, when that fills the chip,
 // else the 4-wave one), 1 = 4-wave kernel (2 LDS stages), 2 = wide kernel (64 positions per wave), 3 = 8-wave
 // kernel; every launch of one unit must use the same variant (the carry layouts differ).
+// n_heads > 1: one launch over a group of KV heads; q is [n_heads][G][chunk_len][128], out likewise, the causal
+// segment's rows [n_heads][chunk_len][128], the other segment's heads head_stride bytes apart.
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& a,
                          const PrefillSegment& b, int first, int last, void* carry, void* out, int out_fp32,
-                         int variant);
+                         int variant, int n_heads = 1);
 
 // Split-KV decode over rows [0, n) of one slice: writes n_split partials starting at partial index part0.
+// n_heads > 1: q is [n_heads][G][128], the heads' K (V) rows kv_head_stride bytes apart, their partials
+// part_head_stride floats apart.
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
-                                int n_split, void* partials, int part0);
+                                int n_split, void* partials, int part0, int n_heads = 1, int64_t kv_head_stride = 0,
+                                int64_t part_head_stride = 0);
 // Merge n_part partials with the token's own row and write out[G][128]; if k_append/v_append are not null the
-// token's K/V row is also copied there (device rows of an HBM-resident cache).
+// token's K/V row is also copied there (device rows of an HBM-resident cache; heads append_head_stride bytes
+// apart).  n_heads > 1: q and out are [n_heads][G][128], k_new / v_new [n_heads][128].
 hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
                                 const void* partials, int n_part, void* out, int out_fp32, void* k_append,
-                                void* v_append);
+                                void* v_append, int n_heads = 1, int64_t part_head_stride = 0,
+                                int64_t append_head_stride = 0);
 
 }  // namespace hi

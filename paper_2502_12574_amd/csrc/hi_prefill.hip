@@ -44,7 +44,22 @@ struct PrefillArgs {
   int G, C, first, last, out_fp32;
   float c;                // log2(e) / sqrt(d)
   int split;              // 8-wave kernel: workgroups along grid z share a block of positions and divide the rows
+  int gy;                 // grid y per head; blockIdx.y / gy is the head of a group launch
+  int64_t a_head_stride;  // bytes between the heads' rows in the past segment
 };
+
+// Group launches: point the arguments at this workgroup's head; returns blockIdx.y within the head.
+__device__ __forceinline__ int pf_select_head(PrefillArgs& a) {
+  const int head = blockIdx.y / a.gy;
+  const int64_t rows = (int64_t)head * a.C;
+  a.q += rows * a.G * kHeadDim;
+  a.out = (char*)a.out + rows * a.G * kHeadDim * (a.out_fp32 ? 4 : 2);
+  a.ka += head * a.a_head_stride;
+  a.va += head * a.a_head_stride;
+  a.kb += rows * kRowBytes;
+  a.vb += rows * kRowBytes;
+  return blockIdx.y - head * a.gy;
+}
 
 __device__ __forceinline__ int swz_k(int row) { return row & 15; }
 __device__ __forceinline__ int swz_v(int row) { return ((row & 3) << 2) | (row & 2); }
@@ -369,7 +384,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   const int gl = a.G < 4 ? a.G : 4;
   const int strip = 32 * (4 / gl);
   const int bx = gridDim.x - 1 - blockIdx.x;        // deepest causal rows are dispatched first
-  const int g = blockIdx.y * 4 + (wave % gl);
+  const int g = pf_select_head(a) * 4 + (wave % gl);
   const int i0 = bx * strip + 32 * (wave / gl);     // first query position of this wave
   const int i_hi = bx * strip + strip - 1;          // last query position of the workgroup
   int qi = i0 + col;
@@ -534,7 +549,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   const int gl = a.G < 4 ? a.G : 4;
   const int strip = 32 * (kPdWaves / gl);
   const int bx = gridDim.x - 1 - blockIdx.x;
-  const int g = blockIdx.y * 4 + (wave % gl);
+  const int g = pf_select_head(a) * 4 + (wave % gl);
   const int i0 = bx * strip + 32 * (wave / gl);
   const int i_hi = bx * strip + strip - 1;
   int qi = i0 + col;
@@ -846,7 +861,7 @@ __global__ __launch_bounds__(512) void prefill_merge_kernel(PrefillArgs a) {
   const int gl = a.G < 4 ? a.G : 4;
   const int strip = 32 * (kPdWaves / gl);
   const int bx = gridDim.x - 1 - blockIdx.x;
-  const int g = blockIdx.y * 4 + (wave % gl);
+  const int g = pf_select_head(a) * 4 + (wave % gl);
   const int my_i = bx * strip + 32 * (wave / gl) + col;
   constexpr int kLanes = kPdWaves * 64;
   const int64_t wg_per_split = (int64_t)gridDim.y * gridDim.x;
@@ -911,7 +926,7 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel_wide(PrefillArgs a) {
   const int gl = a.G < 4 ? a.G : 4;
   const int strip = 64 * (4 / gl);
   const int bx = gridDim.x - 1 - blockIdx.x;
-  const int g = blockIdx.y * 4 + (wave % gl);
+  const int g = pf_select_head(a) * 4 + (wave % gl);
   const int i0 = bx * strip + 64 * (wave / gl);     // first query position of this wave
   const int i_hi = bx * strip + strip - 1;
   int my_i[2];
@@ -1164,7 +1179,8 @@ static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   //
 
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& sa,
                          const PrefillSegment& sb, int first, int last, void* carry, void* out, int out_fp32,
-                         int variant) {
+                         int variant, int n_heads) {
+  if (n_heads < 1 || (n_heads > 1 && variant == 2)) { set_last_error("prefill launch: head group"); return HI_ERR_UNSUPPORTED; }
   if (chunk_len < 1 || !(G == 1 || G == 2 || G == 4 || G == 8)) { set_last_error("prefill launch: bad shape"); return HI_ERR_ARG; }
   if (sa.causal || (sb.n > 0 && !sb.causal)) { set_last_error("prefill launch: segment order"); return HI_ERR_ARG; }
   if (sa.n + sb.n <= 0) { set_last_error("prefill launch: no rows"); return HI_ERR_ARG; }
@@ -1178,9 +1194,11 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   a.c = kScaleLog2e;
   const int strip = prefill_strip(G);
   const int gy = prefill_grid_y(G);
+  a.gy = gy;
+  a.a_head_stride = sa.head_stride;
   const bool wide = variant == 2;
-  const int split = prefill_split(G, chunk_len);
-  const int64_t deep_wgs = ceil_div(chunk_len, 2 * strip) * gy;
+  const int split = prefill_split(G, chunk_len, n_heads);
+  const int64_t deep_wgs = ceil_div(chunk_len, 2 * strip) * gy * n_heads;
   const bool deep = variant == 3 || (variant == 0 && deep_wgs * split >= kPrefillDeepMinWorkgroups);
   a.split = 1;
   if (wide || deep) {
@@ -1199,7 +1217,7 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
       hipLaunchKernelGGL(prefill_kernel_wide, grid, dim3(kWgThreads), kPwLdsBytes, (hipStream_t)stream, a);
     } else {
       a.split = split;
-      dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)gy, (unsigned)split);
+      dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)(gy * n_heads), (unsigned)split);
       hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
       if (split > 1 && last) {
         hipError_t e1 = hipGetLastError();
@@ -1208,7 +1226,7 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
       }
     }
   } else {
-    dim3 grid((unsigned)ceil_div(chunk_len, strip), (unsigned)gy);
+    dim3 grid((unsigned)ceil_div(chunk_len, strip), (unsigned)(gy * n_heads));
     hipLaunchKernelGGL(prefill_kernel, grid, dim3(kWgThreads), 0, (hipStream_t)stream, a);
   }
   hipError_t e = hipGetLastError();

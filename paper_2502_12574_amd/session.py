@@ -48,6 +48,17 @@ class Session:
         nl, nh, npast = nxt if nxt is not None else (-1, 0, 0)
         return hb.hi_decode_head(self.ctx, layer, head, q, k_new, v_new, past_len, out, nl, nh, npast)
 
+    def prefill_group(self, layer, head, n_heads, q, k_new, v_new, past_len, out, nxt=None):
+        """q [n_heads][G][C][128], k_new / v_new [n_heads][C][128]; nxt = (layer, first head, n_heads, past) or None"""
+        nl, nh, nn, npast = nxt if nxt is not None else (-1, 0, 1, 0)
+        return hb.hi_prefill_group(self.ctx, layer, head, n_heads, q, k_new, v_new, past_len, k_new.shape[1], out,
+                                   nl, nh, nn, npast)
+
+    def decode_group(self, layer, head, n_heads, q, k_new, v_new, past_len, out, nxt=None):
+        """q [n_heads][G][128], k_new / v_new [n_heads][128]"""
+        nl, nh, nn, npast = nxt if nxt is not None else (-1, 0, 1, 0)
+        return hb.hi_decode_group(self.ctx, layer, head, n_heads, q, k_new, v_new, past_len, out, nl, nh, nn, npast)
+
     def sync(self):
         hb.hi_sync(self.ctx)
 

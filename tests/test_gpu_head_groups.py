@@ -1,0 +1,117 @@
+"""Head groups (Section 4, adaptive head-wise offloading): several KV heads per call give the same results as one
+head per call, element by element against the fp64 oracle, in both modes, for prefill and decode."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from paper_2502_12574_amd import binding as hb
+from paper_2502_12574_amd import synth
+from paper_2502_12574_amd.session import Session
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_L2 = 1e-2, 5e-3
+
+
+def check(got, ref, what):
+    got = got.detach().to("cpu").to(torch.float64).numpy()
+    assert got.shape == ref.shape and np.isfinite(got).all(), what
+    err = float(np.abs(got - ref).max())
+    rel = float(np.sqrt(((got - ref) ** 2).sum() / (ref ** 2).sum()))
+    assert err <= MAX_ABS and rel <= REL_L2, (what, err, rel)
+
+
+def run(mode, H, G, S, C, n_decode, group, seed, flags=0):
+    """Chunked prefill then decode steps of one layer with `group` heads per call; returns outputs per head."""
+    dev = "cuda:0"
+    n_tok = S + n_decode
+    with Session(1, H, G, n_tok, C, mode=mode, out_fp32=1) as ss:
+        if flags:
+            hb.hi_ctx_set_flags(ss.ctx, flags)
+        pre = [[] for _ in range(H)]
+        dec = [[] for _ in range(H)]
+        with torch.cuda.stream(ss.s_compute):
+            Q = torch.stack([synth.draw_q(seed, 0, a, 0, n_tok, device=dev) for a in range(H * G)]).view(H, G, n_tok, 128)
+            K = torch.stack([synth.draw_k(seed, 0, h, 0, n_tok, device=dev) for h in range(H)])
+            V = torch.stack([synth.draw_v(seed, 0, h, 0, n_tok, device=dev) for h in range(H)])
+            units = []
+            for p in range(0, S, C):
+                for h0 in range(0, H, group):
+                    units.append((p, min(C, S - p), h0, min(group, H - h0)))
+            for u, (p, n, h0, nh) in enumerate(units):
+                q = Q[h0:h0 + nh, :, p:p + n].contiguous()
+                k = K[h0:h0 + nh, p:p + n].contiguous()
+                v = V[h0:h0 + nh, p:p + n].contiguous()
+                out = torch.empty(nh, G, n, 128, dtype=torch.float32, device=dev)
+                nxt = None
+                if u + 1 < len(units):
+                    np_, _, nh0, nnh = units[u + 1]
+                    nxt = (0, nh0, nnh, np_)
+                ss.prefill_group(0, h0, nh, q, k, v, p, out, nxt)
+                for j in range(nh):
+                    pre[h0 + j].append(out[j])
+            for t in range(n_decode):
+                p = S + t
+                for h0 in range(0, H, group):
+                    nh = min(group, H - h0)
+                    q = Q[h0:h0 + nh, :, p].contiguous()
+                    k = K[h0:h0 + nh, p].contiguous()
+                    v = V[h0:h0 + nh, p].contiguous()
+                    out = torch.empty(nh, G, 128, dtype=torch.float32, device=dev)
+                    ss.decode_group(0, h0, nh, q, k, v, p, out, None)
+                    for j in range(nh):
+                        dec[h0 + j].append(out[j])
+        ss.sync()
+        cache = ss.cache_view()[0].to("cpu").clone()          # [H][2][S_max][128]
+        stats = ss.stats()
+    pre = [torch.cat(x, dim=1).cpu() for x in pre]
+    dec = [torch.stack(x, dim=1).cpu() for x in dec] if n_decode else None
+    return pre, dec, cache, Q.cpu(), K.cpu(), V.cpu(), stats
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
+@pytest.mark.parametrize("group", [2, 3, 4])
+def test_groups_match_oracle_and_single_head_calls(mode, group):
+    H, G, S, C, nd, seed = 4, 4, 1350, 200, 3, 6100
+    pre, dec, cache, Q, K, V, stats = run(mode, H, G, S, C, nd, group, seed)
+    pre1, dec1, cache1, *_ = run(mode, H, G, S, C, nd, 1, seed)
+    assert torch.equal(cache, cache1)
+    for h in range(H):
+        ref = oa.attn_head(synth.to_f64(Q[h]), synth.to_f64(K[h]), synth.to_f64(V[h]))     # [G][S+nd][128]
+        for g in range(G):
+            check(pre[h][g], ref[g, :S], f"prefill group {group} head {h} q {g}")
+            check(dec[h][g], ref[g, S:], f"decode group {group} head {h} q {g}")
+        # the grouping only changes where the rows are cut into slices and splits (hence which bf16 roundings of
+        # the probabilities meet), not the result
+        assert (pre[h] - pre1[h]).abs().max() < 4e-3
+        assert (dec[h] - dec1[h]).abs().max() < 4e-3
+        assert torch.equal(cache[h, 0, :S + nd], K[h]) and torch.equal(cache[h, 1, :S + nd], V[h])
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
+def test_all_heads_in_one_group_with_the_8wave_kernel(mode):
+    # group of all 8 heads = layer-wise granularity; forced 8-wave kernel (split-KV over a group launch)
+    H, G, S, C, seed = 8, 4, 4700, 520, 6200
+    pre, _, cache, Q, K, V, stats = run(mode, H, G, S, C, 0, 8, seed, flags=hb.HI_FLAG_PREFILL_DEEP)
+    for h in (0, 3, 7):
+        ref = oa.attn_head(synth.to_f64(Q[h]), synth.to_f64(K[h]), synth.to_f64(V[h]))
+        for g in range(G):
+            check(pre[h][g], ref[g], f"8-head group, head {h} q {g}")
+    if mode == hb.HI_MODE_OFFLOAD:
+        assert stats.peak_staging_bytes <= (S * 512)      # still at most one head's worth of K/V in HBM
+
+
+def test_group_argument_errors():
+    with Session(1, 4, 4, 512, 64, mode=hb.HI_MODE_OFFLOAD, out_fp32=1) as ss:
+        dev = "cuda:0"
+        q = torch.zeros(4, 4, 64, 128, dtype=torch.bfloat16, device=dev)
+        k = torch.zeros(4, 64, 128, dtype=torch.bfloat16, device=dev)
+        out = torch.zeros(4, 4, 64, 128, dtype=torch.float32, device=dev)
+        assert hb.hi_prefill_group(ss.ctx, 0, 2, 3, q, k, k, 0, 64, out, check=False) == hb.HI_ERR_ARG      # heads 2..4
+        assert hb.hi_prefill_group(ss.ctx, 0, 0, 0, q, k, k, 0, 64, out, check=False) == hb.HI_ERR_ARG
+        # 512-token budget -> 128-row slices: 4 heads x 64 rows do not fit
+        assert ss.plan.slice_tokens == 128
+        assert hb.hi_prefill_group(ss.ctx, 0, 0, 4, q, k, k, 0, 64, out, check=False) == hb.HI_ERR_HBM_BUDGET
+        assert hb.hi_prefill_group(ss.ctx, 0, 0, 2, q, k, k, 0, 64, out, -1, 0, 1, 0, check=False) == hb.HI_OK
+        ss.sync()
