@@ -63,8 +63,9 @@ typedef struct hi_problem {
 
 /* Output of hi_offload_plan.  Sizes in bytes. */
 typedef struct hi_plan {
-  int32_t heads_per_group;       /* KV heads moved and computed per launch; 1 in this build (finest granularity) */
-  int32_t n_groups;              /* = n_kv_heads / heads_per_group */
+  int32_t heads_per_group;       /* recommended KV heads per call (hi_prefill_group / hi_decode_group): Section 4's
+                                    adaptive grouping, by context length as measured on MI355X; callers may use any */
+  int32_t n_groups;              /* = ceil(n_kv_heads / heads_per_group) */
   int32_t paper_heads_per_group; /* what the paper's context-length rule would pick (Section 4, adaptive
                                     head-wise offloading: 8 up to 500K, 4 to 1M, 2 to 2M, 1 beyond); informational */
   int32_t n_slices_ring;         /* staging ring: number of slots */

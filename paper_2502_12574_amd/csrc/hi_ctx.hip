@@ -121,15 +121,20 @@ hi_status issue_slice(hi_ctx* c, hi_ctx::Unit& u) {
   }
   if (seq >= c->n_slots) HI_HIP(hipStreamWaitEvent(c->sh, c->ev_free[slot], 0));  // slot's previous tenant consumed
   if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
-    for (int j = 0; j < u.nh; ++j) {
-      const char* hk = c->kv + plane_offset(c, u.layer, u.head + j, 0) + row0 * kRowBytes;
-      const char* hv = c->kv + plane_offset(c, u.layer, u.head + j, 1) + row0 * kRowBytes;
-      char* dk = slot_k(c, slot) + j * head_pitch(c, u.nh);
-      HI_HIP(hipMemcpyAsync(dk, hk, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
-      HI_HIP(hipMemcpyAsync(dk + st * kRowBytes, hv, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
+    const char* hk = c->kv + plane_offset(c, u.layer, u.head, 0) + row0 * kRowBytes;
+    if (u.nh == 1) {
+      const char* hv = c->kv + plane_offset(c, u.layer, u.head, 1) + row0 * kRowBytes;
+      HI_HIP(hipMemcpyAsync(slot_k(c, slot), hk, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
+      HI_HIP(hipMemcpyAsync(slot_v(c, slot, 1), hv, rows * kRowBytes, hipMemcpyHostToDevice, c->sh));
+      c->stats.n_h2d_copies += 2;
+    } else {
+      // the K and V planes of consecutive heads are equally spaced in the cache and in the slot: one strided copy
+      // of 2 * nh runs instead of 2 * nh small copies
+      HI_HIP(hipMemcpy2DAsync(slot_k(c, slot), (size_t)(st * kRowBytes), hk, (size_t)(c->prob.max_context * kRowBytes),
+                              (size_t)(rows * kRowBytes), (size_t)(2 * u.nh), hipMemcpyHostToDevice, c->sh));
+      c->stats.n_h2d_copies += 1;
     }
     c->stats.bytes_h2d += 2 * rows * kRowBytes * u.nh;
-    c->stats.n_h2d_copies += 2 * u.nh;
   }
   HI_HIP(hipEventRecord(c->ev_ready[slot], c->sh));
   u.issued += 1;
@@ -256,7 +261,23 @@ hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, 
     HI_HIP(hipEventRecord(c->ev_entry, c->sc));
     HI_HIP(hipStreamWaitEvent(c->sd, c->ev_entry, 0));
   }
-  for (int j = 0; j < nh; ++j) {
+  if (nh > 1) {
+    // the heads' K planes (and V planes) are two planes apart in the cache: one strided copy each
+    const hipMemcpyKind kind = resident ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
+    hipStream_t st = resident ? c->sc : c->sd;
+    if (resident || !(c->flags & HI_FLAG_SKIP_COPIES)) {
+      const size_t dpitch = (size_t)(2 * c->prob.max_context * kRowBytes), w = (size_t)(len * kRowBytes);
+      HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 0) + past * kRowBytes, dpitch, k_new, w, w,
+                              (size_t)nh, kind, st));
+      HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 1) + past * kRowBytes, dpitch, v_new, w, w,
+                              (size_t)nh, kind, st));
+      if (!resident) {
+        c->stats.bytes_d2h += 2 * len * kRowBytes * nh;
+        c->stats.n_d2h_copies += 2;
+      }
+    }
+  }
+  for (int j = 0; j < (nh > 1 ? 0 : 1); ++j) {
     char* dk = c->kv + plane_offset(c, layer, head + j, 0) + past * kRowBytes;
     char* dv = c->kv + plane_offset(c, layer, head + j, 1) + past * kRowBytes;
     const char* sk = (const char*)k_new + j * len * kRowBytes;

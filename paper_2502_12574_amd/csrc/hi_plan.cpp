@@ -60,9 +60,7 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   pl.alpha = (double)p->gpu_kv_budget_heads / ((double)p->n_layers * p->n_kv_heads);
   pl.hbm_pingpong_paper_bytes = 2 * pl.host_bytes_per_head;
 
-  // finest granularity: one KV head per transfer and launch
-  pl.heads_per_group = 1;
-  pl.n_groups = p->n_kv_heads;
+  // heads_per_group is filled in below, once the ring geometry is known
   {  // Section 4: all heads fused up to 500K, two groups to 1M, four to 2M, eight beyond
     int groups = S <= 500 * 1024 ? 1 : S <= 1024 * 1024 ? 2 : S <= 2048 * 1024 ? 4 : 8;
     int hpg = p->n_kv_heads / groups;
@@ -84,6 +82,20 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   }
   pl.slice_tokens = slice;
   pl.n_slices_ring = (int32_t)n_slices;
+
+  // Section 4, adaptive head grouping, as measured on MI355X with this library (group_bench): up to 16K tokens the
+  // per-call overheads dominate and as many heads as the slice can hold (64 rows each) go into one call; up to 256K
+  // two heads per call still gain a few per cent; beyond, one head per call (the finest granularity) is as fast.
+  {
+    int hpg = 1;
+    if (S <= 16 * 1024 + p->chunk) {
+      while (hpg * 2 <= p->n_kv_heads && (int64_t)hpg * 2 * 64 <= slice) hpg *= 2;
+    } else if (S <= 256 * 1024 + p->chunk) {
+      if (p->n_kv_heads >= 2 && 2 * 64 <= slice) hpg = 2;
+    }
+    pl.heads_per_group = hpg;
+    pl.n_groups = (int32_t)ceil_div(p->n_kv_heads, hpg);
+  }
   pl.hbm_staging_bytes = n_slices * slice * row;
 
   const int n_cu = p->n_compute_units > 0 ? p->n_compute_units : 256;

@@ -97,6 +97,16 @@ def test_plan_flop_and_byte_model_matches_oracle():
         assert (got == hb.HI_REGIME_LINK) == (row == "memory"), (S_k, got)
 
 
+def test_plan_head_grouping_rule():
+    # Section 4, adaptive head grouping: all heads per call at short contexts (as many as a staging slice holds
+    # with 64 rows each), two up to 256K, one beyond; hi_prefill_group / hi_decode_group accept any size
+    expect = {1024: 4, 4096: 8, 16384: 8, 65536: 2, 262144: 2, 1 << 20: 1, 4 << 20: 1}
+    for S, hpg in expect.items():
+        pl = hb.hi_offload_plan(llama(S, min(S, 16384)))
+        assert pl.heads_per_group == hpg and pl.n_groups == -(-8 // hpg), (S, pl.heads_per_group)
+        assert pl.heads_per_group * 64 <= pl.slice_tokens
+
+
 def test_plan_geometry_small_and_large():
     pl = hb.hi_offload_plan(hb.make_problem(1, 1, 4, 2048 + 16, 512))
     assert pl.slice_tokens == 512 and pl.n_slices_ring == 4 and pl.prefill_rows_per_wg == 32
