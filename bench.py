@@ -33,9 +33,9 @@ PEAK_MFMA_TFLOPS = 2500.0     # dense bf16
 PEAK_HBM_GBPS = 8000.0
 PEAK_LINK_GBPS = 64.0         # PCIe Gen5 x16, one direction
 # HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/*_pmc.md), each scaled by
-# what the same counter read for a 1 GiB copy kernel in the same run: a prefill launch over one 131072-row
+# what the same counter read for a 1 GiB copy kernel in the same run: a prefill launch over one 262144-row
 # staging slice with chunk 16384, and the resident decode launch over 1M rows (reads each K/V byte once).
-PREFILL_TRAFFIC_PER_LAUNCH = 591.5 * 2 ** 20 + 16 * 2 ** 20
+PREFILL_TRAFFIC_PER_LAUNCH = 1103.8 * 2 ** 20 + 16 * 2 ** 20
 DECODE_TRAFFIC_PER_ROW = 512.0
 
 
