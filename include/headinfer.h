@@ -50,11 +50,13 @@ typedef struct hi_problem {
   int32_t head_dim;            /* D_h; 128 */
   int64_t max_context;         /* S_max: rows pre-allocated per head in the cache */
   int32_t chunk;               /* C: largest number of rows one hi_prefill_head call may carry */
-  int32_t gpu_kv_budget_heads; /* HBM KV budget, in whole-head equivalents of S_max rows (>= 1) */
+  int32_t gpu_kv_budget_heads; /* HBM KV budget, in whole-head equivalents of S_max rows (>= 1 + resident_heads) */
   int32_t dtype_bytes;         /* 2 (bf16) */
   int32_t out_fp32;            /* 0: outputs are bf16, 1: outputs are fp32 */
   int32_t n_compute_units;     /* 0 = 256 (MI355X) */
-  int32_t reserved0;
+  int32_t resident_heads;      /* Algorithm 1's H_on: the first resident_heads (layer, KV head) pairs, in layer-major
+                                  order, keep their K/V in HBM and never cross the link (offload mode); the rest of
+                                  the budget is the staging ring of the offloaded heads.  0 = none */
   int64_t host_mem_limit_bytes;/* 0 = no check */
   double link_GBps;            /* host link peak used by the regime prediction; 0 = 64 (PCIe Gen5 x16) */
   double hbm_GBps;             /* 0 = 8000 */
@@ -74,7 +76,8 @@ typedef struct hi_plan {
   int32_t prefill_rows_per_wg;   /* query positions one prefill workgroup covers */
   int64_t host_bytes_per_head;   /* Eq. 11: 2 * S_max * D_h * sizeof */
   int64_t host_bytes_total;      /* Eq. 4:  L * H * host_bytes_per_head */
-  int64_t hbm_staging_bytes;     /* n_slices_ring * slice_tokens * 2 * D_h * sizeof  (<= budget * host_bytes_per_head) */
+  int64_t hbm_staging_bytes;     /* the ring, n_slices_ring * slice_tokens * 2 * D_h * sizeof, followed by the resident
+                                    heads' K/V (hbm_resident_bytes at hbm_resident_offset); <= budget * host_bytes_per_head */
   int64_t hbm_pingpong_paper_bytes; /* the paper's two-whole-heads ping-pong buffer, for comparison (Appendix A.3) */
   int64_t workspace_bytes;       /* fp32 (m, l, O) carry of a prefill unit + split-KV partials of a decode unit */
   int64_t ws_partials_offset;    /* byte offset of the decode partials inside the workspace */
@@ -85,6 +88,8 @@ typedef struct hi_plan {
   double t_comp_prefill_s, t_link_prefill_s, t_hbm_prefill_s; /* Section 5: T ~ max(T_comp, T_mem) */
   double t_comp_decode_s, t_link_decode_s, t_hbm_decode_s;
   int32_t regime_prefill, regime_decode;                      /* HI_REGIME_* with offloading */
+  int64_t hbm_resident_offset;   /* inside the staging buffer: [resident head][K|V][S_max][D_h] */
+  int64_t hbm_resident_bytes;    /* resident_heads * host_bytes_per_head */
 } hi_plan;
 
 typedef struct hi_stats {
@@ -114,7 +119,10 @@ hi_status hi_offload_plan(const hi_problem* problem, hi_plan* plan);
  *                                    [layer][kv_head][K|V][S_max][D_h] bf16 (each head's K rows contiguous, then
  *                                    its V rows: the head-wise partition of Eq. 7-8);
  *                  HI_MODE_RESIDENT: DEVICE memory of the same size and layout (no copies; HBM-roofline runs).
- *   hbm_staging    DEVICE, plan.hbm_staging_bytes (ignored in resident mode; may be null there).
+ *   hbm_staging    DEVICE, plan.hbm_staging_bytes (ignored in resident mode; may be null there).  With
+ *                  hi_problem.resident_heads > 0 its tail holds those heads' K/V: units of a resident head read
+ *                  and append there, move nothing over the link and leave the host cache rows of that head
+ *                  untouched; a head group must be all resident or all offloaded.
  *   hbm_workspace  DEVICE, plan.workspace_bytes.
  *   stream_*       hipStream_t handles (as void*), all at default priority.  Kernels run on stream_compute,
  *                  host-to-device prefetches on stream_h2d, write-backs on stream_d2h.

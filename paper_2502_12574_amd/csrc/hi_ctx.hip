@@ -91,6 +91,17 @@ inline int64_t rows_of(const hi_ctx* c, int nh) {
   return r < 64 ? 64 : r;
 }
 inline int64_t head_pitch(const hi_ctx* c, int nh) { return rows_of(c, nh) * 2 * kRowBytes; }
+// Algorithm 1, "if h in H_on": the unit's K/V live in HBM (the whole cache in resident mode; the first
+// resident_heads (layer, head) pairs, kept behind the ring in the staging buffer, in offload mode)
+inline bool unit_resident(const hi_ctx* c, int layer, int head) {
+  return c->mode == HI_MODE_RESIDENT || (int64_t)layer * c->prob.n_kv_heads + head < c->prob.resident_heads;
+}
+inline char* res_plane(const hi_ctx* c, int layer, int head, int which) {
+  if (c->mode == HI_MODE_RESIDENT) return c->kv + plane_offset(c, layer, head, which);
+  const int64_t plane = c->prob.max_context * kRowBytes;
+  return c->staging + c->plan.hbm_resident_offset + (((int64_t)layer * c->prob.n_kv_heads + head) * 2 + which) * plane;
+}
+
 inline char* slot_k(const hi_ctx* c, int slot) { return c->staging + (int64_t)slot * c->slice_tokens * 2 * kRowBytes; }
 inline char* slot_v(const hi_ctx* c, int slot, int nh) { return slot_k(c, slot) + rows_of(c, nh) * kRowBytes; }
 
@@ -216,6 +227,11 @@ hi_status check_unit_args(const hi_ctx* c, int layer, int head, int nh, const vo
   if (!q || !k || !v || !out) { set_last_error("null buffer"); return HI_ERR_ARG; }
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) { set_last_error("buffers must be 16-byte aligned"); return HI_ERR_ARG; }
   if (layer < 0 || layer >= c->prob.n_layers || head < 0 || nh < 1 || head + nh > c->prob.n_kv_heads) { set_last_error("layer/head out of range"); return HI_ERR_ARG; }
+  if (unit_resident(c, layer, head) != unit_resident(c, layer, head + nh - 1) ||
+      (next_layer >= 0 && unit_resident(c, next_layer, next_head) != unit_resident(c, next_layer, next_head + next_nh - 1))) {
+    set_last_error("a head group must be all HBM-resident or all offloaded");
+    return HI_ERR_ARG;
+  }
   if (c->mode == HI_MODE_OFFLOAD && ((int64_t)nh * 64 > c->slice_tokens || (next_layer >= 0 && (int64_t)next_nh * 64 > c->slice_tokens))) {
     set_last_error("a staging slice of %lld rows cannot hold 64 rows of each head of the group", (long long)c->slice_tokens);
     return HI_ERR_HBM_BUDGET;
@@ -249,7 +265,7 @@ hi_status adopt_unit(hi_ctx* c, int layer, int head, int nh, int64_t past) {
 // k_new / v_new: [nh][len][128]
 hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, const void* v_new, int64_t past,
                      int64_t len) {
-  const bool resident = c->mode == HI_MODE_RESIDENT;
+  const bool resident = unit_resident(c, layer, head);
   if (!resident) {
     // the new rows were produced by earlier work on the compute stream
     HI_HIP(hipEventRecord(c->ev_entry, c->sc));
@@ -261,10 +277,10 @@ hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, 
     hipStream_t st = resident ? c->sc : c->sd;
     if (resident || !(c->flags & HI_FLAG_SKIP_COPIES)) {
       const size_t dpitch = (size_t)(2 * c->prob.max_context * kRowBytes), w = (size_t)(len * kRowBytes);
-      HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 0) + past * kRowBytes, dpitch, k_new, w, w,
-                              (size_t)nh, kind, st));
-      HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 1) + past * kRowBytes, dpitch, v_new, w, w,
-                              (size_t)nh, kind, st));
+      char* dk = resident ? res_plane(c, layer, head, 0) : c->kv + plane_offset(c, layer, head, 0);
+      char* dv = resident ? res_plane(c, layer, head, 1) : c->kv + plane_offset(c, layer, head, 1);
+      HI_HIP(hipMemcpy2DAsync(dk + past * kRowBytes, dpitch, k_new, w, w, (size_t)nh, kind, st));
+      HI_HIP(hipMemcpy2DAsync(dv + past * kRowBytes, dpitch, v_new, w, w, (size_t)nh, kind, st));
       if (!resident) {
         c->stats.bytes_d2h += 2 * len * kRowBytes * nh;
         c->stats.n_d2h_copies += 2;
@@ -272,8 +288,8 @@ hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, 
     }
   }
   for (int j = 0; j < (nh > 1 ? 0 : 1); ++j) {
-    char* dk = c->kv + plane_offset(c, layer, head + j, 0) + past * kRowBytes;
-    char* dv = c->kv + plane_offset(c, layer, head + j, 1) + past * kRowBytes;
+    char* dk = (resident ? res_plane(c, layer, head + j, 0) : c->kv + plane_offset(c, layer, head + j, 0)) + past * kRowBytes;
+    char* dv = (resident ? res_plane(c, layer, head + j, 1) : c->kv + plane_offset(c, layer, head + j, 1)) + past * kRowBytes;
     const char* sk = (const char*)k_new + j * len * kRowBytes;
     const char* sv = (const char*)v_new + j * len * kRowBytes;
     if (resident) {
@@ -389,6 +405,31 @@ extern "C" hi_status hi_ctx_set_run_ahead(hi_ctx* c, int32_t units) {
   return HI_OK;
 }
 
+// The unit a call names as its successor (not valid: no hint, or an HBM-resident unit, which has nothing to fetch)
+static hi_ctx::Unit hinted_unit(const hi_ctx* c, int32_t next_layer, int32_t next_kv_head, int32_t next_nh,
+                                int64_t next_past_len) {
+  hi_ctx::Unit next;
+  if (next_layer >= 0 && !unit_resident(c, next_layer, next_kv_head)) {
+    next.valid = true;
+    next.layer = next_layer; next.head = next_kv_head; next.nh = next_nh; next.past = next_past_len;
+    next.n_slices = slices_of(c, next_past_len, next_nh);
+  }
+  return next;
+}
+
+// An HBM-resident unit of an offloading context runs: start (or keep) the prefetch of the hinted offloaded unit
+static hi_status prefetch_hint(hi_ctx* c, const hi_ctx::Unit& next) {
+  if (c->mode != HI_MODE_OFFLOAD || !next.valid) return HI_OK;
+  auto& p = c->pend;
+  if (p.valid && (p.layer != next.layer || p.head != next.head || p.nh != next.nh || p.past != next.past)) {
+    for (int64_t i = 0; i < p.issued; ++i) HI_TRY(retire_slice(c, (int)((p.first_seq + i) % c->n_slots)));
+    p.valid = false;
+  }
+  if (!p.valid) p = next;
+  hi_ctx::Unit none;
+  return top_up(c, none, p);
+}
+
 // One prefill unit: a group of nh KV heads starting at kv_head (nh = 1: the paper's finest granularity).
 static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t nh, const void* q_dev,
                               const void* k_new_dev, const void* v_new_dev, int64_t past_len, int32_t chunk_len,
@@ -408,9 +449,11 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
     return HI_OK;
   };
 
-  if (c->mode == HI_MODE_RESIDENT) {
-    PrefillSegment pastseg{c->kv + plane_offset(c, layer, kv_head, 0), c->kv + plane_offset(c, layer, kv_head, 1),
-                           past_len, 0, 2 * c->prob.max_context * kRowBytes};
+  hi_ctx::Unit next = hinted_unit(c, next_layer, next_kv_head, next_nh, next_past_len);
+  if (unit_resident(c, layer, kv_head)) {
+    PrefillSegment pastseg{res_plane(c, layer, kv_head, 0), res_plane(c, layer, kv_head, 1), past_len, 0,
+                           2 * c->prob.max_context * kRowBytes};
+    HI_TRY(prefetch_hint(c, next));
     if (run) HI_TRY(launch(pastseg, diag, 1, 1));
     return write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, chunk_len);
   }
@@ -418,12 +461,6 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
   HI_TRY(adopt_unit(c, layer, kv_head, nh, past_len));
   HI_TRY(write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, chunk_len));
 
-  hi_ctx::Unit next;
-  if (next_layer >= 0) {
-    next.valid = true;
-    next.layer = next_layer; next.head = next_kv_head; next.nh = next_nh; next.past = next_past_len;
-    next.n_slices = slices_of(c, next_past_len, next_nh);
-  }
   hi_ctx::Unit& cur = c->pend;
   const int64_t ns = cur.n_slices;
   const int64_t st = rows_of(c, nh);
@@ -473,18 +510,19 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
     return HI_OK;
   };
 
-  if (c->mode == HI_MODE_RESIDENT) {
+  hi_ctx::Unit next = hinted_unit(c, next_layer, next_kv_head, next_nh, next_past_len);
+  if (unit_resident(c, layer, kv_head)) {
     const int64_t plane2 = 2 * c->prob.max_context * kRowBytes;
     int n_part = 0;
+    HI_TRY(prefetch_hint(c, next));
     if (run) {
       if (past_len > 0) {
         n_part = splits_for(past_len);
-        HI_TRY(partial(c->kv + plane_offset(c, layer, kv_head, 0), c->kv + plane_offset(c, layer, kv_head, 1), past_len,
-                       n_part, 0, plane2));
+        HI_TRY(partial(res_plane(c, layer, kv_head, 0), res_plane(c, layer, kv_head, 1), past_len, n_part, 0, plane2));
       }
       HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32,
-                                   c->kv + plane_offset(c, layer, kv_head, 0) + past_len * kRowBytes,
-                                   c->kv + plane_offset(c, layer, kv_head, 1) + past_len * kRowBytes, nh, part_stride,
+                                   res_plane(c, layer, kv_head, 0) + past_len * kRowBytes,
+                                   res_plane(c, layer, kv_head, 1) + past_len * kRowBytes, nh, part_stride,
                                    plane2));
       c->stats.n_combine_kernels += 1;
       return HI_OK;
@@ -494,12 +532,6 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
 
   HI_TRY(adopt_unit(c, layer, kv_head, nh, past_len));
   HI_TRY(write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, 1));
-  hi_ctx::Unit next;
-  if (next_layer >= 0) {
-    next.valid = true;
-    next.layer = next_layer; next.head = next_kv_head; next.nh = next_nh; next.past = next_past_len;
-    next.n_slices = slices_of(c, next_past_len, next_nh);
-  }
   hi_ctx::Unit& cur = c->pend;
   const int64_t ns = cur.n_slices;
   const int64_t st = rows_of(c, nh);

@@ -26,6 +26,15 @@ hi_status validate_problem(const hi_problem* p) {
     return HI_ERR_ARG;
   }
   if (p->chunk > p->max_context) { set_last_error("chunk %d exceeds max_context", p->chunk); return HI_ERR_ARG; }
+  if (p->resident_heads < 0 || (int64_t)p->resident_heads > (int64_t)p->n_layers * p->n_kv_heads) {
+    set_last_error("resident_heads out of range");
+    return HI_ERR_ARG;
+  }
+  if (p->gpu_kv_budget_heads < p->resident_heads + 1) {
+    set_last_error("an HBM budget of %d heads cannot keep %d heads resident and stream the others", p->gpu_kv_budget_heads,
+                   p->resident_heads);
+    return HI_ERR_HBM_BUDGET;
+  }
   if (p->head_dim != kHeadDim) { set_last_error("head_dim %d unsupported (128 only)", p->head_dim); return HI_ERR_UNSUPPORTED; }
   if (p->dtype_bytes != 2) { set_last_error("dtype_bytes %d unsupported (bf16 only)", p->dtype_bytes); return HI_ERR_UNSUPPORTED; }
   const int g = p->gqa_group;
@@ -68,7 +77,8 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   }
 
   // staging ring: sequence slices inside the HBM budget, so that a slice can land while another is consumed
-  const int64_t budget_tokens = (int64_t)p->gpu_kv_budget_heads * S;
+  // (Algorithm 1's H_on heads take whole-head shares of the budget; the ring gets what is left)
+  const int64_t budget_tokens = (int64_t)(p->gpu_kv_budget_heads - p->resident_heads) * S;
   // (four slices: measured against eight, the larger copies and fewer launches win 1-3 % of prefill time and up to
   // 14 % of offloaded decode time at a 128K context, and nothing is lost in overlap)
   int64_t slice = (budget_tokens / 4) / 64 * 64;
@@ -96,7 +106,9 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
     pl.heads_per_group = hpg;
     pl.n_groups = (int32_t)ceil_div(p->n_kv_heads, hpg);
   }
-  pl.hbm_staging_bytes = n_slices * slice * row;
+  pl.hbm_resident_offset = n_slices * slice * row;
+  pl.hbm_resident_bytes = (int64_t)p->resident_heads * pl.host_bytes_per_head;
+  pl.hbm_staging_bytes = pl.hbm_resident_offset + pl.hbm_resident_bytes;
 
   const int n_cu = p->n_compute_units > 0 ? p->n_compute_units : 256;
   pl.n_split_decode = n_cu;

@@ -11,14 +11,15 @@ from . import binding as hb
 
 class Session:
     def __init__(self, n_layers, n_kv_heads, gqa_group, max_context, chunk, mode=hb.HI_MODE_OFFLOAD, out_fp32=1,
-                 device="cuda:0", gpu_kv_budget_heads=1, n_compute_units=0):
+                 device="cuda:0", gpu_kv_budget_heads=1, n_compute_units=0, resident_heads=0):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the library has no CPU path")
         self.device = torch.device(device)
         self.mode = mode
         self.G = gqa_group
         self.problem = hb.make_problem(n_layers, n_kv_heads, gqa_group, max_context, chunk, out_fp32=out_fp32,
-                                       gpu_kv_budget_heads=gpu_kv_budget_heads, n_compute_units=n_compute_units)
+                                       gpu_kv_budget_heads=gpu_kv_budget_heads, n_compute_units=n_compute_units,
+                                       resident_heads=resident_heads)
         self.plan = hb.hi_offload_plan(self.problem)
         nbytes = self.plan.host_bytes_total
         if mode == hb.HI_MODE_OFFLOAD:
@@ -39,6 +40,12 @@ class Session:
     def cache_view(self) -> torch.Tensor:
         p = self.problem
         return self.kv.view(torch.bfloat16).view(p.n_layers, p.n_kv_heads, 2, p.max_context, p.head_dim)
+
+    # [resident head][K|V][S_max][d] bf16 view of the HBM-resident heads' K/V (offload mode, resident_heads > 0)
+    def resident_view(self) -> torch.Tensor:
+        p, pl = self.problem, self.plan
+        raw = self.staging[pl.hbm_resident_offset:pl.hbm_resident_offset + pl.hbm_resident_bytes]
+        return raw.view(torch.bfloat16).view(p.resident_heads, 2, p.max_context, p.head_dim)
 
     def prefill_head(self, layer, head, q, k_new, v_new, past_len, out, nxt=None):
         nl, nh, npast = nxt if nxt is not None else (-1, 0, 0)

@@ -107,6 +107,14 @@ def test_plan_head_grouping_rule():
         assert pl.heads_per_group * 64 <= pl.slice_tokens
 
 
+def test_resident_heads_need_budget():
+    st, _ = hb.hi_offload_plan(hb.make_problem(1, 8, 4, 4096, 512, gpu_kv_budget_heads=2, resident_heads=2), check=False)
+    assert st == hb.HI_ERR_HBM_BUDGET
+    pl = hb.hi_offload_plan(hb.make_problem(1, 8, 4, 4096, 512, gpu_kv_budget_heads=8, resident_heads=4))
+    assert pl.hbm_resident_bytes == 4 * pl.host_bytes_per_head
+    assert pl.hbm_staging_bytes <= 8 * pl.host_bytes_per_head
+
+
 def test_plan_geometry_small_and_large():
     pl = hb.hi_offload_plan(hb.make_problem(1, 1, 4, 2048 + 16, 512))
     assert pl.slice_tokens == 512 and pl.n_slices_ring == 4 and pl.prefill_rows_per_wg == 32
