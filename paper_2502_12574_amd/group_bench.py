@@ -21,14 +21,15 @@ from .session import Session
 H, G, D = 8, 4, 128
 
 
-def run(S, C, group, n_dec, mode, reps):
+def run(S, C, group, n_dec, mode, reps, resident_heads=0, decode_only=False):
     dev = "cuda:0"
-    with Session(1, H, G, S + n_dec, C, mode=mode, out_fp32=0) as ss:
+    with Session(1, H, G, S + n_dec, C, mode=mode, out_fp32=0, gpu_kv_budget_heads=resident_heads + 1,
+                 resident_heads=resident_heads) as ss:
         if mode == hb.HI_MODE_OFFLOAD and group * 64 > ss.plan.slice_tokens:
             return None
         gen = torch.Generator(device=dev).manual_seed(1)
         chunks = []
-        for p in range(0, S, C):
+        for p in range(0, 0 if decode_only else S, C):
             n = min(C, S - p)
             chunks.append((p, n, torch.randn(H, G, n, D, device=dev, generator=gen).to(torch.bfloat16),
                            torch.randn(H, n, D, device=dev, generator=gen).to(torch.bfloat16),
@@ -60,12 +61,14 @@ def run(S, C, group, n_dec, mode, reps):
                                         outd[h0:h0 + group], nxt)
             ss.sync()
 
-        prefill()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
+        t_pre = float("nan")
+        if not decode_only:
             prefill()
-        t_pre = (time.perf_counter() - t0) / reps
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                prefill()
+            t_pre = (time.perf_counter() - t0) / reps
         decode()
         t0 = time.perf_counter()
         for _ in range(reps):
@@ -80,6 +83,10 @@ def main():
     ap.add_argument("--chunk", type=int, default=16384)
     ap.add_argument("--decode-tokens", type=int, default=16)
     ap.add_argument("--resident", action="store_true")
+    ap.add_argument("--resident-heads", default="", help="comma list: instead of the group sweep, keep that many of "
+                    "the 8 KV heads in HBM (Algorithm 1's H_on, budget = that many + 1 heads), one head per call")
+    ap.add_argument("--decode-only", action="store_true", help="skip the prefill timing (the cache content is "
+                    "irrelevant to the decode timing)")
     args = ap.parse_args()
     mode = hb.HI_MODE_RESIDENT if args.resident else hb.HI_MODE_OFFLOAD
     print(f"one layer, {H} KV heads x G = {G}, chunk min(context, {args.chunk}), "
@@ -88,6 +95,12 @@ def main():
     for S in [int(x) for x in args.contexts.split(",")]:
         C = min(S, args.chunk)
         reps = 20 if S <= 16384 else 5 if S <= 65536 else 2
+        if args.resident_heads:
+            for r in [int(x) for x in args.resident_heads.split(",")]:
+                t_pre, t_dec = run(S, C, 1, args.decode_tokens, hb.HI_MODE_OFFLOAD, reps, r, args.decode_only)
+                print(f"context {S:8d}: {r} of {H} heads in HBM: prefill {t_pre * 1e3:10.3f} ms per layer, "
+                      f"decode {t_dec * 1e3:8.3f} ms per token per layer", flush=True)
+            continue
         cells = []
         for group in (1, 2, 4, 8):
             r = run(S, C, group, args.decode_tokens, mode, reps)
