@@ -36,9 +36,11 @@ enum { HI_MODE_OFFLOAD = 0, HI_MODE_RESIDENT = 1 };
 enum { HI_REGIME_COMPUTE = 0, HI_REGIME_LINK = 1, HI_REGIME_HBM = 2 };
 /* debug/measurement switches for hi_ctx_set_flags: skip the attention kernels (transfer-only timing) or
  * skip the H2D/D2H copies (compute-only timing on stale staging contents) - results are meaningless then;
- * time the attention kernels with HIP events; force a prefill kernel variant (by default the library
- * picks by chunk length between NARROW: 4 waves, 2 LDS stages, and DEEP: 8 waves, 4 LDS stages; WIDE: 64 query
- * positions per wavefront). Do not change the variant between the calls of one (chunk, head) unit. */
+ * time the attention kernels with HIP events; force a prefill kernel variant (by default the library picks by
+ * chunk length and group size between DEEP: 8 wavefronts per workgroup alternating matrix and softmax phases,
+ * split over the K/V rows when the chunk alone would not fill the chip, and NARROW: 4 wavefronts, for very short
+ * chunks; WIDE: 64 query positions per wavefront, one head per call only). Do not change the variant between
+ * the calls of one (chunk, head) unit. */
 enum { HI_FLAG_SKIP_KERNELS = 1, HI_FLAG_SKIP_COPIES = 2, HI_FLAG_TIME_KERNELS = 4, HI_FLAG_PREFILL_NARROW = 8,
        HI_FLAG_PREFILL_WIDE = 16, HI_FLAG_PREFILL_DEEP = 32 };
 
