@@ -530,6 +530,11 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
     return write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, 1);
   }
 
+  if (slices_of(c, past_len, nh) * n_split > part_cap) {      // before anything is enqueued
+    set_last_error("decode: the partial workspace cannot hold %lld slices x %d partitions",
+                   (long long)slices_of(c, past_len, nh), n_split);
+    return HI_ERR_UNSUPPORTED;
+  }
   HI_TRY(adopt_unit(c, layer, kv_head, nh, past_len));
   HI_TRY(write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, 1));
   hi_ctx::Unit& cur = c->pend;
