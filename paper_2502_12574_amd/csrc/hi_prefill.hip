@@ -299,15 +299,21 @@ constexpr int kPdLdsBytes = 2 * kPdStages * kPfTileBytes;   // 128 KiB
 // (sb, u, db) = (i / 8, i / 4 % 2, i % 4); operand 16 + j is the K fragment of step (kk, sb) = (j / 2, j % 2).
 constexpr int kPfAhead = 4;
 
+// step i of a matrix phase: which sub-block, half, dim block (i < 16) or contraction step (i >= 16) it is
+__device__ __forceinline__ constexpr int pd_sb(int i) { return i < 16 ? i >> 3 : (i - 16) & 1; }
+__device__ __forceinline__ constexpr int pd_u(int i) { return (i >> 2) & 1; }
+__device__ __forceinline__ constexpr int pd_db(int i) { return i & 3; }
+__device__ __forceinline__ constexpr int pd_kk(int i) { return (i - 16) >> 1; }
+
 __device__ __forceinline__ bf16x8 pd_operand(int i, uint32_t v_off, uint32_t k_off, const PfLaneConst& lc) {
   if (i < 16) {
-    const int sb = i >> 3, u = (i >> 2) & 1, db = i & 3;
+    const int sb = pd_sb(i), u = pd_u(i), db = pd_db(i);
     const uint32_t ad = lc.voff[db] + v_off + sb * 8192 + u * 4096;
     const bf16x4 v0 = lds_read_tr8((lds_char*)(uintptr_t)ad);
     const bf16x4 v1 = lds_read_tr8((lds_char*)(uintptr_t)(ad + 2048));
     return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
   }
-  const int kk = (i - 16) >> 1, sb = (i - 16) & 1;
+  const int kk = pd_kk(i), sb = pd_sb(i);
   return *(lds_bf16x8*)(uintptr_t)(lc.koff[kk] + k_off + sb * 8192);
 }
 
@@ -347,10 +353,10 @@ __device__ __forceinline__ void pd_matrix_phase(uint32_t v_off, uint32_t k_off, 
     if (i + kPfAhead < 32) op[(i + kPfAhead) % (kPfAhead + 1)] = pd_operand(i + kPfAhead, v_off, k_off, lc);
     const bf16x8 x = op[i % (kPfAhead + 1)];
     if (i < 16) {
-      const int sb = i >> 3, u = (i >> 2) & 1, db = i & 3;
+      const int sb = pd_sb(i), u = pd_u(i), db = pd_db(i);
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, pb[sb][u], st.o[db], 0, 0, 0);
     } else {
-      const int kk = (i - 16) >> 1, sb = (i - 16) & 1;
+      const int kk = pd_kk(i), sb = pd_sb(i);
       if (CINIT && kk == 0) s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qf[kk], cinit, 0, 0, 0);
       else s[sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, qf[kk], s[sb], 0, 0, 0);
     }
@@ -719,7 +725,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   for (int r = 0; r < 16; ++r) { sc[0][r] = 0.f; sc[1][r] = 0.f; }
 #pragma unroll
   for (int i = 16; i < 32; ++i)
-    sc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, 0, 0, lc), qf[(i - 16) >> 1], sc[i & 1], 0, 0, 0);
+    sc[pd_sb(i)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, 0, 0, lc), qf[pd_kk(i)], sc[pd_sb(i)], 0, 0, 0);
   phase_barrier();
   softmax_phase(0);
   wait_landed(0);
@@ -812,8 +818,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     const uint32_t v_off = (uint32_t)((T - 1) & (kPdStages - 1)) * kPfTileBytes;
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-      st.o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, v_off, 0, lc), pb[i >> 3][(i >> 2) & 1],
-                                                            st.o[i & 3], 0, 0, 0);
+      st.o[pd_db(i)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, v_off, 0, lc), pb[pd_sb(i)][pd_u(i)],
+                                                               st.o[pd_db(i)], 0, 0, 0);
   }
   if (group == 0) phase_barrier();
 
