@@ -138,7 +138,7 @@ def test_prefill_other_kernel_variants_ragged_shapes(G, P, C, mode, variant):
 
 
 @pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
-@pytest.mark.parametrize("G,P,C", [(4, 8000, 192), (4, 7003, 70), (2, 6500, 260), (8, 6160, 64)])
+@pytest.mark.parametrize("G,P,C", [(4, 8000, 192), (4, 7003, 70), (2, 6500, 260), (8, 6160, 64), (1, 6000, 300)])
 def test_prefill_8wave_kernel_steady_state(G, P, C, mode):
     # pasts long enough that the 8-wave kernel runs its unrolled steady-state loop (at least 11 full tiles per
     # launch: in offload mode the staging slices of these shapes hold 768-1024 rows, so it is entered in every
