@@ -158,3 +158,34 @@ def test_rows_match_full_and_positions_are_absolute():
     past, C = 20, 30
     part = oa.attn_head(Q[:, past:], K, V, past_len=past)
     assert np.max(np.abs(part - full[:, past:])) <= 1e-15
+
+
+def test_o7_library_routine_scaled_dot_product_attention():
+    """Special case that is a library routine: torch's CPU scaled_dot_product_attention in fp64 (causal flag with no
+    past; an explicit boolean mask for a chunk behind a past), with the KV heads repeated for the query groups."""
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(77)
+    Hkv, G, S, d = 2, 4, 45, 16
+    Q, K, V = _rand(rng, Hkv * G, S, d), _rand(rng, Hkv, S, d), _rand(rng, Hkv, S, d)
+    tq, tk, tv = (torch.from_numpy(x) for x in (Q, np.repeat(K, G, axis=0), np.repeat(V, G, axis=0)))
+    ref = F.scaled_dot_product_attention(tq[None], tk[None], tv[None], is_causal=True)[0].numpy()
+    np.testing.assert_allclose(oa.attn_layer(Q, K, V), ref, rtol=0, atol=1e-12)
+    # rows [P, S) of head 1's group against keys [0, S): mask[i, j] = j <= P + i
+    P = 29
+    mask = torch.arange(S)[None, :] <= (P + torch.arange(S - P))[:, None]
+    refp = F.scaled_dot_product_attention(tq[G:2 * G, P:][None], tk[G:2 * G][None], tv[G:2 * G][None],
+                                          attn_mask=mask)[0].numpy()
+    got = oa.attn_head(Q[G:2 * G, P:], K[1], V[1], past_len=P)
+    np.testing.assert_allclose(got, refp, rtol=0, atol=1e-12)
+
+
+def test_o8_decode_step_is_the_last_row_of_the_full_evaluation():
+    rng = np.random.default_rng(78)
+    L, Hkv, G, S, d = 1, 2, 2, 23, 8
+    Q, K, V = _rand(rng, L, Hkv * G, S + 1, d), _rand(rng, L, Hkv, S + 1, d), _rand(rng, L, Hkv, S + 1, d)
+    full = oa.attn_layer(Q[0], K[0], V[0])
+    cache = oa.HeadwiseCache(L, Hkv, d)
+    oa.prefill_chunked(cache, Q[:, :, :S], K[:, :, :S], V[:, :, :S], chunk=7)
+    out = oa.decode_step(cache, Q[:, :, S], K[:, :, S], V[:, :, S])
+    np.testing.assert_allclose(np.asarray(out)[0], full[:, S], rtol=0, atol=1e-12)
