@@ -443,7 +443,7 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
     TimedSpan sp;
     if (timed) HI_TRY(span_begin(c, 0, &sp));
     HI_TRY(launch_prefill(c->sc, q_dev, G, chunk_len, seg, own, first, last, c->ws, out_dev, c->prob.out_fp32,
-                          pf_variant(c), nh));
+                          pf_variant(c), nh, c->plan.ws_partials_offset));
     if (timed) HI_TRY(span_end(c, sp));
     c->stats.n_prefill_kernels += 1;
     return HI_OK;

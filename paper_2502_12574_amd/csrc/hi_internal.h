@@ -35,12 +35,13 @@ inline int prefill_split(int G, int64_t chunk_len, int n_heads = 1) {
   return split;
 }
 // upper bound, in images of a 4-wave workgroup's state (256 lanes x 66 floats), of the carry any prefill launch
-// of chunks up to C rows over groups of up to n_heads heads can need: split * workgroups stays below
-// 2 * kPrefillFillWorkgroups 8-wave images
+// of chunks up to C rows over groups of up to n_heads heads can need.  The 8-wave kernel's images count double;
+// its split keeps workgroups * split below 2 * kPrefillFillWorkgroups unless the chunk alone exceeds that, and a
+// triangle-dominated unit doubles the split once more.
 inline int64_t prefill_carry_images(int G, int64_t C, int n_heads) {
   const int64_t narrow = (ceil_div(C, prefill_strip(G)) + 1) * prefill_grid_y(G) * n_heads;
   const int64_t split_bound = 2 * (2 * kPrefillFillWorkgroups + prefill_grid_y(G) * n_heads);
-  return narrow > split_bound ? narrow : split_bound;
+  return 2 * (narrow > split_bound ? narrow : split_bound);
 }
 
 // floats of decode partials one head can produce (one launch per staging slice, n_split partials each; a head of
@@ -66,11 +67,12 @@ struct PrefillSegment {
 // variant: 0 = pick by chunk length (the 8-wave kernel, split over the rows if need be, when that fills the chip,
 // else the 4-wave one), 1 = 4-wave kernel (2 LDS stages), 2 = wide kernel (64 positions per wave), 3 = 8-wave
 // kernel; every launch of one unit must use the same variant (the carry layouts differ).
+// carry_bytes: size of the carry buffer (checked against what the launch will use; -1: not checked).
 // n_heads > 1: one launch over a group of KV heads; q is [n_heads][G][chunk_len][128], out likewise, the causal
 // segment's rows [n_heads][chunk_len][128], the other segment's heads head_stride bytes apart.
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& a,
                          const PrefillSegment& b, int first, int last, void* carry, void* out, int out_fp32,
-                         int variant, int n_heads = 1);
+                         int variant, int n_heads = 1, int64_t carry_bytes = -1);
 
 // Split-KV decode over rows [0, n) of one slice: writes n_split partials starting at partial index part0.
 // n_heads > 1: q is [n_heads][G][128], the heads' K (V) rows kv_head_stride bytes apart, their partials
