@@ -150,6 +150,32 @@ struct PfState {
   float m, l;
 };
 
+// Normalise one query row's accumulators and write out[g][i][:]: register r of block db is dim
+// 32*db + 8*(r/4) + 4*hl + r%4; l is this half-wave's part of the row sum.
+__device__ __forceinline__ void pf_write_row(void* out, int out_fp32, int C, int g, int i, int hl,
+                                             const f32x16 (&o)[4], float l) {
+  const float inv = 1.0f / sum_halves(l);
+  if (i >= C) return;
+  const int64_t base = ((int64_t)g * C + i) * kHeadDim;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int rq = 0; rq < 4; ++rq) {
+      const int dim = 32 * db + 8 * rq + 4 * hl;
+      const float x0 = o[db][4 * rq] * inv, x1 = o[db][4 * rq + 1] * inv;
+      const float x2 = o[db][4 * rq + 2] * inv, x3 = o[db][4 * rq + 3] * inv;
+      if (out_fp32) {
+        *(float4*)((float*)out + base + dim) = make_float4(x0, x1, x2, x3);
+      } else {
+        uint2 pk;
+        pk.x = (uint32_t)float_to_bf16_bits(x0) | ((uint32_t)float_to_bf16_bits(x1) << 16);
+        pk.y = (uint32_t)float_to_bf16_bits(x2) | ((uint32_t)float_to_bf16_bits(x3) << 16);
+        *(uint2*)((uint16_t*)out + base + dim) = pk;
+      }
+    }
+}
+
+
 // S^T = K Q^T for one 64-row K tile at kt: register r of sub-block sb is tile row 32*sb + 8*(r/4) + 4*hl + r%4
 // (query row = lane % 32).  The two sub-blocks' accumulation chains alternate, so consecutive MFMAs never
 // depend on each other.
@@ -514,28 +540,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
     return;
   }
 
-  // normalise and write out[g][i][:]; register r of block db is dim 32*db + 8*(r/4) + 4*hl + r%4
-  const float l_tot = sum_halves(st.l);
-  const float inv = 1.0f / l_tot;
-  if (my_i < a.C) {
-    const int64_t base = ((int64_t)g * a.C + my_i) * kHeadDim;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int dim = 32 * db + 8 * rq + 4 * hl;
-        const float x0 = st.o[db][4 * rq] * inv, x1 = st.o[db][4 * rq + 1] * inv;
-        const float x2 = st.o[db][4 * rq + 2] * inv, x3 = st.o[db][4 * rq + 3] * inv;
-        if (a.out_fp32) {
-          *(float4*)((float*)a.out + base + dim) = make_float4(x0, x1, x2, x3);
-        } else {
-          uint2 pk;
-          pk.x = (uint32_t)float_to_bf16_bits(x0) | ((uint32_t)float_to_bf16_bits(x1) << 16);
-          pk.y = (uint32_t)float_to_bf16_bits(x2) | ((uint32_t)float_to_bf16_bits(x3) << 16);
-          *(uint2*)((uint16_t*)a.out + base + dim) = pk;
-        }
-      }
-  }
+  pf_write_row(a.out, a.out_fp32, a.C, g, my_i, hl, st.o, st.l);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -833,27 +838,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     return;
   }
 
-  const float l_tot = sum_halves(st.l);
-  const float inv = 1.0f / l_tot;
-  if (my_i < a.C) {
-    const int64_t base = ((int64_t)g * a.C + my_i) * kHeadDim;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int dim = 32 * db + 8 * rq + 4 * hl;
-        const float x0 = st.o[db][4 * rq] * inv, x1 = st.o[db][4 * rq + 1] * inv;
-        const float x2 = st.o[db][4 * rq + 2] * inv, x3 = st.o[db][4 * rq + 3] * inv;
-        if (a.out_fp32) {
-          *(float4*)((float*)a.out + base + dim) = make_float4(x0, x1, x2, x3);
-        } else {
-          uint2 pk;
-          pk.x = (uint32_t)float_to_bf16_bits(x0) | ((uint32_t)float_to_bf16_bits(x1) << 16);
-          pk.y = (uint32_t)float_to_bf16_bits(x2) | ((uint32_t)float_to_bf16_bits(x3) << 16);
-          *(uint2*)((uint16_t*)a.out + base + dim) = pk;
-        }
-      }
-  }
+  pf_write_row(a.out, a.out_fp32, a.C, g, my_i, hl, st.o, st.l);
 }
 
 // Merge of the split-KV states of the 8-wave kernel, run once after a unit's last launch: the same grid (without
@@ -876,37 +861,22 @@ __global__ __launch_bounds__(512) void prefill_merge_kernel(PrefillArgs a) {
   float m = kNegBig;
   for (int z = 0; z < a.split; ++z)
     m = fmaxf(m, a.carry[(z * wg_per_split + wg_linear) * (kCarryFloatsPerLane * kLanes) + 64 * kLanes + threadIdx.x]);
-  float o[64];
+  f32x16 o[4];
 #pragma unroll
-  for (int i = 0; i < 64; ++i) o[i] = 0.f;
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
   float l = 0.f;
   for (int z = 0; z < a.split; ++z) {
     const float* cz = a.carry + (z * wg_per_split + wg_linear) * (kCarryFloatsPerLane * kLanes) + threadIdx.x;
     const float w = fast_exp2((cz[64 * kLanes] - m) * a.c);
     l += w * cz[65 * kLanes];
 #pragma unroll
-    for (int i = 0; i < 64; ++i) o[i] += w * cz[i * kLanes];
-  }
-  const float inv = 1.0f / sum_halves(l);
-  if (my_i < a.C) {
-    const int64_t base = ((int64_t)g * a.C + my_i) * kHeadDim;
-#pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int dim = 32 * db + 8 * rq + 4 * hl;
-        const float x0 = o[db * 16 + 4 * rq] * inv, x1 = o[db * 16 + 4 * rq + 1] * inv;
-        const float x2 = o[db * 16 + 4 * rq + 2] * inv, x3 = o[db * 16 + 4 * rq + 3] * inv;
-        if (a.out_fp32) {
-          *(float4*)((float*)a.out + base + dim) = make_float4(x0, x1, x2, x3);
-        } else {
-          uint2 pk;
-          pk.x = (uint32_t)float_to_bf16_bits(x0) | ((uint32_t)float_to_bf16_bits(x1) << 16);
-          pk.y = (uint32_t)float_to_bf16_bits(x2) | ((uint32_t)float_to_bf16_bits(x3) << 16);
-          *(uint2*)((uint16_t*)a.out + base + dim) = pk;
-        }
-      }
+      for (int r = 0; r < 16; ++r) o[db][r] += w * cz[(db * 16 + r) * kLanes];
   }
+  pf_write_row(a.out, a.out_fp32, a.C, g, my_i, hl, o, l);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -1156,29 +1126,8 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel_wide(PrefillArgs a) {
     return;
   }
 
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    const float inv = 1.0f / sum_halves(l[rb]);
-    if (my_i[rb] < a.C) {
-      const int64_t base = ((int64_t)g * a.C + my_i[rb]) * kHeadDim;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          const int dim = 32 * db + 8 * rq + 4 * hl;
-          const float x0 = o[rb][db][4 * rq] * inv, x1 = o[rb][db][4 * rq + 1] * inv;
-          const float x2 = o[rb][db][4 * rq + 2] * inv, x3 = o[rb][db][4 * rq + 3] * inv;
-          if (a.out_fp32) {
-            *(float4*)((float*)a.out + base + dim) = make_float4(x0, x1, x2, x3);
-          } else {
-            uint2 pk;
-            pk.x = (uint32_t)float_to_bf16_bits(x0) | ((uint32_t)float_to_bf16_bits(x1) << 16);
-            pk.y = (uint32_t)float_to_bf16_bits(x2) | ((uint32_t)float_to_bf16_bits(x3) << 16);
-            *(uint2*)((uint16_t*)a.out + base + dim) = pk;
-          }
-        }
-    }
-  }
+  pf_write_row(a.out, a.out_fp32, a.C, g, my_i[0], hl, o[0], l[0]);
+  pf_write_row(a.out, a.out_fp32, a.C, g, my_i[1], hl, o[1], l[1]);
 }
 
 static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   // log2(e) / sqrt(128)
