@@ -56,13 +56,20 @@ typedef struct hi_problem {
   int32_t dtype_bytes;         /* 2 (bf16) */
   int32_t out_fp32;            /* 0: outputs are bf16, 1: outputs are fp32 */
   int32_t n_compute_units;     /* 0 = 256 (MI355X) */
-  int32_t resident_heads;      /* Algorithm 1's H_on: the first resident_heads (layer, KV head) pairs, in layer-major
-                                  order, keep their K/V in HBM and never cross the link (offload mode); the rest of
-                                  the budget is the staging ring of the offloaded heads.  0 = none */
+  int32_t resident_heads;      /* Algorithm 1's H_on: the first resident_heads (layer, retrieval KV head) pairs, in
+                                  layer-major order, keep their K/V in HBM and never cross the link (offload mode); the
+                                  rest of the budget is the staging ring of the offloaded heads.  0 = none */
   int64_t host_mem_limit_bytes;/* 0 = no check */
   double link_GBps;            /* host link peak used by the regime prediction; 0 = 64 (PCIe Gen5 x16) */
   double hbm_GBps;             /* 0 = 8000 */
   double mfma_TFLOPs;          /* 0 = 2500 (dense bf16) */
+  int32_t streaming_heads;     /* Appendix E (head-wise sparsity): the LAST streaming_heads KV heads of every layer are
+                                  streaming heads, which keep only sink_tokens initial and recent_tokens most recent
+                                  tokens, in HBM; the other heads ("retrieval heads") keep everything and are offloaded
+                                  or resident as above.  0 = none; at most n_kv_heads - 1 */
+  int32_t sink_tokens;         /* n_sink >= 0 */
+  int32_t recent_tokens;       /* n_recent >= 1 (the token itself included) when streaming_heads > 0 */
+  int32_t reserved0;           /* 0 */
 } hi_problem;
 
 /* Output of hi_offload_plan.  Sizes in bytes. */
@@ -77,9 +84,10 @@ typedef struct hi_plan {
   int32_t n_split_decode;        /* workgroups (KV partitions) of one decode launch */
   int32_t prefill_rows_per_wg;   /* query positions one prefill workgroup covers */
   int64_t host_bytes_per_head;   /* Eq. 11: 2 * S_max * D_h * sizeof */
-  int64_t host_bytes_total;      /* Eq. 4:  L * H * host_bytes_per_head */
+  int64_t host_bytes_total;      /* Eq. 4:  L * H * host_bytes_per_head (H less the streaming heads) */
   int64_t hbm_staging_bytes;     /* the ring, n_slices_ring * slice_tokens * 2 * D_h * sizeof, followed by the resident
-                                    heads' K/V (hbm_resident_bytes at hbm_resident_offset); <= budget * host_bytes_per_head */
+                                    heads' K/V (hbm_resident_bytes at hbm_resident_offset); <= budget * host_bytes_per_head;
+                                    then the streaming heads' stores (hbm_stream_bytes more) */
   int64_t hbm_pingpong_paper_bytes; /* the paper's two-whole-heads ping-pong buffer, for comparison (Appendix A.3) */
   int64_t workspace_bytes;       /* fp32 (m, l, O) carry of a prefill unit + split-KV partials of a decode unit */
   int64_t ws_partials_offset;    /* byte offset of the decode partials inside the workspace */
@@ -92,6 +100,11 @@ typedef struct hi_plan {
   int32_t regime_prefill, regime_decode;                      /* HI_REGIME_* with offloading */
   int64_t hbm_resident_offset;   /* inside the staging buffer: [resident head][K|V][S_max][D_h] */
   int64_t hbm_resident_bytes;    /* resident_heads * host_bytes_per_head */
+  int64_t hbm_stream_offset;     /* inside the staging buffer: the streaming heads' stores,
+                                    [layer][streaming head][K|V][stream_rows][D_h] */
+  int64_t hbm_stream_bytes;      /* L * streaming_heads * 2 * stream_rows * D_h * sizeof; outside the whole-head budget */
+  int64_t stream_rows;           /* sink_tokens + recent_tokens (0 without streaming heads): sink token j at row j,
+                                    token j >= sink_tokens at row sink_tokens + (j - sink_tokens) mod recent_tokens */
 } hi_plan;
 
 typedef struct hi_stats {
@@ -119,9 +132,11 @@ hi_status hi_offload_plan(const hi_problem* problem, hi_plan* plan);
  * Context.  The caller owns every large buffer and keeps it alive until hi_ctx_destroy:
  *   kv_cache       HI_MODE_OFFLOAD : pinned HOST memory, plan.host_bytes_total bytes, layout
  *                                    [layer][kv_head][K|V][S_max][D_h] bf16 (each head's K rows contiguous, then
- *                                    its V rows: the head-wise partition of Eq. 7-8);
+ *                                    its V rows: the head-wise partition of Eq. 7-8; kv_head runs over the
+ *                                    n_kv_heads - streaming_heads retrieval heads only);
  *                  HI_MODE_RESIDENT: DEVICE memory of the same size and layout (no copies; HBM-roofline runs).
- *   hbm_staging    DEVICE, plan.hbm_staging_bytes (ignored in resident mode; may be null there).  With
+ *   hbm_staging    DEVICE, plan.hbm_staging_bytes (in resident mode only the streaming heads' stores are used; may
+ *                  be null there without streaming heads).  With
  *                  hi_problem.resident_heads > 0 its tail holds those heads' K/V: units of a resident head read
  *                  and append there, move nothing over the link and leave the host cache rows of that head
  *                  untouched; a head group must be all resident or all offloaded.
@@ -193,6 +208,21 @@ hi_status hi_prefill_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t 
 hi_status hi_decode_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n_heads, const void* q_dev,
                           const void* k_new_dev, const void* v_new_dev, int64_t past_len, void* out_dev,
                           int32_t next_layer, int32_t next_kv_head, int32_t next_n_heads, int64_t next_past_len);
+
+/*
+ * Streaming heads (Appendix E, "Efficient Management of KV cache": retrieval heads retain all tokens and are
+ * offloaded, streaming heads retain only recent tokens and stay on the GPU).  With hi_problem.streaming_heads > 0
+ * the same four calls serve the last streaming_heads KV heads of a layer, with these differences:
+ *   - row at absolute position p attends over key j iff j <= p and (j < sink_tokens or p - j < recent_tokens)
+ *     - a different function from the exact attention of the other heads, by design of the extension;
+ *   - the head's K/V is the bounded HBM store described at hi_plan.stream_rows; nothing crosses the link and the
+ *     host cache has no rows for it; a prefill call reads the store, then enters the chunk's rows into it; a
+ *     decode call writes the token's row over the row that left the window and attends over the store;
+ *   - past_len is still the absolute position of the call's first row, and calls of one head must come in
+ *     position order without gaps (the store holds only what earlier calls left in it);
+ *   - a head group must not mix streaming and retrieval heads (HI_ERR_ARG); a hint naming a streaming unit
+ *     prefetches nothing.
+ */
 
 /* T4 - drain the three streams; surfaces deferred HIP errors (HI_ERR_HIP). */
 hi_status hi_sync(hi_ctx* ctx);

@@ -27,7 +27,9 @@ class hi_problem(C.Structure):
                 ("head_dim", C.c_int32), ("max_context", C.c_int64), ("chunk", C.c_int32),
                 ("gpu_kv_budget_heads", C.c_int32), ("dtype_bytes", C.c_int32), ("out_fp32", C.c_int32),
                 ("n_compute_units", C.c_int32), ("resident_heads", C.c_int32), ("host_mem_limit_bytes", C.c_int64),
-                ("link_GBps", C.c_double), ("hbm_GBps", C.c_double), ("mfma_TFLOPs", C.c_double)]
+                ("link_GBps", C.c_double), ("hbm_GBps", C.c_double), ("mfma_TFLOPs", C.c_double),
+                ("streaming_heads", C.c_int32), ("sink_tokens", C.c_int32), ("recent_tokens", C.c_int32),
+                ("reserved0", C.c_int32)]
 
 
 class hi_plan(C.Structure):
@@ -41,7 +43,8 @@ class hi_plan(C.Structure):
                 ("t_comp_prefill_s", C.c_double), ("t_link_prefill_s", C.c_double), ("t_hbm_prefill_s", C.c_double),
                 ("t_comp_decode_s", C.c_double), ("t_link_decode_s", C.c_double), ("t_hbm_decode_s", C.c_double),
                 ("regime_prefill", C.c_int32), ("regime_decode", C.c_int32),
-                ("hbm_resident_offset", C.c_int64), ("hbm_resident_bytes", C.c_int64)]
+                ("hbm_resident_offset", C.c_int64), ("hbm_resident_bytes", C.c_int64),
+                ("hbm_stream_offset", C.c_int64), ("hbm_stream_bytes", C.c_int64), ("stream_rows", C.c_int64)]
 
 
 class hi_stats(C.Structure):
@@ -117,10 +120,10 @@ def _stream(s):
 
 def make_problem(n_layers, n_kv_heads, gqa_group, max_context, chunk, head_dim=128, gpu_kv_budget_heads=1,
                  dtype_bytes=2, out_fp32=0, n_compute_units=0, host_mem_limit_bytes=0, link_GBps=0.0, hbm_GBps=0.0,
-                 mfma_TFLOPs=0.0, resident_heads=0) -> hi_problem:
+                 mfma_TFLOPs=0.0, resident_heads=0, streaming_heads=0, sink_tokens=0, recent_tokens=0) -> hi_problem:
     return hi_problem(n_layers, n_kv_heads, gqa_group, head_dim, max_context, chunk, gpu_kv_budget_heads,
                       dtype_bytes, out_fp32, n_compute_units, resident_heads, host_mem_limit_bytes, link_GBps, hbm_GBps,
-                      mfma_TFLOPs)
+                      mfma_TFLOPs, streaming_heads, sink_tokens, recent_tokens, 0)
 
 
 def hi_offload_plan(problem: hi_problem, check: bool = True):

@@ -78,9 +78,14 @@ struct hi_ctx {
 
 namespace {
 
+// heads of a layer that keep their whole history (Appendix E: "retrieval heads"); the last streaming_heads heads
+// of each layer are streaming heads, which have no rows in the cache
+inline int n_retrieval(const hi_ctx* c) { return c->prob.n_kv_heads - c->prob.streaming_heads; }
+inline bool unit_streaming(const hi_ctx* c, int head) { return head >= n_retrieval(c); }
+
 inline int64_t plane_offset(const hi_ctx* c, int layer, int head, int which /*0 K, 1 V*/) {
   const int64_t plane = c->prob.max_context * kRowBytes;
-  return (((int64_t)layer * c->prob.n_kv_heads + head) * 2 + which) * plane;
+  return (((int64_t)layer * n_retrieval(c) + head) * 2 + which) * plane;
 }
 
 // A ring slot holds one sequence slice of every head of a group: rows_of(nh) rows of K then of V per head, the
@@ -94,12 +99,23 @@ inline int64_t head_pitch(const hi_ctx* c, int nh) { return rows_of(c, nh) * 2 *
 // Algorithm 1, "if h in H_on": the unit's K/V live in HBM (the whole cache in resident mode; the first
 // resident_heads (layer, head) pairs, kept behind the ring in the staging buffer, in offload mode)
 inline bool unit_resident(const hi_ctx* c, int layer, int head) {
-  return c->mode == HI_MODE_RESIDENT || (int64_t)layer * c->prob.n_kv_heads + head < c->prob.resident_heads;
+  if (unit_streaming(c, head)) return false;
+  return c->mode == HI_MODE_RESIDENT || (int64_t)layer * n_retrieval(c) + head < c->prob.resident_heads;
 }
 inline char* res_plane(const hi_ctx* c, int layer, int head, int which) {
   if (c->mode == HI_MODE_RESIDENT) return c->kv + plane_offset(c, layer, head, which);
   const int64_t plane = c->prob.max_context * kRowBytes;
-  return c->staging + c->plan.hbm_resident_offset + (((int64_t)layer * c->prob.n_kv_heads + head) * 2 + which) * plane;
+  return c->staging + c->plan.hbm_resident_offset + (((int64_t)layer * n_retrieval(c) + head) * 2 + which) * plane;
+}
+// 0 offloaded, 1 HBM-resident, 2 streaming: a head group is of one kind
+inline int unit_kind(const hi_ctx* c, int layer, int head) {
+  return unit_streaming(c, head) ? 2 : unit_resident(c, layer, head) ? 1 : 0;
+}
+// a streaming head's bounded store (K plane, then V plane, stream_rows rows each)
+inline int64_t stream_head_stride(const hi_ctx* c) { return 2 * c->plan.stream_rows * kRowBytes; }
+inline char* stream_plane(const hi_ctx* c, int layer, int head, int which) {
+  const int64_t t = (int64_t)layer * c->prob.streaming_heads + (head - n_retrieval(c));
+  return c->staging + c->plan.hbm_stream_offset + t * stream_head_stride(c) + which * c->plan.stream_rows * kRowBytes;
 }
 
 inline char* slot_k(const hi_ctx* c, int slot) { return c->staging + (int64_t)slot * c->slice_tokens * 2 * kRowBytes; }
@@ -227,22 +243,25 @@ hi_status check_unit_args(const hi_ctx* c, int layer, int head, int nh, const vo
   if (!q || !k || !v || !out) { set_last_error("null buffer"); return HI_ERR_ARG; }
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) { set_last_error("buffers must be 16-byte aligned"); return HI_ERR_ARG; }
   if (layer < 0 || layer >= c->prob.n_layers || head < 0 || nh < 1 || head + nh > c->prob.n_kv_heads) { set_last_error("layer/head out of range"); return HI_ERR_ARG; }
-  if (unit_resident(c, layer, head) != unit_resident(c, layer, head + nh - 1) ||
-      (next_layer >= 0 && unit_resident(c, next_layer, next_head) != unit_resident(c, next_layer, next_head + next_nh - 1))) {
-    set_last_error("a head group must be all HBM-resident or all offloaded");
+  if (next_layer >= 0 && (next_layer >= c->prob.n_layers || next_head < 0 || next_nh < 1 || next_head + next_nh > c->prob.n_kv_heads || next_past < 0)) {
+    set_last_error("prefetch hint out of range");
     return HI_ERR_ARG;
   }
-  if (c->mode == HI_MODE_OFFLOAD && ((int64_t)nh * 64 > c->slice_tokens || (next_layer >= 0 && (int64_t)next_nh * 64 > c->slice_tokens))) {
+  if (unit_kind(c, layer, head) != unit_kind(c, layer, head + nh - 1) ||
+      (next_layer >= 0 && unit_kind(c, next_layer, next_head) != unit_kind(c, next_layer, next_head + next_nh - 1))) {
+    set_last_error("a head group must be all HBM-resident, all offloaded or all streaming");
+    return HI_ERR_ARG;
+  }
+  const bool ring_now = unit_kind(c, layer, head) == 0;
+  const bool ring_next = next_layer >= 0 && unit_kind(c, next_layer, next_head) == 0;
+  if (c->mode == HI_MODE_OFFLOAD && ((ring_now && (int64_t)nh * 64 > c->slice_tokens) || (ring_next && (int64_t)next_nh * 64 > c->slice_tokens))) {
     set_last_error("a staging slice of %lld rows cannot hold 64 rows of each head of the group", (long long)c->slice_tokens);
     return HI_ERR_HBM_BUDGET;
   }
   if (nh > 1 && (c->flags & HI_FLAG_PREFILL_WIDE)) { set_last_error("the 64-positions-per-wave kernel takes one head per launch"); return HI_ERR_UNSUPPORTED; }
   if (past < 0 || len < 1) { set_last_error("negative past_len or empty call"); return HI_ERR_ARG; }
   if (len > c->prob.chunk || past + len > c->prob.max_context) { set_last_error("past_len %lld + len %lld exceeds the plan", (long long)past, (long long)len); return HI_ERR_RANGE; }
-  if (next_layer >= 0) {
-    if (next_layer >= c->prob.n_layers || next_head < 0 || next_nh < 1 || next_head + next_nh > c->prob.n_kv_heads || next_past < 0) { set_last_error("prefetch hint out of range"); return HI_ERR_ARG; }
-    if (next_past > c->prob.max_context) { set_last_error("prefetch hint beyond max_context"); return HI_ERR_RANGE; }
-  }
+  if (next_layer >= 0 && next_past > c->prob.max_context) { set_last_error("prefetch hint beyond max_context"); return HI_ERR_RANGE; }
   return HI_OK;
 }
 
@@ -320,7 +339,7 @@ extern "C" hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* pla
   if (!out || !plan) { set_last_error("null argument"); return HI_ERR_ARG; }
   HI_TRY(validate_problem(problem));
   if (mode != HI_MODE_OFFLOAD && mode != HI_MODE_RESIDENT) { set_last_error("unknown mode"); return HI_ERR_ARG; }
-  if (!kv_cache || !hbm_workspace || (mode == HI_MODE_OFFLOAD && !hbm_staging)) { set_last_error("null buffer"); return HI_ERR_ARG; }
+  if (!kv_cache || !hbm_workspace || ((mode == HI_MODE_OFFLOAD || problem->streaming_heads > 0) && !hbm_staging)) { set_last_error("null buffer"); return HI_ERR_ARG; }
   hi_plan ref;
   HI_TRY(hi_offload_plan(problem, &ref));
   if (std::memcmp(&ref, plan, sizeof(ref)) != 0) { set_last_error("plan does not belong to this problem"); return HI_ERR_ARG; }
@@ -409,7 +428,7 @@ extern "C" hi_status hi_ctx_set_run_ahead(hi_ctx* c, int32_t units) {
 static hi_ctx::Unit hinted_unit(const hi_ctx* c, int32_t next_layer, int32_t next_kv_head, int32_t next_nh,
                                 int64_t next_past_len) {
   hi_ctx::Unit next;
-  if (next_layer >= 0 && !unit_resident(c, next_layer, next_kv_head)) {
+  if (next_layer >= 0 && unit_kind(c, next_layer, next_kv_head) == 0) {
     next.valid = true;
     next.layer = next_layer; next.head = next_kv_head; next.nh = next_nh; next.past = next_past_len;
     next.n_slices = slices_of(c, next_past_len, next_nh);
@@ -450,6 +469,23 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
   };
 
   hi_ctx::Unit next = hinted_unit(c, next_layer, next_kv_head, next_nh, next_past_len);
+  if (unit_streaming(c, kv_head)) {
+    // Appendix E: attention over what the bounded store holds of the past plus the chunk, then the chunk's rows
+    // enter the store; nothing crosses the link
+    char* sk = stream_plane(c, layer, kv_head, 0);
+    char* sv = stream_plane(c, layer, kv_head, 1);
+    HI_TRY(prefetch_hint(c, next));
+    if (run) {
+      TimedSpan sp;
+      if (timed) HI_TRY(span_begin(c, 0, &sp));
+      HI_TRY(launch_prefill_window(c->sc, q_dev, G, chunk_len, sk, sv, stream_head_stride(c), k_new_dev, v_new_dev,
+                                   past_len, c->prob.sink_tokens, c->prob.recent_tokens, out_dev, c->prob.out_fp32, nh));
+      if (timed) HI_TRY(span_end(c, sp));
+      c->stats.n_prefill_kernels += 1;
+    }
+    return launch_stream_store_update(c->sc, k_new_dev, v_new_dev, chunk_len, past_len, c->prob.sink_tokens,
+                                      c->prob.recent_tokens, sk, sv, stream_head_stride(c), nh);
+  }
   if (unit_resident(c, layer, kv_head)) {
     PrefillSegment pastseg{res_plane(c, layer, kv_head, 0), res_plane(c, layer, kv_head, 1), past_len, 0,
                            2 * c->prob.max_context * kRowBytes};
@@ -500,17 +536,48 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
     const int64_t need = ceil_div(rows, 64);      // one workgroup covers at least 64 rows
     return (int)(need < n_split ? need : n_split);
   };
-  auto partial = [&](const void* k, const void* v, int64_t rows, int np, int part0, int64_t kv_stride) -> hi_status {
+  auto partial = [&](const void* k, const void* v, int64_t rows, int np, int part0, int64_t kv_stride,
+                     int64_t skip_row = -1) -> hi_status {
     if (part0 + np > part_cap) { set_last_error("decode: partial workspace exhausted"); return HI_ERR_UNSUPPORTED; }
     TimedSpan sp;
     if (timed) HI_TRY(span_begin(c, 1, &sp));
-    HI_TRY(launch_decode_partial(c->sc, q_dev, G, k, v, rows, np, partials, part0, nh, kv_stride, part_stride));
+    HI_TRY(launch_decode_partial(c->sc, q_dev, G, k, v, rows, np, partials, part0, nh, kv_stride, part_stride, skip_row));
     if (timed) HI_TRY(span_end(c, sp));
     c->stats.n_decode_kernels += 1;
     return HI_OK;
   };
 
   hi_ctx::Unit next = hinted_unit(c, next_layer, next_kv_head, next_nh, next_past_len);
+  if (unit_streaming(c, kv_head)) {
+    // Appendix E: the store holds the sink tokens and the n_recent tokens before this one; the oldest of those
+    // has just left the window: it takes no part, and the token's row replaces it
+    const int64_t n_sink = c->prob.sink_tokens, n_recent = c->prob.recent_tokens;
+    const int64_t in_ring = past_len > n_sink ? (past_len - n_sink < n_recent ? past_len - n_sink : n_recent) : 0;
+    const int64_t n_store = (past_len < n_sink ? past_len : n_sink) + in_ring;
+    const int64_t slot = past_len < n_sink ? past_len : n_sink + (past_len - n_sink) % n_recent;
+    const int64_t skip = in_ring == n_recent ? slot : -1;
+    char* sk = stream_plane(c, layer, kv_head, 0);
+    char* sv = stream_plane(c, layer, kv_head, 1);
+    HI_TRY(prefetch_hint(c, next));
+    if (!run) {
+      for (int j = 0; j < nh; ++j) {
+        HI_HIP(hipMemcpyAsync(sk + j * stream_head_stride(c) + slot * kRowBytes, (const char*)k_new_dev + j * kRowBytes,
+                              kRowBytes, hipMemcpyDeviceToDevice, c->sc));
+        HI_HIP(hipMemcpyAsync(sv + j * stream_head_stride(c) + slot * kRowBytes, (const char*)v_new_dev + j * kRowBytes,
+                              kRowBytes, hipMemcpyDeviceToDevice, c->sc));
+      }
+      return HI_OK;
+    }
+    int n_part = 0;
+    if (n_store > 0) {
+      n_part = splits_for(n_store);
+      HI_TRY(partial(sk, sv, n_store, n_part, 0, stream_head_stride(c), skip));
+    }
+    HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32,
+                                 sk + slot * kRowBytes, sv + slot * kRowBytes, nh, part_stride, stream_head_stride(c)));
+    c->stats.n_combine_kernels += 1;
+    return HI_OK;
+  }
   if (unit_resident(c, layer, kv_head)) {
     const int64_t plane2 = 2 * c->prob.max_context * kRowBytes;
     int n_part = 0;

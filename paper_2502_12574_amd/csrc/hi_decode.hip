@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __r
                                                              const char* __restrict__ k, const char* __restrict__ v,
                                                              int64_t n, float* __restrict__ partials, int part0,
                                                              float c, int64_t kv_head_stride,
-                                                             int64_t part_head_stride) {
+                                                             int64_t part_head_stride, int64_t skip_row) {
   // group launches: blockIdx.y is the head
   q += (int64_t)blockIdx.y * G * kHeadDim;
   k += blockIdx.y * kv_head_stride;
@@ -73,6 +73,7 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __r
   const int64_t n_waves = (int64_t)gridDim.x * 4;
   const int64_t wid = (int64_t)blockIdx.x * 4 + wave;
   const int64_t cnt = wid < n_blocks ? (n_blocks - wid + n_waves - 1) / n_waves : 0;   // blocks of this wave
+  const int64_t skip_blk = skip_row >= 0 ? skip_row / kDecBlockRows : -1;
 
   float m = kNegBig, l = 0.f;
   f32x4 o[8];
@@ -108,10 +109,14 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __r
       s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qf[kk], s, 0, 0, 0);
     }
     // register r of lane (g4, head) is the score of row 16*b + 4*g4 + r
-    if ((b + 1) * kDecBlockRows > n) {
+    // hidden rows: beyond the end, or the one row a streaming head's token is about to replace
+    const bool hides = (b + 1) * kDecBlockRows > n || b == skip_blk;
+    if (hides) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (b * kDecBlockRows + 4 * g4 + r >= n) s[r] = kNegBig;
+      for (int r = 0; r < 4; ++r) {
+        const int64_t row = b * kDecBlockRows + 4 * g4 + r;
+        if (row >= n || row == skip_row) s[r] = kNegBig;
+      }
     }
     float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -128,6 +133,11 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __r
     float p[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) p[r] = fast_exp2(__builtin_fmaf(s[r], c, -mc));
+    if (hides) {   // exactly zero even while nothing visible has been seen (m still at its initial value)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        if (s[r] == kNegBig) p[r] = 0.f;
+    }
     l += (p[0] + p[1]) + (p[2] + p[3]);
     bf16x4 pb;
 #pragma unroll
@@ -267,7 +277,7 @@ static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   //
 
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
                                 int n_split, void* partials, int part0, int n_heads, int64_t kv_head_stride,
-                                int64_t part_head_stride) {
+                                int64_t part_head_stride, int64_t skip_row) {
   if (n <= 0 || n_split <= 0 || n_heads < 1) { set_last_error("decode partial: empty launch"); return HI_ERR_ARG; }
   static bool attr_set = false;
   if (!attr_set) {
@@ -278,7 +288,7 @@ hi_status launch_decode_partial(void* stream, const void* q, int G, const void* 
   }
   hipLaunchKernelGGL(decode_partial_kernel, dim3(n_split, n_heads), dim3(256), kDecLdsBytes, (hipStream_t)stream,
                      (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e,
-                     kv_head_stride, part_head_stride);
+                     kv_head_stride, part_head_stride, skip_row);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("decode_partial launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
   return HI_OK;

@@ -77,9 +77,10 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
 // Split-KV decode over rows [0, n) of one slice: writes n_split partials starting at partial index part0.
 // n_heads > 1: q is [n_heads][G][128], the heads' K (V) rows kv_head_stride bytes apart, their partials
 // part_head_stride floats apart.
+// skip_row >= 0: that row takes no part (the row of a streaming head's store that the token replaces).
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
                                 int n_split, void* partials, int part0, int n_heads = 1, int64_t kv_head_stride = 0,
-                                int64_t part_head_stride = 0);
+                                int64_t part_head_stride = 0, int64_t skip_row = -1);
 // Merge n_part partials with the token's own row and write out[G][128]; if k_append/v_append are not null the
 // token's K/V row is also copied there (device rows of an HBM-resident cache; heads append_head_stride bytes
 // apart).  n_heads > 1: q and out are [n_heads][G][128], k_new / v_new [n_heads][128].
@@ -87,5 +88,19 @@ hi_status launch_decode_combine(void* stream, const void* q, int G, const void* 
                                 const void* partials, int n_part, void* out, int out_fp32, void* k_append,
                                 void* v_append, int n_heads = 1, int64_t part_head_stride = 0,
                                 int64_t append_head_stride = 0);
+
+// Streaming heads (Appendix E): a head that keeps n_sink initial and n_recent recent tokens in an HBM store of
+// n_sink + n_recent rows (sink token j at row j; token j >= n_sink at row n_sink + (j - n_sink) mod n_recent).
+constexpr int64_t kStreamMaxRows = 1 << 22;
+// One chunk of such a head (a group of n_heads, their stores store_head_stride bytes apart): row past_len + i
+// sees key j iff j <= past_len + i and (j < n_sink or past_len + i - j < n_recent); the past comes from the
+// store, the chunk's own rows from k_new / v_new.  Layouts of q, k_new, v_new, out as in launch_prefill.
+hi_status launch_prefill_window(void* stream, const void* q, int G, int chunk_len, const void* store_k,
+                                const void* store_v, int64_t store_head_stride, const void* k_new, const void* v_new,
+                                int64_t past_len, int n_sink, int n_recent, void* out, int out_fp32, int n_heads);
+// The chunk's rows enter the store (run it after the chunk's attention, on the same stream).
+hi_status launch_stream_store_update(void* stream, const void* k_new, const void* v_new, int chunk_len,
+                                     int64_t past_len, int n_sink, int n_recent, void* store_k, void* store_v,
+                                     int64_t store_head_stride, int n_heads);
 
 }  // namespace hi

@@ -26,7 +26,18 @@ hi_status validate_problem(const hi_problem* p) {
     return HI_ERR_ARG;
   }
   if (p->chunk > p->max_context) { set_last_error("chunk %d exceeds max_context", p->chunk); return HI_ERR_ARG; }
-  if (p->resident_heads < 0 || (int64_t)p->resident_heads > (int64_t)p->n_layers * p->n_kv_heads) {
+  if (p->streaming_heads < 0 || p->streaming_heads >= p->n_kv_heads || p->reserved0 != 0) {
+    set_last_error("streaming_heads must be in [0, n_kv_heads)");
+    return HI_ERR_ARG;
+  }
+  if (p->streaming_heads > 0 && (p->sink_tokens < 0 || p->recent_tokens < 1 ||
+                                 (int64_t)p->sink_tokens + p->recent_tokens > kStreamMaxRows)) {
+    set_last_error("streaming heads need sink_tokens >= 0, recent_tokens >= 1 and at most %lld rows in all",
+                   (long long)kStreamMaxRows);
+    return HI_ERR_ARG;
+  }
+  if (p->resident_heads < 0 ||
+      (int64_t)p->resident_heads > (int64_t)p->n_layers * (p->n_kv_heads - p->streaming_heads)) {
     set_last_error("resident_heads out of range");
     return HI_ERR_ARG;
   }
@@ -60,7 +71,7 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
 
   // Eq. 11 and Eq. 4
   pl.host_bytes_per_head = S * row;
-  pl.host_bytes_total = (int64_t)p->n_layers * p->n_kv_heads * pl.host_bytes_per_head;
+  pl.host_bytes_total = (int64_t)p->n_layers * (p->n_kv_heads - p->streaming_heads) * pl.host_bytes_per_head;
   if (p->host_mem_limit_bytes > 0 && pl.host_bytes_total > p->host_mem_limit_bytes) {
     set_last_error("host cache of %lld bytes exceeds the limit", (long long)pl.host_bytes_total);
     return HI_ERR_HOST_MEM;
@@ -97,18 +108,23 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   // per-call overheads dominate and as many heads as the slice can hold (64 rows each) go into one call; up to 256K
   // two heads per call still gain a few per cent; beyond, one head per call (the finest granularity) is as fast.
   {
+    const int n_retrieval = p->n_kv_heads - p->streaming_heads;   // a group never mixes the two kinds of head
     int hpg = 1;
     if (S <= 16 * 1024 + p->chunk) {
-      while (hpg * 2 <= p->n_kv_heads && (int64_t)hpg * 2 * 64 <= slice) hpg *= 2;
+      while (hpg * 2 <= n_retrieval && (int64_t)hpg * 2 * 64 <= slice) hpg *= 2;
     } else if (S <= 256 * 1024 + p->chunk) {
-      if (p->n_kv_heads >= 2 && 2 * 64 <= slice) hpg = 2;
+      if (n_retrieval >= 2 && 2 * 64 <= slice) hpg = 2;
     }
     pl.heads_per_group = hpg;
-    pl.n_groups = (int32_t)ceil_div(p->n_kv_heads, hpg);
+    pl.n_groups = (int32_t)(ceil_div(n_retrieval, hpg) + ceil_div(p->streaming_heads, hpg));
   }
   pl.hbm_resident_offset = n_slices * slice * row;
   pl.hbm_resident_bytes = (int64_t)p->resident_heads * pl.host_bytes_per_head;
-  pl.hbm_staging_bytes = pl.hbm_resident_offset + pl.hbm_resident_bytes;
+  // Appendix E: the streaming heads' bounded stores, small and outside the whole-head budget
+  pl.stream_rows = p->streaming_heads > 0 ? (int64_t)p->sink_tokens + p->recent_tokens : 0;
+  pl.hbm_stream_offset = pl.hbm_resident_offset + pl.hbm_resident_bytes;
+  pl.hbm_stream_bytes = (int64_t)p->n_layers * p->streaming_heads * pl.stream_rows * row;
+  pl.hbm_staging_bytes = pl.hbm_stream_offset + pl.hbm_stream_bytes;
 
   const int n_cu = p->n_compute_units > 0 ? p->n_compute_units : 256;
   pl.n_split_decode = n_cu;

@@ -394,6 +394,31 @@ __device__ __forceinline__ void pd_matrix_phase(uint32_t v_off, uint32_t k_off, 
   }
 }
 
+// Lane constants of a 4-wavefront workgroup whose LDS stage is a K tile followed by a V tile (offsets relative
+// to the tile).
+__device__ __forceinline__ PfLaneConst pf_lane_const_4w(int wave, int lane) {
+  PfLaneConst lc;
+  const int hl = lane >> 5, col = lane & 31;
+  const int r_in = lane >> 4, cpos = lane & 15;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = (wave * 4 + i) * 4 + r_in;
+    lc.gk[i] = (uint32_t)(r * kRowBytes + ((cpos ^ swz_k(r)) << 4));
+  }
+  const int r0 = wave * 16 + r_in;                // swz_v depends on r & 3 only, so +4 rows = +1024 bytes
+  lc.gv = (uint32_t)(r0 * kRowBytes + ((cpos ^ swz_v(r0)) << 4));
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) lc.koff[kk] = (uint32_t)(col * kRowBytes + (((2 * kk + hl) ^ swz_k(col)) << 4));
+  const int s16 = lane & 15, q16 = col >> 4;
+  const int row_lo = 4 * hl + (s16 >> 2);
+#pragma unroll
+  for (int db = 0; db < 4; ++db) {
+    const int chunk = 4 * db + 2 * q16 + ((s16 & 3) >> 1);
+    lc.voff[db] = (uint32_t)(row_lo * kRowBytes + ((chunk ^ swz_v(row_lo)) << 4) + ((s16 & 1) << 3));
+  }
+  return lc;
+}
+
 // One 64-row tile out of the LDS stage starting at kt, straight through.
 __device__ __forceinline__ void pf_compute_tile(lds_char* kt, const PfLaneConst& lc, const bf16x8 (&qf)[8],
                                                 PfState& st, float c, bool masked, int mask_rel, int hl) {
@@ -423,26 +448,7 @@ __global__ __launch_bounds__(256, 2) void prefill_kernel(PrefillArgs a) {
   const int my_i = qi;
   if (qi > a.C - 1) qi = a.C - 1;
 
-  PfLaneConst lc;
-  {
-    const int r_in = lane >> 4, cpos = lane & 15;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = (wave * 4 + i) * 4 + r_in;
-      lc.gk[i] = (uint32_t)(r * kRowBytes + ((cpos ^ swz_k(r)) << 4));
-    }
-    const int r0 = wave * 16 + r_in;                // swz_v depends on r & 3 only, so +4 rows = +1024 bytes
-    lc.gv = (uint32_t)(r0 * kRowBytes + ((cpos ^ swz_v(r0)) << 4));
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) lc.koff[kk] = (uint32_t)(col * kRowBytes + (((2 * kk + hl) ^ swz_k(col)) << 4));
-    const int s16 = lane & 15, q16 = col >> 4;
-    const int row_lo = 4 * hl + (s16 >> 2);
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      const int chunk = 4 * db + 2 * q16 + ((s16 & 3) >> 1);
-      lc.voff[db] = (uint32_t)(row_lo * kRowBytes + ((chunk ^ swz_v(row_lo)) << 4) + ((s16 & 1) << 3));
-    }
-  }
+  const PfLaneConst lc = pf_lane_const_4w(wave, lane);
 
   // Q^T operand: lane holds q[g][qi][16*kk + 8*hl .. +7]
   bf16x8 qf[8];
@@ -1130,6 +1136,242 @@ __global__ __launch_bounds__(256, 1) void prefill_kernel_wide(PrefillArgs a) {
   pf_write_row(a.out, a.out_fp32, a.C, g, my_i[1], hl, o[1], l[1]);
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Streaming heads (Appendix E, head-wise sparsity: a streaming head keeps only recent tokens - here n_sink initial
+// tokens and the n_recent most recent ones - and lives in HBM).  Query row at absolute position p sees key j iff
+// j <= p and (j < n_sink or p - j < n_recent).  The head's K/V is a bounded store of n_sink + n_recent rows: sink
+// row j at row j, token j >= n_sink in ring slot n_sink + (j - n_sink) mod n_recent.
+//
+// One launch computes a chunk.  The keys form two sequences: A, what the store holds of the past (its ns sink
+// rows, then the m most recent past rows in token order, read through the ring mapping), and B, the chunk's own
+// rows.  A workgroup visits only the 64-row tiles some of its rows can see: the sink tiles and the tiles from its
+// first row's window start on, in each sequence.
+struct PrefillWindowArgs {
+  const uint16_t* q;      // [G][C][128]
+  const char* ks; const char* vs;   // the store's K and V planes
+  const char* kb; const char* vb;   // the chunk's own rows
+  void* out;
+  int G, C, out_fp32, gy;
+  float c;
+  int n_sink, n_recent;
+  int ns;                 // sink rows of the past: min(P, n_sink)
+  int m;                  // recent rows of the past held by the ring: tokens t0 .. P-1, t0 = max(n_sink, P-n_recent+1)
+  int ring0;              // ring slot of token t0
+  int lo0;                // index in A of the first recent row visible to chunk row 0 (row i: lo0 + i); may be < ns
+  int sink_b;             // chunk rows that are sink tokens: clamp(n_sink - P, 0, C)
+  int64_t s_head_stride;  // bytes between the heads' stores
+};
+
+// pf_softmax for a tile in which lane-dependent sets of rows are hidden: row is visible iff row <= hi and
+// (row < sk or row >= lo).  A lane may see nothing of the tile (and nothing so far): hidden entries contribute
+// exactly zero whatever the running maximum is.
+__device__ __forceinline__ void pf_softmax_window(f32x16 (&s)[2], PfState& st, float c, bool masked, int hi, int sk,
+                                                  int lo, int hl, bf16x8 (&pb)[2][2]) {
+  if (masked) {
+#pragma unroll
+    for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
+        const bool vis = row <= hi && (row < sk || row >= lo);
+        if (!vis) s[sb][r] = kNegBig;
+      }
+  }
+  float mx = s[0][0];
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sb][r]);
+  mx = max_halves(mx);
+  const float m_new = fmaxf(st.m, mx);
+  if (__builtin_amdgcn_ballot_w64(m_new > st.m) != 0) {
+    const float alpha = fast_exp2((st.m - m_new) * c);
+    st.l *= alpha;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
+    st.m = m_new;
+  }
+  const float mc = st.m * c;
+  float lsum = 0.f;
+#pragma unroll
+  for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float p = fast_exp2(__builtin_fmaf(s[sb][8 * u + j], c, -mc));
+        if (masked && s[sb][8 * u + j] == kNegBig) p = 0.f;
+        lsum += p;
+        pb[sb][u][j] = (__bf16)p;
+      }
+  st.l += lsum;
+}
+
+__global__ __launch_bounds__(256, 2) void prefill_window_kernel(PrefillWindowArgs a) {
+  __shared__ __attribute__((aligned(1024))) char lds_raw[kPfLdsBytes];
+  lds_char* lds = (lds_char*)lds_raw;
+  const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+  const int lane = lane_id();
+  const int wave = wave_id();
+  const int hl = lane >> 5;
+  const int col = lane & 31;
+
+  const int gl = a.G < 4 ? a.G : 4;
+  const int strip = 32 * (4 / gl);
+  const int bx = blockIdx.x;
+  const int head = blockIdx.y / a.gy;
+  {  // group launches: this workgroup's head
+    const int64_t rows = (int64_t)head * a.C;
+    a.q += rows * a.G * kHeadDim;
+    a.out = (char*)a.out + rows * a.G * kHeadDim * (a.out_fp32 ? 4 : 2);
+    a.ks += head * a.s_head_stride;
+    a.vs += head * a.s_head_stride;
+    a.kb += rows * kRowBytes;
+    a.vb += rows * kRowBytes;
+  }
+  const int g = (blockIdx.y - head * a.gy) * 4 + (wave % gl);
+  const int i_lo = bx * strip;                      // first and last query position of the workgroup
+  const int i_hi = i_lo + strip - 1;
+  const int i0 = i_lo + 32 * (wave / gl);           // first query position of this wave
+  const int my_i = i0 + col;
+  const int qi = my_i > a.C - 1 ? a.C - 1 : my_i;
+
+  const PfLaneConst lc = pf_lane_const_4w(wave, lane);
+
+  bf16x8 qf[8];
+  {
+    const uint16_t* qrow = a.q + ((int64_t)g * a.C + qi) * kHeadDim + 8 * hl;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 16 * kk));
+  }
+  PfState st;
+  st.m = kNegBig;
+  st.l = 0.f;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) asm volatile("" : "+v"(qf[kk]));
+
+  // tiles this workgroup visits: A [0, a1) and [a2, ta), then B [0, b1) and [b2, tb)
+  const int nA = a.ns + a.m;
+  const int ta = (nA + kPfTileRows - 1) / kPfTileRows;
+  const int nb_vis = a.C < i_hi + 1 ? a.C : i_hi + 1;
+  const int tb = (nb_vis + kPfTileRows - 1) / kPfTileRows;
+  int a1 = (a.ns + kPfTileRows - 1) / kPfTileRows;
+  if (a1 > ta) a1 = ta;
+  const int loA = a.lo0 + i_lo;
+  int a2 = loA <= 0 ? 0 : loA / kPfTileRows;
+  a2 = a2 < a1 ? a1 : (a2 > ta ? ta : a2);
+  int b1 = (a.sink_b + kPfTileRows - 1) / kPfTileRows;
+  if (b1 > tb) b1 = tb;
+  const int loB = i_lo - a.n_recent + 1;
+  int b2 = loB <= 0 ? 0 : loB / kPfTileRows;
+  b2 = b2 < b1 ? b1 : (b2 > tb ? tb : b2);
+  const int nAv = a1 + (ta - a2);
+  const int T = nAv + b1 + (tb - b2);            // >= 1: the tile holding the workgroup's first row
+
+  // visit v -> (sequence, tile)
+  auto locate = [&](int v, bool& in_b) __attribute__((always_inline)) {
+    in_b = v >= nAv;
+    if (!in_b) return v < a1 ? v : a2 + (v - a1);
+    const int w = v - nAv;
+    return w < b1 ? w : b2 + (w - b1);
+  };
+
+  auto issue = [&](int v) __attribute__((always_inline)) {
+    const uint32_t stage = lds_base + (uint32_t)(v & (kPfStages - 1)) * kPfStageBytes;
+    bool in_b;
+    const int tile = locate(v, in_b);
+    if (in_b) {
+      const int row0 = tile * kPfTileRows;
+      const int left = a.C - row0;
+      pf_issue_tile<4>(a.kb + (int64_t)row0 * kRowBytes, a.vb + (int64_t)row0 * kRowBytes,
+                       left < kPfTileRows ? left : kPfTileRows, stage, wave, lane, lc);
+    } else {
+      // rows of A come through the ring mapping: per-lane addresses
+      const int r_in = lane >> 4, cpos = lane & 15;
+      const uint32_t ld = stage + wave * 4096;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int r = (wave * 4 + i) * 4 + r_in;
+        int u = tile * kPfTileRows + r;
+        if (u > nA - 1) u = nA - 1;
+        int phys = u;
+        if (u >= a.ns) {
+          int w = a.ring0 + (u - a.ns);
+          if (w >= a.n_recent) w -= a.n_recent;
+          phys = a.n_sink + w;
+        }
+        g2lds16_s<0>(a.ks, (uint32_t)phys * kRowBytes + ((cpos ^ swz_k(r)) << 4), ld + i * 1024);
+        g2lds16_s<0>(a.vs, (uint32_t)phys * kRowBytes + ((cpos ^ swz_v(r)) << 4), ld + kPfTileBytes + i * 1024);
+      }
+    }
+  };
+
+  issue(0);
+  const float c = a.c;
+  auto step = [&](int v, auto stage_tag) __attribute__((always_inline)) {
+    constexpr int STAGE = decltype(stage_tag)::value;
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (v + 1 < T) issue(v + 1);
+    bool in_b;
+    const int j0 = locate(v, in_b) * kPfTileRows;
+    // per lane: row visible iff row <= hi and (row < sk or row >= lo), rows relative to the tile
+    int hi, sk, lo;
+    bool full;          // wave-uniform: every row of the tile is visible to every query row of this wave
+    if (in_b) {
+      hi = (my_i < a.C - 1 ? my_i : a.C - 1) - j0;
+      sk = a.sink_b - j0;
+      lo = my_i - a.n_recent + 1 - j0;
+      full = j0 + kPfTileRows - 1 <= (i0 < a.C - 1 ? i0 : a.C - 1) &&
+             (j0 + kPfTileRows - 1 < a.sink_b || j0 >= i0 + 31 - a.n_recent + 1);
+    } else {
+      hi = nA - 1 - j0;
+      sk = a.ns - j0;
+      lo = a.lo0 + my_i - j0;
+      full = j0 + kPfTileRows - 1 <= nA - 1 && (j0 + kPfTileRows - 1 < a.ns || j0 >= a.lo0 + i0 + 31);
+    }
+    lds_char* kt = lds + STAGE * kPfStageBytes;
+    f32x16 s[2];
+    bf16x8 pb[2][2];
+    pf_scores(kt, lc, qf, s);
+    pf_softmax_window(s, st, c, !full, hi, sk, lo, hl, pb);
+    pf_pv(kt + kPfTileBytes, lc, pb, st);
+  };
+  int v = 0;
+  for (; v + 1 < T; v += 2) {
+    step(v, std::integral_constant<int, 0>());
+    step(v + 1, std::integral_constant<int, 1>());
+  }
+  if (v < T) step(v, std::integral_constant<int, 0>());
+
+  pf_write_row(a.out, a.out_fp32, a.C, g, my_i, hl, st.o, st.l);
+}
+
+// The chunk's rows enter a streaming head's store (after the chunk's attention has read it): chunk rows that are
+// sink tokens go to their sink rows, the last n_recent rows (that are not sinks) to their ring slots.
+// grid (row blocks, heads, 2: K and V); 16 bytes per thread.
+__global__ __launch_bounds__(256) void stream_store_update_kernel(const char* __restrict__ k_new,
+                                                                  const char* __restrict__ v_new,
+                                                                  char* __restrict__ ks, char* __restrict__ vs, int C,
+                                                                  int64_t P, int n_sink, int n_recent, int cs, int u0r,
+                                                                  int cr, int64_t s_head_stride) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int r = (int)(idx >> 4), part = (int)(idx & 15);
+  if (r >= cs + cr) return;
+  const int u = r < cs ? r : u0r + (r - cs);                       // chunk row
+  const int64_t j = P + u;                                         // its token
+  const int64_t dst = r < cs ? j : n_sink + (j - n_sink) % n_recent;
+  const char* src = (blockIdx.z ? v_new : k_new) + ((int64_t)blockIdx.y * C + u) * kRowBytes + part * 16;
+  char* d = (blockIdx.z ? vs : ks) + blockIdx.y * s_head_stride + dst * kRowBytes + part * 16;
+  *(uint4*)d = *(const uint4*)src;
+}
+
 static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   // log2(e) / sqrt(128)
 
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& sa,
@@ -1200,6 +1442,59 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("prefill launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+  return HI_OK;
+}
+
+hi_status launch_prefill_window(void* stream, const void* q, int G, int chunk_len, const void* store_k,
+                                const void* store_v, int64_t store_head_stride, const void* k_new, const void* v_new,
+                                int64_t past_len, int n_sink, int n_recent, void* out, int out_fp32, int n_heads) {
+  if (n_heads < 1 || chunk_len < 1 || !(G == 1 || G == 2 || G == 4 || G == 8) || past_len < 0 || n_sink < 0 ||
+      n_recent < 1 || (int64_t)n_sink + n_recent > kStreamMaxRows) {
+    set_last_error("windowed prefill launch: bad shape");
+    return HI_ERR_ARG;
+  }
+  PrefillWindowArgs a;
+  a.q = (const uint16_t*)q;
+  a.ks = (const char*)store_k; a.vs = (const char*)store_v;
+  a.kb = (const char*)k_new; a.vb = (const char*)v_new;
+  a.out = out;
+  a.G = G; a.C = chunk_len; a.out_fp32 = out_fp32;
+  a.gy = prefill_grid_y(G);
+  a.c = kScaleLog2e;
+  a.n_sink = n_sink; a.n_recent = n_recent;
+  const int64_t P = past_len;
+  const int64_t t0 = P - n_recent + 1 > n_sink ? P - n_recent + 1 : n_sink;
+  a.ns = (int)(P < n_sink ? P : n_sink);
+  a.m = (int)(P > t0 ? P - t0 : 0);
+  a.ring0 = a.m > 0 ? (int)((t0 - n_sink) % n_recent) : 0;
+  a.lo0 = (int)(P - n_recent - t0 + 1) + a.ns;       // token P - n_recent + 1 as an index into A
+  a.sink_b = (int)(n_sink > P ? (n_sink - P < chunk_len ? n_sink - P : chunk_len) : 0);
+  a.s_head_stride = store_head_stride;
+  dim3 grid((unsigned)ceil_div(chunk_len, prefill_strip(G)), (unsigned)(a.gy * n_heads));
+  hipLaunchKernelGGL(prefill_window_kernel, grid, dim3(kWgThreads), 0, (hipStream_t)stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_error("windowed prefill launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+  return HI_OK;
+}
+
+hi_status launch_stream_store_update(void* stream, const void* k_new, const void* v_new, int chunk_len,
+                                     int64_t past_len, int n_sink, int n_recent, void* store_k, void* store_v,
+                                     int64_t store_head_stride, int n_heads) {
+  if (n_heads < 1 || chunk_len < 1 || past_len < 0 || n_sink < 0 || n_recent < 1) {
+    set_last_error("store update launch: bad shape");
+    return HI_ERR_ARG;
+  }
+  const int cs = (int)(n_sink > past_len ? (n_sink - past_len < chunk_len ? n_sink - past_len : chunk_len) : 0);
+  int u0r = chunk_len - n_recent;
+  if (u0r < cs) u0r = cs;
+  const int cr = chunk_len - u0r;
+  if (cs + cr == 0) return HI_OK;
+  dim3 grid((unsigned)ceil_div((int64_t)(cs + cr) * 16, 256), (unsigned)n_heads, 2);
+  hipLaunchKernelGGL(stream_store_update_kernel, grid, dim3(256), 0, (hipStream_t)stream, (const char*)k_new,
+                     (const char*)v_new, (char*)store_k, (char*)store_v, chunk_len, past_len, n_sink, n_recent, cs, u0r,
+                     cr, store_head_stride);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_error("store update launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
   return HI_OK;
 }
 

@@ -11,7 +11,8 @@ from . import binding as hb
 
 class Session:
     def __init__(self, n_layers, n_kv_heads, gqa_group, max_context, chunk, mode=hb.HI_MODE_OFFLOAD, out_fp32=1,
-                 device="cuda:0", gpu_kv_budget_heads=1, n_compute_units=0, resident_heads=0):
+                 device="cuda:0", gpu_kv_budget_heads=1, n_compute_units=0, resident_heads=0, streaming_heads=0,
+                 sink_tokens=0, recent_tokens=0):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the library has no CPU path")
         self.device = torch.device(device)
@@ -19,7 +20,8 @@ class Session:
         self.G = gqa_group
         self.problem = hb.make_problem(n_layers, n_kv_heads, gqa_group, max_context, chunk, out_fp32=out_fp32,
                                        gpu_kv_budget_heads=gpu_kv_budget_heads, n_compute_units=n_compute_units,
-                                       resident_heads=resident_heads)
+                                       resident_heads=resident_heads, streaming_heads=streaming_heads,
+                                       sink_tokens=sink_tokens, recent_tokens=recent_tokens)
         self.plan = hb.hi_offload_plan(self.problem)
         nbytes = self.plan.host_bytes_total
         if mode == hb.HI_MODE_OFFLOAD:
@@ -28,6 +30,8 @@ class Session:
         else:
             self.kv = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
             self.staging = None
+            if self.plan.hbm_stream_bytes > 0:      # only the streaming heads' stores are used
+                self.staging = torch.empty(self.plan.hbm_staging_bytes, dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(self.plan.workspace_bytes, dtype=torch.uint8, device=self.device)
         self.s_compute = torch.cuda.Stream(self.device)
         self.s_h2d = torch.cuda.Stream(self.device)
@@ -36,10 +40,17 @@ class Session:
                                     self.s_compute, self.s_h2d, self.s_d2h)
         self.out_dtype = torch.float32 if out_fp32 else torch.bfloat16
 
-    # [layer][kv_head][K|V][S_max][d] bf16 views of the cache (host or device)
+    # [layer][retrieval kv_head][K|V][S_max][d] bf16 views of the cache (host or device)
     def cache_view(self) -> torch.Tensor:
         p = self.problem
-        return self.kv.view(torch.bfloat16).view(p.n_layers, p.n_kv_heads, 2, p.max_context, p.head_dim)
+        return self.kv.view(torch.bfloat16).view(p.n_layers, p.n_kv_heads - p.streaming_heads, 2, p.max_context,
+                                                 p.head_dim)
+
+    # [layer][streaming head][K|V][stream_rows][d] bf16 view of the streaming heads' bounded stores
+    def stream_view(self) -> torch.Tensor:
+        p, pl = self.problem, self.plan
+        raw = self.staging[pl.hbm_stream_offset:pl.hbm_stream_offset + pl.hbm_stream_bytes]
+        return raw.view(torch.bfloat16).view(p.n_layers, p.streaming_heads, 2, pl.stream_rows, p.head_dim)
 
     # [resident head][K|V][S_max][d] bf16 view of the HBM-resident heads' K/V (offload mode, resident_heads > 0)
     def resident_view(self) -> torch.Tensor:

@@ -163,3 +163,28 @@ def test_entry_points_reject_null_context_without_touching_the_gpu():
     other = hb.hi_offload_plan(hb.make_problem(1, 1, 4, 8192, 512))
     st, _ = hb.hi_ctx_create(prob, other, hb.HI_MODE_OFFLOAD, 1, 1, 1, None, None, None, check=False)
     assert st == hb.HI_ERR_ARG and "plan" in hb.last_error()
+
+
+def test_plan_streaming_heads():
+    """Appendix E: streaming heads take a bounded HBM store each and no host rows."""
+    base = dict(n_layers=32, n_kv_heads=8, gqa_group=4, max_context=1 << 20, chunk=16384)
+    ref = hb.hi_offload_plan(hb.make_problem(**base))
+    pl = hb.hi_offload_plan(hb.make_problem(**base, streaming_heads=4, sink_tokens=64, recent_tokens=1024))
+    assert pl.stream_rows == 1088
+    assert pl.hbm_stream_bytes == 32 * 4 * 1088 * 512
+    assert pl.hbm_stream_offset == pl.hbm_resident_offset + pl.hbm_resident_bytes
+    assert pl.hbm_staging_bytes == ref.hbm_staging_bytes + pl.hbm_stream_bytes
+    assert pl.host_bytes_total == ref.host_bytes_total // 2            # 50 % sparsity: half of the host cache
+    assert (pl.slice_tokens, pl.n_slices_ring) == (ref.slice_tokens, ref.n_slices_ring)
+    assert ref.stream_rows == 0 and ref.hbm_stream_bytes == 0
+    bad = [dict(streaming_heads=8, sink_tokens=4, recent_tokens=4), dict(streaming_heads=-1),
+           dict(streaming_heads=2, sink_tokens=4, recent_tokens=0), dict(streaming_heads=2, sink_tokens=-1, recent_tokens=4),
+           dict(streaming_heads=2, sink_tokens=1 << 22, recent_tokens=1),
+           dict(streaming_heads=4, sink_tokens=4, recent_tokens=4, resident_heads=32 * 4 + 1, gpu_kv_budget_heads=200)]
+    for kw in bad:
+        st, _ = hb.hi_offload_plan(hb.make_problem(**base, **kw), check=False)
+        assert st == hb.HI_ERR_ARG, kw
+    # resident heads count over the retrieval heads only
+    ok = hb.hi_offload_plan(hb.make_problem(**base, streaming_heads=4, sink_tokens=4, recent_tokens=4,
+                                            resident_heads=3, gpu_kv_budget_heads=4))
+    assert ok.hbm_resident_bytes == 3 * ok.host_bytes_per_head
