@@ -224,6 +224,33 @@ hi_status hi_decode_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n
  *     prefetches nothing.
  */
 
+/*
+ * The steps either side of the head-wise attention calls (Section 3.1, Eq. 1: the key and value - and the query -
+ * of a token are linear projections of its hidden state; Eq. 9: the head outputs are concatenated, then projected
+ * by the model's output matrix).  Stateless: no context, only device buffers and a stream.  Weights are bf16 in
+ * [out_features][in_features] layout (y = x W^T); accumulation is fp32.
+ *
+ * hi_qkv_rope: for a chunk X [chunk_len][d_model] of hidden states whose first row is at absolute position
+ *   past_len, computes [Q | K | V] = X W_qkv^T with W_qkv [(n_q_heads + 2 n_kv_heads) * 128][d_model] (the rows of
+ *   W_Q, then W_K, then W_V), rotates every query and key head by the rotary position embedding of the evaluated
+ *   model (dimension i < 64 paired with i + 64, angle position * rope_theta^(-i / 64); rope_theta = 0: no
+ *   rotation) and writes head-major q_out [n_q_heads][chunk_len][128], k_out and v_out
+ *   [n_kv_heads][chunk_len][128] - exactly the q_dev / k_new_dev / v_new_dev of hi_prefill_group over all heads
+ *   (bf16, or fp32 with out_fp32 = 1 for checking).  workspace_dev: DEVICE, hi_proj_workspace_bytes(chunk_len)
+ *   bytes (the chunk's cos / sin table, computed in double precision); may be null when rope_theta = 0.
+ * hi_out_proj: Y [chunk_len][d_model] = Concat_h(attn[h]) W_o^T for the head-major attention output
+ *   attn [n_q_heads][chunk_len][128] (the out_dev of the attention calls) and W_o [d_model][n_q_heads * 128].
+ * d_model must be a multiple of 64; every operand must be smaller than 4 GiB; all pointers 16-byte aligned.
+ * Both enqueue on `stream` (a hipStream_t) and return.  Errors: HI_ERR_ARG, HI_ERR_UNSUPPORTED, HI_ERR_HIP.
+ * chunk_len = 1 (decode) works but runs the same 256-row tiles, mostly empty.
+ */
+hi_status hi_proj_workspace_bytes(int32_t chunk_len, int64_t* bytes);
+hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model, int32_t n_q_heads,
+                      int32_t n_kv_heads, int32_t chunk_len, int64_t past_len, double rope_theta, int32_t out_fp32,
+                      void* q_out_dev, void* k_out_dev, void* v_out_dev, void* workspace_dev);
+hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, int32_t n_q_heads, int32_t d_model,
+                      int32_t chunk_len, int32_t out_fp32, void* y_out_dev);
+
 /* T4 - drain the three streams; surfaces deferred HIP errors (HI_ERR_HIP). */
 hi_status hi_sync(hi_ctx* ctx);
 

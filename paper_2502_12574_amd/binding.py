@@ -19,7 +19,8 @@ HI_FLAG_SKIP_KERNELS, HI_FLAG_SKIP_COPIES, HI_FLAG_TIME_KERNELS = 1, 2, 4
 HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_WIDE, HI_FLAG_PREFILL_DEEP = 8, 16, 32
 
 EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
-           "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
+           "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_proj_workspace_bytes",
+           "hi_qkv_rope", "hi_out_proj", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
 
 
 class hi_problem(C.Structure):
@@ -82,6 +83,9 @@ def lib() -> C.CDLL:
         L.hi_decode_head.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp, i32, i32, i64]
         L.hi_prefill_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, i32, vp, i32, i32, i32, i64]
         L.hi_decode_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, vp, i32, i32, i32, i64]
+        L.hi_proj_workspace_bytes.argtypes = [i32, C.POINTER(i64)]
+        L.hi_qkv_rope.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp, vp]
+        L.hi_out_proj.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
         L.hi_sync.argtypes = [vp]
         L.hi_get_stats.argtypes = [vp, C.POINTER(hi_stats)]
         L.hi_reset_stats.argtypes = [vp]
@@ -196,6 +200,32 @@ def hi_decode_group(ctx, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, p
                                _ptr(out_dev), next_layer, next_kv_head, next_n_heads, next_past_len)
     if check and st != HI_OK:
         raise HiError(st, "hi_decode_group")
+    return st
+
+
+def hi_proj_workspace_bytes(chunk_len: int) -> int:
+    n = C.c_int64()
+    st = lib().hi_proj_workspace_bytes(chunk_len, C.byref(n))
+    if st != HI_OK:
+        raise HiError(st, "hi_proj_workspace_bytes")
+    return n.value
+
+
+def hi_qkv_rope(stream, x_dev, w_qkv_dev, d_model, n_q_heads, n_kv_heads, chunk_len, past_len, rope_theta, out_fp32,
+                q_out_dev, k_out_dev, v_out_dev, workspace_dev, check: bool = True):
+    st = lib().hi_qkv_rope(_stream(stream), _ptr(x_dev), _ptr(w_qkv_dev), d_model, n_q_heads, n_kv_heads, chunk_len,
+                           past_len, float(rope_theta), out_fp32, _ptr(q_out_dev), _ptr(k_out_dev), _ptr(v_out_dev),
+                           _ptr(workspace_dev))
+    if check and st != HI_OK:
+        raise HiError(st, "hi_qkv_rope")
+    return st
+
+
+def hi_out_proj(stream, attn_dev, w_o_dev, n_q_heads, d_model, chunk_len, out_fp32, y_out_dev, check: bool = True):
+    st = lib().hi_out_proj(_stream(stream), _ptr(attn_dev), _ptr(w_o_dev), n_q_heads, d_model, chunk_len, out_fp32,
+                           _ptr(y_out_dev))
+    if check and st != HI_OK:
+        raise HiError(st, "hi_out_proj")
     return st
 
 

@@ -1,0 +1,346 @@
+// The steps either side of head-wise attention, for gfx950: Q/K/V projection (Section 3.1, Eq. 1: K_t = W_K E(x_t),
+// V_t = W_V E(x_t), the query likewise) with the rotary position embedding of the evaluated model fused into its
+// epilogue and the results written head-major - the layout the attention calls take - and the output projection
+// that consumes the concatenated head outputs (Eq. 9).
+//
+// Both are one bf16 MFMA contraction D[a][b] = sum_k A[a][k] B[b][k] over two row-major operands whose contraction
+// index is contiguous (activations [tokens][features] and weights [out_features][in_features] both are):
+//   * a workgroup (8 wavefronts, two per SIMD) owns a 256 x 256 tile of D and walks the contraction in steps of 64;
+//     each step's 256 x 64 slices of A and of B (32 KiB each) go HBM/L2 -> LDS by direct-to-LDS 128-bit loads into
+//     one of two stages, one barrier per step, the next step's loads in flight while this one is multiplied;
+//   * rows are 128 bytes in LDS; 16-byte chunk c of row r sits at chunk position c ^ ((r >> 1) & 7), which makes
+//     the 32x32x16 MFMA operand reads (16 lanes = 16 consecutive rows, one chunk each) bank-conflict free;
+//   * a wavefront owns 64 rows of A (two 32-row blocks) x 128 rows of B (four blocks): 8 accumulator blocks, 6 operand
+//     reads per 8 MFMAs.  In the Q/K/V projection A is the weight, and a wavefront's two blocks are the dimensions
+//     i .. i+31 and i+64 .. i+95 of one head, so the two members of every rotary pair meet in one lane;
+//   * the tiles of one XCD (workgroups are dealt to the 8 XCDs round-robin) form a compact block of the tile grid
+//     and advance through the contraction together, so each operand slice is fetched into that XCD's L2 about once.
+#include <type_traits>
+#include "hi_device.h"
+#include "hi_internal.h"
+
+namespace hi {
+
+typedef __attribute__((address_space(3))) bf16x8* lds_bf16x8_p;
+
+constexpr int kPjTile = 256;                              // rows of A, and of B, per workgroup
+constexpr int kPjK = 64;                                  // contraction elements per step
+constexpr int kPjRowBytes = kPjK * 2;
+constexpr int kPjOperandBytes = kPjTile * kPjRowBytes;    // 32 KiB
+constexpr int kPjStageBytes = 2 * kPjOperandBytes;        // A slice then B slice
+constexpr int kPjLdsBytes = 2 * kPjStageBytes;            // 128 KiB
+constexpr int kPjWaves = 8;
+
+enum { kPjQkv = 0, kPjOut = 1 };
+
+struct ProjArgs {
+  const char* a; const char* b;       // operand rows (bf16), contraction index contiguous
+  int a_rows, b_rows;                 // valid rows (loads clamp, the epilogue masks)
+  uint32_t a_stride, b_stride;        // bytes between rows
+  int64_t a_head_stride;              // kPjOut: A[row][k] is at a + (k / 128) * a_head_stride + row * 256 + (k % 128) * 2
+  int K;                              // contraction length, a multiple of 64
+  int a_tiles, b_tiles, ga;           // tile grid; tiles are ordered in groups of ga A-tiles (see pj_tile_of)
+  int out_fp32;
+  // kPjQkv: A = W_qkv [(Hq + 2 Hkv) * 128][K], B = X [C][K]
+  void* q_out; void* k_out; void* v_out;   // [Hq][C][128], [Hkv][C][128], [Hkv][C][128]
+  int n_q_heads, n_kv_heads;
+  const float2* rope;                 // [C][64] (cos, sin) of the chunk's positions; null: no rotation
+  // kPjOut: A = attention output [Hq][C][128], B = W_o [D][Hq * 128]
+  void* y; int64_t y_stride;          // [C][y_stride] elements
+};
+
+// tile j of the grid: groups of ga A-tiles; inside a group B-major with the A-tile index fastest, so that any run of
+// consecutive j is a compact block
+__device__ __forceinline__ void pj_tile_of(const ProjArgs& p, int j, int& ta, int& tb) {
+  const int full = p.a_tiles / p.ga;            // groups of exactly ga A-tiles
+  const int per_group = p.ga * p.b_tiles;
+  const int g = j / per_group;
+  if (g < full) {
+    const int w = j - g * per_group;
+    ta = g * p.ga + w % p.ga;
+    tb = w / p.ga;
+  } else {
+    const int rem = p.a_tiles - full * p.ga;
+    const int w = j - full * per_group;
+    ta = full * p.ga + w % rem;
+    tb = w / rem;
+  }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(512, 2) void proj_gemm_kernel(ProjArgs p) {
+  extern __shared__ __attribute__((aligned(1024))) char lds_dyn[];
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_char*)lds_dyn;
+  const int lane = lane_id();
+  const int wave = wave_id();
+  const int l = lane & 31, hl = lane >> 5;
+  const int wa = wave & 3, wb = wave >> 2;
+
+  // this workgroup's tile: XCD x (= blockIdx % 8) takes tiles [x * per, (x + 1) * per) of the ordered list
+  const int total = p.a_tiles * p.b_tiles;
+  const int per = (total + 7) >> 3;
+  const int j = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= per || j >= total) return;
+  int ta, tb;
+  pj_tile_of(p, j, ta, tb);
+
+  // ---- tile traffic: this wavefront's 4 load instructions per operand cover rows 32 w + 8 u + lane / 8
+  uint32_t ga_off[4], gb_off[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int row = 32 * wave + 8 * u + (lane >> 3);
+    const int chunk = (lane & 7) ^ (4 * (u & 1) + (lane >> 4));      // = (lane & 7) ^ ((row >> 1) & 7)
+    int ra = ta * kPjTile + row, rb = tb * kPjTile + row;
+    ra = ra < p.a_rows ? ra : p.a_rows - 1;
+    rb = rb < p.b_rows ? rb : p.b_rows - 1;
+    ga_off[u] = (uint32_t)ra * p.a_stride + (chunk << 4);
+    gb_off[u] = (uint32_t)rb * p.b_stride + (chunk << 4);
+  }
+  auto issue = [&](int t, int stage) __attribute__((always_inline)) {
+    const int k0 = t * kPjK;
+    const char* ab = MODE == kPjOut ? p.a + (int64_t)(k0 >> 7) * p.a_head_stride + (k0 & 127) * 2 : p.a + (int64_t)k0 * 2;
+    const char* bb = p.b + (int64_t)k0 * 2;
+    const uint32_t la = lds_base + stage * kPjStageBytes + wave * 4096;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) g2lds16_s<0>(ab, ga_off[u], la + u * 1024);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) g2lds16_s<0>(bb, gb_off[u], la + kPjOperandBytes + u * 1024);
+  };
+
+  // ---- operand reads: lane l reads row (block row0 + l), chunk (2 kk + hl), of the A and of the B slice
+  uint32_t koff[4];
+  {
+    const int sw = (l >> 1) & 7;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) koff[kk] = (uint32_t)(l * kPjRowBytes + (((2 * kk + hl) ^ sw) << 4));
+  }
+  const int a_row0 = (wa >> 1) * 128 + (wa & 1) * 32;       // block ia adds 64 rows
+  const uint32_t a_lds = lds_base + a_row0 * kPjRowBytes;   // + ia * 8192
+  const uint32_t b_lds = lds_base + kPjOperandBytes + wb * 128 * kPjRowBytes;   // + ib * 4096
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int ia = 0; ia < 2; ++ia)
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ia][ib][r] = 0.f;
+
+  auto compute = [&](auto stage_tag) __attribute__((always_inline)) {
+    constexpr uint32_t ST = decltype(stage_tag)::value * kPjStageBytes;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      bf16x8 af[2], bf[4];
+#pragma unroll
+      for (int ia = 0; ia < 2; ++ia) af[ia] = *(lds_bf16x8_p)(uintptr_t)(a_lds + ST + ia * 8192 + koff[kk]);
+#pragma unroll
+      for (int ib = 0; ib < 4; ++ib) bf[ib] = *(lds_bf16x8_p)(uintptr_t)(b_lds + ST + ib * 4096 + koff[kk]);
+#pragma unroll
+      for (int ia = 0; ia < 2; ++ia)
+#pragma unroll
+        for (int ib = 0; ib < 4; ++ib)
+          acc[ia][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ia], bf[ib], acc[ia][ib], 0, 0, 0);
+    }
+  };
+
+  const int T = p.K / kPjK;
+  issue(0, 0);
+  int t = 0;
+  for (; t + 1 < T; t += 2) {
+    wait_vmcnt<0>();
+    __syncthreads();
+    issue(t + 1, 1);
+    compute(std::integral_constant<int, 0>());
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (t + 2 < T) issue(t + 2, 0);
+    compute(std::integral_constant<int, 1>());
+  }
+  if (t < T) {
+    wait_vmcnt<0>();
+    __syncthreads();
+    compute(std::integral_constant<int, 0>());
+  }
+
+  // ---- epilogue.  Register r of block (ia, ib): A-row a_row0 + 64 ia + 8 (r / 4) + 4 hl + r % 4, B-row 128 wb + 32 ib + l
+  if (MODE == kPjQkv) {
+    const int head = 2 * ta + (wa >> 1);
+    if (head >= p.n_q_heads + 2 * p.n_kv_heads) return;
+    const bool rotate = p.rope != nullptr && head < p.n_q_heads + p.n_kv_heads;
+    char* base;
+    int hh;
+    if (head < p.n_q_heads) { base = (char*)p.q_out; hh = head; }
+    else if (head < p.n_q_heads + p.n_kv_heads) { base = (char*)p.k_out; hh = head - p.n_q_heads; }
+    else { base = (char*)p.v_out; hh = head - p.n_q_heads - p.n_kv_heads; }
+    const int esz = p.out_fp32 ? 4 : 2;
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) {
+      const int m = tb * kPjTile + wb * 128 + ib * 32 + l;          // token of this lane
+      if (m >= p.b_rows) continue;
+      char* row = base + ((int64_t)hh * p.b_rows + m) * kHeadDim * esz;
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int i0 = (wa & 1) * 32 + 8 * rq + 4 * hl;              // dims i0 .. i0+3 and 64 + i0 .. 64 + i0+3
+        float lo[4], hi[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { lo[e] = acc[0][ib][4 * rq + e]; hi[e] = acc[1][ib][4 * rq + e]; }
+        if (rotate) {
+          const float4* cs = (const float4*)(p.rope + (int64_t)m * 64 + i0);
+          const float4 c01 = cs[0], c23 = cs[1];                     // (cos, sin) of two dims each
+          const float cv[4] = {c01.x, c01.z, c23.x, c23.z}, sv[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float x = lo[e], y = hi[e];
+            lo[e] = x * cv[e] - y * sv[e];
+            hi[e] = y * cv[e] + x * sv[e];
+          }
+        }
+        if (p.out_fp32) {
+          *(float4*)(row + i0 * 4) = make_float4(lo[0], lo[1], lo[2], lo[3]);
+          *(float4*)(row + (64 + i0) * 4) = make_float4(hi[0], hi[1], hi[2], hi[3]);
+        } else {
+          uint2 pl, ph;
+          pl.x = (uint32_t)float_to_bf16_bits(lo[0]) | ((uint32_t)float_to_bf16_bits(lo[1]) << 16);
+          pl.y = (uint32_t)float_to_bf16_bits(lo[2]) | ((uint32_t)float_to_bf16_bits(lo[3]) << 16);
+          ph.x = (uint32_t)float_to_bf16_bits(hi[0]) | ((uint32_t)float_to_bf16_bits(hi[1]) << 16);
+          ph.y = (uint32_t)float_to_bf16_bits(hi[2]) | ((uint32_t)float_to_bf16_bits(hi[3]) << 16);
+          *(uint2*)(row + i0 * 2) = pl;
+          *(uint2*)(row + (64 + i0) * 2) = ph;
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int ib = 0; ib < 4; ++ib) {
+      const int n = tb * kPjTile + wb * 128 + ib * 32 + l;          // output feature of this lane
+      if (n >= p.b_rows) continue;
+#pragma unroll
+      for (int ia = 0; ia < 2; ++ia)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = ta * kPjTile + a_row0 + 64 * ia + 8 * (r >> 2) + 4 * hl + (r & 3);
+          if (m >= p.a_rows) continue;
+          const int64_t at = (int64_t)m * p.y_stride + n;
+          if (p.out_fp32) ((float*)p.y)[at] = acc[ia][ib][r];
+          else ((uint16_t*)p.y)[at] = float_to_bf16_bits(acc[ia][ib][r]);
+        }
+    }
+  }
+}
+
+// (cos, sin) of position (past + t) times theta^(-i / 64) for i < 64, in double precision: at a million tokens the
+// angle of the fastest pair is a million radians, beyond what fp32 can reduce
+struct RopeFreqs { double inv[64]; };
+__global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ out, int64_t past, int n, RopeFreqs f) {
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n * 64) return;
+  const int t = idx >> 6, i = idx & 63;
+  double s, c;
+  sincos((double)(past + t) * f.inv[i], &s, &c);
+  out[idx] = make_float2((float)c, (float)s);
+}
+
+static hi_status pj_launch(void* stream, ProjArgs& p, int mode) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)proj_gemm_kernel<kPjQkv>, hipFuncAttributeMaxDynamicSharedMemorySize, kPjLdsBytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)proj_gemm_kernel<kPjOut>, hipFuncAttributeMaxDynamicSharedMemorySize, kPjLdsBytes);
+    if (e != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+    attr_set = true;
+  }
+  p.a_tiles = (int)ceil_div(p.a_rows, kPjTile);
+  p.b_tiles = (int)ceil_div(p.b_rows, kPjTile);
+  p.ga = p.a_tiles / 8 > 0 ? p.a_tiles / 8 : 1;
+  const int total = p.a_tiles * p.b_tiles;
+  const int per = (total + 7) / 8;
+  dim3 grid((unsigned)(per * 8));
+  if (mode == kPjQkv) hipLaunchKernelGGL(proj_gemm_kernel<kPjQkv>, grid, dim3(kPjWaves * 64), kPjLdsBytes, (hipStream_t)stream, p);
+  else hipLaunchKernelGGL(proj_gemm_kernel<kPjOut>, grid, dim3(kPjWaves * 64), kPjLdsBytes, (hipStream_t)stream, p);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_error("projection launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+  return HI_OK;
+}
+
+static bool pj_aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
+
+}  // namespace hi
+
+using namespace hi;
+
+extern "C" hi_status hi_proj_workspace_bytes(int32_t chunk, int64_t* bytes) {
+  if (chunk < 1 || !bytes) { set_last_error("projection workspace: bad argument"); return HI_ERR_ARG; }
+  *bytes = (int64_t)chunk * 64 * sizeof(float2);
+  return HI_OK;
+}
+
+extern "C" hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model,
+                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t chunk_len, int64_t past_len,
+                                 double rope_theta, int32_t out_fp32, void* q_out_dev, void* k_out_dev,
+                                 void* v_out_dev, void* workspace_dev) {
+  if (!x_dev || !w_qkv_dev || !q_out_dev || !k_out_dev || !v_out_dev || (rope_theta > 0 && !workspace_dev)) {
+    set_last_error("qkv projection: null buffer");
+    return HI_ERR_ARG;
+  }
+  if (!pj_aligned16(x_dev) || !pj_aligned16(w_qkv_dev) || !pj_aligned16(q_out_dev) || !pj_aligned16(k_out_dev) ||
+      !pj_aligned16(v_out_dev) || !pj_aligned16(workspace_dev)) {
+    set_last_error("qkv projection: buffers must be 16-byte aligned");
+    return HI_ERR_ARG;
+  }
+  if (n_q_heads < 1 || n_kv_heads < 1 || chunk_len < 1 || past_len < 0 || rope_theta < 0 || (out_fp32 != 0 && out_fp32 != 1)) {
+    set_last_error("qkv projection: bad shape");
+    return HI_ERR_ARG;
+  }
+  const int64_t n_out = (int64_t)(n_q_heads + 2 * n_kv_heads) * kHeadDim;
+  if (d_model < kPjK || d_model % kPjK != 0 || n_out * d_model * 2 >= (1LL << 32) ||
+      (int64_t)chunk_len * d_model * 2 >= (1LL << 32)) {
+    set_last_error("qkv projection: d_model must be a multiple of %d and each operand smaller than 4 GiB", kPjK);
+    return HI_ERR_UNSUPPORTED;
+  }
+  ProjArgs p = {};
+  p.a = (const char*)w_qkv_dev; p.b = (const char*)x_dev;
+  p.a_rows = (int)n_out; p.b_rows = chunk_len;
+  p.a_stride = (uint32_t)d_model * 2; p.b_stride = (uint32_t)d_model * 2;
+  p.K = d_model;
+  p.out_fp32 = out_fp32;
+  p.q_out = q_out_dev; p.k_out = k_out_dev; p.v_out = v_out_dev;
+  p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads;
+  p.rope = nullptr;
+  if (rope_theta > 0) {
+    RopeFreqs f;
+    for (int i = 0; i < 64; ++i) f.inv[i] = pow(rope_theta, -(double)i / 64.0);
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)ceil_div((int64_t)chunk_len * 64, 256)), dim3(256), 0,
+                       (hipStream_t)stream, (float2*)workspace_dev, past_len, chunk_len, f);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { set_last_error("rope table launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+    p.rope = (const float2*)workspace_dev;
+  }
+  return pj_launch(stream, p, kPjQkv);
+}
+
+extern "C" hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, int32_t n_q_heads,
+                                 int32_t d_model, int32_t chunk_len, int32_t out_fp32, void* y_out_dev) {
+  if (!attn_dev || !w_o_dev || !y_out_dev) { set_last_error("output projection: null buffer"); return HI_ERR_ARG; }
+  if (!pj_aligned16(attn_dev) || !pj_aligned16(w_o_dev) || !pj_aligned16(y_out_dev)) {
+    set_last_error("output projection: buffers must be 16-byte aligned");
+    return HI_ERR_ARG;
+  }
+  if (n_q_heads < 1 || d_model < 1 || chunk_len < 1 || (out_fp32 != 0 && out_fp32 != 1)) {
+    set_last_error("output projection: bad shape");
+    return HI_ERR_ARG;
+  }
+  const int64_t K = (int64_t)n_q_heads * kHeadDim;
+  if ((int64_t)d_model * K * 2 >= (1LL << 32) || (int64_t)chunk_len * kRowBytes >= (1LL << 32)) {
+    set_last_error("output projection: each operand must be smaller than 4 GiB");
+    return HI_ERR_UNSUPPORTED;
+  }
+  ProjArgs p = {};
+  p.a = (const char*)attn_dev; p.b = (const char*)w_o_dev;
+  p.a_rows = chunk_len; p.b_rows = d_model;
+  p.a_stride = kRowBytes; p.b_stride = (uint32_t)K * 2;
+  p.a_head_stride = (int64_t)chunk_len * kRowBytes;
+  p.K = (int)K;
+  p.out_fp32 = out_fp32;
+  p.y = y_out_dev; p.y_stride = d_model;
+  return pj_launch(stream, p, kPjOut);
+}

@@ -25,6 +25,7 @@ import numpy as np
 import torch
 
 TENSOR_Q, TENSOR_K, TENSOR_V, TENSOR_SCALE = 1, 2, 3, 4
+TENSOR_X, TENSOR_WQKV, TENSOR_WO = 5, 6, 7
 
 _M32 = 0xFFFFFFFF
 # odd multipliers below 2**31 (so a 32-bit value times one of them stays below 2**63)
@@ -135,6 +136,21 @@ def draw_k(seed, layer, kv_head, tok_start, n_tok, head_dim=128, device="cpu", p
 
 def draw_v(seed, layer, kv_head, tok_start, n_tok, head_dim=128, device="cpu"):
     return draw(seed, TENSOR_V, layer, kv_head, tok_start, n_tok, head_dim, device)
+
+
+def draw_hidden(seed, layer, tok_start, n_tok, d_model, device="cpu"):
+    """bf16 N(0,1) hidden states [n_tok, d_model] entering a layer's attention block."""
+    return draw(seed, TENSOR_X, layer, 0, tok_start, n_tok, d_model, device)
+
+
+def draw_weight(seed, tensor, layer, out_features, in_features, device="cpu"):
+    """bf16 weight [out_features, in_features] (the layout of y = x W^T): N(0,1) scaled by the power of two nearest
+    to 1/sqrt(in_features) (exact in bf16), so that projections of N(0,1) rows come out near unit variance."""
+    import math
+
+    w = draw(seed, tensor, layer, 0, 0, out_features, in_features, device)
+    scale = 2.0 ** (-round(math.log2(in_features) / 2.0))
+    return (w.to(torch.float32) * scale).to(torch.bfloat16)
 
 
 def to_f64(x: torch.Tensor) -> np.ndarray:
