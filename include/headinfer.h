@@ -240,7 +240,7 @@ hi_status hi_decode_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n
  *   bytes (the chunk's cos / sin table, computed in double precision); may be null when rope_theta = 0.
  * hi_out_proj: Y [chunk_len][d_model] = Concat_h(attn[h]) W_o^T for the head-major attention output
  *   attn [n_q_heads][chunk_len][128] (the out_dev of the attention calls) and W_o [d_model][n_q_heads * 128].
- * d_model must be a multiple of 64; every operand must be smaller than 4 GiB; all pointers 16-byte aligned.
+ * d_model must be a multiple of 128; every operand must be smaller than 4 GiB; all pointers 16-byte aligned.
  * Both enqueue on `stream` (a hipStream_t) and return.  Errors: HI_ERR_ARG, HI_ERR_UNSUPPORTED, HI_ERR_HIP.
  * chunk_len = 1 (decode) works but runs the same 256-row tiles, mostly empty.
  */

@@ -29,7 +29,7 @@ constexpr int kPjRowBytes = kPjK * 2;
 constexpr int kPjOperandBytes = kPjTile * kPjRowBytes;    // 32 KiB
 constexpr int kPjStageBytes = 2 * kPjOperandBytes;        // A slice then B slice
 constexpr int kPjLdsBytes = 2 * kPjStageBytes;            // 128 KiB
-constexpr int kPjWaves = 8;
+constexpr int kPjWaves = 4;
 
 enum { kPjQkv = 0, kPjOut = 1 };
 
@@ -38,7 +38,7 @@ struct ProjArgs {
   int a_rows, b_rows;                 // valid rows (loads clamp, the epilogue masks)
   uint32_t a_stride, b_stride;        // bytes between rows
   int64_t a_head_stride;              // kPjOut: A[row][k] is at a + (k / 128) * a_head_stride + row * 256 + (k % 128) * 2
-  int K;                              // contraction length, a multiple of 64
+  int K;                              // contraction length, a multiple of 128 (an even number of steps)
   int a_tiles, b_tiles, ga;           // tile grid; tiles are ordered in groups of ga A-tiles (see pj_tile_of)
   int out_fp32;
   // kPjQkv: A = W_qkv [(Hq + 2 Hkv) * 128][K], B = X [C][K]
@@ -68,13 +68,13 @@ __device__ __forceinline__ void pj_tile_of(const ProjArgs& p, int j, int& ta, in
 }
 
 template <int MODE>
-__global__ __launch_bounds__(512, 2) void proj_gemm_kernel(ProjArgs p) {
+__global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
   extern __shared__ __attribute__((aligned(1024))) char lds_dyn[];
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_char*)lds_dyn;
   const int lane = lane_id();
   const int wave = wave_id();
   const int l = lane & 31, hl = lane >> 5;
-  const int wa = wave & 3, wb = wave >> 2;
+  const int wa = wave & 1, wb = wave >> 1;      // this wavefront: A rows 128 wa .. +127, B rows 128 wb .. +127
 
   // this workgroup's tile: XCD x (= blockIdx % 8) takes tiles [x * per, (x + 1) * per) of the ordered list
   const int total = p.a_tiles * p.b_tiles;
@@ -84,11 +84,11 @@ __global__ __launch_bounds__(512, 2) void proj_gemm_kernel(ProjArgs p) {
   int ta, tb;
   pj_tile_of(p, j, ta, tb);
 
-  // ---- tile traffic: this wavefront's 4 load instructions per operand cover rows 32 w + 8 u + lane / 8
-  uint32_t ga_off[4], gb_off[4];
+  // ---- tile traffic: this wavefront's 8 load instructions per operand cover rows 64 w + 8 u + lane / 8
+  uint32_t ga_off[8], gb_off[8];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int row = 32 * wave + 8 * u + (lane >> 3);
+  for (int u = 0; u < 8; ++u) {
+    const int row = 64 * wave + 8 * u + (lane >> 3);
     const int chunk = (lane & 7) ^ (4 * (u & 1) + (lane >> 4));      // = (lane & 7) ^ ((row >> 1) & 7)
     int ra = ta * kPjTile + row, rb = tb * kPjTile + row;
     ra = ra < p.a_rows ? ra : p.a_rows - 1;
@@ -96,75 +96,122 @@ __global__ __launch_bounds__(512, 2) void proj_gemm_kernel(ProjArgs p) {
     ga_off[u] = (uint32_t)ra * p.a_stride + (chunk << 4);
     gb_off[u] = (uint32_t)rb * p.b_stride + (chunk << 4);
   }
-  auto issue = [&](int t, int stage) __attribute__((always_inline)) {
+  // one of the 16 load instructions (8 of A, then 8 of B) of step t's slices into `stage`
+  auto issue_one = [&](int t, int stage, int u) __attribute__((always_inline)) {
     const int k0 = t * kPjK;
-    const char* ab = MODE == kPjOut ? p.a + (int64_t)(k0 >> 7) * p.a_head_stride + (k0 & 127) * 2 : p.a + (int64_t)k0 * 2;
-    const char* bb = p.b + (int64_t)k0 * 2;
-    const uint32_t la = lds_base + stage * kPjStageBytes + wave * 4096;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) g2lds16_s<0>(ab, ga_off[u], la + u * 1024);
-#pragma unroll
-    for (int u = 0; u < 4; ++u) g2lds16_s<0>(bb, gb_off[u], la + kPjOperandBytes + u * 1024);
+    const uint32_t la = lds_base + stage * kPjStageBytes + wave * 8192;
+    if (u < 8) {
+      const char* ab = MODE == kPjOut ? p.a + (int64_t)(k0 >> 7) * p.a_head_stride + (k0 & 127) * 2 : p.a + (int64_t)k0 * 2;
+      g2lds16_s<0>(ab, ga_off[u], la + u * 1024);
+    } else {
+      g2lds16_s<0>(p.b + (int64_t)k0 * 2, gb_off[u - 8], la + kPjOperandBytes + (u - 8) * 1024);
+    }
   };
 
-  // ---- operand reads: lane l reads row (block row0 + l), chunk (2 kk + hl), of the A and of the B slice
-  uint32_t koff[4];
+  // ---- operand reads: lane l reads row (32 * block + l), chunk (2 kk + hl), of the A and of the B slice.  The
+  // addresses are kept whole in registers per (stage, sub-step), the block is an immediate: no vector ALU work in
+  // the loop (with one wavefront per SIMD every such instruction between two MFMAs is matrix-pipe time lost)
+  uint32_t va[2][4], vb[2][4];
   {
     const int sw = (l >> 1) & 7;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) koff[kk] = (uint32_t)(l * kPjRowBytes + (((2 * kk + hl) ^ sw) << 4));
-  }
-  const int a_row0 = (wa >> 1) * 128 + (wa & 1) * 32;       // block ia adds 64 rows
-  const uint32_t a_lds = lds_base + a_row0 * kPjRowBytes;   // + ia * 8192
-  const uint32_t b_lds = lds_base + kPjOperandBytes + wb * 128 * kPjRowBytes;   // + ib * 4096
-
-  f32x16 acc[2][4];
+    for (int st = 0; st < 2; ++st)
 #pragma unroll
-  for (int ia = 0; ia < 2; ++ia)
+      for (int kk = 0; kk < 4; ++kk) {
+        const uint32_t ko = (uint32_t)(l * kPjRowBytes + (((2 * kk + hl) ^ sw) << 4));
+        va[st][kk] = lds_base + st * kPjStageBytes + wa * 128 * kPjRowBytes + ko;
+        vb[st][kk] = lds_base + st * kPjStageBytes + kPjOperandBytes + wb * 128 * kPjRowBytes + ko;
+      }
+  }
+  // operand i of a contraction sub-step, in the order the MFMAs below first need them: A0 B0 A1 A2 A3 B1 B2 B3
+  auto read_op = [&](int st, int kk, int i) __attribute__((always_inline)) -> bf16x8 {
+    const bool is_a = i == 0 || (i >= 2 && i < 5);
+    const int blk = i == 0 ? 0 : i == 1 ? 0 : i < 5 ? i - 1 : i - 4;
+    return *(lds_bf16x8_p)((lds_char*)(uintptr_t)(is_a ? va[st][kk] : vb[st][kk]) + blk * 4096);
+  };
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int ia = 0; ia < 4; ++ia)
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[ia][ib][r] = 0.f;
 
-  auto compute = [&](auto stage_tag) __attribute__((always_inline)) {
-    constexpr uint32_t ST = decltype(stage_tag)::value * kPjStageBytes;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 af[2], bf[4];
-#pragma unroll
-      for (int ia = 0; ia < 2; ++ia) af[ia] = *(lds_bf16x8_p)(uintptr_t)(a_lds + ST + ia * 8192 + koff[kk]);
-#pragma unroll
-      for (int ib = 0; ib < 4; ++ib) bf[ib] = *(lds_bf16x8_p)(uintptr_t)(b_lds + ST + ib * 4096 + koff[kk]);
-#pragma unroll
-      for (int ia = 0; ia < 2; ++ia)
-#pragma unroll
-        for (int ib = 0; ib < 4; ++ib)
-          acc[ia][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ia], bf[ib], acc[ia][ib], 0, 0, 0);
-    }
+  // MFMA j of a sub-step multiplies A block j % 4 with B block j / 4
+  auto mfma_j = [&](const bf16x8 (&o)[8], int j) __attribute__((always_inline)) {
+    const int ia = j & 3, ib = j >> 2;
+    acc[ia][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o[ia == 0 ? 0 : ia + 1], o[ib == 0 ? 1 : ib + 4], acc[ia][ib], 0, 0, 0);
   };
 
   const int T = p.K / kPjK;
-  issue(0, 0);
-  int t = 0;
-  for (; t + 1 < T; t += 2) {
-    wait_vmcnt<0>();
-    __syncthreads();
-    issue(t + 1, 1);
-    compute(std::integral_constant<int, 0>());
-    wait_vmcnt<0>();
-    __syncthreads();
-    if (t + 2 < T) issue(t + 2, 0);
-    compute(std::integral_constant<int, 1>());
-  }
-  if (t < T) {
-    wait_vmcnt<0>();
-    __syncthreads();
-    compute(std::integral_constant<int, 0>());
-  }
+  // The schedule.  One wavefront per SIMD keeps the matrix pipe busy on its own: operand reads run one sub-step (16
+  // contraction elements, 16 MFMAs) ahead of their use, across the step boundary too.  The barrier that publishes
+  // step t+1's slices sits before the LAST sub-step of step t, whose MFMAs then cover the first operand reads of
+  // step t+1 and the issue of step t+2's loads into the stage step t has just finished reading.  One barrier per
+  // step; a wavefront waiting at it still has 16 MFMAs in the pipe.
+  bf16x8 cur[8], nxt[8];
+#pragma unroll
+  for (int u = 0; u < 16; ++u) issue_one(0, 0, u);
+#pragma unroll
+  for (int u = 0; u < 16; ++u) issue_one(1, 1, u);
+  wait_vmcnt<16>();
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) cur[i] = read_op(0, 0, i);
 
-  // ---- epilogue.  Register r of block (ia, ib): A-row a_row0 + 64 ia + 8 (r / 4) + 4 hl + r % 4, B-row 128 wb + 32 ib + l
+  // MORE1: step t + 1 exists (its first operands are read here); MORE2: step t + 2 exists (its loads are issued here)
+  auto step = [&](int t, auto stage_tag, auto more1_tag, auto more2_tag) __attribute__((always_inline)) {
+    constexpr int STAGE = decltype(stage_tag)::value;
+    constexpr int ST = STAGE, SN = 1 - STAGE;             // this stage and the other one
+    constexpr bool MORE1 = decltype(more1_tag)::value, MORE2 = decltype(more2_tag)::value;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < 3; ++kk) {
+      // sub-step kk from one operand set while sub-step kk + 1 is read into the other
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+#ifdef PJ_DIAG_HALFREAD
+        if (j < 4) {
+#else
+        if (j < 8) {
+#endif
+          if (kk & 1) cur[j] = read_op(ST, kk + 1, j); else nxt[j] = read_op(ST, kk + 1, j);
+        }
+        mfma_j((kk & 1) ? nxt : cur, j);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+    // every read of this stage has been issued; the last sub-step's operands are in nxt
+    wait_vmcnt<0>();                                      // this wave's loads of step t + 1 have landed
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave is done reading this stage
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if (j < 8 && MORE1) cur[j] = read_op(SN, 0, j);
+      mfma_j(nxt, j);
+#ifndef PJ_DIAG_NOLOAD
+      if (MORE2) issue_one(t + 2, STAGE, j);
+#endif
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  using S0 = std::integral_constant<int, 0>;
+  using S1 = std::integral_constant<int, 1>;
+  // T is even (the contraction length is a multiple of 128): pairs of steps, the last pair without look-ahead.
+  // Straight-line code around one loop: the 256 accumulators never meet at a control-flow join.
+  int t = 0;
+  for (; t + 2 < T; t += 2) {
+    step(t, S0(), std::true_type(), std::true_type());
+    step(t + 1, S1(), std::true_type(), std::true_type());
+  }
+  step(t, S0(), std::true_type(), std::false_type());
+  step(t + 1, S1(), std::false_type(), std::false_type());
+
+  // ---- epilogue.  Register r of block (ia, ib): A-row 128 wa + 32 ia + 8 (r / 4) + 4 hl + r % 4, B-row 128 wb + 32 ib + l
   if (MODE == kPjQkv) {
-    const int head = 2 * ta + (wa >> 1);
+    const int head = 2 * ta + wa;
     if (head >= p.n_q_heads + 2 * p.n_kv_heads) return;
     const bool rotate = p.rope != nullptr && head < p.n_q_heads + p.n_kv_heads;
     char* base;
@@ -179,35 +226,37 @@ __global__ __launch_bounds__(512, 2) void proj_gemm_kernel(ProjArgs p) {
       if (m >= p.b_rows) continue;
       char* row = base + ((int64_t)hh * p.b_rows + m) * kHeadDim * esz;
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int i0 = (wa & 1) * 32 + 8 * rq + 4 * hl;              // dims i0 .. i0+3 and 64 + i0 .. 64 + i0+3
-        float lo[4], hi[4];
+      for (int ip = 0; ip < 2; ++ip)                                // blocks ip and ip + 2 hold the rotary pairs
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { lo[e] = acc[0][ib][4 * rq + e]; hi[e] = acc[1][ib][4 * rq + e]; }
-        if (rotate) {
-          const float4* cs = (const float4*)(p.rope + (int64_t)m * 64 + i0);
-          const float4 c01 = cs[0], c23 = cs[1];                     // (cos, sin) of two dims each
-          const float cv[4] = {c01.x, c01.z, c23.x, c23.z}, sv[4] = {c01.y, c01.w, c23.y, c23.w};
+        for (int rq = 0; rq < 4; ++rq) {
+          const int i0 = ip * 32 + 8 * rq + 4 * hl;                  // dims i0 .. i0+3 and 64 + i0 .. 64 + i0+3
+          float lo[4], hi[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const float x = lo[e], y = hi[e];
-            lo[e] = x * cv[e] - y * sv[e];
-            hi[e] = y * cv[e] + x * sv[e];
+          for (int e = 0; e < 4; ++e) { lo[e] = acc[ip][ib][4 * rq + e]; hi[e] = acc[ip + 2][ib][4 * rq + e]; }
+          if (rotate) {
+            const float4* cs = (const float4*)(p.rope + (int64_t)m * 64 + i0);
+            const float4 c01 = cs[0], c23 = cs[1];                   // (cos, sin) of two dims each
+            const float cv[4] = {c01.x, c01.z, c23.x, c23.z}, sv[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float x = lo[e], y = hi[e];
+              lo[e] = x * cv[e] - y * sv[e];
+              hi[e] = y * cv[e] + x * sv[e];
+            }
+          }
+          if (p.out_fp32) {
+            *(float4*)(row + i0 * 4) = make_float4(lo[0], lo[1], lo[2], lo[3]);
+            *(float4*)(row + (64 + i0) * 4) = make_float4(hi[0], hi[1], hi[2], hi[3]);
+          } else {
+            uint2 pl, ph;
+            pl.x = (uint32_t)float_to_bf16_bits(lo[0]) | ((uint32_t)float_to_bf16_bits(lo[1]) << 16);
+            pl.y = (uint32_t)float_to_bf16_bits(lo[2]) | ((uint32_t)float_to_bf16_bits(lo[3]) << 16);
+            ph.x = (uint32_t)float_to_bf16_bits(hi[0]) | ((uint32_t)float_to_bf16_bits(hi[1]) << 16);
+            ph.y = (uint32_t)float_to_bf16_bits(hi[2]) | ((uint32_t)float_to_bf16_bits(hi[3]) << 16);
+            *(uint2*)(row + i0 * 2) = pl;
+            *(uint2*)(row + (64 + i0) * 2) = ph;
           }
         }
-        if (p.out_fp32) {
-          *(float4*)(row + i0 * 4) = make_float4(lo[0], lo[1], lo[2], lo[3]);
-          *(float4*)(row + (64 + i0) * 4) = make_float4(hi[0], hi[1], hi[2], hi[3]);
-        } else {
-          uint2 pl, ph;
-          pl.x = (uint32_t)float_to_bf16_bits(lo[0]) | ((uint32_t)float_to_bf16_bits(lo[1]) << 16);
-          pl.y = (uint32_t)float_to_bf16_bits(lo[2]) | ((uint32_t)float_to_bf16_bits(lo[3]) << 16);
-          ph.x = (uint32_t)float_to_bf16_bits(hi[0]) | ((uint32_t)float_to_bf16_bits(hi[1]) << 16);
-          ph.y = (uint32_t)float_to_bf16_bits(hi[2]) | ((uint32_t)float_to_bf16_bits(hi[3]) << 16);
-          *(uint2*)(row + i0 * 2) = pl;
-          *(uint2*)(row + (64 + i0) * 2) = ph;
-        }
-      }
     }
   } else {
 #pragma unroll
@@ -215,10 +264,10 @@ __global__ __launch_bounds__(512, 2) void proj_gemm_kernel(ProjArgs p) {
       const int n = tb * kPjTile + wb * 128 + ib * 32 + l;          // output feature of this lane
       if (n >= p.b_rows) continue;
 #pragma unroll
-      for (int ia = 0; ia < 2; ++ia)
+      for (int ia = 0; ia < 4; ++ia)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int m = ta * kPjTile + a_row0 + 64 * ia + 8 * (r >> 2) + 4 * hl + (r & 3);
+          const int m = ta * kPjTile + wa * 128 + 32 * ia + 8 * (r >> 2) + 4 * hl + (r & 3);
           if (m >= p.a_rows) continue;
           const int64_t at = (int64_t)m * p.y_stride + n;
           if (p.out_fp32) ((float*)p.y)[at] = acc[ia][ib][r];
@@ -292,9 +341,9 @@ extern "C" hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_
     return HI_ERR_ARG;
   }
   const int64_t n_out = (int64_t)(n_q_heads + 2 * n_kv_heads) * kHeadDim;
-  if (d_model < kPjK || d_model % kPjK != 0 || n_out * d_model * 2 >= (1LL << 32) ||
+  if (d_model < 2 * kPjK || d_model % (2 * kPjK) != 0 || n_out * d_model * 2 >= (1LL << 32) ||
       (int64_t)chunk_len * d_model * 2 >= (1LL << 32)) {
-    set_last_error("qkv projection: d_model must be a multiple of %d and each operand smaller than 4 GiB", kPjK);
+    set_last_error("qkv projection: d_model must be a multiple of %d and each operand smaller than 4 GiB", 2 * kPjK);
     return HI_ERR_UNSUPPORTED;
   }
   ProjArgs p = {};
