@@ -242,7 +242,7 @@ hi_status hi_decode_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n
  *   attn [n_q_heads][chunk_len][128] (the out_dev of the attention calls) and W_o [d_model][n_q_heads * 128].
  * d_model must be a multiple of 128; every operand must be smaller than 4 GiB; all pointers 16-byte aligned.
  * Both enqueue on `stream` (a hipStream_t) and return.  Errors: HI_ERR_ARG, HI_ERR_UNSUPPORTED, HI_ERR_HIP.
- * chunk_len = 1 (decode) works but runs the same 256-row tiles, mostly empty.
+ * chunk_len = 1 (decode) takes a matrix-vector kernel bound by the HBM read of the weights (workspace not used).
  */
 hi_status hi_proj_workspace_bytes(int32_t chunk_len, int64_t* bytes);
 hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model, int32_t n_q_heads,

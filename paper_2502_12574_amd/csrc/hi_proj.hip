@@ -288,6 +288,95 @@ __global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ ou
   out[idx] = make_float2((float)c, (float)s);
 }
 
+// ---- one token (decode): the same two projections as matrix-vector products, bound by the HBM read of the weights.
+// A wavefront takes pairs of weight rows (for Q/K/V: dimension i and i + 64 of a head, the two members of a rotary
+// pair), each lane 16 bytes of every 1 KiB of the row against the matching 16 bytes of x, fp32 accumulation, one
+// cross-lane reduction per row.
+struct GemvArgs {
+  const uint16_t* w;      // [rows][K] bf16
+  const uint16_t* x;      // [K] bf16
+  int rows, K;
+  int mode, out_fp32;
+  void* q_out; void* k_out; void* v_out; int n_q_heads, n_kv_heads;   // kPjQkv
+  int64_t position; double log2_theta;                                // rotation angle position * 2^(-i/64 * log2_theta); < 0: none
+  void* y;                                                            // kPjOut
+};
+
+__device__ __forceinline__ float gemv_dot8(uint4 a, uint4 b) {
+  const uint32_t av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+  float s = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    s = __builtin_fmaf(__uint_as_float(av[e] << 16), __uint_as_float(bv[e] << 16), s);
+    s = __builtin_fmaf(__uint_as_float(av[e] & 0xFFFF0000u), __uint_as_float(bv[e] & 0xFFFF0000u), s);
+  }
+  return s;
+}
+
+__global__ __launch_bounds__(256) void proj_gemv_kernel(GemvArgs g) {
+  const int lane = lane_id();
+  const int wave_global = blockIdx.x * 4 + wave_id();
+  const int n_waves = gridDim.x * 4;
+  const int n_pairs = g.mode == kPjQkv ? g.rows / 2 : (g.rows + 1) / 2;
+  for (int pr = wave_global; pr < n_pairs; pr += n_waves) {
+    int ra, rb;
+    if (g.mode == kPjQkv) { ra = (pr >> 6) * kHeadDim + (pr & 63); rb = ra + 64; }
+    else { ra = 2 * pr; rb = ra + 1 < g.rows ? ra + 1 : ra; }
+    const uint16_t* wa = g.w + (int64_t)ra * g.K;
+    const uint16_t* wb = g.w + (int64_t)rb * g.K;
+    float sa = 0.f, sb = 0.f;
+    for (int k0 = lane * 8; k0 < g.K; k0 += 4 * 512) {
+      uint4 a[4], b[4], xv[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int k = k0 + c * 512;
+        const int kc = k < g.K ? k : 0;                  // in bounds; the product is dropped below
+        a[c] = *(const uint4*)(wa + kc);
+        b[c] = *(const uint4*)(wb + kc);
+        xv[c] = *(const uint4*)(g.x + kc);
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (k0 + c * 512 < g.K) { sa += gemv_dot8(a[c], xv[c]); sb += gemv_dot8(b[c], xv[c]); }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { sa += __shfl_xor(sa, off); sb += __shfl_xor(sb, off); }
+    if (lane != 0) continue;
+    if (g.mode == kPjQkv) {
+      const int head = pr >> 6, i = pr & 63;
+      char* base;
+      int hh;
+      if (head < g.n_q_heads) { base = (char*)g.q_out; hh = head; }
+      else if (head < g.n_q_heads + g.n_kv_heads) { base = (char*)g.k_out; hh = head - g.n_q_heads; }
+      else { base = (char*)g.v_out; hh = head - g.n_q_heads - g.n_kv_heads; }
+      float lo = sa, hi = sb;
+      if (g.log2_theta >= 0 && head < g.n_q_heads + g.n_kv_heads) {
+        double sn, cs;
+        sincos((double)g.position * exp2(-(double)i / 64.0 * g.log2_theta), &sn, &cs);
+        const float c = (float)cs, s = (float)sn;
+        lo = sa * c - sb * s;
+        hi = sb * c + sa * s;
+      }
+      const int64_t at = (int64_t)hh * kHeadDim + i;
+      if (g.out_fp32) { ((float*)base)[at] = lo; ((float*)base)[at + 64] = hi; }
+      else { ((uint16_t*)base)[at] = float_to_bf16_bits(lo); ((uint16_t*)base)[at + 64] = float_to_bf16_bits(hi); }
+    } else {
+      if (g.out_fp32) { ((float*)g.y)[ra] = sa; if (rb != ra) ((float*)g.y)[rb] = sb; }
+      else { ((uint16_t*)g.y)[ra] = float_to_bf16_bits(sa); if (rb != ra) ((uint16_t*)g.y)[rb] = float_to_bf16_bits(sb); }
+    }
+  }
+}
+
+static hi_status gemv_launch(void* stream, const GemvArgs& g) {
+  const int n_pairs = (g.rows + 1) / 2;
+  int wgs = (n_pairs + 3) / 4;              // at least one pair per wavefront
+  if (wgs > 2048) wgs = 2048;
+  hipLaunchKernelGGL(proj_gemv_kernel, dim3((unsigned)wgs), dim3(256), 0, (hipStream_t)stream, g);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { set_last_error("projection (one token) launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+  return HI_OK;
+}
+
 static hi_status pj_launch(void* stream, ProjArgs& p, int mode) {
   static bool attr_set = false;
   if (!attr_set) {
@@ -326,7 +415,7 @@ extern "C" hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_
                                  int32_t n_q_heads, int32_t n_kv_heads, int32_t chunk_len, int64_t past_len,
                                  double rope_theta, int32_t out_fp32, void* q_out_dev, void* k_out_dev,
                                  void* v_out_dev, void* workspace_dev) {
-  if (!x_dev || !w_qkv_dev || !q_out_dev || !k_out_dev || !v_out_dev || (rope_theta > 0 && !workspace_dev)) {
+  if (!x_dev || !w_qkv_dev || !q_out_dev || !k_out_dev || !v_out_dev || (rope_theta > 0 && chunk_len > 1 && !workspace_dev)) {
     set_last_error("qkv projection: null buffer");
     return HI_ERR_ARG;
   }
@@ -344,6 +433,17 @@ extern "C" hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_
       (int64_t)chunk_len * d_model * 2 >= (1LL << 32)) {
     set_last_error("qkv projection: d_model must be a multiple of %d and each operand smaller than 4 GiB", 2 * kPjK);
     return HI_ERR_UNSUPPORTED;
+  }
+  if (chunk_len == 1) {
+    GemvArgs g = {};
+    g.w = (const uint16_t*)w_qkv_dev; g.x = (const uint16_t*)x_dev;
+    g.rows = (int)n_out; g.K = d_model;
+    g.mode = kPjQkv; g.out_fp32 = out_fp32;
+    g.q_out = q_out_dev; g.k_out = k_out_dev; g.v_out = v_out_dev;
+    g.n_q_heads = n_q_heads; g.n_kv_heads = n_kv_heads;
+    g.position = past_len;
+    g.log2_theta = rope_theta > 0 ? log2(rope_theta) : -1.0;
+    return gemv_launch(stream, g);
   }
   ProjArgs p = {};
   p.a = (const char*)w_qkv_dev; p.b = (const char*)x_dev;
@@ -381,6 +481,15 @@ extern "C" hi_status hi_out_proj(void* stream, const void* attn_dev, const void*
   if ((int64_t)d_model * K * 2 >= (1LL << 32) || (int64_t)chunk_len * kRowBytes >= (1LL << 32)) {
     set_last_error("output projection: each operand must be smaller than 4 GiB");
     return HI_ERR_UNSUPPORTED;
+  }
+  if (chunk_len == 1) {                      // one token: the head-major output is the concatenation itself
+    GemvArgs g = {};
+    g.w = (const uint16_t*)w_o_dev; g.x = (const uint16_t*)attn_dev;
+    g.rows = d_model; g.K = (int)K;
+    g.mode = kPjOut; g.out_fp32 = out_fp32;
+    g.log2_theta = -1.0;
+    g.y = y_out_dev;
+    return gemv_launch(stream, g);
   }
   ProjArgs p = {};
   p.a = (const char*)attn_dev; p.b = (const char*)w_o_dev;

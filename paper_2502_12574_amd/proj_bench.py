@@ -57,5 +57,28 @@ def main():
           f"algorithmic flops {f2:.3e}", flush=True)
 
 
+    # one token (decode): matrix-vector kernels, bound by the read of the weights.  The weights of 12 "layers" are
+    # cycled through (about 1 GB), so that they come from HBM and not from the 256 MB last-level cache.
+    x1, q1, k1, v1, y1 = x[:1].contiguous(), q[:, :1].contiguous(), k[:, :1].contiguous(), v[:, :1].contiguous(), y[:1].contiguous()
+    ws_, wos_ = [w.clone() for _ in range(12)], [wo.clone() for _ in range(12)]
+
+    def timed_cycle(fn, n=60):
+        for i in range(12):
+            fn(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(i % 12)
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / n * 1e-3
+
+    t3 = timed_cycle(lambda i: hb.hi_qkv_rope(s, x1, ws_[i], D, Hq, Hkv, 1, a.past, 500000.0, 0, q1, k1, v1, None))
+    t4 = timed_cycle(lambda i: hb.hi_out_proj(s, q1, wos_[i], Hq, D, 1, 0, y1))
+    b3, b4 = w.numel() * 2.0, wo.numel() * 2.0
+    print(f"qkv+rope  C=1: {t3 * 1e6:.1f} us, {b3 / t3 / 1e9:.0f} GB/s ({b3 / t3 / 8e12 * 100:.1f}% of 8 TB/s); weight bytes {b3:.3e}", flush=True)
+    print(f"out_proj  C=1: {t4 * 1e6:.1f} us, {b4 / t4 / 1e9:.0f} GB/s ({b4 / t4 / 8e12 * 100:.1f}% of 8 TB/s); weight bytes {b4:.3e}", flush=True)
+
+
 if __name__ == "__main__":
     main()
