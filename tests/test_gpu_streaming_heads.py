@@ -178,3 +178,55 @@ def test_streaming_heads_with_a_resident_cache():
         ss.staging.view(torch.int16).fill_(NAN16)
         Q, K, V, pre, dec = run_heads(ss, 8400, L, H, G, S, (200,), nd)
     compare(Q, K, V, pre, dec, L, H, T, G, S, nd, n_sink, n_recent)
+
+
+def test_streaming_head_deep_in_a_4m_context():
+    """A chunk and decode steps of a streaming head at the end of a 4M-token context (the largest configuration): the
+    store is filled with what calls at earlier positions would have left in it, then sampled rows are checked
+    against the exact oracle evaluated over the row's visible keys (the masked definition, keys regenerated)."""
+    H, T, G, n_sink, n_recent, C, nd, seed = 2, 1, 4, 128, 512, 32768, 3, 8500
+    S_max = 1 << 22
+    P = S_max - C - nd
+    h = H - 1
+    with Session(1, H, G, S_max, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, streaming_heads=T, sink_tokens=n_sink,
+                 recent_tokens=n_recent) as ss:
+        store = ss.stream_view()
+        with torch.cuda.stream(ss.s_compute):
+            store.view(torch.int16).fill_(NAN16)
+            store[0, 0, 0, :n_sink] = synth.draw_k(seed, 0, h, 0, n_sink, device="cuda:0")
+            store[0, 0, 1, :n_sink] = synth.draw_v(seed, 0, h, 0, n_sink, device="cuda:0")
+            tok = torch.arange(P - n_recent, P, device="cuda:0")
+            slots = n_sink + (tok - n_sink) % n_recent
+            store[0, 0, 0, slots] = synth.draw_k(seed, 0, h, P - n_recent, n_recent, device="cuda:0")
+            store[0, 0, 1, slots] = synth.draw_v(seed, 0, h, P - n_recent, n_recent, device="cuda:0")
+            Q = torch.stack([synth.draw_q(seed, 0, h * G + g, P, C + nd, device="cuda:0") for g in range(G)])
+            K = synth.draw_k(seed, 0, h, P, C + nd, device="cuda:0")
+            V = synth.draw_v(seed, 0, h, P, C + nd, device="cuda:0")
+            out = torch.empty(G, C, 128, dtype=torch.float32, device="cuda:0")
+            ss.prefill_head(0, h, Q[:, :C].contiguous(), K[:C], V[:C], P, out)
+            dec = []
+            for t in range(nd):
+                o = torch.empty(G, 128, dtype=torch.float32, device="cuda:0")
+                ss.decode_head(0, h, Q[:, C + t].contiguous(), K[C + t], V[C + t], P + C + t, o)
+                dec.append(o)
+        ss.sync()
+        out, dec = out.cpu(), [o.cpu() for o in dec]
+
+    def reference(p):
+        vis = list(range(n_sink)) + list(range(p - n_recent + 1, p + 1))
+        Kv = np.concatenate([synth.to_f64(synth.draw_k(seed, 0, h, 0, n_sink)),
+                             synth.to_f64(synth.draw_k(seed, 0, h, p - n_recent + 1, n_recent))])
+        Vv = np.concatenate([synth.to_f64(synth.draw_v(seed, 0, h, 0, n_sink)),
+                             synth.to_f64(synth.draw_v(seed, 0, h, p - n_recent + 1, n_recent))])
+        q = np.stack([synth.to_f64(synth.draw_q(seed, 0, h * G + g, p, 1))[0] for g in range(G)])
+        return np.stack([oa.attn_rows(q[g][None], Kv, Vv, [len(vis) - 1])[0] for g in range(G)])
+
+    rows = [0, 1, 31, 32, 63, 64, 510, 511, 512, 513, 16383, 16384, C - 2, C - 1] + list(range(5000, C, 4099))
+    for i in rows:
+        ref = reference(P + i)
+        for g in range(G):
+            check(out[g, i][None], ref[g][None], f"row {i} q {g}")
+    for t in range(nd):
+        ref = reference(P + C + t)
+        for g in range(G):
+            check(dec[t][g][None], ref[g][None], f"decode {t} q {g}")
