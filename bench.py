@@ -231,6 +231,18 @@ def main():
     }
     result.update(extra)
     ss.close()
+    del ss
+    if not args.no_extra_legs:
+        # the rows built after the hot path met its bar: streaming heads (Appendix E: 4 of the 8 heads keep sink +
+        # recent tokens in HBM) on the same layer, and the projections either side of the attention calls
+        from paper_2502_12574_amd import proj_bench, sparsity_bench
+        torch.cuda.empty_cache()
+        sp = sparsity_bench.run(S, C, HKV // 2, 128, 512, 8, HKV // 2)
+        sp["prefill_speedup_vs_all_retrieval"] = prefill_s / sp["prefill_s"]
+        if nd:
+            sp["decode_speedup_vs_all_retrieval"] = decode_ms_tok / sp["decode_ms_per_token"]
+        result["streaming_heads_50pct"] = sp
+        result["projections"] = proj_bench.measure(C)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args.seed, S, C)
     print(json.dumps(result))
