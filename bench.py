@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--resident-decode-tokens", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-legs", action="store_true", help="skip transfer-only and resident-decode legs")
+    ap.add_argument("--layers", type=int, default=1, help="layers run in Algorithm 1's order (chunk -> layer -> head); "
+                    "every figure stays per layer")
     ap.add_argument("--seed", type=int, default=20250216)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -101,12 +103,13 @@ def main():
     dev = "cuda:0"
     S, C, nd = args.context, args.chunk, args.decode_tokens
     S_max = S + max(nd, args.resident_decode_tokens)
-    ss = Session(1, HKV, G, S_max, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0)
+    NL = max(1, args.layers)
+    ss = Session(NL, HKV, G, S_max, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0)
     t_gen = time.perf_counter()
     with torch.cuda.stream(ss.s_compute):
-        inp = driver.LayerInputs(args.seed, 1, HKV, G, S, C, dev)
+        inp = driver.LayerInputs(args.seed, NL, HKV, G, S, C, dev)
         dec_rows = [inp.decode_rows(S + t) for t in range(max(nd, args.resident_decode_tokens))]
-        out_buf = [[torch.empty(G, C, D, dtype=ss.out_dtype, device=dev) for _ in range(HKV)]]
+        out_buf = [[torch.empty(G, C, D, dtype=ss.out_dtype, device=dev) for _ in range(HKV)] for _ in range(NL)]
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
@@ -143,10 +146,10 @@ def main():
     torch.cuda.synchronize()
     t_all = time.perf_counter() - t_all0
     K = max(args.steps, 1)
-    prefill_s = sum(pre_s) / K
-    decode_ms_tok = (sum(dec_s) / K) / max(nd, 1) * 1e3
+    prefill_s = sum(pre_s) / K / NL                       # per layer
+    decode_ms_tok = (sum(dec_s) / K) / max(nd, 1) * 1e3 / NL
     flops = causal_flops_layer(S)
-    kern_s = kern_pre_ms / K * 1e-3
+    kern_s = kern_pre_ms / K * 1e-3 / NL
 
     extra = {}
     if not args.no_extra_legs:
@@ -157,7 +160,7 @@ def main():
         with torch.cuda.stream(ss.s_compute):
             driver.prefill(ss, inp, out_buf=out_buf)
         ss.sync()
-        t_xfer = time.perf_counter() - t0
+        t_xfer = (time.perf_counter() - t0) / NL
         stx = ss.stats()
         hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_TIME_KERNELS)
         link_bytes = 512.0 * HKV * sum(range(0, S, C)) + 512.0 * HKV * S
@@ -167,7 +170,7 @@ def main():
                             "transfer_only_GBps": link_bytes / t_xfer / 1e9}
         # HBM-resident decode over the same cache (device copy of the host cache)
         ss_r = Session(1, HKV, G, S_max, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0)
-        ss_r.kv.copy_(ss.kv, non_blocking=False)
+        ss_r.kv.copy_(ss.kv[:ss_r.kv.numel()], non_blocking=False)        # layer 0
         hb.hi_ctx_set_flags(ss_r.ctx, hb.HI_FLAG_TIME_KERNELS)
         nr = args.resident_decode_tokens
         # all KV heads of the layer in one call per token (head groups; with everything in HBM nothing speaks
@@ -207,13 +210,13 @@ def main():
         "value": S / prefill_s,
         "unit": "tokens/s per layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": t_all / K * 1e3,
+        "ms_per_step": t_all / K * 1e3,                    # one step = prefill + decode tokens of all timed layers
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 inputs, fp32 accumulate (MFMA)", "data": "synthetic",
         "config": {"workload": f"one Llama-3-8B-shaped attention layer of the 32-layer 1M-token configuration: "
                                f"{HQ} Q / {HKV} KV heads, head_dim {D}, context {S}, head-wise chunked prefill "
                                f"chunk {C} + {nd} decode tokens, K/V offloaded to pinned host DRAM, 1-KV-head HBM "
-                               f"budget", "context": S, "chunk": C, "decode_tokens": nd, "layers_timed": 1,
+                               f"budget", "context": S, "chunk": C, "decode_tokens": nd, "layers_timed": NL,
                    "seed": args.seed},
         "prefill_s_per_layer": prefill_s,
         "decode_ms_per_token_per_layer_offloaded": decode_ms_tok if nd else None,
@@ -226,7 +229,7 @@ def main():
                      "traffic": PREFILL_TRAFFIC_PER_LAUNCH if (S, C) == (1 << 20, 16384) else None,
                      "kernel": "prefill_kernel_deep",
                      "launches_per_step": n_pre_k / K, "avg_launch_ms": kern_pre_ms / max(n_pre_k, 1),
-                     "flops_per_launch": flops / (n_pre_k / K),
+                     "flops_per_launch": flops * NL / (n_pre_k / K),
                      "wall_TFLOPs": flops / prefill_s / 1e12},
     }
     result.update(extra)
