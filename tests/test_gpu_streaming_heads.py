@@ -230,3 +230,40 @@ def test_streaming_head_deep_in_a_4m_context():
         ref = reference(P + C + t)
         for g in range(G):
             check(dec[t][g][None], ref[g][None], f"decode {t} q {g}")
+
+
+def test_streaming_resident_and_offloaded_heads_in_one_layer():
+    """All three kinds of head side by side: (layer 0, heads 0-1) resident in HBM, the other retrieval heads
+    offloaded, the last head of each layer streaming."""
+    L, H, T, R, G, S, nd, n_sink, n_recent = 2, 4, 1, 2, 4, 500, 3, 4, 100
+    with Session(L, H, G, S + nd, 128, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, gpu_kv_budget_heads=R + 1, resident_heads=R,
+                 streaming_heads=T, sink_tokens=n_sink, recent_tokens=n_recent) as ss:
+        assert ss.plan.hbm_stream_offset == ss.plan.hbm_resident_offset + R * ss.plan.host_bytes_per_head
+        ss.kv.view(torch.int16).fill_(NAN16)
+        ss.staging.view(torch.int16).fill_(NAN16)
+        Q, K, V, pre, dec = run_heads(ss, 8600, L, H, G, S, (128,), nd)
+        stats = ss.stats()
+        res = ss.resident_view().to("cpu")
+        cache = ss.cache_view().to("cpu")
+    compare(Q, K, V, pre, dec, L, H, T, G, S, nd, n_sink, n_recent)
+    n_tok = S + nd
+    for idx in range(R):             # resident pairs count over the retrieval heads: (0, 0), (0, 1)
+        assert torch.equal(res[idx, 0, :n_tok], K[0, idx].cpu()) and torch.equal(res[idx, 1, :n_tok], V[0, idx].cpu())
+        assert (cache[0, idx].view(torch.int16) == NAN16).all()
+    assert torch.equal(cache[0, 2, 0, :n_tok], K[0, 2].cpu()) and torch.equal(cache[1, 0, 1, :n_tok], V[1, 0].cpu())
+    n_off = L * (H - T) - R
+    assert stats.bytes_d2h == n_off * 512 * n_tok
+
+
+def test_streaming_store_is_maintained_with_kernels_skipped():
+    """The measurement switch that skips the attention kernels must still leave the store as the calls would."""
+    H, T, G, S, nd, n_sink, n_recent = 2, 1, 4, 300, 5, 8, 64
+    with Session(1, H, G, S + nd, 128, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, streaming_heads=T, sink_tokens=n_sink,
+                 recent_tokens=n_recent) as ss:
+        ss.staging.view(torch.int16).fill_(NAN16)
+        hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_SKIP_KERNELS)
+        Q, K, V, pre, dec = run_heads(ss, 8700, 1, H, G, S, (128,), nd)
+        store = ss.stream_view().to("cpu")
+    for which, X in ((0, K), (1, V)):
+        rows, held = expected_store(X[0, 1].cpu(), S + nd, n_sink, n_recent)
+        assert torch.equal(store[0, 0, which][held], rows[held])
