@@ -31,8 +31,8 @@ __device__ __forceinline__ void dec_issue_block(const char* __restrict__ k, cons
     row = row < n ? row : n - 1;
     const int ck = cpos ^ (r & 15);          // K swizzle
     const int cv = cpos ^ ((r & 7) << 1);    // V swizzle
-    g2lds16(k + row * kRowBytes + ck * 16, stage + i * 1024);
-    g2lds16(v + row * kRowBytes + cv * 16, stage + kDecTileBytes + i * 1024);
+    g2lds16_stream(k + row * kRowBytes + ck * 16, stage + i * 1024);
+    g2lds16_stream(v + row * kRowBytes + cv * 16, stage + kDecTileBytes + i * 1024);
   }
 }
 

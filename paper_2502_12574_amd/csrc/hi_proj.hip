@@ -302,6 +302,12 @@ struct GemvArgs {
   void* y;                                                            // kPjOut
 };
 
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+__device__ __forceinline__ uint4 gemv_load_stream(const uint16_t* p) {
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 __device__ __forceinline__ float gemv_dot8(uint4 a, uint4 b) {
   const uint32_t av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
   float s = 0.f;
@@ -331,8 +337,8 @@ __global__ __launch_bounds__(256) void proj_gemv_kernel(GemvArgs g) {
       for (int c = 0; c < 4; ++c) {
         const int k = k0 + c * 512;
         const int kc = k < g.K ? k : 0;                  // in bounds; the product is dropped below
-        a[c] = *(const uint4*)(wa + kc);
-        b[c] = *(const uint4*)(wb + kc);
+        a[c] = gemv_load_stream(wa + kc);                // the weights are read once: non-temporal
+        b[c] = gemv_load_stream(wb + kc);
         xv[c] = *(const uint4*)(g.x + kc);
       }
 #pragma unroll
