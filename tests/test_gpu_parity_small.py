@@ -279,3 +279,44 @@ def test_pipeline_hazards_poisoned_staging_and_unhonoured_hints():
             assert torch.equal(a, b), (c, h)
             for g in range(G):
                 check(a[g:g + 1], ref[g:g + 1, c * C:(c + 1) * C], f"hazard test chunk {c} head {h} q {g}")
+
+
+def test_resume_from_a_saved_host_cache():
+    """The host cache is the whole state and past_len is the caller's: a prefill stopped at a chunk boundary is
+    continued by a NEW context over a copy of the cache (what a checkpoint / restore would do), then decoded."""
+    dev, seed, G, S, C, nd = "cuda:0", 6100, 4, 1200, 256, 3
+    n_tok = S + nd
+    with torch.cuda.device(0):
+        Q = torch.stack([synth.draw_q(seed, 0, g, 0, n_tok, device=dev) for g in range(G)])
+        K = synth.draw_k(seed, 0, 0, 0, n_tok, device=dev)
+        V = synth.draw_v(seed, 0, 0, 0, n_tok, device=dev)
+    stop = 2 * C
+    outs = []
+    with Session(1, 1, G, n_tok, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1) as a:
+        with torch.cuda.stream(a.s_compute):
+            for p in range(0, stop, C):
+                out = torch.empty(G, C, 128, dtype=torch.float32, device=dev)
+                a.prefill_head(0, 0, Q[:, p:p + C].contiguous(), K[p:p + C], V[p:p + C], p, out)
+                outs.append(out)
+        a.sync()
+        saved = a.kv.clone()                    # the checkpoint: pinned host bytes only
+    with Session(1, 1, G, n_tok, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1) as b:
+        b.kv.copy_(saved)
+        b.staging.view(torch.int16).fill_(0x7FC1)
+        dec = []
+        with torch.cuda.stream(b.s_compute):
+            for p in range(stop, S, C):
+                n = min(C, S - p)
+                out = torch.empty(G, n, 128, dtype=torch.float32, device=dev)
+                b.prefill_head(0, 0, Q[:, p:p + n].contiguous(), K[p:p + n], V[p:p + n], p, out)
+                outs.append(out)
+            for t in range(nd):
+                out = torch.empty(G, 128, dtype=torch.float32, device=dev)
+                b.decode_head(0, 0, Q[:, S + t].contiguous(), K[S + t], V[S + t], S + t, out)
+                dec.append(out)
+        b.sync()
+        cache = b.cache_view()[0, 0].to("cpu").clone()
+    ref = oa.attn_head(synth.to_f64(Q.cpu()), synth.to_f64(K.cpu()), synth.to_f64(V.cpu()))
+    check(torch.cat(outs, dim=1), ref[:, :S], "prefill across the restart")
+    check(torch.stack(dec, dim=1), ref[:, S:], "decode after the restart")
+    assert torch.equal(cache[0, :n_tok], K.cpu()) and torch.equal(cache[1, :n_tok], V.cpu())
