@@ -106,3 +106,31 @@ def test_projection_argument_errors():
     assert hb.hi_qkv_rope(s, None, w, 256, 1, 1, 8, 0, 1e4, 0, o, o, o, ws, check=False) == hb.HI_ERR_ARG
     assert hb.hi_out_proj(s, o, w, 0, 256, 8, 0, x, check=False) == hb.HI_ERR_ARG
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("case_id", range(16))
+def test_projection_random_shapes(case_id):
+    import random
+    rng = random.Random(9500 + case_id)
+    D = rng.choice([128, 256, 384, 640, 1024])
+    Hq, Hkv = rng.randint(1, 6), rng.randint(1, 3)
+    C = rng.choice([1, 2, 31, 255, 256, 257, rng.randint(1, 700)])
+    past = rng.choice([0, 5, 99999, 4000000])
+    theta = rng.choice([0.0, 10000.0, 500000.0])
+    seed = 9500 + case_id
+    X = synth.draw_hidden(seed, 0, past, C, D, device=DEV)
+    W = synth.draw_weight(seed, synth.TENSOR_WQKV, 0, (Hq + 2 * Hkv) * 128, D, device=DEV)
+    Wf = synth.to_f64(W.cpu())
+    Qr, Kr, Vr = op.qkv_rope(synth.to_f64(X.cpu()), Wf[:Hq * 128], Wf[Hq * 128:(Hq + Hkv) * 128],
+                             Wf[(Hq + Hkv) * 128:], np.arange(past, past + C), 128, theta if theta > 0 else None)
+    q, k, v = qkv_on_gpu(X, W, D, Hq, Hkv, C, past, theta, 1)
+    what = f"D={D} Hq={Hq} Hkv={Hkv} C={C} past={past} theta={theta}"
+    for got, ref, name in ((q, Qr, "Q"), (k, Kr, "K"), (v, Vr, "V")):
+        close(got, ref, 2e-4, 2e-5, f"{name} {what}")
+    Dm = rng.choice([128, 200, 256, 777])            # the output width need not be a multiple of anything
+    A = torch.stack([synth.draw_q(seed, 0, h, 0, C, device=DEV) for h in range(Hq)])
+    Wo = synth.draw_weight(seed, synth.TENSOR_WO, 0, Dm, Hq * 128, device=DEV)
+    y = torch.full((C, Dm), float("nan"), dtype=torch.float32, device=DEV)
+    hb.hi_out_proj(torch.cuda.current_stream(), A, Wo, Hq, Dm, C, 1, y)
+    torch.cuda.synchronize()
+    close(y, op.out_proj(synth.to_f64(A.cpu()), synth.to_f64(Wo.cpu())), 2e-4, 2e-5, f"Y Dm={Dm} {what}")
