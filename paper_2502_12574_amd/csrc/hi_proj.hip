@@ -35,22 +35,23 @@ constexpr int kPjOperandBytes = kPjTile * kPjRowBytes;    // 32 KiB
 constexpr int kPjStageBytes = 2 * kPjOperandBytes;        // A slice then B slice
 constexpr int kPjLdsBytes = 2 * kPjStageBytes;            // 128 KiB
 constexpr int kPjWaves = 4;
+constexpr int kPjWgsPerXcd = 32;
 
 enum { kPjQkv = 0, kPjOut = 1 };
 
 struct ProjArgs {
-  const char* a; const char* b;       // operand rows (bf16), contraction index contiguous
+  const char* a; const char* b;       // operand rows (bf16), contraction index contiguous: A the weight, B the activations
   int a_rows, b_rows;                 // valid rows (loads clamp, the epilogue masks)
   uint32_t a_stride, b_stride;        // bytes between rows
-  int64_t a_head_stride;              // kPjOut: A[row][k] is at a + (k / 128) * a_head_stride + row * 256 + (k % 128) * 2
+  int64_t b_head_stride;              // kPjOut: B[row][k] is at b + (k / 128) * b_head_stride + row * 256 + (k % 128) * 2
   int K;                              // contraction length, a multiple of 128 (an even number of steps)
   int a_tiles, b_tiles, ga;           // tile grid; tiles are ordered in groups of ga A-tiles (see pj_tile_of)
   int out_fp32;
   // kPjQkv: A = W_qkv [(Hq + 2 Hkv) * 128][K], B = X [C][K]
   void* q_out; void* k_out; void* v_out;   // [Hq][C][128], [Hkv][C][128], [Hkv][C][128]
   int n_q_heads, n_kv_heads;
-  const float2* rope;                 // [C][64] (cos, sin) of the chunk's positions; null: no rotation
-  // kPjOut: A = attention output [Hq][C][128], B = W_o [D][Hq * 128]
+  const float2* rope;                 // [16][C][4] (cos, sin) of pair 4 g + e at the chunk's token t: [g][t][e]; null: no rotation
+  // kPjOut: A = W_o [D][Hq * 128], B = attention output [Hq][C][128]
   void* y; int64_t y_stride;          // [C][y_stride] elements
 };
 
@@ -72,6 +73,24 @@ __device__ __forceinline__ void pj_tile_of(const ProjArgs& p, int j, int& ta, in
   }
 }
 
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+__device__ __forceinline__ uint32_t pj_pack2(float x, float y) {
+  const bf16x2 v = {(__bf16)x, (__bf16)y};      // round to nearest even
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// Write 16 rows (features 16 rp .. 16 rp + 15 of a 32-row block of D) of this lane's token as bf16 to dst + 2 * row.
+// o[0..3] are the lane's rows 16 rp + 4 hl + 0..3, o[4..7] its rows 16 rp + 8 + 4 hl + 0..3: the two half-waves
+// exchange, so that each lane stores 8 consecutive rows (16 bytes) at once.
+__device__ __forceinline__ void pj_store_rows_bf16(char* dst, const float (&o)[8], int rp, int hl, bool ok) {
+  uint32_t x0 = pj_pack2(o[0], o[1]), x1 = pj_pack2(o[2], o[3]);
+  uint32_t y0 = pj_pack2(o[4], o[5]), y1 = pj_pack2(o[6], o[7]);
+  // lanes < 32 end up with rows 16 rp .. +7 (their own x, then the partner's x), lanes >= 32 with rows 16 rp + 8 .. +15
+  auto s0 = __builtin_amdgcn_permlane32_swap(x0, y0, false, false);
+  auto s1 = __builtin_amdgcn_permlane32_swap(x1, y1, false, false);
+  if (ok) *(uint4*)(dst + (16 * rp + 8 * hl) * 2) = make_uint4(s0[0], s1[0], s0[1], s1[1]);
+}
+
 template <int MODE>
 __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
   extern __shared__ __attribute__((aligned(1024))) char lds_dyn[];
@@ -81,35 +100,36 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
   const int l = lane & 31, hl = lane >> 5;
   const int wa = wave & 1, wb = wave >> 1;      // this wavefront: A rows 128 wa .. +127, B rows 128 wb .. +127
 
-  // this workgroup's tile: XCD x (= blockIdx % 8) takes tiles [x * per, (x + 1) * per) of the ordered list
+  // Persistent workgroups: XCD x (= blockIdx % 8) owns tiles [x * per, (x + 1) * per) of the ordered list, and its
+  // workgroups take them round-robin; a workgroup's next tile starts loading while this one's results are written.
   const int total = p.a_tiles * p.b_tiles;
   const int per = (total + 7) >> 3;
-  const int j = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
-  if ((int)(blockIdx.x >> 3) >= per || j >= total) return;
-  int ta, tb;
-  pj_tile_of(p, j, ta, tb);
+  const int xcd = (int)(blockIdx.x & 7), li = (int)(blockIdx.x >> 3), n_li = (int)(gridDim.x >> 3);
+  auto tile_index = [&](int s) __attribute__((always_inline)) { return s < per && xcd * per + s < total ? xcd * per + s : -1; };
 
   // ---- tile traffic: this wavefront's 8 load instructions per operand cover rows 64 w + 8 u + lane / 8
   uint32_t ga_off[8], gb_off[8];
+  auto set_offsets = [&](int ta, int tb) __attribute__((always_inline)) {
 #pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    const int row = 64 * wave + 8 * u + (lane >> 3);
-    const int chunk = (lane & 7) ^ (4 * (u & 1) + (lane >> 4));      // = (lane & 7) ^ ((row >> 1) & 7)
-    int ra = ta * kPjTile + row, rb = tb * kPjTile + row;
-    ra = ra < p.a_rows ? ra : p.a_rows - 1;
-    rb = rb < p.b_rows ? rb : p.b_rows - 1;
-    ga_off[u] = (uint32_t)ra * p.a_stride + (chunk << 4);
-    gb_off[u] = (uint32_t)rb * p.b_stride + (chunk << 4);
-  }
+    for (int u = 0; u < 8; ++u) {
+      const int row = 64 * wave + 8 * u + (lane >> 3);
+      const int chunk = (lane & 7) ^ (4 * (u & 1) + (lane >> 4));      // = (lane & 7) ^ ((row >> 1) & 7)
+      int ra = ta * kPjTile + row, rb = tb * kPjTile + row;
+      ra = ra < p.a_rows ? ra : p.a_rows - 1;
+      rb = rb < p.b_rows ? rb : p.b_rows - 1;
+      ga_off[u] = (uint32_t)ra * p.a_stride + (chunk << 4);
+      gb_off[u] = (uint32_t)rb * p.b_stride + (chunk << 4);
+    }
+  };
   // one of the 16 load instructions (8 of A, then 8 of B) of step t's slices into `stage`
   auto issue_one = [&](int t, int stage, int u) __attribute__((always_inline)) {
     const int k0 = t * kPjK;
     const uint32_t la = lds_base + stage * kPjStageBytes + wave * 8192;
     if (u < 8) {
-      const char* ab = MODE == kPjOut ? p.a + (int64_t)(k0 >> 7) * p.a_head_stride + (k0 & 127) * 2 : p.a + (int64_t)k0 * 2;
-      g2lds16_s<0>(ab, ga_off[u], la + u * 1024);
+      g2lds16_s<0>(p.a + (int64_t)k0 * 2, ga_off[u], la + u * 1024);
     } else {
-      g2lds16_s<0>(p.b + (int64_t)k0 * 2, gb_off[u - 8], la + kPjOperandBytes + (u - 8) * 1024);
+      const char* bb = MODE == kPjOut ? p.b + (int64_t)(k0 >> 7) * p.b_head_stride + (k0 & 127) * 2 : p.b + (int64_t)k0 * 2;
+      g2lds16_s<0>(bb, gb_off[u - 8], la + kPjOperandBytes + (u - 8) * 1024);
     }
   };
 
@@ -135,143 +155,175 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
     return *(lds_bf16x8_p)((lds_char*)(uintptr_t)(is_a ? va[st][kk] : vb[st][kk]) + blk * 4096);
   };
 
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int ia = 0; ia < 4; ++ia)
-#pragma unroll
-    for (int ib = 0; ib < 4; ++ib)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[ia][ib][r] = 0.f;
-
-  // MFMA j of a sub-step multiplies A block j % 4 with B block j / 4
-  auto mfma_j = [&](const bf16x8 (&o)[8], int j) __attribute__((always_inline)) {
-    const int ia = j & 3, ib = j >> 2;
-    acc[ia][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o[ia == 0 ? 0 : ia + 1], o[ib == 0 ? 1 : ib + 4], acc[ia][ib], 0, 0, 0);
-  };
-
   const int T = p.K / kPjK;
-  // The schedule.  One wavefront per SIMD keeps the matrix pipe busy on its own: operand reads run one sub-step (16
-  // contraction elements, 16 MFMAs) ahead of their use, across the step boundary too.  The barrier that publishes
-  // step t+1's slices sits before the LAST sub-step of step t, whose MFMAs then cover the first operand reads of
-  // step t+1 and the issue of step t+2's loads into the stage step t has just finished reading.  One barrier per
-  // step; a wavefront waiting at it still has 16 MFMAs in the pipe.
-  bf16x8 cur[8], nxt[8];
+  int cur_j = tile_index(li);
+  if (cur_j < 0) return;
+  int ta, tb;
+  pj_tile_of(p, cur_j, ta, tb);
+  set_offsets(ta, tb);
 #pragma unroll
   for (int u = 0; u < 16; ++u) issue_one(0, 0, u);
 #pragma unroll
   for (int u = 0; u < 16; ++u) issue_one(1, 1, u);
-  wait_vmcnt<16>();
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < 8; ++i) cur[i] = read_op(0, 0, i);
 
-  // MORE1: step t + 1 exists (its first operands are read here); MORE2: step t + 2 exists (its loads are issued here)
-  auto step = [&](int t, auto stage_tag, auto more1_tag, auto more2_tag) __attribute__((always_inline)) {
-    constexpr int STAGE = decltype(stage_tag)::value;
-    constexpr int ST = STAGE, SN = 1 - STAGE;             // this stage and the other one
-    constexpr bool MORE1 = decltype(more1_tag)::value, MORE2 = decltype(more2_tag)::value;
-    __builtin_amdgcn_sched_barrier(0);
+  for (int s = li; cur_j >= 0; s += n_li) {
+    f32x16 acc[4][4];
 #pragma unroll
-    for (int kk = 0; kk < 3; ++kk) {
-      // sub-step kk from one operand set while sub-step kk + 1 is read into the other
+    for (int ia = 0; ia < 4; ++ia)
+#pragma unroll
+      for (int ib = 0; ib < 4; ++ib)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[ia][ib][r] = 0.f;
+
+    // MFMA j of a sub-step multiplies A block j % 4 with B block j / 4
+    auto mfma_j = [&](const bf16x8 (&o)[8], int j) __attribute__((always_inline)) {
+      const int ia = j & 3, ib = j >> 2;
+      acc[ia][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o[ia == 0 ? 0 : ia + 1], o[ib == 0 ? 1 : ib + 4], acc[ia][ib], 0, 0, 0);
+    };
+
+    // The schedule.  One wavefront per SIMD keeps the matrix pipe busy on its own: operand reads run one sub-step (16
+    // contraction elements, 16 MFMAs) ahead of their use, across the step boundary too.  The barrier that publishes
+    // step t+1's slices sits before the LAST sub-step of step t, whose MFMAs then cover the first operand reads of
+    // step t+1 and the issue of step t+2's loads into the stage step t has just finished reading.  One barrier per
+    // step; a wavefront waiting at it still has 16 MFMAs in the pipe.
+    bf16x8 cur[8], nxt[8];
+    wait_vmcnt<16>();          // step 0 has landed (at most step 1's loads and earlier stores are still in flight)
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cur[i] = read_op(0, 0, i);
+
+    // MORE1: step t + 1 exists (its first operands are read here); MORE2: step t + 2 exists (its loads are issued here)
+    auto step = [&](int t, auto stage_tag, auto more1_tag, auto more2_tag) __attribute__((always_inline)) {
+      constexpr int STAGE = decltype(stage_tag)::value;
+      constexpr int ST = STAGE, SN = 1 - STAGE;             // this stage and the other one
+      constexpr bool MORE1 = decltype(more1_tag)::value, MORE2 = decltype(more2_tag)::value;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kk = 0; kk < 3; ++kk) {
+        // sub-step kk from one operand set while sub-step kk + 1 is read into the other
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          if (j < 8) {
+            if (kk & 1) cur[j] = read_op(ST, kk + 1, j); else nxt[j] = read_op(ST, kk + 1, j);
+          }
+          mfma_j((kk & 1) ? nxt : cur, j);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      // every read of this stage has been issued; the last sub-step's operands are in nxt
+      wait_vmcnt<0>();                                      // this wave's loads of step t + 1 have landed
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave is done reading this stage
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        if (j < 8) {
-          if (kk & 1) cur[j] = read_op(ST, kk + 1, j); else nxt[j] = read_op(ST, kk + 1, j);
-        }
-        mfma_j((kk & 1) ? nxt : cur, j);
+        if (j < 8 && MORE1) cur[j] = read_op(SN, 0, j);
+        mfma_j(nxt, j);
+        if (MORE2) issue_one(t + 2, STAGE, j);
         __builtin_amdgcn_sched_barrier(0);
       }
+    };
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    // T is even (the contraction length is a multiple of 128): pairs of steps, the last pair without look-ahead.
+    // Straight-line code around one loop: the 256 accumulators never meet at a control-flow join.
+    int t = 0;
+    for (; t + 2 < T; t += 2) {
+      step(t, S0(), std::true_type(), std::true_type());
+      step(t + 1, S1(), std::true_type(), std::true_type());
     }
-    // every read of this stage has been issued; the last sub-step's operands are in nxt
-    wait_vmcnt<0>();                                      // this wave's loads of step t + 1 have landed
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave is done reading this stage
-    __syncthreads();
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      if (j < 8 && MORE1) cur[j] = read_op(SN, 0, j);
-      mfma_j(nxt, j);
-      if (MORE2) issue_one(t + 2, STAGE, j);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  using S0 = std::integral_constant<int, 0>;
-  using S1 = std::integral_constant<int, 1>;
-  // T is even (the contraction length is a multiple of 128): pairs of steps, the last pair without look-ahead.
-  // Straight-line code around one loop: the 256 accumulators never meet at a control-flow join.
-  int t = 0;
-  for (; t + 2 < T; t += 2) {
-    step(t, S0(), std::true_type(), std::true_type());
-    step(t + 1, S1(), std::true_type(), std::true_type());
-  }
-  step(t, S0(), std::true_type(), std::false_type());
-  step(t + 1, S1(), std::false_type(), std::false_type());
+    step(t, S0(), std::true_type(), std::false_type());
+    step(t + 1, S1(), std::false_type(), std::false_type());
 
-  // ---- epilogue.  Register r of block (ia, ib): A-row 128 wa + 32 ia + 8 (r / 4) + 4 hl + r % 4, B-row 128 wb + 32 ib + l
-  if (MODE == kPjQkv) {
-    const int head = 2 * ta + wa;
-    if (head >= p.n_q_heads + 2 * p.n_kv_heads) return;
-    const bool rotate = p.rope != nullptr && head < p.n_q_heads + p.n_kv_heads;
-    char* base;
-    int hh;
-    if (head < p.n_q_heads) { base = (char*)p.q_out; hh = head; }
-    else if (head < p.n_q_heads + p.n_kv_heads) { base = (char*)p.k_out; hh = head - p.n_q_heads; }
-    else { base = (char*)p.v_out; hh = head - p.n_q_heads - p.n_kv_heads; }
+    // nobody reads LDS after the last barrier: the next tile's first two steps start loading under the epilogue
+    const int my_ta = ta, my_tb = tb;
+    cur_j = tile_index(s + n_li);
+    if (cur_j >= 0) {
+      pj_tile_of(p, cur_j, ta, tb);
+      set_offsets(ta, tb);
+#pragma unroll
+      for (int u = 0; u < 16; ++u) issue_one(0, 0, u);
+#pragma unroll
+      for (int u = 0; u < 16; ++u) issue_one(1, 1, u);
+    }
+
+    // ---- epilogue.  Register r of block (ia, ib): A-row 128 wa + 32 ia + 8 (r / 4) + 4 hl + r % 4 (an output
+    // feature), B-row 128 wb + 32 ib + l (a token): a lane owns one token and, with its partner in the other
+    // half-wave, runs of 8 consecutive features.
+    char* base = nullptr;        // where feature 0 of this wavefront's 128 A-rows goes, for token 0
+    int64_t row_bytes = 0;       // bytes from one token's output row to the next
+    bool rotate = false;
+    int n_valid = 128;           // valid A-rows of the wavefront
     const int esz = p.out_fp32 ? 4 : 2;
+    if (MODE == kPjQkv) {
+      const int head = 2 * my_ta + wa;
+      int hh;
+      if (head < p.n_q_heads) { base = (char*)p.q_out; hh = head; }
+      else if (head < p.n_q_heads + p.n_kv_heads) { base = (char*)p.k_out; hh = head - p.n_q_heads; }
+      else { base = (char*)p.v_out; hh = head - p.n_q_heads - p.n_kv_heads; }
+      if (head >= p.n_q_heads + 2 * p.n_kv_heads) n_valid = 0;
+      rotate = p.rope != nullptr && head < p.n_q_heads + p.n_kv_heads;
+      base += (int64_t)hh * p.b_rows * kHeadDim * esz;
+      row_bytes = (int64_t)kHeadDim * esz;
+    } else {
+      const int n0 = my_ta * kPjTile + wa * 128;
+      base = (char*)p.y + (int64_t)n0 * esz;
+      row_bytes = p.y_stride * esz;
+      n_valid = p.a_rows - n0 < 128 ? (p.a_rows - n0 > 0 ? p.a_rows - n0 : 0) : 128;
+    }
+    // 16-byte stores need whole groups of 8 features and an aligned row pitch
+    const bool wide_ok = !p.out_fp32 && n_valid == 128 && (row_bytes & 15) == 0;
+    int hl_slow = hl;            // opaque per tile: keeps the element-wise path's offsets from being hoisted out of the
+    asm volatile("" : "+v"(hl_slow));   // tile loop, where they would sit in registers (or scratch) for nothing
 #pragma unroll
     for (int ib = 0; ib < 4; ++ib) {
-      const int m = tb * kPjTile + wb * 128 + ib * 32 + l;          // token of this lane
-      if (m >= p.b_rows) continue;
-      char* row = base + ((int64_t)hh * p.b_rows + m) * kHeadDim * esz;
+      const int m = my_tb * kPjTile + wb * 128 + ib * 32 + l;          // token of this lane
+      const bool tok_ok = m < p.b_rows;
+      char* row = base + (int64_t)(tok_ok ? m : 0) * row_bytes;
 #pragma unroll
-      for (int ip = 0; ip < 2; ++ip)                                // blocks ip and ip + 2 hold the rotary pairs
+      for (int ip = 0; ip < 2; ++ip) {                                // blocks ip and ip + 2 hold the rotary pairs
+        float lo[16], hi[16];
 #pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          const int i0 = ip * 32 + 8 * rq + 4 * hl;                  // dims i0 .. i0+3 and 64 + i0 .. 64 + i0+3
-          float lo[4], hi[4];
+        for (int r = 0; r < 16; ++r) { lo[r] = acc[ip][ib][r]; hi[r] = acc[ip + 2][ib][r]; }
+        if (MODE == kPjQkv && rotate) {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) { lo[e] = acc[ip][ib][4 * rq + e]; hi[e] = acc[ip + 2][ib][4 * rq + e]; }
-          if (rotate) {
-            const float4* cs = (const float4*)(p.rope + (int64_t)m * 64 + i0);
-            const float4 c01 = cs[0], c23 = cs[1];                   // (cos, sin) of two dims each
+          for (int rq = 0; rq < 4; ++rq) {
+            const int i0 = ip * 32 + 8 * rq + 4 * hl;                  // dims i0 .. i0+3 and 64 + i0 .. 64 + i0+3
+            // table layout [16 groups of 4 pairs][token][4]: consecutive lanes (tokens) read consecutive 32 bytes
+            const float4* cs = (const float4*)(p.rope + ((int64_t)(i0 >> 2) * p.b_rows + (tok_ok ? m : 0)) * 4);
+            const float4 c01 = cs[0], c23 = cs[1];                     // (cos, sin) of two pairs each
             const float cv[4] = {c01.x, c01.z, c23.x, c23.z}, sv[4] = {c01.y, c01.w, c23.y, c23.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const float x = lo[e], y = hi[e];
-              lo[e] = x * cv[e] - y * sv[e];
-              hi[e] = y * cv[e] + x * sv[e];
+              const float x = lo[4 * rq + e], y = hi[4 * rq + e];
+              lo[4 * rq + e] = x * cv[e] - y * sv[e];
+              hi[4 * rq + e] = y * cv[e] + x * sv[e];
             }
           }
-          if (p.out_fp32) {
-            *(float4*)(row + i0 * 4) = make_float4(lo[0], lo[1], lo[2], lo[3]);
-            *(float4*)(row + (64 + i0) * 4) = make_float4(hi[0], hi[1], hi[2], hi[3]);
-          } else {
-            uint2 pl, ph;
-            pl.x = (uint32_t)float_to_bf16_bits(lo[0]) | ((uint32_t)float_to_bf16_bits(lo[1]) << 16);
-            pl.y = (uint32_t)float_to_bf16_bits(lo[2]) | ((uint32_t)float_to_bf16_bits(lo[3]) << 16);
-            ph.x = (uint32_t)float_to_bf16_bits(hi[0]) | ((uint32_t)float_to_bf16_bits(hi[1]) << 16);
-            ph.y = (uint32_t)float_to_bf16_bits(hi[2]) | ((uint32_t)float_to_bf16_bits(hi[3]) << 16);
-            *(uint2*)(row + i0 * 2) = pl;
-            *(uint2*)(row + (64 + i0) * 2) = ph;
+        }
+        if (wide_ok) {
+#pragma unroll
+          for (int rp = 0; rp < 2; ++rp) {
+            const float l8[8] = {lo[8 * rp], lo[8 * rp + 1], lo[8 * rp + 2], lo[8 * rp + 3],
+                                 lo[8 * rp + 4], lo[8 * rp + 5], lo[8 * rp + 6], lo[8 * rp + 7]};
+            const float h8[8] = {hi[8 * rp], hi[8 * rp + 1], hi[8 * rp + 2], hi[8 * rp + 3],
+                                 hi[8 * rp + 4], hi[8 * rp + 5], hi[8 * rp + 6], hi[8 * rp + 7]};
+            pj_store_rows_bf16(row + 32 * ip * 2, l8, rp, hl, tok_ok);
+            pj_store_rows_bf16(row + 32 * (ip + 2) * 2, h8, rp, hl, tok_ok);
           }
+        } else if (tok_ok) {
+#pragma unroll
+          for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int f = 32 * (ip + 2 * half) + 8 * (r >> 2) + 4 * hl_slow + (r & 3);
+              const float x = half ? hi[r] : lo[r];
+              if (f >= n_valid) continue;
+              if (p.out_fp32) *(float*)(row + f * 4) = x;
+              else *(uint16_t*)(row + f * 2) = float_to_bf16_bits(x);
+            }
         }
-    }
-  } else {
-#pragma unroll
-    for (int ib = 0; ib < 4; ++ib) {
-      const int n = tb * kPjTile + wb * 128 + ib * 32 + l;          // output feature of this lane
-      if (n >= p.b_rows) continue;
-#pragma unroll
-      for (int ia = 0; ia < 4; ++ia)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int m = ta * kPjTile + wa * 128 + 32 * ia + 8 * (r >> 2) + 4 * hl + (r & 3);
-          if (m >= p.a_rows) continue;
-          const int64_t at = (int64_t)m * p.y_stride + n;
-          if (p.out_fp32) ((float*)p.y)[at] = acc[ia][ib][r];
-          else ((uint16_t*)p.y)[at] = float_to_bf16_bits(acc[ia][ib][r]);
-        }
+      }
     }
   }
 }
@@ -285,7 +337,7 @@ __global__ __launch_bounds__(256) void rope_table_kernel(float2* __restrict__ ou
   const int t = idx >> 6, i = idx & 63;
   double s, c;
   sincos((double)(past + t) * f.inv[i], &s, &c);
-  out[idx] = make_float2((float)c, (float)s);
+  out[((int64_t)(i >> 2) * n + t) * 4 + (i & 3)] = make_float2((float)c, (float)s);   // [i / 4][token][i % 4]
 }
 
 // ---- one token (decode): the same two projections as matrix-vector products, bound by the HBM read of the weights.
@@ -397,7 +449,8 @@ static hi_status pj_launch(void* stream, ProjArgs& p, int mode) {
   p.ga = p.a_tiles / 8 > 0 ? p.a_tiles / 8 : 1;
   const int total = p.a_tiles * p.b_tiles;
   const int per = (total + 7) / 8;
-  dim3 grid((unsigned)(per * 8));
+  // persistent workgroups: at most 32 per XCD (one per compute unit), each looping over its share of the tiles
+  dim3 grid((unsigned)(8 * (per < kPjWgsPerXcd ? per : kPjWgsPerXcd)));
   if (mode == kPjQkv) hipLaunchKernelGGL(proj_gemm_kernel<kPjQkv>, grid, dim3(kPjWaves * 64), kPjLdsBytes, (hipStream_t)stream, p);
   else hipLaunchKernelGGL(proj_gemm_kernel<kPjOut>, grid, dim3(kPjWaves * 64), kPjLdsBytes, (hipStream_t)stream, p);
   hipError_t e = hipGetLastError();
@@ -498,10 +551,10 @@ extern "C" hi_status hi_out_proj(void* stream, const void* attn_dev, const void*
     return gemv_launch(stream, g);
   }
   ProjArgs p = {};
-  p.a = (const char*)attn_dev; p.b = (const char*)w_o_dev;
-  p.a_rows = chunk_len; p.b_rows = d_model;
-  p.a_stride = kRowBytes; p.b_stride = (uint32_t)K * 2;
-  p.a_head_stride = (int64_t)chunk_len * kRowBytes;
+  p.a = (const char*)w_o_dev; p.b = (const char*)attn_dev;
+  p.a_rows = d_model; p.b_rows = chunk_len;
+  p.a_stride = (uint32_t)K * 2; p.b_stride = kRowBytes;
+  p.b_head_stride = (int64_t)chunk_len * kRowBytes;
   p.K = (int)K;
   p.out_fp32 = out_fp32;
   p.y = y_out_dev; p.y_stride = d_model;
