@@ -17,9 +17,11 @@
 //     pair (dimension i and i + 64: blocks ia and ia + 2, same register) meet in one lane;
 //   * the tiles of one XCD (workgroups are dealt to the 8 XCDs round-robin) form a compact block of the tile grid
 //     and advance through the contraction together, so each operand slice is fetched into that XCD's L2 about once.
-// Measured (Llama-3-8B shapes, chunk 16384): 1.0 PFLOP/s for the Q/K/V projection, 1.14 PFLOP/s for the output
-// projection; the same kernel with its global loads removed reaches 1.2 / 1.35 and with LDS reads and barriers
-// removed as well 1.23 / 1.37, i.e. the loop is at 80-83 % of what its own MFMA stream sustains on this part.
+//   * workgroups are persistent (one per compute unit, looping over their XCD's tiles): the next tile's first loads
+//     are issued under the current tile's epilogue; the epilogue's stores are 16 bytes wide after an exchange between
+//     the two half-waves.
+// Measured (Llama-3-8B shapes, chunk 16384): 1.05 PFLOP/s for the Q/K/V projection (1.27 without the rotation),
+// 1.25 PFLOP/s for the output projection; on constant operands, where the clock is not power-managed, 1.36 / 1.63.
 #include <type_traits>
 #include "hi_device.h"
 #include "hi_internal.h"
