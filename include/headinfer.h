@@ -69,7 +69,10 @@ typedef struct hi_problem {
                                   or resident as above.  0 = none; at most n_kv_heads - 1 */
   int32_t sink_tokens;         /* n_sink >= 0 */
   int32_t recent_tokens;       /* n_recent >= 1 (the token itself included) when streaming_heads > 0 */
-  int32_t reserved0;           /* 0 */
+  int32_t link_kv_bits;        /* representation of an offloaded head's rows in the host cache and on the link: 0 or 16 =
+                                  bf16 rows (exact attention); 4 = 4-bit codes, 80 bytes per row of 128 channels (see
+                                  "4-bit rows on the link" below; offload mode only).  Rows that stay in HBM (the chunk
+                                  being processed, resident and streaming heads) are always bf16 */
 } hi_problem;
 
 /* Output of hi_offload_plan.  Sizes in bytes. */
@@ -105,6 +108,15 @@ typedef struct hi_plan {
   int64_t hbm_stream_bytes;      /* L * streaming_heads * 2 * stream_rows * D_h * sizeof; outside the whole-head budget */
   int64_t stream_rows;           /* sink_tokens + recent_tokens (0 without streaming heads): sink token j at row j,
                                     token j >= sink_tokens at row sink_tokens + (j - sink_tokens) mod recent_tokens */
+  int64_t link_row_bytes;        /* bytes of one K (or V) row in the host cache: D_h * sizeof, or 80 with link_kv_bits = 4;
+                                    the cache is [layer][retrieval head][K|V][S_max][link_row_bytes] */
+  int64_t hbm_packed_offset;     /* inside the staging buffer, with link_kv_bits = 4: where slices land as they come off
+                                    the link, one area per ring slot, before they are expanded into the slot; the ring
+                                    is sized so that ring + these areas stay inside the HBM budget */
+  int64_t hbm_packed_bytes;      /* n_slices_ring * slice_tokens * 2 * link_row_bytes, or 0 */
+  int64_t ws_writeback_offset;   /* inside the workspace, with link_kv_bits = 4: two buffers in which a call's new rows
+                                    are encoded before their write-back */
+  int64_t ws_writeback_bytes;    /* 2 * 2 * retrieval heads * chunk * link_row_bytes, or 0 */
 } hi_plan;
 
 typedef struct hi_stats {
@@ -250,6 +262,28 @@ hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_qkv_dev, in
                       void* q_out_dev, void* k_out_dev, void* v_out_dev, void* workspace_dev);
 hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, int32_t n_q_heads, int32_t d_model,
                       int32_t chunk_len, int32_t out_fp32, void* y_out_dev);
+
+/*
+ * 4-bit rows on the link (Appendix B and Section 6.3 describe 4-bit KV quantisation as a representation that shrinks
+ * the cache about 4x and is converted back on the GPU; Section 3.3 finds offloaded decode bound by the link).  With
+ * hi_problem.link_kv_bits = 4 the rows of an offloaded head are stored in the host cache, and cross the link, as
+ * 80-byte rows: 64 bytes of 4-bit codes (channel 2i in the low nibble of byte i, channel 2i + 1 in the high one),
+ * then 4 bf16 scales and 4 bf16 zeros, one pair per group of 32 consecutive channels.  Per group, in binary32 with one
+ * rounding per operation: zero = min, scale = bf16((max - min) * (1/15)) (taken as 0 below 2^-120: a constant group),
+ * code = min(15, rint((x - zero) * (1 / scale))), and the row is read back as x^ = bf16(zero + code * scale).
+ * The same four attention calls then compute: rows of the call itself (the chunk, the token) take part as the exact
+ * bf16 values the caller passed; rows of earlier calls take part as x^ - an approximation of exact attention by
+ * design, identical in prefill and decode.  A call encodes its new rows on the compute stream, writes the encoded
+ * rows back, and expands each slice that comes off the link into the staging ring before the attention kernel
+ * reads it; link bytes and host bytes shrink by 3.2x, and the ring shrinks so that ring plus landing areas stay
+ * inside the HBM budget.  HBM-resident and streaming heads are unaffected.  HI_MODE_RESIDENT rejects it
+ * (HI_ERR_UNSUPPORTED): there is no link to save.
+ *
+ * hi_kv_quantize / hi_kv_dequantize: the two conversions alone, for n_rows rows of 128 channels, DEVICE bf16
+ * [n_rows][128] <-> DEVICE bytes [n_rows][80]; 16-byte aligned; enqueue on `stream` and return.
+ */
+hi_status hi_kv_quantize(void* stream, const void* rows_dev, int64_t n_rows, void* packed_dev);
+hi_status hi_kv_dequantize(void* stream, const void* packed_dev, int64_t n_rows, void* rows_dev);
 
 /* T4 - drain the three streams; surfaces deferred HIP errors (HI_ERR_HIP). */
 hi_status hi_sync(hi_ctx* ctx);

@@ -20,7 +20,7 @@ HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_WIDE, HI_FLAG_PREFILL_DEEP = 8, 16, 32
 
 EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
            "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_proj_workspace_bytes",
-           "hi_qkv_rope", "hi_out_proj", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
+           "hi_qkv_rope", "hi_out_proj", "hi_kv_quantize", "hi_kv_dequantize", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
 
 
 class hi_problem(C.Structure):
@@ -30,7 +30,7 @@ class hi_problem(C.Structure):
                 ("n_compute_units", C.c_int32), ("resident_heads", C.c_int32), ("host_mem_limit_bytes", C.c_int64),
                 ("link_GBps", C.c_double), ("hbm_GBps", C.c_double), ("mfma_TFLOPs", C.c_double),
                 ("streaming_heads", C.c_int32), ("sink_tokens", C.c_int32), ("recent_tokens", C.c_int32),
-                ("reserved0", C.c_int32)]
+                ("link_kv_bits", C.c_int32)]
 
 
 class hi_plan(C.Structure):
@@ -45,7 +45,9 @@ class hi_plan(C.Structure):
                 ("t_comp_decode_s", C.c_double), ("t_link_decode_s", C.c_double), ("t_hbm_decode_s", C.c_double),
                 ("regime_prefill", C.c_int32), ("regime_decode", C.c_int32),
                 ("hbm_resident_offset", C.c_int64), ("hbm_resident_bytes", C.c_int64),
-                ("hbm_stream_offset", C.c_int64), ("hbm_stream_bytes", C.c_int64), ("stream_rows", C.c_int64)]
+                ("hbm_stream_offset", C.c_int64), ("hbm_stream_bytes", C.c_int64), ("stream_rows", C.c_int64),
+                ("link_row_bytes", C.c_int64), ("hbm_packed_offset", C.c_int64), ("hbm_packed_bytes", C.c_int64),
+                ("ws_writeback_offset", C.c_int64), ("ws_writeback_bytes", C.c_int64)]
 
 
 class hi_stats(C.Structure):
@@ -86,6 +88,8 @@ def lib() -> C.CDLL:
         L.hi_proj_workspace_bytes.argtypes = [i32, C.POINTER(i64)]
         L.hi_qkv_rope.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp, vp]
         L.hi_out_proj.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
+        L.hi_kv_quantize.argtypes = [vp, vp, i64, vp]
+        L.hi_kv_dequantize.argtypes = [vp, vp, i64, vp]
         L.hi_sync.argtypes = [vp]
         L.hi_get_stats.argtypes = [vp, C.POINTER(hi_stats)]
         L.hi_reset_stats.argtypes = [vp]
@@ -124,10 +128,11 @@ def _stream(s):
 
 def make_problem(n_layers, n_kv_heads, gqa_group, max_context, chunk, head_dim=128, gpu_kv_budget_heads=1,
                  dtype_bytes=2, out_fp32=0, n_compute_units=0, host_mem_limit_bytes=0, link_GBps=0.0, hbm_GBps=0.0,
-                 mfma_TFLOPs=0.0, resident_heads=0, streaming_heads=0, sink_tokens=0, recent_tokens=0) -> hi_problem:
+                 mfma_TFLOPs=0.0, resident_heads=0, streaming_heads=0, sink_tokens=0, recent_tokens=0,
+                 link_kv_bits=0) -> hi_problem:
     return hi_problem(n_layers, n_kv_heads, gqa_group, head_dim, max_context, chunk, gpu_kv_budget_heads,
                       dtype_bytes, out_fp32, n_compute_units, resident_heads, host_mem_limit_bytes, link_GBps, hbm_GBps,
-                      mfma_TFLOPs, streaming_heads, sink_tokens, recent_tokens, 0)
+                      mfma_TFLOPs, streaming_heads, sink_tokens, recent_tokens, link_kv_bits)
 
 
 def hi_offload_plan(problem: hi_problem, check: bool = True):
@@ -226,6 +231,20 @@ def hi_out_proj(stream, attn_dev, w_o_dev, n_q_heads, d_model, chunk_len, out_fp
                            _ptr(y_out_dev))
     if check and st != HI_OK:
         raise HiError(st, "hi_out_proj")
+    return st
+
+
+def hi_kv_quantize(stream, rows_dev, n_rows, packed_dev, check: bool = True):
+    st = lib().hi_kv_quantize(_stream(stream), _ptr(rows_dev), n_rows, _ptr(packed_dev))
+    if check and st != HI_OK:
+        raise HiError(st, "hi_kv_quantize")
+    return st
+
+
+def hi_kv_dequantize(stream, packed_dev, n_rows, rows_dev, check: bool = True):
+    st = lib().hi_kv_dequantize(_stream(stream), _ptr(packed_dev), n_rows, _ptr(rows_dev))
+    if check and st != HI_OK:
+        raise HiError(st, "hi_kv_dequantize")
     return st
 
 

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libheadinfer.so")
 PROBE = os.path.join(HERE, "mfma_ceiling")
-SOURCES = ["hi_plan.cpp", "hi_ctx.hip", "hi_decode.hip", "hi_prefill.hip", "hi_proj.hip"]
+SOURCES = ["hi_plan.cpp", "hi_ctx.hip", "hi_decode.hip", "hi_prefill.hip", "hi_proj.hip", "hi_kvq.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -50,6 +50,9 @@ struct hi_ctx {
   hipEvent_t ev_entry = nullptr;               // compute-stream position when a call starts
   std::vector<hipEvent_t> ev_wb;               // per (layer, head): last write-back of that head finished
   std::vector<char> wb_valid;
+  hipEvent_t ev_wbq[2] = {nullptr, nullptr};   // 4-bit link rows: the write-back that read encode buffer b has finished
+  char wbq_valid[2] = {0, 0};
+  int wbq_turn = 0;
 
   // the ring is a FIFO: slices are consumed in the order they were fetched
   int64_t seq_issued = 0;     // slices whose H2D has been enqueued
@@ -83,8 +86,12 @@ namespace {
 inline int n_retrieval(const hi_ctx* c) { return c->prob.n_kv_heads - c->prob.streaming_heads; }
 inline bool unit_streaming(const hi_ctx* c, int head) { return head >= n_retrieval(c); }
 
+// one K (or V) row in the host cache and on the link: bf16, or 4-bit codes with a scale and a zero per 32 channels
+inline int64_t link_row(const hi_ctx* c) { return c->plan.link_row_bytes; }
+inline bool link_packed(const hi_ctx* c) { return c->prob.link_kv_bits == 4; }
+
 inline int64_t plane_offset(const hi_ctx* c, int layer, int head, int which /*0 K, 1 V*/) {
-  const int64_t plane = c->prob.max_context * kRowBytes;
+  const int64_t plane = c->prob.max_context * link_row(c);
   return (((int64_t)layer * n_retrieval(c) + head) * 2 + which) * plane;
 }
 
@@ -120,13 +127,18 @@ inline char* stream_plane(const hi_ctx* c, int layer, int head, int which) {
 
 inline char* slot_k(const hi_ctx* c, int slot) { return c->staging + (int64_t)slot * c->slice_tokens * 2 * kRowBytes; }
 inline char* slot_v(const hi_ctx* c, int slot, int nh) { return slot_k(c, slot) + rows_of(c, nh) * kRowBytes; }
+// where a slot's slice lands when it crosses the link as 4-bit rows: the same planes, link_row bytes per row
+inline char* packed_slot(const hi_ctx* c, int slot) {
+  return c->staging + c->plan.hbm_packed_offset + (int64_t)slot * c->slice_tokens * 2 * link_row(c);
+}
 
 inline int64_t slices_of(const hi_ctx* c, int64_t past, int nh) { return ceil_div(past, rows_of(c, nh)); }
 
 inline bool can_issue(const hi_ctx* c) { return c->seq_issued - c->n_slots < c->seq_consumed; }
 
 void note_peak(hi_ctx* c) {
-  const int64_t live = (c->seq_issued - c->seq_consumed) * c->slice_tokens * 2 * kRowBytes;
+  const int64_t live = (c->seq_issued - c->seq_consumed) * c->slice_tokens * 2 *
+                       (kRowBytes + (link_packed(c) ? link_row(c) : 0));
   if (live > c->stats.peak_staging_bytes) c->stats.peak_staging_bytes = live;
 }
 
@@ -151,11 +163,13 @@ hi_status issue_slice(hi_ctx* c, hi_ctx::Unit& u) {
     // The K and V planes of consecutive heads are equally spaced in the cache and in the slot: one strided copy of
     // 2 * nh runs per slice (also for a single head: one call instead of two measured 48 -> 54 GB/s with 8 MiB
     // runs and 55 -> 57.6 GB/s with 64 MiB runs).
-    const char* hk = c->kv + plane_offset(c, u.layer, u.head, 0) + row0 * kRowBytes;
-    HI_HIP(hipMemcpy2DAsync(slot_k(c, slot), (size_t)(st * kRowBytes), hk, (size_t)(c->prob.max_context * kRowBytes),
-                            (size_t)(rows * kRowBytes), (size_t)(2 * u.nh), hipMemcpyHostToDevice, c->sh));
+    const int64_t lr = link_row(c);
+    const char* hk = c->kv + plane_offset(c, u.layer, u.head, 0) + row0 * lr;
+    char* dst = link_packed(c) ? packed_slot(c, slot) : slot_k(c, slot);
+    HI_HIP(hipMemcpy2DAsync(dst, (size_t)(st * lr), hk, (size_t)(c->prob.max_context * lr), (size_t)(rows * lr),
+                            (size_t)(2 * u.nh), hipMemcpyHostToDevice, c->sh));
     c->stats.n_h2d_copies += 1;
-    c->stats.bytes_h2d += 2 * rows * kRowBytes * u.nh;
+    c->stats.bytes_h2d += 2 * rows * lr * u.nh;
   }
   HI_HIP(hipEventRecord(c->ev_ready[slot], c->sh));
   u.issued += 1;
@@ -170,6 +184,14 @@ hi_status top_up(hi_ctx* c, hi_ctx::Unit& cur, hi_ctx::Unit& next) {
   if (cur.valid && cur.issued < cur.n_slices) return HI_OK;     // keep FIFO order
   while (next.valid && next.issued < next.n_slices && can_issue(c)) HI_TRY(issue_slice(c, next));
   return HI_OK;
+}
+
+// 4-bit link rows: expand the slice that has landed for `slot` into the slot's bf16 planes (compute stream, after
+// the wait on the slot's arrival)
+hi_status expand_slice(hi_ctx* c, int slot, int64_t rows, int nh) {
+  if (!link_packed(c)) return HI_OK;
+  const int64_t st = rows_of(c, nh);
+  return launch_kv_dequant(c->sc, packed_slot(c, slot), st * link_row(c), slot_k(c, slot), st * kRowBytes, rows, 2 * nh);
 }
 
 // a slice has been handed to a kernel (or dropped): its slot becomes free when the compute stream gets here
@@ -285,6 +307,38 @@ hi_status adopt_unit(hi_ctx* c, int layer, int head, int nh, int64_t past) {
 hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, const void* v_new, int64_t past,
                      int64_t len) {
   const bool resident = unit_resident(c, layer, head);
+  if (!resident && link_packed(c)) {
+    // encode the rows on the compute stream into one of two buffers, then write the encoded rows back; a buffer
+    // is encoded into again only after the write-back that read it has finished
+    const int b = c->wbq_turn;
+    c->wbq_turn ^= 1;
+    const int64_t lr = link_row(c);
+    char* qk = c->ws + c->plan.ws_writeback_offset + b * (c->plan.ws_writeback_bytes / 2);
+    char* qv = qk + (int64_t)nh * len * lr;
+    if (2 * (int64_t)nh * len * lr > c->plan.ws_writeback_bytes / 2) { set_last_error("write-back buffer too small"); return HI_ERR_RANGE; }
+    if (c->wbq_valid[b]) HI_HIP(hipStreamWaitEvent(c->sc, c->ev_wbq[b], 0));
+    HI_TRY(launch_kv_quant(c->sc, k_new, len * kRowBytes, qk, len * lr, len, nh));
+    HI_TRY(launch_kv_quant(c->sc, v_new, len * kRowBytes, qv, len * lr, len, nh));
+    HI_HIP(hipEventRecord(c->ev_entry, c->sc));
+    HI_HIP(hipStreamWaitEvent(c->sd, c->ev_entry, 0));
+    if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
+      const size_t dpitch = (size_t)(2 * c->prob.max_context * lr), w = (size_t)(len * lr);
+      HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 0) + past * lr, dpitch, qk, w, w, (size_t)nh,
+                              hipMemcpyDeviceToHost, c->sd));
+      HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 1) + past * lr, dpitch, qv, w, w, (size_t)nh,
+                              hipMemcpyDeviceToHost, c->sd));
+      c->stats.bytes_d2h += 2 * len * lr * nh;
+      c->stats.n_d2h_copies += 2;
+    }
+    HI_HIP(hipEventRecord(c->ev_wbq[b], c->sd));
+    c->wbq_valid[b] = 1;
+    for (int j = 0; j < nh; ++j) {
+      const int idx = layer * c->prob.n_kv_heads + head + j;
+      HI_HIP(hipEventRecord(c->ev_wb[idx], c->sd));
+      c->wb_valid[idx] = 1;
+    }
+    return HI_OK;
+  }
   if (!resident) {
     // the new rows were produced by earlier work on the compute stream
     HI_HIP(hipEventRecord(c->ev_entry, c->sc));
@@ -340,6 +394,10 @@ extern "C" hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* pla
   HI_TRY(validate_problem(problem));
   if (mode != HI_MODE_OFFLOAD && mode != HI_MODE_RESIDENT) { set_last_error("unknown mode"); return HI_ERR_ARG; }
   if (!kv_cache || !hbm_workspace || ((mode == HI_MODE_OFFLOAD || problem->streaming_heads > 0) && !hbm_staging)) { set_last_error("null buffer"); return HI_ERR_ARG; }
+  if (problem->link_kv_bits == 4 && mode != HI_MODE_OFFLOAD) {
+    set_last_error("link_kv_bits = 4 describes the host link: offload mode only");
+    return HI_ERR_UNSUPPORTED;
+  }
   hi_plan ref;
   HI_TRY(hi_offload_plan(problem, &ref));
   if (std::memcmp(&ref, plan, sizeof(ref)) != 0) { set_last_error("plan does not belong to this problem"); return HI_ERR_ARG; }
@@ -393,6 +451,9 @@ extern "C" hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* pla
     for (int i = 0; i < n_heads; ++i)
       if ((e = hipEventCreateWithFlags(&c->ev_wb[i], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
     if ((e = hipEventCreateWithFlags(&c->ev_entry, hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
+    if (link_packed(c))
+      for (int i = 0; i < 2; ++i)
+        if ((e = hipEventCreateWithFlags(&c->ev_wbq[i], hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreate");
   }
   *out = c;
   return HI_OK;
@@ -405,6 +466,7 @@ extern "C" hi_status hi_ctx_destroy(hi_ctx* c) {
   for (auto ev : c->ev_wb) if (ev) (void)hipEventDestroy(ev);
   for (auto ev : c->ev_unit) if (ev) (void)hipEventDestroy(ev);
   if (c->ev_entry) (void)hipEventDestroy(c->ev_entry);
+  for (auto ev : c->ev_wbq) if (ev) (void)hipEventDestroy(ev);
   for (auto& s : c->spans) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }
   for (auto& s : c->span_pool) { (void)hipEventDestroy(s.start); (void)hipEventDestroy(s.stop); }
   delete c;
@@ -508,6 +570,7 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
     if (rows > st) rows = st;
     HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
     if (run) {
+      HI_TRY(expand_slice(c, slot, rows, nh));
       const bool is_last = (i == ns - 1);
       PrefillSegment seg{slot_k(c, slot), slot_v(c, slot, nh), rows, 0, head_pitch(c, nh)};
       HI_TRY(launch(seg, is_last ? diag : PrefillSegment{nullptr, nullptr, 0, 1}, i == 0, is_last));
@@ -615,6 +678,7 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
     if (rows > st) rows = st;
     HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
     if (run) {
+      HI_TRY(expand_slice(c, slot, rows, nh));
       const int np = splits_for(rows);
       HI_TRY(partial(slot_k(c, slot), slot_v(c, slot, nh), rows, np, n_part, head_pitch(c, nh)));
       n_part += np;

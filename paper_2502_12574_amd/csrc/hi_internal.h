@@ -8,6 +8,7 @@ namespace hi {
 
 constexpr int kHeadDim = 128;
 constexpr int kRowBytes = kHeadDim * 2;          // one K (or V) row of one head, bf16
+constexpr int kLinkRowBytes4 = kHeadDim / 2 + 4 * (kHeadDim / 32);   // a row as 4-bit codes + bf16 scale/zero per 32 channels
 constexpr int kWgThreads = 256;                  // 4 wavefronts of 64
 constexpr int kCarryFloatsPerLane = 66;          // 64 O^T accumulators + running max + running sum
 constexpr int kPartialFloats = kHeadDim + 2;     // O[128], m, l of one (partition, query head)
@@ -102,5 +103,12 @@ hi_status launch_prefill_window(void* stream, const void* q, int G, int chunk_le
 hi_status launch_stream_store_update(void* stream, const void* k_new, const void* v_new, int chunk_len,
                                      int64_t past_len, int n_sink, int n_recent, void* store_k, void* store_v,
                                      int64_t store_head_stride, int n_heads);
+
+// 4-bit rows of the host link: `planes` planes of `rows` rows each, plane p at base + p * pitch on either side
+// (bf16 rows of 256 bytes <-> encoded rows of kLinkRowBytes4 bytes).
+hi_status launch_kv_quant(void* stream, const void* src, int64_t src_pitch, void* dst, int64_t dst_pitch,
+                          int64_t rows, int planes);
+hi_status launch_kv_dequant(void* stream, const void* src, int64_t src_pitch, void* dst, int64_t dst_pitch,
+                            int64_t rows, int planes);
 
 }  // namespace hi

@@ -26,8 +26,12 @@ hi_status validate_problem(const hi_problem* p) {
     return HI_ERR_ARG;
   }
   if (p->chunk > p->max_context) { set_last_error("chunk %d exceeds max_context", p->chunk); return HI_ERR_ARG; }
-  if (p->streaming_heads < 0 || p->streaming_heads >= p->n_kv_heads || p->reserved0 != 0) {
+  if (p->streaming_heads < 0 || p->streaming_heads >= p->n_kv_heads) {
     set_last_error("streaming_heads must be in [0, n_kv_heads)");
+    return HI_ERR_ARG;
+  }
+  if (p->link_kv_bits != 0 && p->link_kv_bits != 16 && p->link_kv_bits != 4) {
+    set_last_error("link_kv_bits must be 0, 16 (bf16 rows) or 4");
     return HI_ERR_ARG;
   }
   if (p->streaming_heads > 0 && (p->sink_tokens < 0 || p->recent_tokens < 1 ||
@@ -67,10 +71,13 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   const int64_t S = p->max_context;
   const int64_t C = p->chunk;
   const int G = p->gqa_group;
-  const int64_t row = 2LL * p->head_dim * p->dtype_bytes;  // K row + V row of one head
+  const int64_t row = 2LL * p->head_dim * p->dtype_bytes;  // K row + V row of one head, in HBM
+  const bool packed = p->link_kv_bits == 4;
+  pl.link_row_bytes = packed ? kLinkRowBytes4 : p->head_dim * p->dtype_bytes;
+  const int64_t link_row = 2 * pl.link_row_bytes;          // the same pair in the host cache and on the link
 
   // Eq. 11 and Eq. 4
-  pl.host_bytes_per_head = S * row;
+  pl.host_bytes_per_head = S * link_row;
   pl.host_bytes_total = (int64_t)p->n_layers * (p->n_kv_heads - p->streaming_heads) * pl.host_bytes_per_head;
   if (p->host_mem_limit_bytes > 0 && pl.host_bytes_total > p->host_mem_limit_bytes) {
     set_last_error("host cache of %lld bytes exceeds the limit", (long long)pl.host_bytes_total);
@@ -78,7 +85,7 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   }
   // Eq. 10
   pl.alpha = (double)p->gpu_kv_budget_heads / ((double)p->n_layers * p->n_kv_heads);
-  pl.hbm_pingpong_paper_bytes = 2 * pl.host_bytes_per_head;
+  pl.hbm_pingpong_paper_bytes = 2 * S * row;
 
   // heads_per_group is filled in below, once the ring geometry is known
   {  // Section 4: all heads fused up to 500K, two groups to 1M, four to 2M, eight beyond
@@ -89,7 +96,10 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
 
   // staging ring: sequence slices inside the HBM budget, so that a slice can land while another is consumed
   // (Algorithm 1's H_on heads take whole-head shares of the budget; the ring gets what is left)
-  const int64_t budget_tokens = (int64_t)(p->gpu_kv_budget_heads - p->resident_heads) * S;
+  // (with 4-bit rows on the link every slot also has a landing area for the encoded slice: the budget then pays
+  // row + link_row bytes per ring row)
+  const int64_t budget_rows = (int64_t)(p->gpu_kv_budget_heads - p->resident_heads) * S;
+  const int64_t budget_tokens = packed ? budget_rows * row / (row + link_row) : budget_rows;
   // (four slices: measured against eight, the larger copies and fewer launches win 1-3 % of prefill time and up to
   // 14 % of offloaded decode time at a 128K context, and nothing is lost in overlap)
   int64_t slice = (budget_tokens / 4) / 64 * 64;
@@ -119,12 +129,14 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
     pl.n_groups = (int32_t)(ceil_div(n_retrieval, hpg) + ceil_div(p->streaming_heads, hpg));
   }
   pl.hbm_resident_offset = n_slices * slice * row;
-  pl.hbm_resident_bytes = (int64_t)p->resident_heads * pl.host_bytes_per_head;
+  pl.hbm_resident_bytes = (int64_t)p->resident_heads * S * row;
   // Appendix E: the streaming heads' bounded stores, small and outside the whole-head budget
   pl.stream_rows = p->streaming_heads > 0 ? (int64_t)p->sink_tokens + p->recent_tokens : 0;
   pl.hbm_stream_offset = pl.hbm_resident_offset + pl.hbm_resident_bytes;
   pl.hbm_stream_bytes = (int64_t)p->n_layers * p->streaming_heads * pl.stream_rows * row;
-  pl.hbm_staging_bytes = pl.hbm_stream_offset + pl.hbm_stream_bytes;
+  pl.hbm_packed_offset = pl.hbm_stream_offset + pl.hbm_stream_bytes;
+  pl.hbm_packed_bytes = packed ? n_slices * slice * link_row : 0;
+  pl.hbm_staging_bytes = pl.hbm_packed_offset + pl.hbm_packed_bytes;
 
   const int n_cu = p->n_compute_units > 0 ? p->n_compute_units : 256;
   pl.n_split_decode = n_cu;
@@ -134,7 +146,9 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   const int64_t carry_bytes = prefill_carry_images(G, C, p->n_kv_heads) * kWgThreads * kCarryFloatsPerLane * 4;
   const int64_t partial_bytes = decode_part_head_stride(S, slice, pl.n_split_decode, G) * 4 * p->n_kv_heads;
   pl.ws_partials_offset = round_up(carry_bytes, 256);
-  pl.workspace_bytes = pl.ws_partials_offset + round_up(partial_bytes, 256);
+  pl.ws_writeback_offset = pl.ws_partials_offset + round_up(partial_bytes, 256);
+  pl.ws_writeback_bytes = packed ? 2 * round_up((int64_t)(p->n_kv_heads - p->streaming_heads) * C * link_row, 256) : 0;
+  pl.workspace_bytes = pl.ws_writeback_offset + pl.ws_writeback_bytes;
 
   // Section 5: T ~ max(T_comp, T_mem), evaluated for the deepest unit
   const double link = (p->link_GBps > 0 ? p->link_GBps : 64.0) * 1e9;
@@ -143,8 +157,8 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   const double P = (double)(S - C);
   const double d = p->head_dim;
   pl.flop_prefill_unit = 4.0 * d * G * ((double)C * P + 0.5 * (double)C * ((double)C + 1.0));
-  pl.bytes_link_prefill_unit = (double)row * (P + (double)C);
-  pl.bytes_link_decode_unit = (double)row * (double)S;
+  pl.bytes_link_prefill_unit = (double)link_row * (P + (double)C);
+  pl.bytes_link_decode_unit = (double)link_row * (double)S;
   const double qo_bytes = 2.0 * G * (double)C * d * p->dtype_bytes;
   pl.t_comp_prefill_s = pl.flop_prefill_unit / mfma;
   pl.t_link_prefill_s = pl.bytes_link_prefill_unit / link;

@@ -12,7 +12,7 @@ from . import binding as hb
 class Session:
     def __init__(self, n_layers, n_kv_heads, gqa_group, max_context, chunk, mode=hb.HI_MODE_OFFLOAD, out_fp32=1,
                  device="cuda:0", gpu_kv_budget_heads=1, n_compute_units=0, resident_heads=0, streaming_heads=0,
-                 sink_tokens=0, recent_tokens=0):
+                 sink_tokens=0, recent_tokens=0, link_kv_bits=0):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the library has no CPU path")
         self.device = torch.device(device)
@@ -21,7 +21,8 @@ class Session:
         self.problem = hb.make_problem(n_layers, n_kv_heads, gqa_group, max_context, chunk, out_fp32=out_fp32,
                                        gpu_kv_budget_heads=gpu_kv_budget_heads, n_compute_units=n_compute_units,
                                        resident_heads=resident_heads, streaming_heads=streaming_heads,
-                                       sink_tokens=sink_tokens, recent_tokens=recent_tokens)
+                                       sink_tokens=sink_tokens, recent_tokens=recent_tokens,
+                                       link_kv_bits=link_kv_bits)
         self.plan = hb.hi_offload_plan(self.problem)
         nbytes = self.plan.host_bytes_total
         if mode == hb.HI_MODE_OFFLOAD:
@@ -40,9 +41,13 @@ class Session:
                                     self.s_compute, self.s_h2d, self.s_d2h)
         self.out_dtype = torch.float32 if out_fp32 else torch.bfloat16
 
-    # [layer][retrieval kv_head][K|V][S_max][d] bf16 views of the cache (host or device)
+    # [layer][retrieval kv_head][K|V][S_max][d] bf16 views of the cache (host or device); with 4-bit rows on the
+    # link, [layer][retrieval kv_head][K|V][S_max][80] bytes
     def cache_view(self) -> torch.Tensor:
         p = self.problem
+        if p.link_kv_bits == 4:
+            return self.kv.view(p.n_layers, p.n_kv_heads - p.streaming_heads, 2, p.max_context,
+                                self.plan.link_row_bytes)
         return self.kv.view(torch.bfloat16).view(p.n_layers, p.n_kv_heads - p.streaming_heads, 2, p.max_context,
                                                  p.head_dim)
 

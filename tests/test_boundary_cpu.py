@@ -188,3 +188,27 @@ def test_plan_streaming_heads():
     ok = hb.hi_offload_plan(hb.make_problem(**base, streaming_heads=4, sink_tokens=4, recent_tokens=4,
                                             resident_heads=3, gpu_kv_budget_heads=4))
     assert ok.hbm_resident_bytes == 3 * ok.host_bytes_per_head
+
+
+def test_plan_four_bit_link_rows():
+    """4-bit rows on the link: 80-byte rows in the host cache, and ring + landing areas inside the same HBM budget."""
+    base = dict(n_layers=32, n_kv_heads=8, gqa_group=4, max_context=1 << 20, chunk=16384)
+    ref = hb.hi_offload_plan(hb.make_problem(**base))
+    same = hb.hi_offload_plan(hb.make_problem(**base, link_kv_bits=16))
+    assert bytes(same) == bytes(ref)
+    pl = hb.hi_offload_plan(hb.make_problem(**base, link_kv_bits=4))
+    assert ref.link_row_bytes == 256 and pl.link_row_bytes == 80
+    assert pl.host_bytes_per_head == (1 << 20) * 160 and pl.host_bytes_total * 256 == ref.host_bytes_total * 80
+    ring = pl.n_slices_ring * pl.slice_tokens
+    assert pl.hbm_packed_bytes == ring * 160 and pl.hbm_packed_offset == pl.hbm_stream_offset + pl.hbm_stream_bytes
+    assert pl.hbm_staging_bytes == ring * 512 + pl.hbm_packed_bytes <= (1 << 20) * 512      # one head's worth of HBM
+    assert pl.slice_tokens % 64 == 0 and pl.n_slices_ring >= 2
+    assert pl.ws_writeback_bytes >= 2 * 8 * 16384 * 160 and pl.workspace_bytes == pl.ws_writeback_offset + pl.ws_writeback_bytes
+    assert ref.hbm_packed_bytes == 0 and ref.ws_writeback_bytes == 0
+    assert pl.bytes_link_decode_unit * 256 == ref.bytes_link_decode_unit * 80
+    # resident heads keep bf16 rows in HBM whatever the link carries
+    r = hb.hi_offload_plan(hb.make_problem(**base, link_kv_bits=4, resident_heads=2, gpu_kv_budget_heads=3))
+    assert r.hbm_resident_bytes == 2 * (1 << 20) * 512
+    for bits in (1, 8, -4, 3):
+        st, _ = hb.hi_offload_plan(hb.make_problem(**base, link_kv_bits=bits), check=False)
+        assert st == hb.HI_ERR_ARG, bits
