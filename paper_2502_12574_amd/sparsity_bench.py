@@ -24,10 +24,10 @@ from .session import Session
 H, G, D = 8, 4, 128
 
 
-def run(S, C, T, n_sink, n_recent, n_dec, stream_group):
+def run(S, C, T, n_sink, n_recent, n_dec, stream_group, link_kv_bits=0):
     dev = "cuda:0"
     with Session(1, H, G, S + n_dec, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0, streaming_heads=T, sink_tokens=n_sink,
-                 recent_tokens=n_recent) as ss:
+                 recent_tokens=n_recent, link_kv_bits=link_kv_bits) as ss:
         gen = torch.Generator(device=dev).manual_seed(1)
         q = torch.randn(H, G, C, D, device=dev, generator=gen).to(torch.bfloat16)
         k = torch.randn(H, C, D, device=dev, generator=gen).to(torch.bfloat16)
@@ -73,9 +73,11 @@ def run(S, C, T, n_sink, n_recent, n_dec, stream_group):
         prefill()
         t_pre = time.perf_counter() - t0
         decode()
+        hb.hi_reset_stats(ss.ctx)
         t0 = time.perf_counter()
         decode()
         t_dec = (time.perf_counter() - t0) / n_dec
+        dec_h2d = ss.stats().bytes_h2d / n_dec
 
         # the streaming heads' kernels alone (HIP events inside the library)
         t_stream_pre = t_stream_dec = 0.0
@@ -98,7 +100,8 @@ def run(S, C, T, n_sink, n_recent, n_dec, stream_group):
             t_stream_dec = ss.stats().decode_kernel_ms * 1e-3
             hb.hi_ctx_set_flags(ss.ctx, 0)
         stats = ss.stats()
-    return dict(streaming_heads=T, prefill_s=t_pre, prefill_tokens_per_s=S / t_pre, decode_ms_per_token=t_dec * 1e3,
+    return dict(streaming_heads=T, link_kv_bits=link_kv_bits or 16, decode_h2d_MB_per_token=dec_h2d / 1e6,
+                decode_link_GBps=dec_h2d / t_dec / 1e9, prefill_s=t_pre, prefill_tokens_per_s=S / t_pre, decode_ms_per_token=t_dec * 1e3,
                 stream_prefill_kernels_s=t_stream_pre, stream_decode_kernels_us=t_stream_dec * 1e6,
                 host_cache_GiB=ss.plan.host_bytes_total / 2**30, hbm_stream_MiB=ss.plan.hbm_stream_bytes / 2**20)
 

@@ -199,3 +199,87 @@ def test_resident_mode_rejects_four_bit_rows():
     with pytest.raises(hb.HiError) as e:
         hb.hi_ctx_create(p, plan, hb.HI_MODE_RESIDENT, kv, None, ws, s, s, s)
     assert e.value.status == hb.HI_ERR_UNSUPPORTED
+
+
+def _cpu_f32(tensor_id, seed, head, n, step=1 << 19):
+    """float32 [n, 128] (bf16 values) of one K/V stream, drawn on the CPU by the seeded integer-only generator."""
+    out = np.empty((n, 128), dtype=np.float32)
+    for a in range(0, n, step):
+        b = min(n, a + step)
+        t = synth.draw_k(seed, 0, head, a, b - a) if tensor_id == synth.TENSOR_K else synth.draw(seed, tensor_id, 0, head, a, b - a)
+        out[a:b] = t.to(torch.float32).numpy()
+    return out
+
+
+@pytest.mark.timeout(900)
+def test_layer_1m_four_bit_rows_sampled_rows_and_decode():
+    """The 1M-token layer (8 KV heads, G = 4, chunk 16384) with 4-bit rows on the link, in the launch configuration
+    the benchmark times: the host cache is pre-filled (by the library's own encoder) up to the last two chunks,
+    which then run through the library, followed by two decode steps.  Sampled rows of one head against the fp64
+    oracle, whose 4-bit history is encoded by the oracle from the CPU-regenerated inputs; the bytes the library
+    left in the host cache are compared with the oracle's on the way."""
+    seed, S, C, H, G, nd, h = 20250217, 1 << 20, 16384, 8, 4, 2, 5
+    P0 = S - 2 * C
+    rng = np.random.default_rng(9)
+    ss = Session(1, H, G, S + nd, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, link_kv_bits=4)
+    cv = ss.cache_view()
+    step = 1 << 18
+    packed = torch.empty(step, 80, dtype=torch.uint8, device=DEV)
+    for hh in range(H):
+        for a in range(0, P0, step):
+            b = min(P0, a + step)
+            for which, draw in ((0, synth.draw_k), (1, synth.draw_v)):
+                hb.hi_kv_quantize(torch.cuda.current_stream(), draw(seed, 0, hh, a, b - a, device=DEV), b - a, packed)
+                cv[0, hh, which, a:b].copy_(packed[:b - a])
+    torch.cuda.synchronize()
+    pos = np.array(sorted({P0, P0 + 1, P0 + 63, P0 + 64, S - C - 1, S - C, S - C + 1, S - 1, S - 2} |
+                          set(int(x) for x in rng.integers(P0, S, 16))), dtype=np.int64)
+    kept, dec = {}, []
+    with torch.cuda.stream(ss.s_compute):
+        for ci, p in enumerate((P0, P0 + C)):
+            for hh in range(H):
+                q = torch.stack([synth.draw_q(seed, 0, hh * G + g, p, C, device=DEV) for g in range(G)])
+                out = torch.empty(G, C, 128, dtype=torch.float32, device=DEV)
+                nxt = (0, hh + 1, p) if hh + 1 < H else ((0, 0, p + C) if ci == 0 else (0, 0, S))
+                ss.prefill_head(0, hh, q, synth.draw_k(seed, 0, hh, p, C, device=DEV),
+                                synth.draw_v(seed, 0, hh, p, C, device=DEV), p, out, nxt)
+                if hh == h:
+                    sel = [int(x - p) for x in pos if p <= x < p + C]
+                    kept[ci] = out.index_select(1, torch.tensor(sel, device=DEV))
+        for t in range(nd):
+            for hh in range(H):
+                q = torch.stack([synth.draw_q(seed, 0, hh * G + g, S + t, 1, device=DEV)[0] for g in range(G)])
+                out = torch.empty(G, 128, dtype=torch.float32, device=DEV)
+                nxt = (0, hh + 1, S + t) if hh + 1 < H else (0, 0, S + t + 1)
+                ss.decode_head(0, hh, q, synth.draw_k(seed, 0, hh, S + t, 1, device=DEV)[0],
+                               synth.draw_v(seed, 0, hh, S + t, 1, device=DEV)[0], S + t, out, nxt if t + 1 < nd or hh + 1 < H else None)
+                if hh == h:
+                    dec.append(out)
+    ss.sync()
+    st = ss.stats()
+    assert st.peak_staging_bytes <= (S + nd) * 512                     # ring + landing areas: one head's worth of HBM
+    assert st.bytes_h2d == 160 * H * (P0 + P0 + C + sum(S + t for t in range(nd)))
+
+    K = _cpu_f32(synth.TENSOR_K, seed, h, S + nd)
+    V = _cpu_f32(synth.TENSOR_V, seed, h, S + nd)
+    kp, vp = kq.pack_rows(*kq.quantize_rows(K)), kq.pack_rows(*kq.quantize_rows(V))
+    got_k, got_v = cv[0, h, 0].numpy(), cv[0, h, 1].numpy()
+    for a, b in ((0, 4096), (P0 - 2048, S + nd)):                      # the pre-fill, and everything the calls wrote
+        assert np.array_equal(got_k[a:b], kp[a:b]) and np.array_equal(got_v[a:b], vp[a:b]), (a, b)
+    Kq = kq.dequantize_rows(*kq.unpack_rows(kp)).astype(np.float64)
+    Vq = kq.dequantize_rows(*kq.unpack_rows(vp)).astype(np.float64)
+    for ci, p in enumerate((P0, P0 + C)):
+        Km, Vm = Kq[:p + C].copy(), Vq[:p + C].copy()
+        Km[p:], Vm[p:] = K[p:p + C], V[p:p + C]                        # the chunk's own rows are exact
+        sel = np.array([x for x in pos if p <= x < p + C], dtype=np.int64)
+        for g in range(G):
+            qrows = synth.to_f64(torch.cat([synth.draw_q(seed, 0, h * G + g, int(x), 1) for x in sel]))
+            ref = oa.attn_rows(qrows, Km, Vm, sel)
+            check(kept[ci][g], ref, ("1M prefill", ci, g))
+    for t in range(nd):
+        Km, Vm = Kq[:S + t + 1].copy(), Vq[:S + t + 1].copy()
+        Km[S + t], Vm[S + t] = K[S + t], V[S + t]
+        q = np.stack([synth.to_f64(synth.draw_q(seed, 0, h * G + g, S + t, 1))[0] for g in range(G)])
+        ref = oa.attn_rows(q, Km, Vm, np.full(G, S + t))
+        check(dec[t], ref, ("1M decode", t))
+    ss.close()
