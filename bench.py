@@ -246,6 +246,14 @@ def main():
             sp["decode_speedup_vs_all_retrieval"] = decode_ms_tok / sp["decode_ms_per_token"]
         result["streaming_heads_50pct"] = sp
         result["projections"] = proj_bench.measure(C)
+        # the same layer with 4-bit rows on the host link (every head offloaded): the link-bound decode should follow
+        # the bytes per row, the prefill should not change
+        torch.cuda.empty_cache()
+        lk = sparsity_bench.run(S, C, 0, 0, 0, 8, 1, link_kv_bits=4)
+        lk["prefill_speedup_vs_bf16_rows"] = prefill_s / lk["prefill_s"]
+        if nd:
+            lk["decode_speedup_vs_bf16_rows"] = decode_ms_tok / lk["decode_ms_per_token"]
+        result["link_kv_4bit"] = lk
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args.seed, S, C)
     print(json.dumps(result))

@@ -82,26 +82,42 @@ __global__ __launch_bounds__(256) void kv_quant_kernel(const char* __restrict__ 
   }
 }
 
+// A thread expands 8 channels (4 bytes of codes -> 16 bytes of bf16): the 16 threads of a row write its 256 bytes
+// side by side, so every store instruction of a wave covers 1 KB of consecutive addresses; a workgroup takes
+// kRowsPerWg rows in 4 passes of 16 rows, all loads issued before the first conversion.
 __global__ __launch_bounds__(256) void kv_dequant_kernel(const char* __restrict__ src, int64_t src_pitch,
                                                          char* __restrict__ dst, int64_t dst_pitch, int64_t rows) {
-  const int g = threadIdx.x & 3;
-  const int64_t row = (int64_t)blockIdx.x * kRowsPerWg + (threadIdx.x >> 2);
-  if (row >= rows) return;
-  const char* s = src + (int64_t)blockIdx.y * src_pitch + row * kLinkRowBytes4;
-  const u32x4 codes = *(const u32x4*)(s + 16 * g);
-  const float scale = bf16_bits_to_float(*(const uint16_t*)(s + 64 + 2 * g));
-  const float zero = bf16_bits_to_float(*(const uint16_t*)(s + 72 + 2 * g));
-  char* d = dst + (int64_t)blockIdx.y * dst_pitch + row * kRowBytes + g * 64;
+  const int c = threadIdx.x & 15;
+  const int g = c >> 2;
+  const int64_t row0 = (int64_t)blockIdx.x * kRowsPerWg + (threadIdx.x >> 4);
+  const char* sp = src + (int64_t)blockIdx.y * src_pitch;
+  char* dp = dst + (int64_t)blockIdx.y * dst_pitch;
+  uint32_t codes[4];
+  uint16_t sb[4], zb[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    u32x4 o;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const float lo = __fmaf_rn((float)((codes[i] >> (8 * j)) & 15u), scale, zero);
-      const float hi = __fmaf_rn((float)((codes[i] >> (8 * j + 4)) & 15u), scale, zero);
-      o[j] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+  for (int it = 0; it < 4; ++it) {
+    const int64_t row = row0 + 16 * it;
+    if (row < rows) {
+      const char* s = sp + row * kLinkRowBytes4;
+      codes[it] = *(const uint32_t*)(s + 4 * c);
+      sb[it] = *(const uint16_t*)(s + 64 + 2 * g);
+      zb[it] = *(const uint16_t*)(s + 72 + 2 * g);
     }
-    *(u32x4*)(d + 16 * i) = o;
+  }
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int64_t row = row0 + 16 * it;
+    if (row < rows) {
+      const float scale = bf16_bits_to_float(sb[it]), zero = bf16_bits_to_float(zb[it]);
+      u32x4 o;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float lo = __fmaf_rn((float)((codes[it] >> (8 * j)) & 15u), scale, zero);
+        const float hi = __fmaf_rn((float)((codes[it] >> (8 * j + 4)) & 15u), scale, zero);
+        o[j] = (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+      }
+      *(u32x4*)(dp + row * kRowBytes + 16 * c) = o;
+    }
   }
 }
 
