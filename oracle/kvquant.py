@@ -143,16 +143,19 @@ class QuantizedHeadCache:
         self.V = np.concatenate([self.V, pack_rows(*quantize_rows(v_rows))], axis=0)
 
 
-def prefill_chunked_kv4(cache: QuantizedHeadCache, Q, K, V, chunk: int) -> np.ndarray:
-    """Algorithm 1's prefill for one KV head with a 4-bit host cache.  Q [G, S, d]; K, V [S, d].  Per chunk: attend
-    to [dequantised past ; the chunk's exact rows] (Eq. 3 with the causal mask), then the chunk's rows go to the
-    cache.  Returns [G, S, d] float64."""
+def prefill_chunked_kv4(cache: QuantizedHeadCache, Q, K, V, chunk) -> np.ndarray:
+    """Algorithm 1's prefill for one KV head with a 4-bit host cache.  Q [G, S, d]; K, V [S, d]; chunk: the chunk
+    length, or the list of the chunks' lengths (summing to S).  Per chunk: attend to [dequantised past ; the chunk's
+    exact rows] (Eq. 3 with the causal mask), then the chunk's rows go to the cache.  Returns [G, S, d] float64."""
     Q = np.asarray(Q, dtype=np.float64)
     K32, V32 = _check_bf16(K), _check_bf16(V)
     S = K32.shape[0]
     out = np.empty_like(Q)
-    for c0 in range(0, S, chunk):
-        c1 = min(S, c0 + chunk)
+    lengths = [chunk] * (-(-S // chunk)) if isinstance(chunk, (int, np.integer)) else list(chunk)
+    starts = np.concatenate([[0], np.cumsum(lengths)])[:len(lengths)]
+    for c0, n in zip(starts, lengths):
+        c0 = int(c0)
+        c1 = min(S, c0 + int(n))
         past = cache.length()
         kp, vp = cache.history()
         Kh = np.concatenate([kp, K32[c0:c1].astype(np.float64)], axis=0)

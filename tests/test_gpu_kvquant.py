@@ -283,3 +283,84 @@ def test_layer_1m_four_bit_rows_sampled_rows_and_decode():
         ref = oa.attn_rows(q, Km, Vm, np.full(G, S + t))
         check(dec[t], ref, ("1M decode", t))
     ss.close()
+
+
+@pytest.mark.parametrize("case_id", range(12))
+def test_random_shapes_over_a_four_bit_cache(case_id):
+    """Seeded random sweep: group size, head count and kinds, ragged chunk lengths, context, heads per call."""
+    import random
+    rng = random.Random(88000 + case_id)
+    G = rng.choice([1, 2, 4, 4, 8])
+    H = rng.choice([2, 3, 4])
+    T = rng.choice([0, 0, 1])
+    n_ret = H - T
+    R = min(rng.choice([0, 0, 1]), n_ret - 1)
+    C = rng.choice([37, 64, 100, 128, 200, 333])
+    S = rng.randint(1, 900)
+    nd = rng.choice([0, 1, 3])
+    n_sink, n_recent = rng.choice([0, 5, 64]), rng.choice([1, 33, 257])
+    group = rng.choice([1, 1, 2])
+    seed, n_tok = 88000 + case_id, S + nd
+    max_ctx = max(n_tok, 1024)
+    kinds = [("res" if h < R else "off") for h in range(n_ret)] + ["str"] * T
+    calls, h = [], 0
+    while h < H:
+        nh = 1
+        while nh < group and h + nh < H and kinds[h + nh] == kinds[h]:
+            nh += 1
+        calls.append((h, nh))
+        h += nh
+    what = dict(G=G, H=H, T=T, R=R, C=C, S=S, nd=nd, sink=n_sink, recent=n_recent, group=group)
+    lengths = []
+    with Session(1, H, G, max_ctx, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, gpu_kv_budget_heads=R + 1, resident_heads=R,
+                 streaming_heads=T, sink_tokens=n_sink if T else 0, recent_tokens=n_recent if T else 0,
+                 link_kv_bits=4) as ss:
+        ss.kv.fill_(0xFF)
+        ss.staging.view(torch.int16).fill_(0x7FC1)
+        pre = {h: [] for h in range(H)}
+        dec = {h: [] for h in range(H)}
+        with torch.cuda.stream(ss.s_compute):
+            Q = {h: torch.stack([synth.draw_q(seed, 0, h * G + g, 0, n_tok, device=DEV) for g in range(G)]) for h in range(H)}
+            K = {h: synth.draw_k(seed, 0, h, 0, n_tok, device=DEV) for h in range(H)}
+            V = {h: synth.draw_v(seed, 0, h, 0, n_tok, device=DEV) for h in range(H)}
+            p = 0
+            while p < S:
+                n = min(rng.choice([C, C, max(1, C // 2), max(1, C - 7)]), S - p)
+                lengths.append(n)
+                for h0, nh in calls:
+                    hs = range(h0, h0 + nh)
+                    out = torch.empty(nh, G, n, 128, dtype=torch.float32, device=DEV)
+                    ss.prefill_group(0, h0, nh, torch.stack([Q[h][:, p:p + n] for h in hs]).contiguous(),
+                                     torch.stack([K[h][p:p + n] for h in hs]).contiguous(),
+                                     torch.stack([V[h][p:p + n] for h in hs]).contiguous(), p, out)
+                    for i, h in enumerate(hs):
+                        pre[h].append(out[i])
+                p += n
+            for t in range(nd):
+                p = S + t
+                for h0, nh in calls:
+                    hs = range(h0, h0 + nh)
+                    out = torch.empty(nh, G, 128, dtype=torch.float32, device=DEV)
+                    ss.decode_group(0, h0, nh, torch.stack([Q[h][:, p] for h in hs]).contiguous(),
+                                    torch.stack([K[h][p] for h in hs]).contiguous(),
+                                    torch.stack([V[h][p] for h in hs]).contiguous(), p, out)
+                    for i, h in enumerate(hs):
+                        dec[h].append(out[i])
+        ss.sync()
+        cache = ss.cache_view()[0].cpu().numpy().copy()
+    for h in range(H):
+        q, k, v = _f32(Q[h]), _f32(K[h]), _f32(V[h])
+        got = torch.cat(pre[h], dim=1).cpu()
+        if kinds[h] == "off":
+            oc = kq.QuantizedHeadCache()
+            want_pre = kq.prefill_chunked_kv4(oc, q[:, :S], k[:S], v[:S], lengths)
+            want_dec = [kq.decode_step_kv4(oc, q[:, S + t], k[S + t], v[S + t]) for t in range(nd)]
+            assert np.array_equal(cache[h, 0, :n_tok], oc.K) and np.array_equal(cache[h, 1, :n_tok], oc.V), (what, h)
+            ref = np.concatenate([want_pre] + [w[:, None] for w in want_dec], axis=1)
+        elif kinds[h] == "str":
+            ref = os_.attn_head_streaming(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64), 0, n_sink, n_recent)
+        else:
+            ref = oa.attn_head(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64))
+        check(got, ref[:, :S], (what, "prefill", h, kinds[h]))
+        if nd:
+            check(torch.stack(dec[h], dim=1).cpu(), ref[:, S:], (what, "decode", h, kinds[h]))

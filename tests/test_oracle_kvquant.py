@@ -156,3 +156,16 @@ def test_k10_one_chunk_sees_exact_rows_later_chunks_see_the_round_trip():
     # and the approximation is a small perturbation of the exact result, not something else
     rel = np.linalg.norm(two - one) / np.linalg.norm(one)
     assert 0 < rel < 0.2
+
+
+def test_k11_chunk_lengths_given_as_a_list():
+    S, G = 50, 1
+    K, V = _rows(17, S), _rows(18, S)
+    Q = _rows(19, G * S).reshape(G, S, 128)
+    a = kq.prefill_chunked_kv4(kq.QuantizedHeadCache(), Q, K, V, 20)
+    b = kq.prefill_chunked_kv4(kq.QuantizedHeadCache(), Q, K, V, [20, 20, 10])
+    assert np.array_equal(a, b)
+    c = kq.prefill_chunked_kv4(kq.QuantizedHeadCache(), Q, K, V, [7, 43])
+    Kmix = np.concatenate([kq.roundtrip(K[:7]), K[7:]]).astype(np.float64)
+    Vmix = np.concatenate([kq.roundtrip(V[:7]), V[7:]]).astype(np.float64)
+    np.testing.assert_allclose(c[:, 7:], oa.attn_head(Q[:, 7:], Kmix, Vmix, 7), rtol=0, atol=1e-12)
