@@ -118,3 +118,58 @@ def test_group_argument_errors():
         assert hb.hi_prefill_group(ss.ctx, 0, 0, 4, q, k, k, 0, 64, out, check=False) == hb.HI_ERR_HBM_BUDGET
         assert hb.hi_prefill_group(ss.ctx, 0, 0, 2, q, k, k, 0, 64, out, -1, 0, 1, 0, check=False) == hb.HI_OK
         ss.sync()
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_OFFLOAD, hb.HI_MODE_RESIDENT])
+def test_a_batch_of_ragged_sequences_is_more_heads(mode):
+    """Eq. 4 has a batch dimension; for attention a batch element is just more KV heads with their own cache rows.
+    Three sequences of different lengths x 2 KV heads as a 6-head layer: each sequence is prefilled and decoded at
+    its own positions (two heads per call), interleaved token by token, and every head matches the oracle."""
+    Hs, G, C, nd, seed, dev = 2, 4, 128, 3, 6400, "cuda:0"
+    lens = [700, 45, 333]                                  # prompt lengths of the batch
+    B = len(lens)
+    H = B * Hs
+    with Session(1, H, G, max(lens) + nd, C, mode=mode, out_fp32=1) as ss:
+        if mode == hb.HI_MODE_OFFLOAD:
+            ss.staging.view(torch.int16).fill_(0x7FC1)
+            ss.kv.view(torch.int16).fill_(0x7FC1)
+        Q, K, V, pre, dec = {}, {}, {}, {}, {}
+        with torch.cuda.stream(ss.s_compute):
+            for b, S in enumerate(lens):
+                for j in range(Hs):
+                    h = b * Hs + j
+                    Q[h] = torch.stack([synth.draw_q(seed, 0, h * G + g, 0, S + nd, device=dev) for g in range(G)])
+                    K[h] = synth.draw_k(seed, 0, h, 0, S + nd, device=dev)
+                    V[h] = synth.draw_v(seed, 0, h, 0, S + nd, device=dev)
+                    pre[h], dec[h] = [], []
+            # prefill: chunk by chunk over the batch; a sequence that has run out of prompt sits the chunk out
+            for p in range(0, max(lens), C):
+                for b, S in enumerate(lens):
+                    n = min(C, S - p)
+                    if n <= 0:
+                        continue
+                    hs = range(b * Hs, (b + 1) * Hs)
+                    out = torch.empty(Hs, G, n, 128, dtype=torch.float32, device=dev)
+                    ss.prefill_group(0, b * Hs, Hs, torch.stack([Q[h][:, p:p + n] for h in hs]).contiguous(),
+                                     torch.stack([K[h][p:p + n] for h in hs]).contiguous(),
+                                     torch.stack([V[h][p:p + n] for h in hs]).contiguous(), p, out)
+                    for i, h in enumerate(hs):
+                        pre[h].append(out[i])
+            for t in range(nd):
+                for b, S in enumerate(lens):
+                    hs = range(b * Hs, (b + 1) * Hs)
+                    out = torch.empty(Hs, G, 128, dtype=torch.float32, device=dev)
+                    nb = (b + 1) % B
+                    nxt = (0, nb * Hs, Hs, lens[nb] + t + (1 if nb == 0 else 0))
+                    ss.decode_group(0, b * Hs, Hs, torch.stack([Q[h][:, S + t] for h in hs]).contiguous(),
+                                    torch.stack([K[h][S + t] for h in hs]).contiguous(),
+                                    torch.stack([V[h][S + t] for h in hs]).contiguous(), S + t, out, nxt)
+                    for i, h in enumerate(hs):
+                        dec[h].append(out[i])
+        ss.sync()
+    for b, S in enumerate(lens):
+        for j in range(Hs):
+            h = b * Hs + j
+            ref = oa.attn_head(synth.to_f64(Q[h].cpu()), synth.to_f64(K[h].cpu()), synth.to_f64(V[h].cpu()))
+            check(torch.cat(pre[h], dim=1), ref[:, :S], f"sequence {b} head {j} prefill")
+            check(torch.stack(dec[h], dim=1), ref[:, S:], f"sequence {b} head {j} decode")
