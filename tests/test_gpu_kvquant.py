@@ -364,3 +364,28 @@ def test_random_shapes_over_a_four_bit_cache(case_id):
         check(got, ref[:, :S], (what, "prefill", h, kinds[h]))
         if nd:
             check(torch.stack(dec[h], dim=1).cpu(), ref[:, S:], (what, "decode", h, kinds[h]))
+
+
+def test_copies_only_run_still_fills_the_four_bit_cache():
+    """HI_FLAG_SKIP_KERNELS (the transfer-only leg of the benchmark) skips the attention kernels and the expansion of
+    fetched slices, not the encoding of the rows that go to the host."""
+    H, G, S, C, seed = 2, 4, 600, 128, 8400
+    with Session(1, H, G, S, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, link_kv_bits=4) as ss:
+        hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_SKIP_KERNELS)
+        ss.kv.fill_(0xFF)
+        with torch.cuda.stream(ss.s_compute):
+            K = torch.stack([synth.draw_k(seed, 0, h, 0, S, device=DEV) for h in range(H)])
+            V = torch.stack([synth.draw_v(seed, 0, h, 0, S, device=DEV) for h in range(H)])
+            Q = torch.zeros(H, G, S, 128, dtype=torch.bfloat16, device=DEV)
+            for p in range(0, S, C):
+                n = min(C, S - p)
+                out = torch.empty(H, G, n, 128, dtype=torch.float32, device=DEV)
+                ss.prefill_group(0, 0, H, Q[:, :, p:p + n].contiguous(), K[:, p:p + n].contiguous(),
+                                 V[:, p:p + n].contiguous(), p, out)
+        ss.sync()
+        st = ss.stats()
+        cache = ss.cache_view()[0].cpu().numpy()
+    assert st.n_prefill_kernels == 0 and st.bytes_d2h == 2 * 80 * H * S
+    for h in range(H):
+        assert np.array_equal(cache[h, 0, :S], kq.pack_rows(*kq.quantize_rows(_f32(K[h]))))
+        assert np.array_equal(cache[h, 1, :S], kq.pack_rows(*kq.quantize_rows(_f32(V[h]))))
