@@ -389,3 +389,65 @@ def test_copies_only_run_still_fills_the_four_bit_cache():
     for h in range(H):
         assert np.array_equal(cache[h, 0, :S], kq.pack_rows(*kq.quantize_rows(_f32(K[h]))))
         assert np.array_equal(cache[h, 1, :S], kq.pack_rows(*kq.quantize_rows(_f32(V[h]))))
+
+
+@pytest.mark.timeout(900)
+def test_4m_context_four_bit_rows_last_chunk_and_decode():
+    """Extreme context with 4-bit rows: 4M tokens, chunk 32768, 8 KV heads (the checked head's planes start 3.7 GiB
+    into the host cache; row offsets beyond 2**31 bytes).  The cache is pre-filled by the library's encoder up to
+    the last chunk, which then runs through the library for one head (13 landed slices), followed by one decode
+    step; sampled rows against the fp64 oracle, whose 4-bit history the oracle encodes itself, slice by slice."""
+    seed, S, C, H, G, h = 20250218, 1 << 22, 32768, 8, 4, 6
+    P0 = S - C
+    rng = np.random.default_rng(11)
+    ss = Session(1, H, G, S + 1, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, link_kv_bits=4)
+    assert ss.plan.host_bytes_total > (5 << 30) and ss.plan.hbm_staging_bytes <= (S + 1) * 512
+    cv = ss.cache_view()
+    step = 1 << 19
+    packed = torch.empty(step, 80, dtype=torch.uint8, device=DEV)
+    for a in range(0, P0, step):
+        b = min(P0, a + step)
+        for which, draw in ((0, synth.draw_k), (1, synth.draw_v)):
+            hb.hi_kv_quantize(torch.cuda.current_stream(), draw(seed, 0, h, a, b - a, device=DEV), b - a, packed)
+            cv[0, h, which, a:b].copy_(packed[:b - a])
+    torch.cuda.synchronize()
+    pos = np.array(sorted({P0, P0 + 1, P0 + 31, P0 + 32, S - 1, S - 2} | set(int(x) for x in rng.integers(P0, S, 8))),
+                   dtype=np.int64)
+    with torch.cuda.stream(ss.s_compute):
+        q = torch.stack([synth.draw_q(seed, 0, h * G + g, P0, C, device=DEV) for g in range(G)])
+        k = synth.draw_k(seed, 0, h, P0, C, device=DEV)
+        v = synth.draw_v(seed, 0, h, P0, C, device=DEV)
+        out = torch.empty(G, C, 128, dtype=torch.float32, device=DEV)
+        ss.prefill_head(0, h, q, k, v, P0, out, (0, h, S))
+        got = out.index_select(1, torch.tensor([int(x - P0) for x in pos], device=DEV))
+        qd = torch.stack([synth.draw_q(seed, 0, h * G + g, S, 1, device=DEV)[0] for g in range(G)])
+        kd = synth.draw_k(seed, 0, h, S, 1, device=DEV)[0]
+        vd = synth.draw_v(seed, 0, h, S, 1, device=DEV)[0]
+        outd = torch.empty(G, 128, dtype=torch.float32, device=DEV)
+        ss.decode_head(0, h, qd, kd, vd, S, outd)
+    ss.sync()
+    st = ss.stats()
+    assert st.peak_staging_bytes <= (S + 1) * 512 and st.bytes_h2d == 160 * (P0 + S)
+
+    # the oracle's history: exact rows regenerated on the CPU, encoded and decoded by the oracle in slices
+    Kx = _cpu_f32(synth.TENSOR_K, seed, h, S + 1)
+    Vx = _cpu_f32(synth.TENSOR_V, seed, h, S + 1)
+    Kq = np.empty((S + 1, 128), dtype=np.float64)
+    Vq = np.empty((S + 1, 128), dtype=np.float64)
+    for a in range(0, S, step):
+        b = min(S, a + step)
+        for X, Xq, which in ((Kx, Kq, 0), (Vx, Vq, 1)):
+            rows = kq.pack_rows(*kq.quantize_rows(X[a:b]))
+            if a == 0 or b == S:                       # first slice of the pre-fill, and the slice the call wrote into
+                assert np.array_equal(cv[0, h, which, a:b].numpy(), rows), (which, a)
+            Xq[a:b] = kq.dequantize_rows(*kq.unpack_rows(rows))
+    Km, Vm = Kq[:S].copy(), Vq[:S].copy()
+    Km[P0:], Vm[P0:] = Kx[P0:S], Vx[P0:S]              # the chunk's own rows are exact
+    for g in range(G):
+        qrows = synth.to_f64(torch.cat([synth.draw_q(seed, 0, h * G + g, int(p), 1) for p in pos]))
+        check(got[g], oa.attn_rows(qrows, Km, Vm, pos), ("4M prefill", g))
+    del Km, Vm
+    Kq[S], Vq[S] = Kx[S], Vx[S]                        # decode: the token's own row is exact
+    ref = oa.attn_rows(synth.to_f64(qd), Kq, Vq, np.full(G, S))
+    check(outd, ref, "4M decode")
+    ss.close()
