@@ -276,9 +276,9 @@ hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, i
  * design, identical in prefill and decode.  A call encodes its new rows on the compute stream, writes the encoded
  * rows back, and expands each slice that comes off the link into the staging ring before the attention kernel
  * reads it; link bytes and host bytes shrink by 3.2x, and the ring shrinks so that ring plus landing areas stay
- * inside the HBM budget.  Inputs must be finite; when a group's minimum is a zero, either sign of zero may be stored
- * for it (the decoded values are equal).  HBM-resident and streaming heads are unaffected.  HI_MODE_RESIDENT rejects it
- * (HI_ERR_UNSUPPORTED): there is no link to save.
+ * inside the HBM budget.  Inputs must be finite with a range (max - min of a group) below 2^127; when a group's
+ * minimum is a zero, either sign of zero may be stored for it (the decoded values are equal).  HBM-resident and
+ * streaming heads are unaffected.  HI_MODE_RESIDENT rejects it (HI_ERR_UNSUPPORTED): there is no link to save.
  *
  * hi_kv_quantize / hi_kv_dequantize: the two conversions alone, for n_rows rows of 128 channels, DEVICE bf16
  * [n_rows][128] <-> DEVICE bytes [n_rows][80]; 16-byte aligned; enqueue on `stream` and return.
