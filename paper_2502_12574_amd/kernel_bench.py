@@ -1,12 +1,13 @@
 #!/usr/bin/env python3
 """Kernel-level micro-benchmark: one HBM-resident prefill unit and one decode unit, HIP-event timed.
 
-    python3 paper_2502_12574_amd/kernel_bench.py [--past P] [--chunk C] [--reps R] [--what prefill|decode|both]
-                                                 [--narrow|--deep|--wide] [--calibrate]
+    python3 paper_2502_12574_amd/kernel_bench.py [--past P] [--chunk C] [--reps R] [--what prefill|decode|both|kvq]
+                                                 [--narrow|--deep|--wide] [--calibrate] [--rows N]
 
 Used for the rocprofv3 counter runs under profiles/ (--calibrate adds a plain 1 GiB device copy whose FETCH_SIZE /
 WRITE_SIZE readings give the scale of those counters).  K/V are resident in HBM, so this isolates K1 / K2+K3 from
-the host link.
+the host link.  --what kvq times the two conversions of the 4-bit link rows alone (hi_kv_quantize / hi_kv_dequantize
+over --rows rows, cycling through buffers larger than the last-level cache) next to a plain device copy.
 """
 from __future__ import annotations
 
@@ -23,18 +24,51 @@ from paper_2502_12574_amd import synth  # noqa: E402
 from paper_2502_12574_amd.session import Session  # noqa: E402
 
 
+def kvq(n, reps, calibrate, dev):
+    s = torch.cuda.current_stream()
+    if calibrate:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        print("calibration: one device copy kernel reading 1 GiB and writing 1 GiB", flush=True)
+        del src, dst
+    n_buf = max(2, (768 << 20) // (n * 336) + 1)
+    rows = [torch.randn(n, 128, device=dev).to(torch.bfloat16) for _ in range(n_buf)]
+    packed = [torch.empty(n, 80, dtype=torch.uint8, device=dev) for _ in range(n_buf)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, what, nbytes):
+        fn(0)
+        e0.record()
+        for _ in range(reps):
+            for i in range(n_buf):
+                fn(i)
+        e1.record()
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * n_buf)
+        print(f"{what} of {n} rows: {us:.1f} us/launch, {nbytes / us / 1e6:.2f} TB/s "
+              f"({nbytes / us / 1e6 / 8 * 100:.0f}% of 8 TB/s)", flush=True)
+
+    timed(lambda i: hb.hi_kv_quantize(s, rows[i], n, packed[i]), "kv_quant_kernel (256 B in, 80 B out per row)", n * 336)
+    timed(lambda i: hb.hi_kv_dequantize(s, packed[i], n, rows[i]), "kv_dequant_kernel (80 B in, 256 B out per row)", n * 336)
+    timed(lambda i: rows[i].copy_(rows[(i + 1) % n_buf]), "device copy (256 B in, 256 B out per row)", n * 512)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--past", type=int, default=1 << 20)
     ap.add_argument("--chunk", type=int, default=16384)
     ap.add_argument("--reps", type=int, default=3)
-    ap.add_argument("--what", default="both", choices=["prefill", "decode", "both"])
+    ap.add_argument("--what", default="both", choices=["prefill", "decode", "both", "kvq"])
+    ap.add_argument("--rows", type=int, default=524288, help="rows per conversion launch (--what kvq)")
     ap.add_argument("--wide", action="store_true", help="use the 64-positions-per-wave prefill kernel")
     ap.add_argument("--narrow", action="store_true", help="force the 4-wave, 2-stage prefill kernel")
     ap.add_argument("--deep", action="store_true", help="force the 8-wave, 4-stage prefill kernel")
     ap.add_argument("--calibrate", action="store_true", help="also run a plain 1 GiB device-to-device copy")
     args = ap.parse_args()
     P, C, G, dev = args.past, args.chunk, 4, "cuda:0"
+    if args.what == "kvq":
+        return kvq(args.rows, args.reps, args.calibrate, dev)
     ss = Session(1, 1, G, P + C, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0)
     flags = hb.HI_FLAG_TIME_KERNELS | (hb.HI_FLAG_PREFILL_WIDE if args.wide else 0)
     flags |= (hb.HI_FLAG_PREFILL_NARROW if args.narrow else 0) | (hb.HI_FLAG_PREFILL_DEEP if args.deep else 0)
