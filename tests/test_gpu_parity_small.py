@@ -149,18 +149,23 @@ def test_prefill_8wave_kernel_steady_state(G, P, C, mode):
         check(out[g:g + 1], ref[g:g + 1], f"8-wave G={G} P={P} C={C} head {g}")
 
 
-@pytest.mark.parametrize("shape", ["rising", "falling", "spikes"])
+@pytest.mark.parametrize("shape", ["rising", "falling", "spikes", "overflow"])
 @pytest.mark.parametrize("variant", ["deep", "narrow"])
 def test_prefill_running_reference_moves(shape, variant):
     # key magnitudes that keep moving the rows' running maxima: rising along the sequence (the steady-state loop of
     # the 8-wave kernel must rescale in place again and again), falling (later probabilities underflow against an
-    # early reference), and isolated rows scaled x8 deep inside the past
+    # early reference), isolated rows scaled x8 deep inside the past, and rows scaled x64
     G, P, C = 4, 4096, 128
     t = torch.arange(P + C, dtype=torch.float32)
     if shape == "rising":
         sc = 1.0 + 5.0 * t / (P + C)
     elif shape == "falling":
         sc = 6.0 - 5.0 * t / (P + C)
+    elif shape == "overflow":
+        # two rows scaled x64 deep inside the steady-state loop: against the reference of the rows before them the
+        # probabilities of such a tile overflow fp32 (2^(c s) with c s in the hundreds) before the reference moves
+        sc = torch.ones(P + C)
+        sc[torch.tensor([1501, 3103])] = 64.0
     else:
         sc = torch.ones(P + C)
         sc[torch.tensor([700, 1501, 2302, 3103, 3904])] = 8.0
