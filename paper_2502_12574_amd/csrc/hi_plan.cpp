@@ -103,10 +103,12 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   // (four slices: measured against eight, the larger copies and fewer launches win 1-3 % of prefill time and up to
   // 14 % of offloaded decode time at a 128K context, and nothing is lost in overlap)
   // (4-bit rows: two slices - a slice is 3.2x fewer link bytes, and the larger copies matter more than the depth of
-  // the ring: measured at a 128K context, decode 4.0 -> 3.5 ms per token and prefill 1 % faster; at 1M, 25.0 -> 24.5 ms)
+  // the ring: measured at a 128K context, decode 4.0 -> 3.5 ms per token and prefill 1 % faster; at 1M, 25.0 -> 24.5 ms,
+  // and 24.2 ms with slices of up to 524288 rows)
   int64_t slice = (budget_tokens / (packed ? 2 : 4)) / 64 * 64;
   if (slice < 64) slice = 64;
-  if (slice > 262144) slice = 262144;
+  const int64_t slice_cap = packed ? 524288 : 262144;     // about 128 MiB (bf16) / 80 MiB (4-bit) of link bytes
+  if (slice > slice_cap) slice = slice_cap;
   if (budget_tokens / slice > 64) slice = round_up(ceil_div(budget_tokens, 64), 64);
   const int64_t n_slices = budget_tokens / slice;
   if (n_slices < 2) {

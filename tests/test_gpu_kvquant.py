@@ -395,7 +395,7 @@ def test_copies_only_run_still_fills_the_four_bit_cache():
 def test_4m_context_four_bit_rows_last_chunk_and_decode():
     """Extreme context with 4-bit rows: 4M tokens, chunk 32768, 8 KV heads (the checked head's planes start 3.7 GiB
     into the host cache; row offsets beyond 2**31 bytes).  The cache is pre-filled by the library's encoder up to
-    the last chunk, which then runs through the library for one head (13 landed slices), followed by one decode
+    the last chunk, which then runs through the library for one head (8 landed slices), followed by one decode
     step; sampled rows against the fp64 oracle, whose 4-bit history the oracle encodes itself, slice by slice."""
     seed, S, C, H, G, h = 20250218, 1 << 22, 32768, 8, 4, 6
     P0 = S - C
