@@ -303,42 +303,46 @@ hi_status adopt_unit(hi_ctx* c, int layer, int head, int nh, int64_t past) {
   return HI_OK;
 }
 
+// 4-bit link rows: encode the new rows of an offloaded unit on the compute stream into one of two buffers, then write
+// the encoded rows back; a buffer is encoded into again only after the write-back that read it has finished
+hi_status write_back_packed(hi_ctx* c, int layer, int head, int nh, const void* k_new, const void* v_new, int64_t past,
+                            int64_t len) {
+  const int b = c->wbq_turn;
+  const int64_t lr = link_row(c);
+  char* qk = c->ws + c->plan.ws_writeback_offset + b * (c->plan.ws_writeback_bytes / 2);
+  char* qv = qk + (int64_t)nh * len * lr;
+  if (2 * (int64_t)nh * len * lr > c->plan.ws_writeback_bytes / 2) { set_last_error("write-back buffer too small"); return HI_ERR_RANGE; }
+  c->wbq_turn ^= 1;
+  if (c->wbq_valid[b]) HI_HIP(hipStreamWaitEvent(c->sc, c->ev_wbq[b], 0));
+  HI_TRY(launch_kv_quant(c->sc, k_new, len * kRowBytes, qk, len * lr, len, nh));
+  HI_TRY(launch_kv_quant(c->sc, v_new, len * kRowBytes, qv, len * lr, len, nh));
+  HI_HIP(hipEventRecord(c->ev_entry, c->sc));
+  HI_HIP(hipStreamWaitEvent(c->sd, c->ev_entry, 0));
+  if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
+    // the heads' K planes (and V planes) are two planes apart in the cache: one strided copy each
+    const size_t dpitch = (size_t)(2 * c->prob.max_context * lr), w = (size_t)(len * lr);
+    HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 0) + past * lr, dpitch, qk, w, w, (size_t)nh,
+                            hipMemcpyDeviceToHost, c->sd));
+    HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 1) + past * lr, dpitch, qv, w, w, (size_t)nh,
+                            hipMemcpyDeviceToHost, c->sd));
+    c->stats.bytes_d2h += 2 * len * lr * nh;
+    c->stats.n_d2h_copies += 2;
+  }
+  HI_HIP(hipEventRecord(c->ev_wbq[b], c->sd));
+  c->wbq_valid[b] = 1;
+  for (int j = 0; j < nh; ++j) {
+    const int idx = layer * c->prob.n_kv_heads + head + j;
+    HI_HIP(hipEventRecord(c->ev_wb[idx], c->sd));
+    c->wb_valid[idx] = 1;
+  }
+  return HI_OK;
+}
+
 // k_new / v_new: [nh][len][128]
 hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, const void* v_new, int64_t past,
                      int64_t len) {
   const bool resident = unit_resident(c, layer, head);
-  if (!resident && link_packed(c)) {
-    // encode the rows on the compute stream into one of two buffers, then write the encoded rows back; a buffer
-    // is encoded into again only after the write-back that read it has finished
-    const int b = c->wbq_turn;
-    c->wbq_turn ^= 1;
-    const int64_t lr = link_row(c);
-    char* qk = c->ws + c->plan.ws_writeback_offset + b * (c->plan.ws_writeback_bytes / 2);
-    char* qv = qk + (int64_t)nh * len * lr;
-    if (2 * (int64_t)nh * len * lr > c->plan.ws_writeback_bytes / 2) { set_last_error("write-back buffer too small"); return HI_ERR_RANGE; }
-    if (c->wbq_valid[b]) HI_HIP(hipStreamWaitEvent(c->sc, c->ev_wbq[b], 0));
-    HI_TRY(launch_kv_quant(c->sc, k_new, len * kRowBytes, qk, len * lr, len, nh));
-    HI_TRY(launch_kv_quant(c->sc, v_new, len * kRowBytes, qv, len * lr, len, nh));
-    HI_HIP(hipEventRecord(c->ev_entry, c->sc));
-    HI_HIP(hipStreamWaitEvent(c->sd, c->ev_entry, 0));
-    if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
-      const size_t dpitch = (size_t)(2 * c->prob.max_context * lr), w = (size_t)(len * lr);
-      HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 0) + past * lr, dpitch, qk, w, w, (size_t)nh,
-                              hipMemcpyDeviceToHost, c->sd));
-      HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 1) + past * lr, dpitch, qv, w, w, (size_t)nh,
-                              hipMemcpyDeviceToHost, c->sd));
-      c->stats.bytes_d2h += 2 * len * lr * nh;
-      c->stats.n_d2h_copies += 2;
-    }
-    HI_HIP(hipEventRecord(c->ev_wbq[b], c->sd));
-    c->wbq_valid[b] = 1;
-    for (int j = 0; j < nh; ++j) {
-      const int idx = layer * c->prob.n_kv_heads + head + j;
-      HI_HIP(hipEventRecord(c->ev_wb[idx], c->sd));
-      c->wb_valid[idx] = 1;
-    }
-    return HI_OK;
-  }
+  if (!resident && link_packed(c)) return write_back_packed(c, layer, head, nh, k_new, v_new, past, len);
   if (!resident) {
     // the new rows were produced by earlier work on the compute stream
     HI_HIP(hipEventRecord(c->ev_entry, c->sc));
