@@ -370,7 +370,10 @@ __device__ __forceinline__ void pd_preread(uint32_t v_off, const PfLaneConst& lc
 
 // PREREAD: the caller has already read the first kPfAhead operands into pre (during its softmax phase).
 // CINIT: the score accumulators start from cinit (minus the row's running reference) instead of zero.
-template <bool LOADS_ALWAYS, bool PREREAD, bool CINIT>
+// EARLY_BARRIER: the workgroup barrier that ends the phase is passed before the last MFMA is issued instead of after
+// it (every LDS operand of the phase is in registers by then), so the barrier's latency and the other group's first
+// issue hide under that MFMA; the caller then omits its own barrier.
+template <bool LOADS_ALWAYS, bool PREREAD, bool CINIT, bool EARLY_BARRIER = false>
 __device__ __forceinline__ void pd_matrix_phase(uint32_t v_off, uint32_t k_off, const PfLaneConst& lc,
                                                 const bf16x8 (&qf)[8], const bf16x8 (&pb)[2][2], PfState& st,
                                                 f32x16 (&s)[2], const PfPhaseLoads& ld,
@@ -387,7 +390,12 @@ __device__ __forceinline__ void pd_matrix_phase(uint32_t v_off, uint32_t k_off, 
 #pragma unroll
   for (int i = 0; i < 32; ++i) {
     if (i + kPfAhead < 32) op[(i + kPfAhead) % (kPfAhead + 1)] = pd_operand(i + kPfAhead, v_off, k_off, lc);
-    const bf16x8 x = op[i % (kPfAhead + 1)];
+    bf16x8 x = op[i % (kPfAhead + 1)];
+    if (EARLY_BARRIER && i == 31) {
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x) : : "memory");
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (i < 16) {
       const int sb = pd_sb(i), u = pd_u(i), db = pd_db(i);
       st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, pb[sb][u], st.o[db], 0, 0, 0);
@@ -792,10 +800,9 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     ld.ldk = ld_wave + ((S + 3) & 3) * kPfTileBytes;
     ld.ldv = ld_wave + kPdVRing + ((S + 2) & 3) * kPfTileBytes;
     __builtin_amdgcn_s_setprio(2);
-    pd_matrix_phase<true, true, true>(((S + 3) & 3) * kPfTileBytes, S * kPfTileBytes, lc, qf, pb, st, sc, ld, pre,
-                                      negm);
+    pd_matrix_phase<true, true, true, true>(((S + 3) & 3) * kPfTileBytes, S * kPfTileBytes, lc, qf, pb, st, sc, ld,
+                                            pre, negm);       // passes the phase's barrier itself
     __builtin_amdgcn_s_setprio(0);
-    phase_barrier();
     pd_preread(S * kPfTileBytes, lc, pre);     // V(t), for the next matrix phase
     __builtin_amdgcn_sched_barrier(0);
     pf_softmax_fast(sc, st, c, negm, pb);
