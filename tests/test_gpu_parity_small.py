@@ -325,3 +325,10 @@ def test_resume_from_a_saved_host_cache():
     check(torch.cat(outs, dim=1), ref[:, :S], "prefill across the restart")
     check(torch.stack(dec, dim=1), ref[:, S:], "decode after the restart")
     assert torch.equal(cache[0, :n_tok], K.cpu()) and torch.equal(cache[1, :n_tok], V.cpu())
+
+
+def test_8wave_kernel_repeats_bit_for_bit():
+    # the same unit three times: the schedule of the 8-wave kernel (two groups of waves passing LDS tiles and
+    # barriers to each other) must not let timing into the result
+    outs = [one_unit(4, 8000, 192, seed=4242, flags=hb.HI_FLAG_PREFILL_DEEP)[0] for _ in range(3)]
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
