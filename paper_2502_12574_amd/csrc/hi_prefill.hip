@@ -258,7 +258,7 @@ __device__ __forceinline__ void pf_softmax_fast(f32x16 (&s)[2], PfState& st, flo
   // p and the lane's share of the row sum first; the sum bounds every p of the lane, so the row maximum is only
   // needed on the rare tile whose sum says the reference has to move
   auto probs = [&]() __attribute__((always_inline)) {
-    float lq[4] = {0.f, 0.f, 0.f, 0.f};     // four short accumulation chains
+    float lq[4];                            // four short accumulation chains, each started by its first term
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
@@ -266,7 +266,7 @@ __device__ __forceinline__ void pf_softmax_fast(f32x16 (&s)[2], PfState& st, flo
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const float p = fast_exp2(s[sb][8 * u + j] * c);
-          lq[2 * sb + u] += p;
+          lq[2 * sb + u] = j == 0 ? p : lq[2 * sb + u] + p;
           pb[sb][u][j] = (__bf16)p;
         }
     return (lq[0] + lq[1]) + (lq[2] + lq[3]);
