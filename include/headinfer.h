@@ -155,7 +155,9 @@ hi_status hi_offload_plan(const hi_problem* problem, hi_plan* plan);
  *   hbm_workspace  DEVICE, plan.workspace_bytes.
  *   stream_*       hipStream_t handles (as void*), all at default priority.  Kernels run on stream_compute,
  *                  host-to-device prefetches on stream_h2d, write-backs on stream_d2h.
- * Errors: HI_ERR_ARG, HI_ERR_NOT_PINNED, HI_ERR_HIP.
+ * With hi_problem.link_kv_bits = 4 the cache layout is [layer][kv_head][K|V][S_max][plan.link_row_bytes] bytes.
+ * A context is used by one host thread at a time (its calls mutate the ring's bookkeeping without locks); different
+ * contexts are independent.  Errors: HI_ERR_ARG, HI_ERR_NOT_PINNED, HI_ERR_UNSUPPORTED, HI_ERR_HIP.
  */
 hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* plan, int32_t mode, void* kv_cache,
                         void* hbm_staging, void* hbm_workspace, void* stream_compute, void* stream_h2d,
