@@ -2,7 +2,7 @@
 """Kernel-level micro-benchmark: one HBM-resident prefill unit and one decode unit, HIP-event timed.
 
     python3 paper_2502_12574_amd/kernel_bench.py [--past P] [--chunk C] [--reps R] [--what prefill|decode|both|kvq]
-                                                 [--narrow|--deep|--wide] [--calibrate] [--rows N]
+                                                 [--narrow|--deep|--wide] [--calibrate] [--rows N] [--gqa G]
 
 Used for the rocprofv3 counter runs under profiles/ (--calibrate adds a plain 1 GiB device copy whose FETCH_SIZE /
 WRITE_SIZE readings give the scale of those counters).  K/V are resident in HBM, so this isolates K1 / K2+K3 from
@@ -61,12 +61,13 @@ def main():
     ap.add_argument("--reps", type=int, default=3)
     ap.add_argument("--what", default="both", choices=["prefill", "decode", "both", "kvq"])
     ap.add_argument("--rows", type=int, default=524288, help="rows per conversion launch (--what kvq)")
+    ap.add_argument("--gqa", type=int, default=4, choices=[1, 2, 4, 8], help="query heads per KV head")
     ap.add_argument("--wide", action="store_true", help="use the 64-positions-per-wave prefill kernel")
     ap.add_argument("--narrow", action="store_true", help="force the 4-wave, 2-stage prefill kernel")
     ap.add_argument("--deep", action="store_true", help="force the 8-wave, 4-stage prefill kernel")
     ap.add_argument("--calibrate", action="store_true", help="also run a plain 1 GiB device-to-device copy")
     args = ap.parse_args()
-    P, C, G, dev = args.past, args.chunk, 4, "cuda:0"
+    P, C, G, dev = args.past, args.chunk, args.gqa, "cuda:0"
     if args.what == "kvq":
         return kvq(args.rows, args.reps, args.calibrate, dev)
     ss = Session(1, 1, G, P + C, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0)
