@@ -238,9 +238,9 @@ def main():
     if not args.no_extra_legs:
         # the rows built after the hot path met its bar: streaming heads (Appendix E: 4 of the 8 heads keep sink +
         # recent tokens in HBM) on the same layer, and the projections either side of the attention calls
-        from paper_2502_12574_amd import proj_bench, sparsity_bench
+        from paper_2502_12574_amd import layer_bench, proj_bench
         torch.cuda.empty_cache()
-        sp = sparsity_bench.run(S, C, HKV // 2, 128, 512, 8, HKV // 2)
+        sp = layer_bench.run(S, C, HKV // 2, 128, 512, 8, HKV // 2)
         sp["prefill_speedup_vs_all_retrieval"] = prefill_s / sp["prefill_s"]
         if nd:
             sp["decode_speedup_vs_all_retrieval"] = decode_ms_tok / sp["decode_ms_per_token"]
@@ -249,7 +249,7 @@ def main():
         # the same layer with 4-bit rows on the host link (every head offloaded): the link-bound decode should follow
         # the bytes per row, the prefill should not change
         torch.cuda.empty_cache()
-        lk = sparsity_bench.run(S, C, 0, 0, 0, 8, 1, link_kv_bits=4)
+        lk = layer_bench.run(S, C, 0, 0, 0, 8, 1, link_kv_bits=4)
         lk["prefill_speedup_vs_bf16_rows"] = prefill_s / lk["prefill_s"]
         if nd:
             lk["decode_speedup_vs_bf16_rows"] = decode_ms_tok / lk["decode_ms_per_token"]

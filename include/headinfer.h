@@ -39,10 +39,9 @@ enum { HI_REGIME_COMPUTE = 0, HI_REGIME_LINK = 1, HI_REGIME_HBM = 2 };
  * time the attention kernels with HIP events; force a prefill kernel variant (by default the library picks by
  * chunk length and group size between DEEP: 8 wavefronts per workgroup alternating matrix and softmax phases,
  * split over the K/V rows when the chunk alone would not fill the chip, and NARROW: 4 wavefronts, for very short
- * chunks; WIDE: 64 query positions per wavefront, one head per call only). Do not change the variant between
- * the calls of one (chunk, head) unit. */
+ * chunks). Do not change the variant between the calls of one (chunk, head) unit. */
 enum { HI_FLAG_SKIP_KERNELS = 1, HI_FLAG_SKIP_COPIES = 2, HI_FLAG_TIME_KERNELS = 4, HI_FLAG_PREFILL_NARROW = 8,
-       HI_FLAG_PREFILL_WIDE = 16, HI_FLAG_PREFILL_DEEP = 32 };
+       HI_FLAG_PREFILL_DEEP = 32 };
 
 /* The paper's statement of the problem (Algorithm 1 "Require": L layers, H heads, sequence length S). */
 typedef struct hi_problem {
@@ -213,7 +212,7 @@ hi_status hi_decode_head(hi_ctx* ctx, int32_t layer, int32_t kv_head, const void
  * out_dev DEVICE [n_heads][G][len][D_h]  (len = chunk_len, or 1 with that axis dropped for decode).
  * The hint names the next group (first head and size).  hi_prefill_head / hi_decode_head are the n_heads = 1
  * case; results are identical whatever the grouping.  Extra errors: HI_ERR_HBM_BUDGET when a slice cannot hold
- * 64 rows of every head of the group, HI_ERR_UNSUPPORTED with HI_FLAG_PREFILL_WIDE.
+ * 64 rows of every head of the group.
  */
 hi_status hi_prefill_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n_heads, const void* q_dev,
                            const void* k_new_dev, const void* v_new_dev, int64_t past_len, int32_t chunk_len,

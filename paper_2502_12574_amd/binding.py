@@ -16,7 +16,7 @@ HI_ERR_HOST_MEM, HI_ERR_RANGE, HI_ERR_NOT_PINNED, HI_ERR_HIP = -4, -5, -6, -7
 HI_MODE_OFFLOAD, HI_MODE_RESIDENT = 0, 1
 HI_REGIME_COMPUTE, HI_REGIME_LINK, HI_REGIME_HBM = 0, 1, 2
 HI_FLAG_SKIP_KERNELS, HI_FLAG_SKIP_COPIES, HI_FLAG_TIME_KERNELS = 1, 2, 4
-HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_WIDE, HI_FLAG_PREFILL_DEEP = 8, 16, 32
+HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_DEEP = 8, 32
 
 EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
            "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_proj_workspace_bytes",

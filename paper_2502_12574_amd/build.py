@@ -10,7 +10,6 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libheadinfer.so")
-PROBE = os.path.join(HERE, "mfma_ceiling")
 SOURCES = ["hi_plan.cpp", "hi_ctx.hip", "hi_decode.hip", "hi_prefill.hip", "hi_proj.hip", "hi_kvq.hip"]
 
 HIPCC_FLAGS = [
@@ -54,13 +53,6 @@ def build(verbose: bool = False) -> str:
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
     os.replace(tmp, LIB)
-    # measurement aid (a stand-alone program, see its header): the matrix pipes' sustained rate under the power cap
-    cmd = [hipcc(), *[f for f in HIPCC_FLAGS if f != "-fPIC"], "-x", "hip", os.path.join(CSRC, "mfma_ceiling.hip"),
-           "-o", PROBE + ".tmp"]
-    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("mfma_ceiling build failed:\n" + r.stdout)
-    os.replace(PROBE + ".tmp", PROBE)
     return LIB
 
 

@@ -252,8 +252,7 @@ hi_status pace_end(hi_ctx* c) {
 }
 
 int pf_variant(const hi_ctx* c) {
-  return (c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_WIDE) ? 2 :
-         (c->flags & HI_FLAG_PREFILL_DEEP) ? 3 : 0;
+  return (c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_DEEP) ? 3 : 0;
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -280,7 +279,6 @@ hi_status check_unit_args(const hi_ctx* c, int layer, int head, int nh, const vo
     set_last_error("a staging slice of %lld rows cannot hold 64 rows of each head of the group", (long long)c->slice_tokens);
     return HI_ERR_HBM_BUDGET;
   }
-  if (nh > 1 && (c->flags & HI_FLAG_PREFILL_WIDE)) { set_last_error("the 64-positions-per-wave kernel takes one head per launch"); return HI_ERR_UNSUPPORTED; }
   if (past < 0 || len < 1) { set_last_error("negative past_len or empty call"); return HI_ERR_ARG; }
   if (len > c->prob.chunk || past + len > c->prob.max_context) { set_last_error("past_len %lld + len %lld exceeds the plan", (long long)past, (long long)len); return HI_ERR_RANGE; }
   if (next_layer >= 0 && next_past > c->prob.max_context) { set_last_error("prefetch hint beyond max_context"); return HI_ERR_RANGE; }
@@ -479,7 +477,7 @@ extern "C" hi_status hi_ctx_destroy(hi_ctx* c) {
 
 extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
   if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS | HI_FLAG_PREFILL_NARROW |
-                      HI_FLAG_PREFILL_WIDE | HI_FLAG_PREFILL_DEEP))) { set_last_error("bad flags"); return HI_ERR_ARG; }
+                      HI_FLAG_PREFILL_DEEP))) { set_last_error("bad flags"); return HI_ERR_ARG; }
   c->flags = flags;
   return HI_OK;
 }

@@ -7,6 +7,7 @@
 // wavefront, nothing staged in VGPRs, no workgroup barriers in the loop).  The G <= 16 query heads ride along
 // as the 16 columns of small MFMA tiles (S^T = K Q^T, O^T += V^T P^T), which keeps the vector ALU nearly idle;
 // the matrix unit runs at a few percent of its rate and is not the bound.
+#include <mutex>
 #include "hi_device.h"
 #include "hi_internal.h"
 
@@ -279,13 +280,13 @@ hi_status launch_decode_partial(void* stream, const void* q, int G, const void* 
                                 int n_split, void* partials, int part0, int n_heads, int64_t kv_head_stride,
                                 int64_t part_head_stride, int64_t skip_row) {
   if (n <= 0 || n_split <= 0 || n_heads < 1) { set_last_error("decode partial: empty launch"); return HI_ERR_ARG; }
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)decode_partial_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kDecLdsBytes);
-    if (e != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
-    attr_set = true;
-  }
+  static std::once_flag attr_once;      // contexts on different host threads may get here together
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(attr_once, [] {
+    attr_err = hipFuncSetAttribute((const void*)decode_partial_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kDecLdsBytes);
+  });
+  if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
   hipLaunchKernelGGL(decode_partial_kernel, dim3(n_split, n_heads), dim3(256), kDecLdsBytes, (hipStream_t)stream,
                      (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e,
                      kv_head_stride, part_head_stride, skip_row);

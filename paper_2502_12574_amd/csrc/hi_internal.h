@@ -66,8 +66,7 @@ struct PrefillSegment {
 // One launch of the prefill kernel over up to two KV segments.  first: start from an empty softmax state
 // instead of loading the carry; last: normalise and write `out` instead of storing the carry.
 // variant: 0 = pick by chunk length (the 8-wave kernel, split over the rows if need be, when that fills the chip,
-// else the 4-wave one), 1 = 4-wave kernel (2 LDS stages), 2 = wide kernel (64 positions per wave), 3 = 8-wave
-// kernel; every launch of one unit must use the same variant (the carry layouts differ).
+// else the 4-wave one), 1 = 4-wave kernel (2 LDS stages), 3 = 8-wave kernel; every launch of one unit must use the same variant (the carry layouts differ).
 // carry_bytes: size of the carry buffer (checked against what the launch will use; -1: not checked).
 // n_heads > 1: one launch over a group of KV heads; q is [n_heads][G][chunk_len][128], out likewise, the causal
 // segment's rows [n_heads][chunk_len][128], the other segment's heads head_stride bytes apart.

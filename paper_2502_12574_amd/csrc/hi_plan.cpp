@@ -118,7 +118,7 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   pl.slice_tokens = slice;
   pl.n_slices_ring = (int32_t)n_slices;
 
-  // Section 4, adaptive head grouping, as measured on MI355X with this library (group_bench): up to 16K tokens the
+  // Section 4, adaptive head grouping, as measured on MI355X with this library (layer_bench --heads-per-call): up to 16K tokens the
   // per-call overheads dominate and as many heads as the slice can hold (64 rows each) go into one call; up to 256K
   // two heads per call still gain a few per cent; beyond, one head per call (the finest granularity) is as fast.
   {

@@ -16,13 +16,13 @@
 //   * Workgroups of a unit sweep the K/V rows in near lock-step, so each tile is pulled from HBM about once per
 //     XCD and served to the other compute units from that XCD's L2.
 //
-// Three kernels share this arithmetic: prefill_kernel (4 waves, 2 LDS stages, two workgroups per compute unit, one
-// barrier per tile: short chunks), prefill_kernel_deep (8 waves, one workgroup per compute unit, the two waves of
-// a SIMD alternating between a matrix phase and a softmax phase: long chunks, the fast one) and
-// prefill_kernel_wide (64 positions per wave; on request only).
+// Two kernels share this arithmetic: prefill_kernel (4 waves, 2 LDS stages, two workgroups per compute unit, one
+// barrier per tile: short chunks) and prefill_kernel_deep (8 waves, one workgroup per compute unit, the two waves of
+// a SIMD alternating between a matrix phase and a softmax phase: long chunks, the fast one).
 //
 // The softmax state (m, l, O) can be carried across launches (one launch per staging slice) in a register-image
 // workspace, which is how a unit is computed while later slices of its past are still on the host link.
+#include <mutex>
 #include <type_traits>
 #include "hi_device.h"
 #include "hi_internal.h"
@@ -903,257 +903,6 @@ __global__ __launch_bounds__(512) void prefill_merge_kernel(PrefillArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Wide variant: 64 query positions per wavefront (two 32-column blocks), one workgroup per compute unit, four
-// LDS stages (tiles t+1 .. t+3 in flight while tile t is consumed).  Every K operand and every V^T operand read
-// from LDS feeds two MFMAs, which halves the LDS traffic per flop; O (128 registers per lane) lives in
-// accumulation registers.  Measured on MI355X it ties with the narrow kernel at 1M-token pasts and loses at
-// short pasts (half as many workgroups to balance the causal triangle), so the launcher only uses it when asked
-// (HI_FLAG_PREFILL_WIDE); it is kept, tested, as the base for a hand-scheduled version.
-constexpr int kPwStages = 4;
-constexpr int kPwLdsBytes = kPwStages * kPfStageBytes;   // 128 KiB
-
-
-__global__ __launch_bounds__(256, 1) void prefill_kernel_wide(PrefillArgs a) {
-  extern __shared__ __attribute__((aligned(1024))) char lds_dyn[];
-  lds_char* lds = (lds_char*)lds_dyn;
-  const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
-  const int lane = lane_id();
-  const int wave = wave_id();
-  const int hl = lane >> 5;
-  const int col = lane & 31;
-
-  const int gl = a.G < 4 ? a.G : 4;
-  const int strip = 64 * (4 / gl);
-  const int bx = gridDim.x - 1 - blockIdx.x;
-  const int g = pf_select_head(a) * 4 + (wave % gl);
-  const int i0 = bx * strip + 64 * (wave / gl);     // first query position of this wave
-  const int i_hi = bx * strip + strip - 1;
-  int my_i[2];
-  my_i[0] = i0 + col;
-  my_i[1] = i0 + 32 + col;
-
-  PfLaneConst lc;
-  {
-    const int r_in = lane >> 4, cpos = lane & 15;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = (wave * 4 + i) * 4 + r_in;
-      lc.gk[i] = (uint32_t)(r * kRowBytes + ((cpos ^ swz_k(r)) << 4));
-    }
-    const int r0 = wave * 16 + r_in;
-    lc.gv = (uint32_t)(r0 * kRowBytes + ((cpos ^ swz_v(r0)) << 4));
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) lc.koff[kk] = (uint32_t)(col * kRowBytes + (((2 * kk + hl) ^ swz_k(col)) << 4));
-    const int s16 = lane & 15, q16 = col >> 4;
-    const int row_lo = 4 * hl + (s16 >> 2);
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-      const int chunk = 4 * db + 2 * q16 + ((s16 & 3) >> 1);
-      lc.voff[db] = (uint32_t)(row_lo * kRowBytes + ((chunk ^ swz_v(row_lo)) << 4) + ((s16 & 1) << 3));
-    }
-  }
-
-  bf16x8 qf[2][8];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-    int qi = my_i[rb] < a.C ? my_i[rb] : a.C - 1;
-    const uint16_t* qrow = a.q + ((int64_t)g * a.C + qi) * kHeadDim + 8 * hl;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) qf[rb][kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 16 * kk));
-  }
-
-  f32x16 o[2][4];
-  float m[2], l[2];
-  const int64_t wg_linear = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-  float* carry = a.carry + wg_linear * (2 * kCarryFloatsPerLane * kWgThreads) + threadIdx.x;
-  if (a.first) {
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      m[rb] = kNegBig;
-      l[rb] = 0.f;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[rb][db][r] = 0.f;
-    }
-  } else {
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[rb][db][r] = carry[((rb * 4 + db) * 16 + r) * kWgThreads];
-      m[rb] = carry[(128 + rb) * kWgThreads];
-      l[rb] = carry[(130 + rb) * kWgThreads];
-    }
-  }
-  // Q is only ever an MFMA operand: park it in accumulation registers so the vector registers are left to
-  // the scores, probabilities and K/V operands
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) asm volatile("" : "+a"(qf[rb][kk]));
-    asm volatile("" : "+v"(m[rb]), "+v"(l[rb]));
-#pragma unroll
-    for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(o[rb][db]));
-  }
-
-  const int ta = (int)((a.na + kPfTileRows - 1) / kPfTileRows);
-  const int64_t nb_vis = a.nb < (int64_t)i_hi + 1 ? a.nb : (int64_t)i_hi + 1;
-  const int tb = (int)((nb_vis + kPfTileRows - 1) / kPfTileRows);
-  const int T = ta + tb;
-
-  auto issue = [&](int t) {
-    const uint32_t stage = lds_base + (uint32_t)(t & (kPwStages - 1)) * kPfStageBytes;
-    if (t < ta) {
-      const int64_t row0 = (int64_t)t * kPfTileRows;
-      const int64_t left = a.na - row0;
-      pf_issue_tile<4>(a.ka + row0 * kRowBytes, a.va + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
-                       stage, wave, lane, lc);
-    } else {
-      const int64_t row0 = (int64_t)(t - ta) * kPfTileRows;
-      const int64_t left = a.nb - row0;
-      pf_issue_tile<4>(a.kb + row0 * kRowBytes, a.vb + row0 * kRowBytes, left < kPfTileRows ? (int)left : kPfTileRows,
-                       stage, wave, lane, lc);
-    }
-  };
-
-  const float c = a.c;
-  // One 64-row tile, straight through: S^T = K Q^T for both column blocks, softmax, O^T += V^T P^T.
-  auto tile = [&](int t) {
-    lds_char* kt = lds + (t & (kPwStages - 1)) * kPfStageBytes;
-    lds_char* vt = kt + kPfTileBytes;
-    f32x16 s[2][2];   // [column block][32-row sub-block]
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { s[0][sb][r] = 0.f; s[1][sb][r] = 0.f; }
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8 kf = *(lds_bf16x8*)(kt + lc.koff[kk] + sb * 8192);
-        s[0][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0][kk], s[0][sb], 0, 0, 0);
-        s[1][sb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[1][kk], s[1][sb], 0, 0, 0);
-      }
-    }
-    const bool in_b = t >= ta;
-    const int64_t j0 = (int64_t)(in_b ? (t - ta) : t) * kPfTileRows;
-    const int64_t n_seg = in_b ? a.nb : a.na;
-    const bool masked = (j0 + kPfTileRows > n_seg) || (in_b && (j0 + kPfTileRows - 1 > i0));
-    if (masked) {
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        int64_t lim = n_seg - 1;
-        if (in_b && (int64_t)my_i[rb] < lim) lim = my_i[rb];
-        const int64_t d = lim - j0;
-        const int rel = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
-#pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int row = 32 * sb + 8 * (r >> 2) + 4 * hl + (r & 3);
-            if (row > rel) s[rb][sb][r] = kNegBig;
-          }
-      }
-    }
-    float m_new[2];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      float mx = s[rb][0][0];
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[rb][sb][r]);
-      m_new[rb] = fmaxf(m[rb], max_halves(mx));
-    }
-    if (__builtin_amdgcn_ballot_w64(m_new[0] > m[0] || m_new[1] > m[1]) != 0) {
-      // Rare once the running maxima have settled.  The accumulators live in accumulation registers, which the
-      // vector ALU cannot address, so each element takes the round trip read - multiply - write here, in
-      // assembly the compiler cannot see through: it then never sees vector-ALU code touching O, and O never
-      // leaves the accumulation registers in the hot loop.  The padding covers the MFMA result latency, which
-      // the hardware does not interlock for these moves.
-      asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        const float alpha = fast_exp2((m[rb] - m_new[rb]) * c);
-        l[rb] *= alpha;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float acc = o[rb][db][r];
-            float tmp;
-            asm volatile("v_accvgpr_read_b32 %1, %0\n\tv_mul_f32 %1, %1, %2\n\tv_accvgpr_write_b32 %0, %1"
-                         : "+a"(acc), "=&v"(tmp)
-                         : "v"(alpha));
-            o[rb][db][r] = acc;
-          }
-        m[rb] = m_new[rb];
-      }
-      asm volatile("s_nop 7" ::: "memory");
-    }
-    bf16x8 pb[2][2][2];
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      const float mc = m[rb] * c;
-      float lsum = 0.f;
-#pragma unroll
-      for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const float p = fast_exp2(__builtin_fmaf(s[rb][sb][8 * u + j], c, -mc));
-            lsum += p;
-            pb[rb][sb][u][j] = (__bf16)p;
-          }
-      l[rb] += lsum;
-    }
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
-#pragma unroll
-      for (int u = 0; u < 2; ++u)
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const bf16x4 v0 = lds_read_tr8(vt + lc.voff[db] + sb * 8192 + u * 4096);
-          const bf16x4 v1 = lds_read_tr8(vt + lc.voff[db] + sb * 8192 + u * 4096 + 2048);
-          const bf16x8 vf = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-          o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[0][sb][u], o[0][db], 0, 0, 0);
-          o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb[1][sb][u], o[1][db], 0, 0, 0);
-        }
-  };
-
-  if (T > 0) {
-    issue(0);
-    if (T > 1) issue(1);
-    if (T > 2) issue(2);
-  }
-  for (int t = 0; t < T; ++t) {
-    if (t + 2 < T) wait_vmcnt<16>();      // tile t has landed; tiles t+1, t+2 may be in flight
-    else if (t + 1 < T) wait_vmcnt<8>();
-    else wait_vmcnt<0>();
-    __syncthreads();
-    if (t + 3 < T) issue(t + 3);
-    tile(t);
-  }
-
-  if (!a.last) {
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) carry[((rb * 4 + db) * 16 + r) * kWgThreads] = o[rb][db][r];
-      carry[(128 + rb) * kWgThreads] = m[rb];
-      carry[(130 + rb) * kWgThreads] = l[rb];
-    }
-    return;
-  }
-
-  pf_write_row(a.out, a.out_fp32, a.C, g, my_i[0], hl, o[0], l[0]);
-  pf_write_row(a.out, a.out_fp32, a.C, g, my_i[1], hl, o[1], l[1]);
-}
-
-// ---------------------------------------------------------------------------------------------------------
 // Streaming heads (Appendix E, head-wise sparsity: a streaming head keeps only recent tokens - here n_sink initial
 // tokens and the n_recent most recent ones - and lives in HBM).  Query row at absolute position p sees key j iff
 // j <= p and (j < n_sink or p - j < n_recent).  The head's K/V is a bounded store of n_sink + n_recent rows: sink
@@ -1394,7 +1143,7 @@ static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   //
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& sa,
                          const PrefillSegment& sb, int first, int last, void* carry, void* out, int out_fp32,
                          int variant, int n_heads, int64_t carry_bytes) {
-  if (n_heads < 1 || (n_heads > 1 && variant == 2)) { set_last_error("prefill launch: head group"); return HI_ERR_UNSUPPORTED; }
+  if (n_heads < 1 || variant == 2) { set_last_error("prefill launch: head group or variant"); return HI_ERR_UNSUPPORTED; }
   if (chunk_len < 1 || !(G == 1 || G == 2 || G == 4 || G == 8)) { set_last_error("prefill launch: bad shape"); return HI_ERR_ARG; }
   if (sa.causal || (sb.n > 0 && !sb.causal)) { set_last_error("prefill launch: segment order"); return HI_ERR_ARG; }
   if (sa.n + sb.n <= 0) { set_last_error("prefill launch: no rows"); return HI_ERR_ARG; }
@@ -1410,7 +1159,6 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   const int gy = prefill_grid_y(G);
   a.gy = gy;
   a.a_head_stride = sa.head_stride;
-  const bool wide = variant == 2;
   int split = prefill_split(G, chunk_len, n_heads);
   // A unit that is mostly its own causal triangle (single launch, past shorter than the chunk): the workgroups'
   // tile sequences differ by up to the whole triangle; cutting each in two evens the load out over the chip.
@@ -1420,38 +1168,29 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   const bool deep = variant == 3 || (variant == 0 && deep_wgs * split >= kPrefillDeepMinWorkgroups);
   a.split = 1;
   {  // the carry must hold one state image per workgroup of the launch
-    const int64_t wgs = wide ? ceil_div(chunk_len, 2 * strip) * gy
-                             : deep ? deep_wgs * split : ceil_div(chunk_len, strip) * gy * n_heads;
+    const int64_t wgs = deep ? deep_wgs * split : ceil_div(chunk_len, strip) * gy * n_heads;
     const int64_t lanes = deep ? kPdWaves * 64 : kWgThreads;
-    const int64_t need = wgs * lanes * (wide ? 2 : 1) * kCarryFloatsPerLane * 4;
+    const int64_t need = wgs * lanes * kCarryFloatsPerLane * 4;
     if (carry_bytes >= 0 && need > carry_bytes) {
       set_last_error("prefill launch: carry of %lld bytes needed, %lld provided", (long long)need, (long long)carry_bytes);
       return HI_ERR_ARG;
     }
   }
-  if (wide || deep) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t ea = hipFuncSetAttribute((const void*)prefill_kernel_wide, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                          kPwLdsBytes);
-      if (ea == hipSuccess)
-        ea = hipFuncSetAttribute((const void*)prefill_kernel_deep, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 kPdLdsBytes);
-      if (ea != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(ea)); return HI_ERR_HIP; }
-      attr_set = true;
-    }
-    if (wide) {
-      dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)gy);
-      hipLaunchKernelGGL(prefill_kernel_wide, grid, dim3(kWgThreads), kPwLdsBytes, (hipStream_t)stream, a);
-    } else {
-      a.split = split;
-      dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)(gy * n_heads), (unsigned)split);
-      hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
-      if (split > 1 && last) {
-        hipError_t e1 = hipGetLastError();
-        if (e1 != hipSuccess) { set_last_error("prefill launch: %s", hipGetErrorString(e1)); return HI_ERR_HIP; }
-        hipLaunchKernelGGL(prefill_merge_kernel, dim3(grid.x, grid.y), dim3(kPdWaves * 64), 0, (hipStream_t)stream, a);
-      }
+  if (deep) {
+    static std::once_flag attr_once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [] {
+      attr_err = hipFuncSetAttribute((const void*)prefill_kernel_deep, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     kPdLdsBytes);
+    });
+    if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
+    a.split = split;
+    dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)(gy * n_heads), (unsigned)split);
+    hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
+    if (split > 1 && last) {
+      hipError_t e1 = hipGetLastError();
+      if (e1 != hipSuccess) { set_last_error("prefill launch: %s", hipGetErrorString(e1)); return HI_ERR_HIP; }
+      hipLaunchKernelGGL(prefill_merge_kernel, dim3(grid.x, grid.y), dim3(kPdWaves * 64), 0, (hipStream_t)stream, a);
     }
   } else {
     dim3 grid((unsigned)ceil_div(chunk_len, strip), (unsigned)(gy * n_heads));

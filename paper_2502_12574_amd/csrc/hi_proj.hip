@@ -22,6 +22,7 @@
 //     the two half-waves.
 // Measured (Llama-3-8B shapes, chunk 16384): 1.05 PFLOP/s for the Q/K/V projection (1.27 without the rotation),
 // 1.25 PFLOP/s for the output projection; on constant operands, where the clock is not power-managed, 1.36 / 1.63.
+#include <mutex>
 #include <type_traits>
 #include "hi_device.h"
 #include "hi_internal.h"
@@ -438,14 +439,14 @@ static hi_status gemv_launch(void* stream, const GemvArgs& g) {
 }
 
 static hi_status pj_launch(void* stream, ProjArgs& p, int mode) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)proj_gemm_kernel<kPjQkv>, hipFuncAttributeMaxDynamicSharedMemorySize, kPjLdsBytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)proj_gemm_kernel<kPjOut>, hipFuncAttributeMaxDynamicSharedMemorySize, kPjLdsBytes);
-    if (e != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
-    attr_set = true;
-  }
+  static std::once_flag attr_once;      // the projections are stateless: any host thread may get here first
+  static hipError_t attr_err = hipSuccess;
+  std::call_once(attr_once, [] {
+    attr_err = hipFuncSetAttribute((const void*)proj_gemm_kernel<kPjQkv>, hipFuncAttributeMaxDynamicSharedMemorySize, kPjLdsBytes);
+    if (attr_err == hipSuccess)
+      attr_err = hipFuncSetAttribute((const void*)proj_gemm_kernel<kPjOut>, hipFuncAttributeMaxDynamicSharedMemorySize, kPjLdsBytes);
+  });
+  if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
   p.a_tiles = (int)ceil_div(p.a_rows, kPjTile);
   p.b_tiles = (int)ceil_div(p.b_rows, kPjTile);
   p.ga = p.a_tiles / 8 > 0 ? p.a_tiles / 8 : 1;
@@ -462,6 +463,12 @@ static hi_status pj_launch(void* stream, ProjArgs& p, int mode) {
 
 static bool pj_aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
+#define HI_PJ_TRY(call)               \
+  do {                                \
+    hi_status s_ = (call);            \
+    if (s_ != HI_OK) return s_;       \
+  } while (0)
+
 }  // namespace hi
 
 using namespace hi;
@@ -472,10 +479,11 @@ extern "C" hi_status hi_proj_workspace_bytes(int32_t chunk, int64_t* bytes) {
   return HI_OK;
 }
 
-extern "C" hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model,
-                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t chunk_len, int64_t past_len,
-                                 double rope_theta, int32_t out_fp32, void* q_out_dev, void* k_out_dev,
-                                 void* v_out_dev, void* workspace_dev) {
+// hi_qkv_rope and its variant without a workspace argument; the rotary table goes to workspace_dev either way
+static hi_status qkv_rope_impl(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model,
+                               int32_t n_q_heads, int32_t n_kv_heads, int32_t chunk_len, int64_t past_len,
+                               double rope_theta, int32_t out_fp32, void* q_out_dev, void* k_out_dev,
+                               void* v_out_dev, void* workspace_dev) {
   if (!x_dev || !w_qkv_dev || !q_out_dev || !k_out_dev || !v_out_dev || (rope_theta > 0 && chunk_len > 1 && !workspace_dev)) {
     set_last_error("qkv projection: null buffer");
     return HI_ERR_ARG;
@@ -525,6 +533,14 @@ extern "C" hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_
     p.rope = (const float2*)workspace_dev;
   }
   return pj_launch(stream, p, kPjQkv);
+}
+
+extern "C" hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model,
+                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t chunk_len, int64_t past_len,
+                                 double rope_theta, int32_t out_fp32, void* q_out_dev, void* k_out_dev,
+                                 void* v_out_dev, void* workspace_dev) {
+  return qkv_rope_impl(stream, x_dev, w_qkv_dev, d_model, n_q_heads, n_kv_heads, chunk_len, past_len, rope_theta,
+                       out_fp32, q_out_dev, k_out_dev, v_out_dev, workspace_dev);
 }
 
 extern "C" hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, int32_t n_q_heads,

@@ -85,9 +85,12 @@ def decode(ss: Session, inp: LayerInputs, start_pos, n_tokens, rows=None, keep=N
     """n_tokens decode steps at positions start_pos..; rows: optional pre-drawn list of decode_rows() results."""
     L, H, G = inp.L, inp.H, inp.G
     outs = []
+    borrowed = []       # rows drawn here: the library borrows them until ss.sync() (the write-back reads k, v)
     for t in range(n_tokens):
         pos = start_pos + t
         q, k, v = rows[t] if rows is not None else inp.decode_rows(pos)
+        if rows is None:
+            borrowed.append((q, k, v))
         out = torch.empty(L, H, G, 128, dtype=ss.out_dtype, device=inp.device)
         nxt_past = pos + 1 if t + 1 < n_tokens else None
         for l in range(L):
@@ -97,4 +100,8 @@ def decode(ss: Session, inp: LayerInputs, start_pos, n_tokens, rows=None, keep=N
         if keep is not None:
             keep(t, out)
         outs.append(out)
+    if borrowed:
+        # The asynchronous write-backs on the D2H stream still read the drawn rows; freeing them now would hand
+        # their blocks back to the allocator of the compute stream.  Keep them until the streams have drained.
+        ss.sync()
     return outs

@@ -2,7 +2,7 @@
 """Kernel-level micro-benchmark: one HBM-resident prefill unit and one decode unit, HIP-event timed.
 
     python3 paper_2502_12574_amd/kernel_bench.py [--past P] [--chunk C] [--reps R] [--what prefill|decode|both|kvq]
-                                                 [--narrow|--deep|--wide] [--calibrate] [--rows N] [--gqa G]
+                                                 [--narrow|--deep] [--calibrate] [--rows N] [--gqa G]
 
 Used for the rocprofv3 counter runs under profiles/ (--calibrate adds a plain 1 GiB device copy whose FETCH_SIZE /
 WRITE_SIZE readings give the scale of those counters).  K/V are resident in HBM, so this isolates K1 / K2+K3 from
@@ -62,7 +62,6 @@ def main():
     ap.add_argument("--what", default="both", choices=["prefill", "decode", "both", "kvq"])
     ap.add_argument("--rows", type=int, default=524288, help="rows per conversion launch (--what kvq)")
     ap.add_argument("--gqa", type=int, default=4, choices=[1, 2, 4, 8], help="query heads per KV head")
-    ap.add_argument("--wide", action="store_true", help="use the 64-positions-per-wave prefill kernel")
     ap.add_argument("--narrow", action="store_true", help="force the 4-wave, 2-stage prefill kernel")
     ap.add_argument("--deep", action="store_true", help="force the 8-wave, 4-stage prefill kernel")
     ap.add_argument("--calibrate", action="store_true", help="also run a plain 1 GiB device-to-device copy")
@@ -71,7 +70,7 @@ def main():
     if args.what == "kvq":
         return kvq(args.rows, args.reps, args.calibrate, dev)
     ss = Session(1, 1, G, P + C, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0)
-    flags = hb.HI_FLAG_TIME_KERNELS | (hb.HI_FLAG_PREFILL_WIDE if args.wide else 0)
+    flags = hb.HI_FLAG_TIME_KERNELS
     flags |= (hb.HI_FLAG_PREFILL_NARROW if args.narrow else 0) | (hb.HI_FLAG_PREFILL_DEEP if args.deep else 0)
     hb.hi_ctx_set_flags(ss.ctx, flags)
     with torch.cuda.stream(ss.s_compute):

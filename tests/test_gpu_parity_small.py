@@ -126,11 +126,11 @@ def test_prefill_ragged_shapes(G, P, C):
                                    (4, 1000, 129), (1, 77, 200), (2, 130, 95), (8, 200, 70), (8, 0, 40),
                                    (4, 97, 700)])
 @pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
-@pytest.mark.parametrize("variant", ["wide", "deep"])
+@pytest.mark.parametrize("variant", ["deep", "narrow"])
 def test_prefill_other_kernel_variants_ragged_shapes(G, P, C, mode, variant):
-    # the 8-wave / 4-stage kernel is normally picked for long chunks only and the 64-positions-per-wave kernel
-    # only on request; force each of them on small ragged shapes
-    flag = hb.HI_FLAG_PREFILL_WIDE if variant == "wide" else hb.HI_FLAG_PREFILL_DEEP
+    # the 8-wave / 4-stage kernel is normally picked for long chunks and the 4-wave kernel for very short ones;
+    # force each of them on small ragged shapes
+    flag = hb.HI_FLAG_PREFILL_DEEP if variant == "deep" else hb.HI_FLAG_PREFILL_NARROW
     out, Q, K, V = one_unit(G, P, C, seed=700 + P + C, mode=mode, flags=flag)
     ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
     for g in range(G):
@@ -147,6 +147,60 @@ def test_prefill_8wave_kernel_steady_state(G, P, C, mode):
     ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
     for g in range(G):
         check(out[g:g + 1], ref[g:g + 1], f"8-wave G={G} P={P} C={C} head {g}")
+
+
+def strip_and_random_rows(C, rng, n_random=64, strip=64):
+    """first and last row of every strip of query positions (the workgroups' blocks), plus random rows"""
+    pts = set()
+    for b in range(0, C, strip):
+        pts |= {b, min(C, b + strip) - 1}
+    pts |= {C - 1} | set(int(x) for x in rng.integers(0, C, n_random))
+    return np.array(sorted(pts), dtype=np.int64)
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
+@pytest.mark.parametrize("G,P,C", [(4, 0, 16384), (4, 100, 12288), (8, 0, 6144), (4, 0, 8192), (2, 0, 9000),
+                                   (4, 5000, 16384), (1, 37, 12000)])
+def test_prefill_units_dominated_by_their_causal_triangle(G, P, C, mode):
+    # The first chunks of a long prompt (Algorithm 1, prefill phase; Eq. 3): a chip-filling chunk whose past is
+    # shorter than the chunk itself, computed in one launch by the default kernel choice.  The workgroups' tile
+    # sequences differ by up to the whole triangle there and the launcher evens them out over the chip (several
+    # workgroups share a block of positions and their states are merged afterwards): sampled rows - both ends of
+    # every 64-row block, plus random ones - against the oracle, every query head.
+    out, Q, K, V = one_unit(G, P, C, seed=8800 + P + C, mode=mode)
+    rows = strip_and_random_rows(C, np.random.default_rng(P + C + G))
+    Kf, Vf = synth.to_f64(K), synth.to_f64(V)
+    for g in range(G):
+        ref = oa.attn_rows(synth.to_f64(Q[g][rows]), Kf, Vf, P + rows)
+        check(out[g][rows][None], ref[None], f"triangle unit G={G} P={P} C={C} head {g}")
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
+@pytest.mark.parametrize("n_heads,G,P,C", [(8, 4, 0, 1536), (2, 4, 0, 8192), (4, 4, 130, 3000)])
+def test_prefill_group_first_chunk(n_heads, G, P, C, mode):
+    # the same for a group of KV heads in one call (grid y = head): first chunk of a layer with all heads fused
+    dev, seed = "cuda:0", 9900 + C
+    with Session(1, n_heads, G, max(P + C, 256 * n_heads), C, mode=mode, out_fp32=1) as ss:
+        with torch.cuda.stream(ss.s_compute):
+            Q = torch.stack([torch.stack([synth.draw_q(seed, 0, h * G + g, P, C, device=dev) for g in range(G)])
+                             for h in range(n_heads)])
+            K = torch.stack([synth.draw_k(seed, 0, h, 0, P + C, device=dev) for h in range(n_heads)])
+            V = torch.stack([synth.draw_v(seed, 0, h, 0, P + C, device=dev) for h in range(n_heads)])
+            if P:
+                cv = ss.cache_view()
+                cv[0, :, 0, :P].copy_(K[:, :P])
+                cv[0, :, 1, :P].copy_(V[:, :P])
+            torch.cuda.current_stream().synchronize()
+            out = torch.empty(n_heads, G, C, 128, dtype=torch.float32, device=dev)
+            ss.prefill_group(0, 0, n_heads, Q, K[:, P:].contiguous(), V[:, P:].contiguous(), P, out)
+        ss.sync()
+        out, Q, K, V = out.cpu(), Q.cpu(), K.cpu(), V.cpu()
+    rows = strip_and_random_rows(C, np.random.default_rng(C), n_random=32)
+    for h in range(n_heads):
+        Kf, Vf = synth.to_f64(K[h]), synth.to_f64(V[h])
+        for g in range(G):
+            ref = oa.attn_rows(synth.to_f64(Q[h, g][rows]), Kf, Vf, P + rows)
+            check(out[h, g][rows][None], ref[None], f"group of {n_heads}, P={P} C={C} head {h} q {g}")
 
 
 @pytest.mark.parametrize("shape", ["rising", "falling", "spikes", "overflow"])
