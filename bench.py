@@ -32,11 +32,30 @@ HQ, HKV, G, D = 32, 8, 4, 128
 PEAK_MFMA_TFLOPS = 2500.0     # dense bf16
 PEAK_HBM_GBPS = 8000.0
 PEAK_LINK_GBPS = 64.0         # PCIe Gen5 x16, one direction
-# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (profiles/*_pmc.md), each scaled by
-# what the same counter read for a 1 GiB copy kernel in the same run: a prefill launch over one 262144-row
-# staging slice with chunk 16384, and the resident decode launch over 1M rows (reads each K/V byte once).
-PREFILL_TRAFFIC_PER_LAUNCH = 1103.8 * 2 ** 20 + 16 * 2 ** 20
+# HBM-side bytes per launch come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, each scaled by what the same
+# counter read for a 1 GiB copy kernel in the same run.  The prefill figure is read from the profile summary that
+# holds it, where it is stored next to the hash of the kernel source it was measured on: a changed kernel or another
+# shape gives null instead of a stale number.  The resident decode launch reads each K/V byte once (measured).
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "prefill_kernel_deep_unit_resident_pmc.md")
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2502_12574_amd", "csrc", "hi_prefill.hip")
 DECODE_TRAFFIC_PER_ROW = 512.0
+
+
+def prefill_traffic_per_launch(S, C):
+    """bytes per staging-slice launch of the dominant kernel, or (None, why)"""
+    import hashlib
+    import re
+    try:
+        sha = hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()[:16]
+        for line in open(TRAFFIC_PROFILE):
+            m = re.match(r"\s*bench-traffic: context=(\d+) chunk=(\d+) source_sha256=(\w+) bytes_per_launch=(\d+)", line)
+            if m and (int(m.group(1)), int(m.group(2))) == (S, C):
+                if m.group(3) == sha:
+                    return int(m.group(4)), os.path.relpath(TRAFFIC_PROFILE, ROOT)
+                return None, "the kernel source changed after the counter run in " + os.path.relpath(TRAFFIC_PROFILE, ROOT)
+    except OSError:
+        pass
+    return None, "no counter run for this shape"
 
 
 def causal_flops_layer(S):
@@ -70,11 +89,126 @@ def cpu_baseline(seed, S, C, seconds_target=15.0):
     layer_pairs = HQ * (S * (S + 1) / 2.0)
     prefill_s = sec_per_pair * layer_pairs
     decode_ms = sec_per_pair * HQ * S * 1e3
+    # the small configuration in full: 4 query heads over one KV head, 2048 tokens, then 16 decode rows
+    n1, nd1 = 2048, 16
+    Q1 = np.stack([synth.to_f64(synth.draw_q(seed, 0, g, 0, n1 + nd1)) for g in range(4)])
+    K1 = synth.to_f64(synth.draw_k(seed, 0, 0, 0, n1 + nd1))
+    V1 = synth.to_f64(synth.draw_v(seed, 0, 0, 0, n1 + nd1))
+    t0 = time.perf_counter()
+    cache = oa.HeadwiseCache(1, 1, D)
+    oa.prefill_chunked(cache, Q1[None, :, :n1], K1[None, None, :n1], V1[None, None, :n1], 512)
+    t_pre1 = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for t in range(nd1):
+        oa.decode_step(cache, Q1[None, :, n1 + t], K1[None, None, n1 + t], V1[None, None, n1 + t])
+    t_dec1 = time.perf_counter() - t0
     return {"value": S / prefill_s, "unit": "tokens/s per layer (prefill)", "cores": cores, "kind": "oracle",
             "decode_ms_per_token_per_layer": decode_ms,
+            "small_config_full": {"what": "4 query heads / 1 KV head, 2048 tokens in 4 chunks of 512, then 16 decode "
+                                          "steps, run in full", "prefill_s": t_pre1,
+                                  "prefill_tokens_per_s": n1 / t_pre1, "decode_ms_per_token": t_dec1 / nd1 * 1e3},
             "sample": f"{total_rows} query rows of one head at positions in the last chunk of the {S}-token "
                       f"context, {total_t:.1f} s of fp64 numpy; extrapolated linearly in row-key pairs to "
                       f"{HQ} heads x S(S+1)/2 pairs"}
+
+
+def run_stack(args):
+    """The literal multi-layer configuration: L attention blocks in Algorithm 1's order (chunk -> layer -> head), each
+    layer's Q/K/V produced chunk by chunk from hidden states by hi_qkv_rope (directly drawn Q/K/V of 32 layers would
+    not fit HBM), one pinned host allocation per layer, a one-head HBM budget for all layers.  One timed pass."""
+    from paper_2502_12574_amd.attention_block import AttentionBlock
+    dev, S, C, nd, d_model = "cuda:0", args.context, args.chunk, args.decode_tokens, HQ * D
+    L, ss = max(1, args.layers), None
+    while ss is None:
+        try:
+            ss = Session(L, HKV, G, S + max(nd, 1), C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0, per_layer_cache=True)
+        except RuntimeError as e:               # the box refuses to pin that much: fewer layers, figures stay per layer
+            print(f"bench.py: {L} layers of pinned cache refused ({str(e)[:80]}); trying {L // 2}", file=sys.stderr, flush=True)
+            torch.cuda.empty_cache()
+            L //= 2
+            if L < 1:
+                raise
+    print(f"bench.py: {L} layers, {ss.plan.host_bytes_total / 2**30:.0f} GiB of pinned cache", file=sys.stderr, flush=True)
+    blocks = []
+    for l in range(L):
+        w_qkv = synth.draw_weight(args.seed, synth.TENSOR_WQKV, l, (HQ + 2 * HKV) * D, d_model, device=dev)
+        w_o = synth.draw_weight(args.seed, synth.TENSOR_WO, l, d_model, HQ * D, device=dev)
+        blocks.append(AttentionBlock(ss, l, w_qkv, w_o))
+    starts = list(range(0, S, C))
+    xs = [synth.draw_hidden(args.seed, 0, p, min(C, S - p), d_model, device=dev) for p in starts]
+    xbuf = [torch.empty(C, d_model, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    first = blocks[0].calls[0]
+    hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_TIME_KERNELS)
+    hb.hi_reset_stats(ss.ctx)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for ci, p in enumerate(starts):
+        n = xs[ci].shape[0]
+        x = xs[ci]
+        for l in range(L):
+            if l + 1 < L:
+                nxt = (l + 1, first[0], first[1], p)
+            elif ci + 1 < len(starts):
+                nxt = (0, first[0], first[1], p + n)
+            else:
+                nxt = (0, first[0], first[1], S) if nd else None
+            y = xbuf[l & 1][:n]
+            blocks[l].forward(x, p, y, nxt)
+            with torch.cuda.stream(ss.s_compute):
+                y.add_(x)                      # the residual connection keeps the hidden states at unit scale
+            x = y
+        if ci % 8 == 7:
+            print(f"bench.py: chunk {ci + 1} of {len(starts)} enqueued, {time.perf_counter() - t0:.0f} s", file=sys.stderr, flush=True)
+    ss.sync()
+    t_pre = time.perf_counter() - t0
+    st = ss.stats()
+    hb.hi_reset_stats(ss.ctx)
+    xd = synth.draw_hidden(args.seed, 0, S, nd + 1, d_model, device=dev)[:, None]
+    t0 = time.perf_counter()
+    for t in range(nd):
+        x = xd[t]
+        for l in range(L):
+            nxt = (l + 1, first[0], first[1], S + t) if l + 1 < L else ((0, first[0], first[1], S + t + 1) if t + 1 < nd else None)
+            y = xbuf[l & 1][:1]
+            blocks[l].forward(x, S + t, y, nxt)
+            with torch.cuda.stream(ss.s_compute):
+                y.add_(x)
+            x = y
+    ss.sync()
+    t_dec = time.perf_counter() - t0
+    sd = ss.stats()
+    flops = causal_flops_layer(S)
+    kern_s = st.prefill_kernel_ms * 1e-3 / L
+    dec_ms = t_dec / max(nd, 1) / L * 1e3
+    result = {
+        "metric": "prefill tokens/s per layer at 1M ctx (decode ms/token per layer and roofline fractions alongside)",
+        "value": S / (t_pre / L), "unit": "tokens/s per layer", "n_gpus": 1, "steps": 1, "warmup": 0,
+        "ms_per_step": (t_pre + t_dec) * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 inputs, fp32 accumulate (MFMA)", "data": "synthetic",
+        "config": {"workload": f"{L}-layer attention stack (attention blocks only, no MLP), Llama-3-8B shapes: {HQ} Q / {HKV} KV "
+                               f"heads, head_dim {D}, d_model {d_model}, context {S}, chunk {C}, loop chunk -> layer -> head, "
+                               f"{nd} decode tokens; each layer's Q/K/V come from hi_qkv_rope on the hidden states, the "
+                               f"layer's output from hi_out_proj; {ss.plan.host_bytes_total / 2**30:.0f} GiB of K/V in "
+                               f"pinned host DRAM (one allocation per layer), 1-KV-head HBM budget",
+                   "context": S, "chunk": C, "decode_tokens": nd, "layers_timed": L, "layers_asked": args.layers,
+                   "seed": args.seed},
+        "prefill_s_total": t_pre, "prefill_s_per_layer": t_pre / L,
+        "decode_ms_per_token_per_layer_offloaded": dec_ms if nd else None,
+        "decode_link": {"achieved_GBps": 512.0 * HKV * S / (dec_ms * 1e-3) / 1e9 if nd else None, "peak_GBps": PEAK_LINK_GBPS},
+        "peak_staging_bytes": max(st.peak_staging_bytes, sd.peak_staging_bytes), "one_head_bytes": ss.plan.host_bytes_per_head,
+        "bytes_h2d_prefill": st.bytes_h2d, "bytes_d2h_prefill": st.bytes_d2h,
+        "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS, "traffic": None, "kernel": "prefill_kernel_deep",
+                     "launches_per_step": st.n_prefill_kernels, "avg_launch_ms": st.prefill_kernel_ms / max(st.n_prefill_kernels, 1),
+                     "wall_TFLOPs": flops / (t_pre / L) / 1e12,
+                     "note": "wall time includes the projections of every chunk and layer (about 1.2 % of a layer)"},
+        "overlap": {"t_pipelined_s": t_pre / L, "t_kernel_sum_pipelined_s": kern_s,
+                    "h2d_copy_engine_s": st.h2d_copy_ms * 1e-3 / L, "d2h_copy_engine_s": st.d2h_copy_ms * 1e-3 / L,
+                    "compute_stream_waiting_for_slices_s": st.exposed_copy_ms * 1e-3 / L,
+                    "hidden_fraction_from_waits": 1.0 - st.exposed_copy_ms / max(st.h2d_copy_ms, 1e-9)},
+    }
+    ss.close()
+    print(json.dumps(result))
 
 
 def main():
@@ -90,7 +224,11 @@ def main():
     ap.add_argument("--no-extra-legs", action="store_true", help="skip transfer-only and resident-decode legs")
     ap.add_argument("--layers", type=int, default=1, help="layers run in Algorithm 1's order (chunk -> layer -> head); "
                     "every figure stays per layer")
+    ap.add_argument("--heads-per-call", type=int, default=0, help="KV heads per call; 0 = what hi_offload_plan "
+                    "recommends for the context (Section 4, adaptive head-wise offloading: 1 beyond 256K tokens)")
     ap.add_argument("--seed", type=int, default=20250216)
+    ap.add_argument("--stack", action="store_true", help="the literal multi-layer configuration: --layers attention blocks "
+                    "whose Q/K/V come from the projections of hidden states, one pinned allocation per layer, one pass")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, no collectives); --gpus must be 1. KV heads are "
@@ -100,16 +238,19 @@ def main():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
 
+    if args.stack:
+        return run_stack(args)
     dev = "cuda:0"
     S, C, nd = args.context, args.chunk, args.decode_tokens
     S_max = S + max(nd, args.resident_decode_tokens)
     NL = max(1, args.layers)
     ss = Session(NL, HKV, G, S_max, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0)
+    hpc = args.heads_per_call if args.heads_per_call > 0 else max(1, ss.plan.heads_per_group)
     t_gen = time.perf_counter()
     with torch.cuda.stream(ss.s_compute):
         inp = driver.LayerInputs(args.seed, NL, HKV, G, S, C, dev)
         dec_rows = [inp.decode_rows(S + t) for t in range(max(nd, args.resident_decode_tokens))]
-        out_buf = [[torch.empty(G, C, D, dtype=ss.out_dtype, device=dev) for _ in range(HKV)] for _ in range(NL)]
+        out_buf = [torch.empty(HKV, G, C, D, dtype=ss.out_dtype, device=dev) for _ in range(NL)]
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
@@ -118,11 +259,11 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         with torch.cuda.stream(ss.s_compute):
-            driver.prefill(ss, inp, out_buf=out_buf, last_hint=(0, 0, S) if nd else None)
+            driver.prefill(ss, inp, out_buf=out_buf, last_hint=(0, 0, S) if nd else None, heads_per_call=hpc)
         ss.sync()
         t1 = time.perf_counter()
         with torch.cuda.stream(ss.s_compute):
-            driver.decode(ss, inp, S, nd, rows=dec_rows)
+            driver.decode(ss, inp, S, nd, rows=dec_rows, heads_per_call=hpc)
         ss.sync()
         torch.cuda.synchronize()
         t2 = time.perf_counter()
@@ -132,6 +273,7 @@ def main():
     for _ in range(args.warmup):
         step(False)
     pre_s, dec_s, kern_pre_ms, kern_dec_ms, n_pre_k, n_dec_k = [], [], 0.0, 0.0, 0, 0
+    copy_ms = {"h2d": 0.0, "d2h": 0.0, "exposed": 0.0}
     bytes_h2d = 0
     peak_staging = 0
     torch.cuda.synchronize()
@@ -142,6 +284,7 @@ def main():
         kern_pre_ms += st.prefill_kernel_ms; kern_dec_ms += st.decode_kernel_ms
         n_pre_k += st.n_prefill_kernels; n_dec_k += st.n_decode_kernels
         bytes_h2d = st.bytes_h2d
+        copy_ms["h2d"] += st.h2d_copy_ms; copy_ms["d2h"] += st.d2h_copy_ms; copy_ms["exposed"] += st.exposed_copy_ms
         peak_staging = max(peak_staging, st.peak_staging_bytes)
     torch.cuda.synchronize()
     t_all = time.perf_counter() - t_all0
@@ -158,25 +301,46 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         with torch.cuda.stream(ss.s_compute):
-            driver.prefill(ss, inp, out_buf=out_buf)
+            driver.prefill(ss, inp, out_buf=out_buf, heads_per_call=hpc)
         ss.sync()
         t_xfer = (time.perf_counter() - t0) / NL
-        stx = ss.stats()
         hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_TIME_KERNELS)
         link_bytes = 512.0 * HKV * sum(range(0, S, C)) + 512.0 * HKV * S
-        hidden = 1.0 - max(0.0, prefill_s - kern_s) / t_xfer
-        extra["overlap"] = {"t_pipelined_s": prefill_s, "t_compute_only_s": kern_s, "t_transfer_only_s": t_xfer,
-                            "hidden_fraction": hidden, "link_bytes": link_bytes,
-                            "transfer_only_GBps": link_bytes / t_xfer / 1e9}
-        # HBM-resident decode over the same cache (device copy of the host cache)
+        # compute-only: the same calls on one layer with K/V resident in HBM (no link, no ring; a unit's past is one
+        # contiguous segment there, so it takes one launch instead of one per staging slice)
         ss_r = Session(1, HKV, G, S_max, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0)
-        ss_r.kv.copy_(ss.kv[:ss_r.kv.numel()], non_blocking=False)        # layer 0
+        inp0 = inp.single_layer(0)
+
+        def resident_prefill():
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            with torch.cuda.stream(ss_r.s_compute):
+                driver.prefill(ss_r, inp0, out_buf=out_buf[:1], heads_per_call=hpc)
+            ss_r.sync()
+            return time.perf_counter() - t0
+
+        resident_prefill()                        # warm-up; also fills the resident cache for the decode leg below
+        t_comp = resident_prefill()
+        # hidden = 1 - max(0, T_pipelined - T_compute_only) / T_transfer_only; two more readings of the same thing ride
+        # along: with the summed kernel time of the pipelined run in place of the resident run, and the time the
+        # compute stream spent waiting for staging slices (HIP events around every wait) over the transfer time
+        exposed_s = copy_ms["exposed"] / K * 1e-3 / NL
+        extra["overlap"] = {"t_pipelined_s": prefill_s, "t_compute_only_s": t_comp, "t_transfer_only_s": t_xfer,
+                            "hidden_fraction": 1.0 - max(0.0, prefill_s - t_comp) / t_xfer,
+                            "compute_only": "the same calls on one layer with K/V resident in HBM, wall time",
+                            "t_kernel_sum_pipelined_s": kern_s,
+                            "hidden_fraction_vs_kernel_sum": 1.0 - max(0.0, prefill_s - kern_s) / t_xfer,
+                            "compute_stream_waiting_for_slices_s": exposed_s,
+                            "hidden_fraction_from_waits": 1.0 - exposed_s / t_xfer,
+                            "h2d_copy_engine_s": copy_ms["h2d"] / K * 1e-3 / NL,
+                            "d2h_copy_engine_s": copy_ms["d2h"] / K * 1e-3 / NL,
+                            "link_bytes": link_bytes, "transfer_only_GBps": link_bytes / t_xfer / 1e9}
+        # HBM-resident decode over the cache the resident prefill has just filled
         hb.hi_ctx_set_flags(ss_r.ctx, hb.HI_FLAG_TIME_KERNELS)
         nr = args.resident_decode_tokens
         # all KV heads of the layer in one call per token (head groups; with everything in HBM nothing speaks
         # against the largest group)
-        grp = [(torch.stack([r[0][0][h] for h in range(HKV)]), torch.stack([r[1][0][h] for h in range(HKV)]),
-                torch.stack([r[2][0][h] for h in range(HKV)])) for r in dec_rows[:nr]]
+        grp = [(r[0][0], r[1][0], r[2][0]) for r in dec_rows[:nr]]          # layer 0, heads stacked
         out_r = torch.empty(HKV, G, D, dtype=ss_r.out_dtype, device=dev)
 
         def resident_decode(n):
@@ -204,6 +368,7 @@ def main():
         ss_r.close()
         del ss_r
 
+    traffic, traffic_src = prefill_traffic_per_launch(S, C)
     dec_link_GBps = 512.0 * HKV * (S + (nd - 1) / 2.0) / (decode_ms_tok * 1e-3) / 1e9 if nd else None
     result = {
         "metric": "prefill tokens/s per layer at 1M ctx (decode ms/token per layer and roofline fractions alongside)",
@@ -216,7 +381,7 @@ def main():
         "config": {"workload": f"one Llama-3-8B-shaped attention layer of the 32-layer 1M-token configuration: "
                                f"{HQ} Q / {HKV} KV heads, head_dim {D}, context {S}, head-wise chunked prefill "
                                f"chunk {C} + {nd} decode tokens, K/V offloaded to pinned host DRAM, 1-KV-head HBM "
-                               f"budget", "context": S, "chunk": C, "decode_tokens": nd, "layers_timed": NL,
+                               f"budget", "context": S, "chunk": C, "decode_tokens": nd, "layers_timed": NL, "heads_per_call": hpc,
                    "seed": args.seed},
         "prefill_s_per_layer": prefill_s,
         "decode_ms_per_token_per_layer_offloaded": decode_ms_tok if nd else None,
@@ -226,7 +391,7 @@ def main():
         "input_generation_s": t_gen,
         "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS,
-                     "traffic": PREFILL_TRAFFIC_PER_LAUNCH if (S, C) == (1 << 20, 16384) else None,
+                     "traffic": traffic, "traffic_source": traffic_src,
                      "kernel": "prefill_kernel_deep",
                      "launches_per_step": n_pre_k / K, "avg_launch_ms": kern_pre_ms / max(n_pre_k, 1),
                      "flops_per_launch": flops * NL / (n_pre_k / K),
@@ -240,7 +405,7 @@ def main():
         # recent tokens in HBM) on the same layer, and the projections either side of the attention calls
         from paper_2502_12574_amd import layer_bench, proj_bench
         torch.cuda.empty_cache()
-        sp = layer_bench.run(S, C, HKV // 2, 128, 512, 8, HKV // 2)
+        sp = layer_bench.run(S, C, HKV // 2, 128, 512, 8, HKV // 2, heads_per_call=hpc)
         sp["prefill_speedup_vs_all_retrieval"] = prefill_s / sp["prefill_s"]
         if nd:
             sp["decode_speedup_vs_all_retrieval"] = decode_ms_tok / sp["decode_ms_per_token"]
@@ -249,7 +414,7 @@ def main():
         # the same layer with 4-bit rows on the host link (every head offloaded): the link-bound decode should follow
         # the bytes per row, the prefill should not change
         torch.cuda.empty_cache()
-        lk = layer_bench.run(S, C, 0, 0, 0, 8, 1, link_kv_bits=4)
+        lk = layer_bench.run(S, C, 0, 0, 0, 8, 1, link_kv_bits=4, heads_per_call=hpc)
         lk["prefill_speedup_vs_bf16_rows"] = prefill_s / lk["prefill_s"]
         if nd:
             lk["decode_speedup_vs_bf16_rows"] = decode_ms_tok / lk["decode_ms_per_token"]

@@ -39,9 +39,13 @@ enum { HI_REGIME_COMPUTE = 0, HI_REGIME_LINK = 1, HI_REGIME_HBM = 2 };
  * time the attention kernels with HIP events; force a prefill kernel variant (by default the library picks by
  * chunk length and group size between DEEP: 8 wavefronts per workgroup alternating matrix and softmax phases,
  * split over the K/V rows when the chunk alone would not fill the chip, and NARROW: 4 wavefronts, for very short
- * chunks). Do not change the variant between the calls of one (chunk, head) unit. */
+ * chunks); with the DEEP kernel, PAIRED / UNPAIRED force or forbid the balanced partition of the causal triangle
+ * (deep and shallow blocks of query positions share their tiles), which the library otherwise picks when it saves
+ * the deepest workgroups at least a few tiles. Do not change the variant between the calls of one (chunk, head) unit. */
 enum { HI_FLAG_SKIP_KERNELS = 1, HI_FLAG_SKIP_COPIES = 2, HI_FLAG_TIME_KERNELS = 4, HI_FLAG_PREFILL_NARROW = 8,
-       HI_FLAG_PREFILL_DEEP = 32 };
+       HI_FLAG_PREFILL_PAIRED = 16, HI_FLAG_PREFILL_DEEP = 32, HI_FLAG_PREFILL_UNPAIRED = 64,
+       HI_FLAG_INJECT_FAILURE = 128 /* test hook: the next unit call fails with HI_ERR_HIP right after its checks, as a
+                                       failed launch or copy would; no GPU work is skipped or broken by it */ };
 
 /* The paper's statement of the problem (Algorithm 1 "Require": L layers, H heads, sequence length S). */
 typedef struct hi_problem {
@@ -126,6 +130,10 @@ typedef struct hi_stats {
   double prefill_kernel_ms, decode_kernel_ms; /* HIP-event time of the attention kernels since the last
                                                  hi_reset_stats; only with HI_FLAG_TIME_KERNELS; hi_get_stats
                                                  synchronises to read them */
+  double h2d_copy_ms, d2h_copy_ms;   /* the same for the prefetch copies (on stream_h2d) and the write-backs (on
+                                        stream_d2h): time the copy engines spent on them */
+  double exposed_copy_ms;            /* time stream_compute spent waiting for a staging slice to land: the part of the
+                                        transfers that no kernel covered (HIP events around each wait) */
 } hi_stats;
 
 typedef struct hi_ctx hi_ctx;
@@ -157,11 +165,21 @@ hi_status hi_offload_plan(const hi_problem* problem, hi_plan* plan);
  * With hi_problem.link_kv_bits = 4 the cache layout is [layer][kv_head][K|V][S_max][plan.link_row_bytes] bytes.
  * A context is used by one host thread at a time (its calls mutate the ring's bookkeeping without locks); different
  * contexts are independent.  Errors: HI_ERR_ARG, HI_ERR_NOT_PINNED, HI_ERR_UNSUPPORTED, HI_ERR_HIP.
+ * kv_cache may be null when every layer's rows are given by hi_ctx_set_layer_cache before the layer is first used.
  */
 hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* plan, int32_t mode, void* kv_cache,
                         void* hbm_staging, void* hbm_workspace, void* stream_compute, void* stream_h2d,
                         void* stream_d2h, hi_ctx** out);
 hi_status hi_ctx_destroy(hi_ctx* ctx);
+/*
+ * One allocation per layer (Eq. 7-8 partition the cache by layer and head; Algorithm 1 only ever touches one
+ * (layer, head) at a time, so nothing requires the layers to be contiguous): kv_layer holds the rows of `layer`,
+ * [kv_head][K|V][S_max][plan.link_row_bytes], plan.host_bytes_total / n_layers bytes, pinned host memory in
+ * HI_MODE_OFFLOAD, device memory in HI_MODE_RESIDENT; it replaces whatever the layer had.  A 1M-token, 32-layer
+ * cache is then 32 allocations of 4 GiB instead of one of 128 GiB.  Synchronises the context's streams first.
+ * Errors: HI_ERR_ARG, HI_ERR_NOT_PINNED, HI_ERR_HIP.
+ */
+hi_status hi_ctx_set_layer_cache(hi_ctx* ctx, int32_t layer, void* kv_layer);
 hi_status hi_ctx_set_flags(hi_ctx* ctx, int32_t flags);
 /* Bounded run-ahead of the caller: hi_prefill_head / hi_decode_head first wait (on the host) until the unit
  * `units` calls earlier has finished on stream_compute; the history of the unit being enqueued is already being
@@ -184,7 +202,10 @@ hi_status hi_ctx_set_run_ahead(hi_ctx* ctx, int32_t units);
  * Asynchronous: enqueues and returns (after the bounded run-ahead wait described at hi_ctx_set_run_ahead).  Results
  * and the cache append are valid after hi_sync.  The caller's
  * buffers are borrowed until then.  1 <= chunk_len <= chunk; past_len >= 0; no alignment is required of either.
- * Errors (synchronous, nothing enqueued, cache untouched): HI_ERR_ARG, HI_ERR_RANGE; HI_ERR_HIP.
+ * Errors (synchronous, nothing enqueued, cache and staging ring untouched): HI_ERR_ARG, HI_ERR_RANGE,
+ * HI_ERR_HBM_BUDGET, HI_ERR_UNSUPPORTED - every check comes before the first enqueue.  HI_ERR_HIP means a HIP call
+ * failed after work had been enqueued: copies, kernels and the ring's bookkeeping are then half-advanced, so the
+ * context is closed - every later unit call returns HI_ERR_HIP - and can only be synchronised and destroyed.
  */
 hi_status hi_prefill_head(hi_ctx* ctx, int32_t layer, int32_t kv_head, const void* q_dev, const void* k_new_dev,
                           const void* v_new_dev, int64_t past_len, int32_t chunk_len, void* out_dev,

@@ -16,9 +16,10 @@ HI_ERR_HOST_MEM, HI_ERR_RANGE, HI_ERR_NOT_PINNED, HI_ERR_HIP = -4, -5, -6, -7
 HI_MODE_OFFLOAD, HI_MODE_RESIDENT = 0, 1
 HI_REGIME_COMPUTE, HI_REGIME_LINK, HI_REGIME_HBM = 0, 1, 2
 HI_FLAG_SKIP_KERNELS, HI_FLAG_SKIP_COPIES, HI_FLAG_TIME_KERNELS = 1, 2, 4
-HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_DEEP = 8, 32
+HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_PAIRED, HI_FLAG_PREFILL_DEEP, HI_FLAG_PREFILL_UNPAIRED = 8, 16, 32, 64
+HI_FLAG_INJECT_FAILURE = 128
 
-EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
+EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_layer_cache", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
            "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_proj_workspace_bytes",
            "hi_qkv_rope", "hi_out_proj", "hi_kv_quantize", "hi_kv_dequantize", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
 
@@ -54,7 +55,8 @@ class hi_stats(C.Structure):
     _fields_ = [("bytes_h2d", C.c_int64), ("bytes_d2h", C.c_int64), ("n_h2d_copies", C.c_int64),
                 ("n_d2h_copies", C.c_int64), ("n_prefill_kernels", C.c_int64), ("n_decode_kernels", C.c_int64),
                 ("n_combine_kernels", C.c_int64), ("peak_staging_bytes", C.c_int64),
-                ("prefill_kernel_ms", C.c_double), ("decode_kernel_ms", C.c_double)]
+                ("prefill_kernel_ms", C.c_double), ("decode_kernel_ms", C.c_double),
+                ("h2d_copy_ms", C.c_double), ("d2h_copy_ms", C.c_double), ("exposed_copy_ms", C.c_double)]
 
 
 class HiError(RuntimeError):
@@ -79,6 +81,7 @@ def lib() -> C.CDLL:
         L.hi_ctx_create.argtypes = [C.POINTER(hi_problem), C.POINTER(hi_plan), i32, vp, vp, vp, vp, vp, vp,
                                     C.POINTER(vp)]
         L.hi_ctx_destroy.argtypes = [vp]
+        L.hi_ctx_set_layer_cache.argtypes = [vp, i32, vp]
         L.hi_ctx_set_flags.argtypes = [vp, i32]
         L.hi_ctx_set_run_ahead.argtypes = [vp, i32]
         L.hi_prefill_head.argtypes = [vp, i32, i32, vp, vp, vp, i64, i32, vp, i32, i32, i64]
@@ -156,6 +159,13 @@ def hi_ctx_create(problem, plan, mode, kv_cache, hbm_staging, hbm_workspace, str
 
 def hi_ctx_destroy(ctx):
     return lib().hi_ctx_destroy(ctx)
+
+
+def hi_ctx_set_layer_cache(ctx, layer: int, kv_layer, check: bool = True):
+    st = lib().hi_ctx_set_layer_cache(ctx, layer, _ptr(kv_layer))
+    if check and st != HI_OK:
+        raise HiError(st, "hi_ctx_set_layer_cache")
+    return st
 
 
 def hi_ctx_set_flags(ctx, flags: int, check: bool = True):

@@ -31,7 +31,8 @@ using namespace hi;
 
 struct TimedSpan {
   hipEvent_t start, stop;
-  int kind;   // 0 prefill, 1 decode
+  int kind;   // 0 prefill kernels, 1 decode kernels, 2 host-to-device copy, 3 device-to-host copy, 4 compute stream
+              // waiting for a slice (the part of a transfer that is not hidden)
 };
 
 struct hi_ctx {
@@ -39,7 +40,9 @@ struct hi_ctx {
   hi_plan plan;
   int mode = HI_MODE_OFFLOAD;
   int flags = 0;
-  char* kv = nullptr;        // host (offload) or device (resident) cache
+  std::vector<char*> kv_layer;   // per layer: host (offload) or device (resident) cache rows, null: not given yet
+  bool failed = false;       // an error after work had been enqueued: the ring's bookkeeping cannot be trusted
+  bool enqueuing = false;    // the running call has passed its checks and started to enqueue
   char* staging = nullptr;
   char* ws = nullptr;
   hipStream_t sc = nullptr, sh = nullptr, sd = nullptr;
@@ -90,9 +93,10 @@ inline bool unit_streaming(const hi_ctx* c, int head) { return head >= n_retriev
 inline int64_t link_row(const hi_ctx* c) { return c->plan.link_row_bytes; }
 inline bool link_packed(const hi_ctx* c) { return c->prob.link_kv_bits == 4; }
 
-inline int64_t plane_offset(const hi_ctx* c, int layer, int head, int which /*0 K, 1 V*/) {
+// rows of (layer, head) in the cache: each layer has its own base pointer, [kv_head][K|V][S_max][row bytes] behind it
+inline char* cache_plane(const hi_ctx* c, int layer, int head, int which /*0 K, 1 V*/) {
   const int64_t plane = c->prob.max_context * link_row(c);
-  return (((int64_t)layer * n_retrieval(c) + head) * 2 + which) * plane;
+  return c->kv_layer[layer] + ((int64_t)head * 2 + which) * plane;
 }
 
 // A ring slot holds one sequence slice of every head of a group: rows_of(nh) rows of K then of V per head, the
@@ -110,7 +114,7 @@ inline bool unit_resident(const hi_ctx* c, int layer, int head) {
   return c->mode == HI_MODE_RESIDENT || (int64_t)layer * n_retrieval(c) + head < c->prob.resident_heads;
 }
 inline char* res_plane(const hi_ctx* c, int layer, int head, int which) {
-  if (c->mode == HI_MODE_RESIDENT) return c->kv + plane_offset(c, layer, head, which);
+  if (c->mode == HI_MODE_RESIDENT) return cache_plane(c, layer, head, which);
   const int64_t plane = c->prob.max_context * kRowBytes;
   return c->staging + c->plan.hbm_resident_offset + (((int64_t)layer * n_retrieval(c) + head) * 2 + which) * plane;
 }
@@ -142,6 +146,27 @@ void note_peak(hi_ctx* c) {
   if (live > c->stats.peak_staging_bytes) c->stats.peak_staging_bytes = live;
 }
 
+hi_status span_begin(hi_ctx* c, int kind, TimedSpan* out, hipStream_t stream = nullptr) {
+  TimedSpan s;
+  if (!c->span_pool.empty()) {
+    s = c->span_pool.back();
+    c->span_pool.pop_back();
+  } else {
+    HI_HIP(hipEventCreate(&s.start));
+    HI_HIP(hipEventCreate(&s.stop));
+  }
+  s.kind = kind;
+  HI_HIP(hipEventRecord(s.start, stream ? stream : c->sc));
+  *out = s;
+  return HI_OK;
+}
+
+hi_status span_end(hi_ctx* c, TimedSpan& s, hipStream_t stream = nullptr) {
+  HI_HIP(hipEventRecord(s.stop, stream ? stream : c->sc));
+  c->spans.push_back(s);
+  return HI_OK;
+}
+
 // enqueue the H2D of the next not-yet-fetched slice of unit u (all heads of its group)
 hi_status issue_slice(hi_ctx* c, hi_ctx::Unit& u) {
   const int64_t i = u.issued;
@@ -164,10 +189,14 @@ hi_status issue_slice(hi_ctx* c, hi_ctx::Unit& u) {
     // 2 * nh runs per slice (also for a single head: one call instead of two measured 48 -> 54 GB/s with 8 MiB
     // runs and 55 -> 57.6 GB/s with 64 MiB runs).
     const int64_t lr = link_row(c);
-    const char* hk = c->kv + plane_offset(c, u.layer, u.head, 0) + row0 * lr;
+    const char* hk = cache_plane(c, u.layer, u.head, 0) + row0 * lr;
     char* dst = link_packed(c) ? packed_slot(c, slot) : slot_k(c, slot);
+    const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
+    TimedSpan sp;
+    if (timed) HI_TRY(span_begin(c, 2, &sp, c->sh));
     HI_HIP(hipMemcpy2DAsync(dst, (size_t)(st * lr), hk, (size_t)(c->prob.max_context * lr), (size_t)(rows * lr),
                             (size_t)(2 * u.nh), hipMemcpyHostToDevice, c->sh));
+    if (timed) HI_TRY(span_end(c, sp, c->sh));
     c->stats.n_h2d_copies += 1;
     c->stats.bytes_h2d += 2 * rows * lr * u.nh;
   }
@@ -201,37 +230,32 @@ hi_status retire_slice(hi_ctx* c, int slot) {
   return HI_OK;
 }
 
-hi_status span_begin(hi_ctx* c, int kind, TimedSpan* out) {
-  TimedSpan s;
-  if (!c->span_pool.empty()) {
-    s = c->span_pool.back();
-    c->span_pool.pop_back();
-  } else {
-    HI_HIP(hipEventCreate(&s.start));
-    HI_HIP(hipEventCreate(&s.stop));
-  }
-  s.kind = kind;
-  HI_HIP(hipEventRecord(s.start, c->sc));
-  *out = s;
-  return HI_OK;
-}
-
-hi_status span_end(hi_ctx* c, TimedSpan& s) {
-  HI_HIP(hipEventRecord(s.stop, c->sc));
-  c->spans.push_back(s);
-  return HI_OK;
-}
-
 hi_status collect_spans(hi_ctx* c) {
   for (auto& s : c->spans) {
     HI_HIP(hipEventSynchronize(s.stop));
     float ms = 0.f;
     HI_HIP(hipEventElapsedTime(&ms, s.start, s.stop));
-    if (s.kind == 0) c->stats.prefill_kernel_ms += ms;
-    else c->stats.decode_kernel_ms += ms;
+    switch (s.kind) {
+      case 0: c->stats.prefill_kernel_ms += ms; break;
+      case 1: c->stats.decode_kernel_ms += ms; break;
+      case 2: c->stats.h2d_copy_ms += ms; break;
+      case 3: c->stats.d2h_copy_ms += ms; break;
+      default: c->stats.exposed_copy_ms += ms; break;
+    }
     c->span_pool.push_back(s);
   }
   c->spans.clear();
+  return HI_OK;
+}
+
+// the compute stream waits for a slice; with timing on, the wait is bracketed by two events of that stream: what
+// they measure is the part of the slice's transfer that no kernel covered
+hi_status wait_slice(hi_ctx* c, int slot) {
+  const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
+  TimedSpan sp;
+  if (timed) HI_TRY(span_begin(c, 4, &sp));
+  HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
+  if (timed) HI_TRY(span_end(c, sp));
   return HI_OK;
 }
 
@@ -252,7 +276,8 @@ hi_status pace_end(hi_ctx* c) {
 }
 
 int pf_variant(const hi_ctx* c) {
-  return (c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_DEEP) ? 3 : 0;
+  return ((c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_DEEP) ? 3 : 0) |
+         ((c->flags & HI_FLAG_PREFILL_PAIRED) ? 4 : 0) | ((c->flags & HI_FLAG_PREFILL_UNPAIRED) ? 8 : 0);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -261,6 +286,10 @@ hi_status check_unit_args(const hi_ctx* c, int layer, int head, int nh, const vo
                           int64_t past, int64_t len, const void* out, int next_layer, int next_head, int next_nh,
                           int64_t next_past) {
   if (!c) { set_last_error("ctx is null"); return HI_ERR_ARG; }
+  if (c->failed) {
+    set_last_error("an earlier call failed after it had enqueued work: the context can only be synchronised and destroyed");
+    return HI_ERR_HIP;
+  }
   if (!q || !k || !v || !out) { set_last_error("null buffer"); return HI_ERR_ARG; }
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) { set_last_error("buffers must be 16-byte aligned"); return HI_ERR_ARG; }
   if (layer < 0 || layer >= c->prob.n_layers || head < 0 || nh < 1 || head + nh > c->prob.n_kv_heads) { set_last_error("layer/head out of range"); return HI_ERR_ARG; }
@@ -278,6 +307,11 @@ hi_status check_unit_args(const hi_ctx* c, int layer, int head, int nh, const vo
   if (c->mode == HI_MODE_OFFLOAD && ((ring_now && (int64_t)nh * 64 > c->slice_tokens) || (ring_next && (int64_t)next_nh * 64 > c->slice_tokens))) {
     set_last_error("a staging slice of %lld rows cannot hold 64 rows of each head of the group", (long long)c->slice_tokens);
     return HI_ERR_HBM_BUDGET;
+  }
+  if ((unit_kind(c, layer, head) != 2 && !c->kv_layer[layer]) ||
+      (next_layer >= 0 && unit_kind(c, next_layer, next_head) != 2 && !c->kv_layer[next_layer])) {
+    set_last_error("no cache was given for this layer (hi_ctx_create / hi_ctx_set_layer_cache)");
+    return HI_ERR_ARG;
   }
   if (past < 0 || len < 1) { set_last_error("negative past_len or empty call"); return HI_ERR_ARG; }
   if (len > c->prob.chunk || past + len > c->prob.max_context) { set_last_error("past_len %lld + len %lld exceeds the plan", (long long)past, (long long)len); return HI_ERR_RANGE; }
@@ -316,16 +350,20 @@ hi_status write_back_packed(hi_ctx* c, int layer, int head, int nh, const void* 
   HI_TRY(launch_kv_quant(c->sc, v_new, len * kRowBytes, qv, len * lr, len, nh));
   HI_HIP(hipEventRecord(c->ev_entry, c->sc));
   HI_HIP(hipStreamWaitEvent(c->sd, c->ev_entry, 0));
+  const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
+  TimedSpan sp;
+  if (timed) HI_TRY(span_begin(c, 3, &sp, c->sd));
   if (!(c->flags & HI_FLAG_SKIP_COPIES)) {
     // the heads' K planes (and V planes) are two planes apart in the cache: one strided copy each
     const size_t dpitch = (size_t)(2 * c->prob.max_context * lr), w = (size_t)(len * lr);
-    HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 0) + past * lr, dpitch, qk, w, w, (size_t)nh,
+    HI_HIP(hipMemcpy2DAsync(cache_plane(c, layer, head, 0) + past * lr, dpitch, qk, w, w, (size_t)nh,
                             hipMemcpyDeviceToHost, c->sd));
-    HI_HIP(hipMemcpy2DAsync(c->kv + plane_offset(c, layer, head, 1) + past * lr, dpitch, qv, w, w, (size_t)nh,
+    HI_HIP(hipMemcpy2DAsync(cache_plane(c, layer, head, 1) + past * lr, dpitch, qv, w, w, (size_t)nh,
                             hipMemcpyDeviceToHost, c->sd));
     c->stats.bytes_d2h += 2 * len * lr * nh;
     c->stats.n_d2h_copies += 2;
   }
+  if (timed) HI_TRY(span_end(c, sp, c->sd));
   HI_HIP(hipEventRecord(c->ev_wbq[b], c->sd));
   c->wbq_valid[b] = 1;
   for (int j = 0; j < nh; ++j) {
@@ -341,10 +379,13 @@ hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, 
                      int64_t len) {
   const bool resident = unit_resident(c, layer, head);
   if (!resident && link_packed(c)) return write_back_packed(c, layer, head, nh, k_new, v_new, past, len);
+  const bool timed = !resident && (c->flags & HI_FLAG_TIME_KERNELS) != 0;
+  TimedSpan sp;
   if (!resident) {
     // the new rows were produced by earlier work on the compute stream
     HI_HIP(hipEventRecord(c->ev_entry, c->sc));
     HI_HIP(hipStreamWaitEvent(c->sd, c->ev_entry, 0));
+    if (timed) HI_TRY(span_begin(c, 3, &sp, c->sd));
   }
   if (nh > 1) {
     // the heads' K planes (and V planes) are two planes apart in the cache: one strided copy each
@@ -352,8 +393,8 @@ hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, 
     hipStream_t st = resident ? c->sc : c->sd;
     if (resident || !(c->flags & HI_FLAG_SKIP_COPIES)) {
       const size_t dpitch = (size_t)(2 * c->prob.max_context * kRowBytes), w = (size_t)(len * kRowBytes);
-      char* dk = resident ? res_plane(c, layer, head, 0) : c->kv + plane_offset(c, layer, head, 0);
-      char* dv = resident ? res_plane(c, layer, head, 1) : c->kv + plane_offset(c, layer, head, 1);
+      char* dk = resident ? res_plane(c, layer, head, 0) : cache_plane(c, layer, head, 0);
+      char* dv = resident ? res_plane(c, layer, head, 1) : cache_plane(c, layer, head, 1);
       HI_HIP(hipMemcpy2DAsync(dk + past * kRowBytes, dpitch, k_new, w, w, (size_t)nh, kind, st));
       HI_HIP(hipMemcpy2DAsync(dv + past * kRowBytes, dpitch, v_new, w, w, (size_t)nh, kind, st));
       if (!resident) {
@@ -363,8 +404,8 @@ hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, 
     }
   }
   for (int j = 0; j < (nh > 1 ? 0 : 1); ++j) {
-    char* dk = (resident ? res_plane(c, layer, head + j, 0) : c->kv + plane_offset(c, layer, head + j, 0)) + past * kRowBytes;
-    char* dv = (resident ? res_plane(c, layer, head + j, 1) : c->kv + plane_offset(c, layer, head + j, 1)) + past * kRowBytes;
+    char* dk = (resident ? res_plane(c, layer, head + j, 0) : cache_plane(c, layer, head + j, 0)) + past * kRowBytes;
+    char* dv = (resident ? res_plane(c, layer, head + j, 1) : cache_plane(c, layer, head + j, 1)) + past * kRowBytes;
     const char* sk = (const char*)k_new + j * len * kRowBytes;
     const char* sv = (const char*)v_new + j * len * kRowBytes;
     if (resident) {
@@ -378,11 +419,30 @@ hi_status write_back(hi_ctx* c, int layer, int head, int nh, const void* k_new, 
     }
   }
   if (!resident) {
+    if (timed) HI_TRY(span_end(c, sp, c->sd));
     for (int j = 0; j < nh; ++j) {
       const int idx = layer * c->prob.n_kv_heads + head + j;
       HI_HIP(hipEventRecord(c->ev_wb[idx], c->sd));
       c->wb_valid[idx] = 1;
     }
+  }
+  return HI_OK;
+}
+
+// the cache must be pinned host memory (offload) or device memory (resident)
+hi_status check_cache_memory(int mode, const void* p) {
+  hipPointerAttribute_t attr;
+  const hipError_t e = hipPointerGetAttributes(&attr, p);
+  if (mode == HI_MODE_OFFLOAD) {
+    if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
+      (void)hipGetLastError();
+      set_last_error("kv_cache is not pinned host memory");
+      return HI_ERR_NOT_PINNED;
+    }
+  } else if (e != hipSuccess || attr.type != hipMemoryTypeDevice) {
+    (void)hipGetLastError();
+    set_last_error("resident kv_cache is not device memory");
+    return HI_ERR_NOT_PINNED;
   }
   return HI_OK;
 }
@@ -395,7 +455,7 @@ extern "C" hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* pla
   if (!out || !plan) { set_last_error("null argument"); return HI_ERR_ARG; }
   HI_TRY(validate_problem(problem));
   if (mode != HI_MODE_OFFLOAD && mode != HI_MODE_RESIDENT) { set_last_error("unknown mode"); return HI_ERR_ARG; }
-  if (!kv_cache || !hbm_workspace || ((mode == HI_MODE_OFFLOAD || problem->streaming_heads > 0) && !hbm_staging)) { set_last_error("null buffer"); return HI_ERR_ARG; }
+  if (!hbm_workspace || ((mode == HI_MODE_OFFLOAD || problem->streaming_heads > 0) && !hbm_staging)) { set_last_error("null buffer"); return HI_ERR_ARG; }
   if (problem->link_kv_bits == 4 && mode != HI_MODE_OFFLOAD) {
     set_last_error("link_kv_bits = 4 describes the host link: offload mode only");
     return HI_ERR_UNSUPPORTED;
@@ -404,26 +464,20 @@ extern "C" hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* pla
   HI_TRY(hi_offload_plan(problem, &ref));
   if (std::memcmp(&ref, plan, sizeof(ref)) != 0) { set_last_error("plan does not belong to this problem"); return HI_ERR_ARG; }
 
-  hipPointerAttribute_t attr;
-  hipError_t e = hipPointerGetAttributes(&attr, kv_cache);
-  if (mode == HI_MODE_OFFLOAD) {
-    if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
-      (void)hipGetLastError();
-      set_last_error("kv_cache is not pinned host memory");
-      return HI_ERR_NOT_PINNED;
-    }
-  } else if (e != hipSuccess || attr.type != hipMemoryTypeDevice) {
-    (void)hipGetLastError();
-    set_last_error("resident kv_cache is not device memory");
-    return HI_ERR_NOT_PINNED;
-  }
+  if (kv_cache) HI_TRY(check_cache_memory(mode, kv_cache));
+  hipError_t e = hipSuccess;
 
   hi_ctx* c = new (std::nothrow) hi_ctx();
   if (!c) { set_last_error("out of host memory"); return HI_ERR_ARG; }
   c->prob = *problem;
   c->plan = *plan;
   c->mode = mode;
-  c->kv = (char*)kv_cache;
+  {  // one pointer for the whole cache: layer l starts l * (bytes of a layer) behind it
+    const int64_t layer_bytes = plan->host_bytes_total / problem->n_layers;
+    c->kv_layer.assign(problem->n_layers, nullptr);
+    if (kv_cache)
+      for (int l = 0; l < problem->n_layers; ++l) c->kv_layer[l] = (char*)kv_cache + l * layer_bytes;
+  }
   c->staging = (char*)hbm_staging;
   c->ws = (char*)hbm_workspace;
   c->sc = (hipStream_t)stream_compute;
@@ -475,9 +529,25 @@ extern "C" hi_status hi_ctx_destroy(hi_ctx* c) {
   return HI_OK;
 }
 
+extern "C" hi_status hi_ctx_set_layer_cache(hi_ctx* c, int32_t layer, void* kv_layer) {
+  if (!c || !kv_layer || layer < 0 || layer >= c->prob.n_layers) { set_last_error("layer cache: bad argument"); return HI_ERR_ARG; }
+  HI_TRY(check_cache_memory(c->mode, kv_layer));
+  // work that reads or writes the layer's previous rows may still be queued
+  HI_HIP(hipStreamSynchronize(c->sh));
+  HI_HIP(hipStreamSynchronize(c->sc));
+  HI_HIP(hipStreamSynchronize(c->sd));
+  if (c->pend.valid && c->pend.layer == layer) {      // a prefetch of the old rows is in the ring: drop it
+    for (int64_t i = 0; i < c->pend.issued; ++i) HI_TRY(retire_slice(c, (int)((c->pend.first_seq + i) % c->n_slots)));
+    c->pend.valid = false;
+  }
+  c->kv_layer[layer] = (char*)kv_layer;
+  return HI_OK;
+}
+
 extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
   if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS | HI_FLAG_PREFILL_NARROW |
-                      HI_FLAG_PREFILL_DEEP))) { set_last_error("bad flags"); return HI_ERR_ARG; }
+                      HI_FLAG_PREFILL_PAIRED | HI_FLAG_PREFILL_DEEP | HI_FLAG_PREFILL_UNPAIRED |
+                      HI_FLAG_INJECT_FAILURE))) { set_last_error("bad flags"); return HI_ERR_ARG; }
   c->flags = flags;
   return HI_OK;
 }
@@ -513,6 +583,24 @@ static hi_status prefetch_hint(hi_ctx* c, const hi_ctx::Unit& next) {
   return top_up(c, none, p);
 }
 
+// A call runs in two parts: checks that can refuse it (nothing enqueued yet, the cache and the ring untouched), then
+// the enqueues.  An error in the second part leaves copies, kernels and the ring's bookkeeping half-advanced - the
+// next call could hand a kernel a slot whose copy was never issued - so it closes the context: every later call is
+// refused until the context is destroyed.
+template <class F>
+static hi_status guarded(hi_ctx* c, F&& body) {
+  c->enqueuing = false;
+  hi_status st = pace_begin(c);
+  if (st == HI_OK) st = body();
+  if (st == HI_OK) {
+    c->enqueuing = true;
+    st = pace_end(c);
+  }
+  if (st != HI_OK && c->enqueuing) c->failed = true;
+  c->enqueuing = false;
+  return st;
+}
+
 // One prefill unit: a group of nh KV heads starting at kv_head (nh = 1: the paper's finest granularity).
 static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t nh, const void* q_dev,
                               const void* k_new_dev, const void* v_new_dev, int64_t past_len, int32_t chunk_len,
@@ -531,6 +619,27 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
     c->stats.n_prefill_kernels += 1;
     return HI_OK;
   };
+
+  // Everything that can be refused is refused here, before the first enqueue: the state images of the chosen
+  // kernel must fit the carry, the encoded rows the write-back buffer.
+  if (!unit_streaming(c, kv_head)) {
+    const PrefillLaunch shape = prefill_launch_shape(G, chunk_len, nh, pf_variant(c), 1, 1);
+    if (shape.carry_bytes > c->plan.ws_partials_offset) {
+      set_last_error("prefill: the workspace holds %lld bytes of attention state, %lld needed",
+                     (long long)c->plan.ws_partials_offset, (long long)shape.carry_bytes);
+      return HI_ERR_UNSUPPORTED;
+    }
+    if (!unit_resident(c, layer, kv_head) && link_packed(c) &&
+        2 * (int64_t)nh * chunk_len * link_row(c) > c->plan.ws_writeback_bytes / 2) {
+      set_last_error("prefill: write-back buffer too small for %d heads x %d rows", nh, chunk_len);
+      return HI_ERR_UNSUPPORTED;
+    }
+  }
+  c->enqueuing = true;
+  if (c->flags & HI_FLAG_INJECT_FAILURE) {       // test hook: behave as if a launch had failed half-way
+    set_last_error("injected failure");
+    return HI_ERR_HIP;
+  }
 
   hi_ctx::Unit next = hinted_unit(c, next_layer, next_kv_head, next_nh, next_past_len);
   if (unit_streaming(c, kv_head)) {
@@ -570,7 +679,7 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
     const int slot = (int)((cur.first_seq + i) % c->n_slots);
     int64_t rows = past_len - i * st;
     if (rows > st) rows = st;
-    HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
+    HI_TRY(wait_slice(c, slot));
     if (run) {
       HI_TRY(expand_slice(c, slot, rows, nh));
       const bool is_last = (i == ns - 1);
@@ -611,6 +720,26 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
     c->stats.n_decode_kernels += 1;
     return HI_OK;
   };
+
+  // refusals come before the first enqueue
+  if (unit_kind(c, layer, kv_head) == 0 && slices_of(c, past_len, nh) * n_split > part_cap) {
+    set_last_error("decode: the partial workspace cannot hold %lld slices x %d partitions",
+                   (long long)slices_of(c, past_len, nh), n_split);
+    return HI_ERR_UNSUPPORTED;
+  }
+  if (unit_kind(c, layer, kv_head) != 0 && n_split > part_cap) {
+    set_last_error("decode: the partial workspace cannot hold %d partitions", n_split);
+    return HI_ERR_UNSUPPORTED;
+  }
+  if (unit_kind(c, layer, kv_head) == 0 && link_packed(c) && 2 * (int64_t)nh * link_row(c) > c->plan.ws_writeback_bytes / 2) {
+    set_last_error("decode: write-back buffer too small for %d heads", nh);
+    return HI_ERR_UNSUPPORTED;
+  }
+  c->enqueuing = true;
+  if (c->flags & HI_FLAG_INJECT_FAILURE) {       // test hook: behave as if a launch had failed half-way
+    set_last_error("injected failure");
+    return HI_ERR_HIP;
+  }
 
   hi_ctx::Unit next = hinted_unit(c, next_layer, next_kv_head, next_nh, next_past_len);
   if (unit_streaming(c, kv_head)) {
@@ -662,11 +791,6 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
     return write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, 1);
   }
 
-  if (slices_of(c, past_len, nh) * n_split > part_cap) {      // before anything is enqueued
-    set_last_error("decode: the partial workspace cannot hold %lld slices x %d partitions",
-                   (long long)slices_of(c, past_len, nh), n_split);
-    return HI_ERR_UNSUPPORTED;
-  }
   HI_TRY(adopt_unit(c, layer, kv_head, nh, past_len));
   HI_TRY(write_back(c, layer, kv_head, nh, k_new_dev, v_new_dev, past_len, 1));
   hi_ctx::Unit& cur = c->pend;
@@ -678,7 +802,7 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
     const int slot = (int)((cur.first_seq + i) % c->n_slots);
     int64_t rows = past_len - i * st;
     if (rows > st) rows = st;
-    HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
+    HI_TRY(wait_slice(c, slot));
     if (run) {
       HI_TRY(expand_slice(c, slot, rows, nh));
       const int np = splits_for(rows);
@@ -705,10 +829,10 @@ extern "C" hi_status hi_prefill_group(hi_ctx* c, int32_t layer, int32_t kv_head,
                                       int32_t next_n_heads, int64_t next_past_len) {
   HI_TRY(check_unit_args(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev,
                          next_layer, next_kv_head, next_n_heads, next_past_len));
-  HI_TRY(pace_begin(c));
-  HI_TRY(prefill_impl(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
-                      next_kv_head, next_n_heads, next_past_len));
-  return pace_end(c);
+  return guarded(c, [&] {
+    return prefill_impl(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, chunk_len, out_dev, next_layer,
+                        next_kv_head, next_n_heads, next_past_len);
+  });
 }
 
 extern "C" hi_status hi_decode_group(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t n_heads, const void* q_dev,
@@ -717,10 +841,10 @@ extern "C" hi_status hi_decode_group(hi_ctx* c, int32_t layer, int32_t kv_head, 
                                      int64_t next_past_len) {
   HI_TRY(check_unit_args(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, 1, out_dev, next_layer,
                          next_kv_head, next_n_heads, next_past_len));
-  HI_TRY(pace_begin(c));
-  HI_TRY(decode_impl(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, out_dev, next_layer,
-                     next_kv_head, next_n_heads, next_past_len));
-  return pace_end(c);
+  return guarded(c, [&] {
+    return decode_impl(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_len, out_dev, next_layer,
+                       next_kv_head, next_n_heads, next_past_len);
+  });
 }
 
 extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,

@@ -23,7 +23,7 @@ inline int prefill_strip(int G) { return 32 * (4 / (G < 4 ? G : 4)); }
 inline int prefill_grid_y(int G) { return G > 4 ? G / 4 : 1; }
 
 // The 8-wave prefill kernel covers 2 * strip positions per workgroup.  When a chunk gives it fewer workgroups than
-// would fill the chip, `split` workgroups share each block of positions and divide the K/V rows of every launch
+// would fill the chip, `split` workgroups share each block of positions and divide the tiles of every launch
 // between them (their states are merged after the unit's last launch).  The launcher picks that kernel when
 // workgroups * split reaches kPrefillDeepMinWorkgroups, the 4-wave kernel otherwise.
 constexpr int kPrefillFillWorkgroups = 192;
@@ -35,14 +35,54 @@ inline int prefill_split(int G, int64_t chunk_len, int n_heads = 1) {
   while (wgs * split < kPrefillFillWorkgroups && split < kPrefillMaxSplit) split *= 2;
   return split;
 }
-// upper bound, in images of a 4-wave workgroup's state (256 lanes x 66 floats), of the carry any prefill launch
-// of chunks up to C rows over groups of up to n_heads heads can need.  The 8-wave kernel's images count double;
-// its split keeps workgroups * split below 2 * kPrefillFillWorkgroups unless the chunk alone exceeds that, and a
-// triangle-dominated unit doubles the split once more.
-inline int64_t prefill_carry_images(int G, int64_t C, int n_heads) {
-  const int64_t narrow = (ceil_div(C, prefill_strip(G)) + 1) * prefill_grid_y(G) * n_heads;
-  const int64_t split_bound = 2 * (2 * kPrefillFillWorkgroups + prefill_grid_y(G) * n_heads);
-  return 2 * (narrow > split_bound ? narrow : split_bound);
+// What one launch of a prefill unit looks like (host side; the kernels derive the rest from these numbers).
+// variant: low two bits 0 = pick the kernel by chunk length, 1 = 4-wave kernel, 3 = 8-wave kernel; + 4: pair deep and
+// shallow blocks in every last launch that has two blocks, + 8: never pair (measurement).
+constexpr int kPdLanes = 512;                   // lanes of an 8-wave workgroup
+constexpr int kPrefillPairMinTiles = 4;         // pair when it saves the deepest workgroup at least this many tiles
+struct PrefillLaunch {
+  int deep;            // 8-wave kernel (else the 4-wave one)
+  int split;           // workgroups per block of positions
+  int paired;          // balanced partition over (deep, shallow) pairs of blocks
+  int nbk;             // blocks of positions per head (8-wave kernel)
+  int merge;           // a merge launch follows
+  int64_t carry_bytes; // state images the launches of this unit address in the carry
+};
+inline PrefillLaunch prefill_launch_shape(int G, int64_t chunk_len, int n_heads, int variant, int last, int has_own) {
+  PrefillLaunch p;
+  const int strip = prefill_strip(G), gy = prefill_grid_y(G), base = variant & 3;
+  p.split = prefill_split(G, chunk_len, n_heads);
+  p.nbk = (int)ceil_div(chunk_len, 2 * strip);
+  p.deep = base == 3 || (base == 0 && (int64_t)p.nbk * gy * n_heads * p.split >= kPrefillDeepMinWorkgroups);
+  p.paired = p.merge = 0;
+  if (p.deep) {
+    // tiles the workgroups of the deepest block sweep beyond the average (the causal triangle), which pairing removes
+    const int64_t saved = (int64_t)(2 * strip / 64) * (p.nbk - 1) / (2 * p.split);
+    p.paired = last && has_own && p.nbk >= 2 && !(variant & 8) && ((variant & 4) || saved >= kPrefillPairMinTiles);
+    p.merge = last && (p.split > 1 || p.paired);
+    p.carry_bytes = (int64_t)2 * p.nbk * p.split * gy * n_heads * kPdLanes * kCarryFloatsPerLane * 4;
+  } else {
+    p.split = 1;
+    p.carry_bytes = ceil_div(chunk_len, strip) * gy * n_heads * kWgThreads * kCarryFloatsPerLane * 4;
+  }
+  return p;
+}
+// the largest carry any launch of chunks up to C rows over groups of up to n_heads heads can address, whatever the
+// kernel variant (both kernels' image counts are step functions of the chunk length with steps at multiples of strip)
+inline int64_t prefill_carry_bound(int G, int64_t C, int n_heads) {
+  const int strip = prefill_strip(G);
+  int64_t worst = 0;
+  for (int64_t len = strip; ; len += strip) {
+    const int64_t l = len < C ? len : C;
+    for (int nh = 1; nh <= n_heads; ++nh)
+      for (int variant = 0; variant <= 3; ++variant) {
+        if (variant == 2) continue;
+        const int64_t need = prefill_launch_shape(G, l, nh, variant, 1, 1).carry_bytes;
+        if (need > worst) worst = need;
+      }
+    if (len >= C) break;
+  }
+  return worst;
 }
 
 // floats of decode partials one head can produce (one launch per staging slice, n_split partials each; a head of
@@ -65,8 +105,7 @@ struct PrefillSegment {
 
 // One launch of the prefill kernel over up to two KV segments.  first: start from an empty softmax state
 // instead of loading the carry; last: normalise and write `out` instead of storing the carry.
-// variant: 0 = pick by chunk length (the 8-wave kernel, split over the rows if need be, when that fills the chip,
-// else the 4-wave one), 1 = 4-wave kernel (2 LDS stages), 3 = 8-wave kernel; every launch of one unit must use the same variant (the carry layouts differ).
+// variant: as at prefill_launch_shape; every launch of one unit must use the same variant (the carry layouts differ).
 // carry_bytes: size of the carry buffer (checked against what the launch will use; -1: not checked).
 // n_heads > 1: one launch over a group of KV heads; q is [n_heads][G][chunk_len][128], out likewise, the causal
 // segment's rows [n_heads][chunk_len][128], the other segment's heads head_stride bytes apart.

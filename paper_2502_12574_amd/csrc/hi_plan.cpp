@@ -147,7 +147,7 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   pl.prefill_rows_per_wg = prefill_strip(G);
 
   // any kernel variant: the same bytes per position, times the split-KV factor of the 8-wave kernel
-  const int64_t carry_bytes = prefill_carry_images(G, C, p->n_kv_heads) * kWgThreads * kCarryFloatsPerLane * 4;
+  const int64_t carry_bytes = prefill_carry_bound(G, C, p->n_kv_heads);
   const int64_t partial_bytes = decode_part_head_stride(S, slice, pl.n_split_decode, G) * 4 * p->n_kv_heads;
   pl.ws_partials_offset = round_up(carry_bytes, 256);
   pl.ws_writeback_offset = pl.ws_partials_offset + round_up(partial_bytes, 256);

@@ -26,6 +26,7 @@
 #include <type_traits>
 #include "hi_device.h"
 #include "hi_internal.h"
+#include "hi_prefill_part.h"
 
 namespace hi {
 
@@ -43,9 +44,11 @@ struct PrefillArgs {
   void* out;              // [G][C][128]
   int G, C, first, last, out_fp32;
   float c;                // log2(e) / sqrt(d)
-  int split;              // 8-wave kernel: workgroups along grid z share a block of positions and divide the rows
+  int split;              // 8-wave kernel: workgroups per block of positions (they divide the block's tile sequence)
   int gy;                 // grid y per head; blockIdx.y / gy is the head of a group launch
   int64_t a_head_stride;  // bytes between the heads' rows in the past segment
+  int paired;             // 8-wave kernel: deep and shallow blocks of the causal triangle share their tiles
+  int nbk;                // 8-wave kernel: blocks of positions per head
 };
 
 // Group launches: point the arguments at this workgroup's head; returns blockIdx.y within the head.
@@ -583,13 +586,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
 
   const int gl = a.G < 4 ? a.G : 4;
   const int strip = 32 * (kPdWaves / gl);
-  const int bx = gridDim.x - 1 - blockIdx.x;
   const int g = pf_select_head(a) * 4 + (wave % gl);
-  const int i0 = bx * strip + 32 * (wave / gl);
-  const int i_hi = bx * strip + strip - 1;
-  int qi = i0 + col;
-  const int my_i = qi;
-  if (qi > a.C - 1) qi = a.C - 1;
 
   PfLaneConst lc;
   {
@@ -615,258 +612,290 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
     }
   }
 
-  // Q^T operand: lane holds q[g][qi][16*kk + 8*hl .. +7]
-  bf16x8 qf[8];
-  {
-    const uint16_t* qrow = a.q + ((int64_t)g * a.C + qi) * kHeadDim + 8 * hl;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 16 * kk));
-  }
 
-  // This workgroup's tile sequence: the past segment's tiles, then the chunk's own tiles up to its causal boundary.
-  // Split-KV: workgroup z of a.split takes the part [T z / split, T (z + 1) / split) of that sequence, keeps its
-  // own state in the carry, and prefill_merge_kernel merges the states after the unit's last launch.  A split with
-  // nothing to do in this launch leaves (or initialises) its state.
-  int b_t0 = 0;                       // first tile of the chunk's own rows this workgroup takes
-  int tb;                             // and how many
-  {
-    const int64_t ta_all = (a.na + kPfTileRows - 1) / kPfTileRows;
-    const int64_t nb_vis = a.nb < (int64_t)i_hi + 1 ? a.nb : (int64_t)i_hi + 1;
-    const int64_t tb_all = (nb_vis + kPfTileRows - 1) / kPfTileRows;
-    tb = (int)tb_all;
-    if (a.split > 1) {
-      const int64_t t_all = ta_all + tb_all;
-      const int64_t g0 = t_all * blockIdx.z / a.split, g1 = t_all * (blockIdx.z + 1) / a.split;
-      const int64_t a0 = g0 < ta_all ? g0 : ta_all, a1 = g1 < ta_all ? g1 : ta_all;
-      const int64_t r0 = a0 * kPfTileRows;
-      int64_t r1 = a1 * kPfTileRows;
-      if (r1 > a.na) r1 = a.na;
-      a.ka += r0 * kRowBytes;
-      a.va += r0 * kRowBytes;
-      a.na = r1 - r0;
-      b_t0 = (int)((g0 > ta_all ? g0 : ta_all) - ta_all);
-      tb = (int)((g1 > ta_all ? g1 : ta_all) - ta_all) - b_t0;
-      a.last = 0;
-    }
-  }
-
-  PfState st;
+  // How the launch divides its tiles among workgroups is pure arithmetic on the launch's shape: at most two passes
+  // per workgroup, each over a range of one block's tile sequence (its past tiles, then the chunk's own tiles up to
+  // the block's causal boundary), each with a softmax state of its own.
+  PfShape sh;
+  sh.nbk = a.nbk; sh.m = strip / kPfTileRows;
+  sh.ta = (int)((a.na + kPfTileRows - 1) / kPfTileRows);
+  sh.tb_all = (int)((a.nb + kPfTileRows - 1) / kPfTileRows);
+  sh.split = a.split; sh.paired = a.paired; sh.carried = !a.first;
   constexpr int kLanes = kPdWaves * 64;
-  const int64_t wg_linear = ((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-  float* carry = a.carry + wg_linear * (kCarryFloatsPerLane * kLanes) + threadIdx.x;
-  if (a.na <= 0 && tb <= 0) {      // no tile for this workgroup in this launch
-    if (a.first) {
-#pragma unroll
-      for (int i = 0; i < 64; ++i) carry[i * kLanes] = 0.f;
-      carry[64 * kLanes] = kNegBig;
-      carry[65 * kLanes] = 0.f;
-    }
-    return;
-  }
-  if (a.first) {
-    st.m = kNegBig;
-    st.l = 0.f;
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
-  } else {
-#pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) st.o[db][r] = carry[(db * 16 + r) * kLanes];
-    st.m = carry[64 * kLanes];
-    st.l = carry[65 * kLanes];
-  }
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) asm volatile("" : "+v"(qf[kk]));
-  asm volatile("" : "+v"(st.m), "+v"(st.l));
-#pragma unroll
-  for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(st.o[db]));
-
-  const int ta = (int)((a.na + kPfTileRows - 1) / kPfTileRows);
-  const int T = ta + tb;
-  const int tb_base = b_t0 - ta;      // tile t >= ta of the sweep is tile t + tb_base of the chunk's own rows
-
-  // K tile t (which = 0) or V tile t (which = 1) of the sweep: this wave's share of its loads
-  auto issue = [&](int t, int which) __attribute__((always_inline)) {
-    if (t >= T) return;
-    const bool in_b = t >= ta;
-    const int64_t row0 = (int64_t)(in_b ? t + tb_base : t) * kPfTileRows;
-    const int64_t left = (in_b ? a.nb : a.na) - row0;
-    const int rows = left < kPfTileRows ? (int)left : kPfTileRows;
-    const uint32_t slot = lds_base + (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes;
-    if (which == 0) pf_issue_k<kPdWaves>((in_b ? a.kb : a.ka) + row0 * kRowBytes, rows, slot, wave, lane, lc);
-    else pf_issue_v<kPdWaves>((in_b ? a.vb : a.va) + row0 * kRowBytes, rows, slot + kPdVRing, wave, lane, lc);
-  };
-  // Every wave issues, in this order: K0 | K1 V0 | K2 V1 | then, in the matrix phase of tile t, K(t+3) V(t+2)
-  // (2 instructions each).  The one wait per tile is at the end of the softmax phase of tile t: everything up to
-  // V(t+1) has landed when at most K(t+3) V(t+2) are still in flight.
-  auto wait_landed = [&](int t) {
-    if (t + 3 < T) wait_vmcnt<4>();
-    else wait_vmcnt<0>();
-  };
-  auto phase_barrier = [&]() {
-    __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
-    __builtin_amdgcn_sched_barrier(0);
-  };
-
-  // The two wavefronts of a SIMD alternate: while one runs its matrix phase (O += V P of the previous tile, then
-  // the scores of the next), the other runs its softmax phase on the vector ALU.  Both groups execute the same
-  // program with two barriers per tile; group 1 passes one extra barrier first, so it is always one phase behind
-  // (and group 0 passes one extra at the end: every wave executes the same number of barriers).
-  //   phase index (barriers passed so far):  group 0: matrix(t) = 2t, softmax(t) = 2t + 1;  group 1: one later.
-  //   Reads: K(t) in phases 2t, 2t+1; V(t) in phases 2t+1 (operands read ahead during softmax(t)) .. 2t+3.
-  //   Writes: K(t+3) replaces K(t-1) (last read in phase 2t-1) and V(t+2) replaces V(t-2) (last read in phase
-  //   2t-1): both are issued in matrix(t), phase >= 2t.
-  //   Landing: each wave waits at the end of softmax(t-1) for its share of everything up to V(t): that is phase
-  //   2t at the latest, and K(t+1) is first read in phase 2t+2, V(t) in phase 2t+1.
-  const int group = wave >> 2;       // waves w and w + 4 share a SIMD
-  const float c = a.c;
-  issue(0, 0);
-  issue(1, 0); issue(0, 1);
-  issue(2, 0); issue(1, 1);
-  wait_landed(-1);                           // K(0), K(1), V(0)
-  phase_barrier();
-  if (group == 1) phase_barrier();
-
-  f32x16 sc[2];
-  bf16x8 pb[2][2];
-  auto softmax_phase = [&](int t) __attribute__((always_inline)) {
-    const bool in_b = t >= ta;
-    const int64_t j0 = (int64_t)(in_b ? t + tb_base : t) * kPfTileRows;
-    const int64_t n_seg = in_b ? a.nb : a.na;
-    const bool masked = (j0 + kPfTileRows > n_seg) || (in_b && (j0 + kPfTileRows - 1 > i0));
-    int rel = kPfTileRows;
-    if (masked) {
-      int64_t lim = n_seg - 1;
-      if (in_b && (int64_t)my_i < lim) lim = my_i;
-      const int64_t d = lim - j0;
-      rel = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
-    }
-    pf_softmax(sc, st, c, masked, rel, hl, pb);
-  };
-  // tile 0: nothing to accumulate yet
-  issue(3, 0);
-  issue(2, 1);
-#pragma unroll
-  for (int r = 0; r < 16; ++r) { sc[0][r] = 0.f; sc[1][r] = 0.f; }
-#pragma unroll
-  for (int i = 16; i < 32; ++i)
-    sc[pd_sb(i)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, 0, 0, lc), qf[pd_kk(i)], sc[pd_sb(i)], 0, 0, 0);
-  phase_barrier();
-  softmax_phase(0);
-  wait_landed(0);
-  phase_barrier();
-  bf16x8 pre[kPfAhead];
-  f32x16 negm;       // minus the row's running reference, the start value of the steady-state score accumulators
-#pragma unroll
-  for (int r = 0; r < 16; ++r) negm[r] = 0.f;
-  // any tile t >= 1
-  auto generic_tile = [&](int t) __attribute__((always_inline)) {
-    // K(t+3) and V(t+2): full tiles are issued from inside the matrix phase, partial ones (row clamping) here
-    PfPhaseLoads ld;
-    ld.k = ld.v = nullptr;
-    const int tk = t + 3, tv = t + 2;
-    const bool kb = tk >= ta, vb = tv >= ta;
-    const int64_t krow0 = (int64_t)(kb ? tk + tb_base : tk) * kPfTileRows;
-    const int64_t vrow0 = (int64_t)(vb ? tv + tb_base : tv) * kPfTileRows;
-    const bool kfull = tk < T && (kb ? a.nb : a.na) - krow0 >= kPfTileRows;
-    const bool vfull = tv < T && (vb ? a.nb : a.na) - vrow0 >= kPfTileRows;
-    if (kfull) ld.k = (kb ? a.kb : a.ka) + krow0 * kRowBytes; else issue(tk, 0);
-    if (vfull) ld.v = (vb ? a.vb : a.va) + vrow0 * kRowBytes; else issue(tv, 1);
-    ld.ldk = lds_base + (uint32_t)(tk & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
-    ld.ldv = lds_base + kPdVRing + (uint32_t)(tv & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
-    pd_matrix_phase<false, false, false>((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes,
-                                         (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes, lc, qf, pb, st, sc, ld, pre,
-                                         negm);
-    phase_barrier();
-    softmax_phase(t);
-    wait_landed(t);
-    phase_barrier();
-  };
-  // Steady state: tile t of the past segment with K(t+3), V(t+2) full tiles of the same segment and nothing
-  // masked.  The stage t % 4 is a compile-time constant (every LDS address is an immediate) and the scalar work
-  // per tile is two pointer increments.
-  const char* kp = a.ka;     // K(t+3), V(t+2) of the next fast tile
-  const char* vp = a.va;
-  const uint32_t ld_wave = lds_base + wave * 2048;
-  auto fast_tile = [&](auto stage_tag) __attribute__((always_inline)) {
-    constexpr int S = decltype(stage_tag)::value;
-    PfPhaseLoads ld;
-    ld.k = kp;
-    ld.v = vp;
-    ld.ldk = ld_wave + ((S + 3) & 3) * kPfTileBytes;
-    ld.ldv = ld_wave + kPdVRing + ((S + 2) & 3) * kPfTileBytes;
-    __builtin_amdgcn_s_setprio(2);
-    pd_matrix_phase<true, true, true, true>(((S + 3) & 3) * kPfTileBytes, S * kPfTileBytes, lc, qf, pb, st, sc, ld,
-                                            pre, negm);       // passes the phase's barrier itself
-    __builtin_amdgcn_s_setprio(0);
-    pd_preread(S * kPfTileBytes, lc, pre);     // V(t), for the next matrix phase
-    __builtin_amdgcn_sched_barrier(0);
-    pf_softmax_fast(sc, st, c, negm, pb);
-    wait_vmcnt<4>();
-    phase_barrier();
-    kp += kPfTileBytes;
-    vp += kPfTileBytes;
-  };
-  // A run of steady-state tiles [t, t_end) of one segment whose tile 0 is tile `tile0` of the sweep and whose rows
-  // start at kbase / vbase: general tiles up to a multiple of four, then the unrolled loop.
-  int t = 1;
-  auto fast_run = [&](int t_end, const char* kbase, const char* vbase, int tile0) __attribute__((always_inline)) {
-    if (t_end - t < 8) return;
-    while (t & 3) { generic_tile(t); ++t; }
-    kp = kbase + (int64_t)(t + 3 - tile0) * kPfTileBytes;
-    vp = vbase + (int64_t)(t + 2 - tile0) * kPfTileBytes;
-    pd_preread((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes, lc, pre);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) negm[r] = -st.m;
-    for (; t + 4 <= t_end; t += 4) {
-      fast_tile(std::integral_constant<int, 0>());
-      fast_tile(std::integral_constant<int, 1>());
-      fast_tile(std::integral_constant<int, 2>());
-      fast_tile(std::integral_constant<int, 3>());
-    }
-  };
-  // past segment: tile t qualifies if K(t+3) and V(t+2) are full tiles of the segment too
-  fast_run((int)(a.na / kPfTileRows) - 3, a.ka, a.va, 0);
-  // the chunk's own rows: tiles that end at or before the first position of the workgroup are not masked for any
-  // of its lanes (own tile j = t + tb_base; its rows are 64 j .. 64 j + 63)
-  while (t < ta && t < T) { generic_tile(t); ++t; }
+  constexpr int kImageFloats = kCarryFloatsPerLane * kLanes;
+  float* const images = a.carry + (int64_t)blockIdx.y * pf_images_per_row(a.nbk, a.split) * kImageFloats + threadIdx.x;
+  // the pass that holds past tiles goes first, so that the workgroups of a range walk the past rows in step
+  int first_which = 0;
   {
-    const int64_t unmasked = ((int64_t)bx * strip + 1) / kPfTileRows;          // own tiles 0 .. unmasked - 1
-    const int64_t loadable = a.nb / kPfTileRows - 3;                           // K(t+3), V(t+2) full
-    const int64_t j_end = unmasked < loadable ? unmasked : loadable;
-    const int64_t t_end = j_end - tb_base < T - 3 ? j_end - tb_base : T - 3;
-    fast_run((int)t_end, a.kb, a.vb, -tb_base);
+    const PfPass d = pf_pass(sh, blockIdx.x, 0, a.last), sw = pf_pass(sh, blockIdx.x, 1, a.last);
+    if (sw.run && sw.a1 > sw.a0 && !(d.run && d.a1 > d.a0)) first_which = 1;
   }
-  for (; t < T; ++t) generic_tile(t);
-  {
-    const uint32_t v_off = (uint32_t)((T - 1) & (kPdStages - 1)) * kPfTileBytes;
+#pragma nounroll
+  for (int pi = 0; pi < 2; ++pi) {
+    const PfPass ps = pf_pass(sh, blockIdx.x, first_which ^ pi, a.last);
+    if (ps.init) {                 // a range without tiles in the first launch of a unit: an empty state
+      float* im = images + (int64_t)ps.store * kImageFloats;
 #pragma unroll
-    for (int i = 0; i < 16; ++i)
-      st.o[pd_db(i)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, v_off, 0, lc), pb[pd_sb(i)][pd_u(i)],
-                                                               st.o[pd_db(i)], 0, 0, 0);
-  }
-  if (group == 0) phase_barrier();
+      for (int i = 0; i < 64; ++i) im[i * kLanes] = 0.f;
+      im[64 * kLanes] = kNegBig;
+      im[65 * kLanes] = 0.f;
+    }
+    if (!ps.run) continue;
+    __syncthreads();               // the LDS rings are free again (a previous pass may still be reading V tiles)
+    const int bx = ps.bx;
+    const int i0 = bx * strip + 32 * (wave / gl);
+    int qi = i0 + col;
+    const int my_i = qi;
+    if (qi > a.C - 1) qi = a.C - 1;
 
-  if (!a.last) {
+    // Q^T operand: lane holds q[g][qi][16*kk + 8*hl .. +7]
+    bf16x8 qf[8];
+    {
+      const uint16_t* qrow = a.q + ((int64_t)g * a.C + qi) * kHeadDim + 8 * hl;
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) carry[(db * 16 + r) * kLanes] = st.o[db][r];
-    carry[64 * kLanes] = st.m;
-    carry[65 * kLanes] = st.l;
-    return;
-  }
+      for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 16 * kk));
+    }
 
-  pf_write_row(a.out, a.out_fp32, a.C, g, my_i, hl, st.o, st.l);
+    // this pass's tiles: past rows [64 a0, min(64 a1, na)) of the launch, own tiles [b0, b1) of the chunk
+    const char* const ka_p = a.ka + (int64_t)ps.a0 * kPfTileBytes;
+    const char* const va_p = a.va + (int64_t)ps.a0 * kPfTileBytes;
+    int64_t na_p = (int64_t)ps.a1 * kPfTileRows;
+    if (na_p > a.na) na_p = a.na;
+    na_p -= (int64_t)ps.a0 * kPfTileRows;
+    const int b_t0 = ps.b0;
+    const int tb = ps.b1 - ps.b0;
+
+    PfState st;
+    if (ps.load < 0) {
+      st.m = kNegBig;
+      st.l = 0.f;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
+    } else {
+      const float* im = images + (int64_t)ps.load * kImageFloats;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.o[db][r] = im[(db * 16 + r) * kLanes];
+      st.m = im[64 * kLanes];
+      st.l = im[65 * kLanes];
+    }
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) asm volatile("" : "+v"(qf[kk]));
+    asm volatile("" : "+v"(st.m), "+v"(st.l));
+#pragma unroll
+    for (int db = 0; db < 4; ++db) asm volatile("" : "+v"(st.o[db]));
+
+    const int ta = (int)((na_p + kPfTileRows - 1) / kPfTileRows);
+    const int T = ta + tb;
+    const int tb_base = b_t0 - ta;      // tile t >= ta of the sweep is tile t + tb_base of the chunk's own rows
+
+    // K tile t (which = 0) or V tile t (which = 1) of the sweep: this wave's share of its loads
+    auto issue = [&](int t, int which) __attribute__((always_inline)) {
+      if (t >= T) return;
+      const bool in_b = t >= ta;
+      const int64_t row0 = (int64_t)(in_b ? t + tb_base : t) * kPfTileRows;
+      const int64_t left = (in_b ? a.nb : na_p) - row0;
+      const int rows = left < kPfTileRows ? (int)left : kPfTileRows;
+      const uint32_t slot = lds_base + (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes;
+      if (which == 0) pf_issue_k<kPdWaves>((in_b ? a.kb : ka_p) + row0 * kRowBytes, rows, slot, wave, lane, lc);
+      else pf_issue_v<kPdWaves>((in_b ? a.vb : va_p) + row0 * kRowBytes, rows, slot + kPdVRing, wave, lane, lc);
+    };
+    // Every wave issues, in this order: K0 | K1 V0 | K2 V1 | then, in the matrix phase of tile t, K(t+3) V(t+2)
+    // (2 instructions each).  The one wait per tile is at the end of the softmax phase of tile t: everything up to
+    // V(t+1) has landed when at most K(t+3) V(t+2) are still in flight.
+    auto wait_landed = [&](int t) {
+      if (t + 3 < T) wait_vmcnt<4>();
+      else wait_vmcnt<0>();
+    };
+    auto phase_barrier = [&]() {
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // The two wavefronts of a SIMD alternate: while one runs its matrix phase (O += V P of the previous tile, then
+    // the scores of the next), the other runs its softmax phase on the vector ALU.  Both groups execute the same
+    // program with two barriers per tile; group 1 passes one extra barrier first, so it is always one phase behind
+    // (and group 0 passes one extra at the end: every wave executes the same number of barriers).
+    //   phase index (barriers passed so far):  group 0: matrix(t) = 2t, softmax(t) = 2t + 1;  group 1: one later.
+    //   Reads: K(t) in phases 2t, 2t+1; V(t) in phases 2t+1 (operands read ahead during softmax(t)) .. 2t+3.
+    //   Writes: K(t+3) replaces K(t-1) (last read in phase 2t-1) and V(t+2) replaces V(t-2) (last read in phase
+    //   2t-1): both are issued in matrix(t), phase >= 2t.
+    //   Landing: each wave waits at the end of softmax(t-1) for its share of everything up to V(t): that is phase
+    //   2t at the latest, and K(t+1) is first read in phase 2t+2, V(t) in phase 2t+1.
+    const int group = wave >> 2;       // waves w and w + 4 share a SIMD
+    const float c = a.c;
+    wait_vmcnt<0>();                   // the waits below count this pass's tile loads only (a previous pass's stores are done)
+    issue(0, 0);
+    issue(1, 0); issue(0, 1);
+    issue(2, 0); issue(1, 1);
+    wait_landed(-1);                           // K(0), K(1), V(0)
+    phase_barrier();
+    if (group == 1) phase_barrier();
+
+    f32x16 sc[2];
+    bf16x8 pb[2][2];
+    auto softmax_phase = [&](int t) __attribute__((always_inline)) {
+      const bool in_b = t >= ta;
+      const int64_t j0 = (int64_t)(in_b ? t + tb_base : t) * kPfTileRows;
+      const int64_t n_seg = in_b ? a.nb : na_p;
+      const bool masked = (j0 + kPfTileRows > n_seg) || (in_b && (j0 + kPfTileRows - 1 > i0));
+      int rel = kPfTileRows;
+      if (masked) {
+        int64_t lim = n_seg - 1;
+        if (in_b && (int64_t)my_i < lim) lim = my_i;
+        const int64_t d = lim - j0;
+        rel = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
+      }
+      pf_softmax(sc, st, c, masked, rel, hl, pb);
+    };
+    // tile 0: nothing to accumulate yet
+    issue(3, 0);
+    issue(2, 1);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sc[0][r] = 0.f; sc[1][r] = 0.f; }
+#pragma unroll
+    for (int i = 16; i < 32; ++i)
+      sc[pd_sb(i)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, 0, 0, lc), qf[pd_kk(i)], sc[pd_sb(i)], 0, 0, 0);
+    phase_barrier();
+    softmax_phase(0);
+    wait_landed(0);
+    phase_barrier();
+    bf16x8 pre[kPfAhead];
+    f32x16 negm;       // minus the row's running reference, the start value of the steady-state score accumulators
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[r] = 0.f;
+    // any tile t >= 1
+    auto generic_tile = [&](int t) __attribute__((always_inline)) {
+      // K(t+3) and V(t+2): full tiles are issued from inside the matrix phase, partial ones (row clamping) here
+      PfPhaseLoads ld;
+      ld.k = ld.v = nullptr;
+      const int tk = t + 3, tv = t + 2;
+      const bool kb = tk >= ta, vb = tv >= ta;
+      const int64_t krow0 = (int64_t)(kb ? tk + tb_base : tk) * kPfTileRows;
+      const int64_t vrow0 = (int64_t)(vb ? tv + tb_base : tv) * kPfTileRows;
+      const bool kfull = tk < T && (kb ? a.nb : na_p) - krow0 >= kPfTileRows;
+      const bool vfull = tv < T && (vb ? a.nb : na_p) - vrow0 >= kPfTileRows;
+      if (kfull) ld.k = (kb ? a.kb : ka_p) + krow0 * kRowBytes; else issue(tk, 0);
+      if (vfull) ld.v = (vb ? a.vb : va_p) + vrow0 * kRowBytes; else issue(tv, 1);
+      ld.ldk = lds_base + (uint32_t)(tk & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
+      ld.ldv = lds_base + kPdVRing + (uint32_t)(tv & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
+      pd_matrix_phase<false, false, false>((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes,
+                                           (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes, lc, qf, pb, st, sc, ld, pre,
+                                           negm);
+      phase_barrier();
+      softmax_phase(t);
+      wait_landed(t);
+      phase_barrier();
+    };
+    // Steady state: tile t of the past segment with K(t+3), V(t+2) full tiles of the same segment and nothing
+    // masked.  The stage t % 4 is a compile-time constant (every LDS address is an immediate) and the scalar work
+    // per tile is two pointer increments.
+    const char* kp = ka_p;     // K(t+3), V(t+2) of the next fast tile
+    const char* vp = va_p;
+    const uint32_t ld_wave = lds_base + wave * 2048;
+    auto fast_tile = [&](auto stage_tag) __attribute__((always_inline)) {
+      constexpr int S = decltype(stage_tag)::value;
+      PfPhaseLoads ld;
+      ld.k = kp;
+      ld.v = vp;
+      ld.ldk = ld_wave + ((S + 3) & 3) * kPfTileBytes;
+      ld.ldv = ld_wave + kPdVRing + ((S + 2) & 3) * kPfTileBytes;
+      __builtin_amdgcn_s_setprio(2);
+      pd_matrix_phase<true, true, true, true>(((S + 3) & 3) * kPfTileBytes, S * kPfTileBytes, lc, qf, pb, st, sc, ld,
+                                              pre, negm);       // passes the phase's barrier itself
+      __builtin_amdgcn_s_setprio(0);
+      pd_preread(S * kPfTileBytes, lc, pre);     // V(t), for the next matrix phase
+      __builtin_amdgcn_sched_barrier(0);
+      pf_softmax_fast(sc, st, c, negm, pb);
+      wait_vmcnt<4>();
+      phase_barrier();
+      kp += kPfTileBytes;
+      vp += kPfTileBytes;
+    };
+    // A run of steady-state tiles [t, t_end) of one segment whose tile 0 is tile `tile0` of the sweep and whose rows
+    // start at kbase / vbase: general tiles up to a multiple of four, then the unrolled loop.
+    int t = 1;
+    auto fast_run = [&](int t_end, const char* kbase, const char* vbase, int tile0) __attribute__((always_inline)) {
+      if (t_end - t < 8) return;
+      while (t & 3) { generic_tile(t); ++t; }
+      kp = kbase + (int64_t)(t + 3 - tile0) * kPfTileBytes;
+      vp = vbase + (int64_t)(t + 2 - tile0) * kPfTileBytes;
+      pd_preread((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes, lc, pre);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) negm[r] = -st.m;
+      for (; t + 4 <= t_end; t += 4) {
+        fast_tile(std::integral_constant<int, 0>());
+        fast_tile(std::integral_constant<int, 1>());
+        fast_tile(std::integral_constant<int, 2>());
+        fast_tile(std::integral_constant<int, 3>());
+      }
+    };
+    // past segment: tile t qualifies if K(t+3) and V(t+2) are full tiles of the segment too
+    fast_run((int)(na_p / kPfTileRows) - 3, ka_p, va_p, 0);
+    // the chunk's own rows: tiles that end at or before the first position of the workgroup are not masked for any
+    // of its lanes (own tile j = t + tb_base; its rows are 64 j .. 64 j + 63)
+    while (t < ta && t < T) { generic_tile(t); ++t; }
+    {
+      const int64_t unmasked = ((int64_t)bx * strip + 1) / kPfTileRows;          // own tiles 0 .. unmasked - 1
+      const int64_t loadable = a.nb / kPfTileRows - 3;                           // K(t+3), V(t+2) full
+      const int64_t j_end = unmasked < loadable ? unmasked : loadable;
+      const int64_t t_end = j_end - tb_base < T - 3 ? j_end - tb_base : T - 3;
+      fast_run((int)t_end, a.kb, a.vb, -tb_base);
+    }
+    for (; t < T; ++t) generic_tile(t);
+    {
+      const uint32_t v_off = (uint32_t)((T - 1) & (kPdStages - 1)) * kPfTileBytes;
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        st.o[pd_db(i)] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pd_operand(i, v_off, 0, lc), pb[pd_sb(i)][pd_u(i)],
+                                                                 st.o[pd_db(i)], 0, 0, 0);
+    }
+    if (group == 0) phase_barrier();
+
+    if (ps.store >= 0) {
+      float* im = images + (int64_t)ps.store * kImageFloats;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) im[(db * 16 + r) * kLanes] = st.o[db][r];
+      im[64 * kLanes] = st.m;
+      im[65 * kLanes] = st.l;
+    } else {
+      pf_write_row(a.out, a.out_fp32, a.C, g, my_i, hl, st.o, st.l);
+    }
+  }
 }
 
-// Merge of the split-KV states of the 8-wave kernel, run once after a unit's last launch: the same grid (without
-// z) and the same lane layout, so every lane combines its own register images - m = max m_s,
-// O = sum O_s 2^(c (m_s - m)), l likewise - then normalises and writes out[g][i][:].
+// One dim block (32 of the 128 output dims) of pf_write_row: register r of o is dim 32*db + 8*(r/4) + 4*hl + r%4.
+__device__ __forceinline__ void pf_write_row_db(void* out, int out_fp32, int C, int g, int i, int hl, int db,
+                                                const f32x16& o, float l) {
+  const float inv = 1.0f / sum_halves(l);
+  if (i >= C) return;
+  const int64_t base = ((int64_t)g * C + i) * kHeadDim;
+#pragma unroll
+  for (int rq = 0; rq < 4; ++rq) {
+    const int dim = 32 * db + 8 * rq + 4 * hl;
+    const float x0 = o[4 * rq] * inv, x1 = o[4 * rq + 1] * inv, x2 = o[4 * rq + 2] * inv, x3 = o[4 * rq + 3] * inv;
+    if (out_fp32) {
+      *(float4*)((float*)out + base + dim) = make_float4(x0, x1, x2, x3);
+    } else {
+      uint2 pk;
+      pk.x = (uint32_t)float_to_bf16_bits(x0) | ((uint32_t)float_to_bf16_bits(x1) << 16);
+      pk.y = (uint32_t)float_to_bf16_bits(x2) | ((uint32_t)float_to_bf16_bits(x3) << 16);
+      *(uint2*)((uint16_t*)out + base + dim) = pk;
+    }
+  }
+}
+
+// Merge of the states of the 8-wave kernel, run once after a unit's last launch when a block of positions can have
+// more than one state (split > 1, or the paired partition): grid (blocks, grid rows, 4 dim blocks), the kernel's
+// own lane layout, so every lane combines its own register images - m = max m_i, O = sum O_i 2^(c (m_i - m)),
+// l likewise - then normalises and writes its part of out[g][i][:].  A block with a single state was written by
+// the pass that computed it.
 __global__ __launch_bounds__(512) void prefill_merge_kernel(PrefillArgs a) {
   const int lane = lane_id();
   const int wave = wave_id();
@@ -874,32 +903,36 @@ __global__ __launch_bounds__(512) void prefill_merge_kernel(PrefillArgs a) {
   const int col = lane & 31;
   const int gl = a.G < 4 ? a.G : 4;
   const int strip = 32 * (kPdWaves / gl);
-  const int bx = gridDim.x - 1 - blockIdx.x;
+  const int bx = blockIdx.x;
+  const int db = blockIdx.z;
   const int g = pf_select_head(a) * 4 + (wave % gl);
   const int my_i = bx * strip + 32 * (wave / gl) + col;
   constexpr int kLanes = kPdWaves * 64;
-  const int64_t wg_per_split = (int64_t)gridDim.y * gridDim.x;
-  const int64_t wg_linear = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-
+  constexpr int kImageFloats = kCarryFloatsPerLane * kLanes;
+  PfShape sh;
+  sh.nbk = a.nbk; sh.m = strip / kPfTileRows;
+  sh.ta = (int)((a.na + kPfTileRows - 1) / kPfTileRows);
+  sh.tb_all = (int)((a.nb + kPfTileRows - 1) / kPfTileRows);
+  sh.split = a.split; sh.paired = a.paired; sh.carried = !a.first;
+  int n_e, n_x;
+  pf_block_images(sh, bx, n_e, n_x);
+  if (n_e + n_x == 1 && a.split == 1) return;
+  const float* images = a.carry + (int64_t)blockIdx.y * pf_images_per_row(a.nbk, a.split) * kImageFloats + threadIdx.x;
+  auto image_of = [&](int i) { return images + (int64_t)(i < n_e ? pf_image_e(sh, bx, i) : pf_image_x(sh, bx, i - n_e)) * kImageFloats; };
   float m = kNegBig;
-  for (int z = 0; z < a.split; ++z)
-    m = fmaxf(m, a.carry[(z * wg_per_split + wg_linear) * (kCarryFloatsPerLane * kLanes) + 64 * kLanes + threadIdx.x]);
-  f32x16 o[4];
+  for (int i = 0; i < n_e + n_x; ++i) m = fmaxf(m, image_of(i)[64 * kLanes]);
+  f32x16 o;
 #pragma unroll
-  for (int db = 0; db < 4; ++db)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+  for (int r = 0; r < 16; ++r) o[r] = 0.f;
   float l = 0.f;
-  for (int z = 0; z < a.split; ++z) {
-    const float* cz = a.carry + (z * wg_per_split + wg_linear) * (kCarryFloatsPerLane * kLanes) + threadIdx.x;
-    const float w = fast_exp2((cz[64 * kLanes] - m) * a.c);
-    l += w * cz[65 * kLanes];
+  for (int i = 0; i < n_e + n_x; ++i) {
+    const float* im = image_of(i);
+    const float w = fast_exp2((im[64 * kLanes] - m) * a.c);
+    l += w * im[65 * kLanes];
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[db][r] += w * cz[(db * 16 + r) * kLanes];
+    for (int r = 0; r < 16; ++r) o[r] += w * im[(db * 16 + r) * kLanes];
   }
-  pf_write_row(a.out, a.out_fp32, a.C, g, my_i, hl, o, l);
+  pf_write_row_db(a.out, a.out_fp32, a.C, g, my_i, hl, db, o, l);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -1159,24 +1192,16 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   const int gy = prefill_grid_y(G);
   a.gy = gy;
   a.a_head_stride = sa.head_stride;
-  int split = prefill_split(G, chunk_len, n_heads);
-  // A unit that is mostly its own causal triangle (single launch, past shorter than the chunk): the workgroups'
-  // tile sequences differ by up to the whole triangle; cutting each in two evens the load out over the chip.
-  // (Only for chunks that fill the chip by themselves: measured +11 % at chunk 16384, a loss at 8192 and below.)
-  if (first && last && sa.n < chunk_len && split == 1) split = 2;
-  const int64_t deep_wgs = ceil_div(chunk_len, 2 * strip) * gy * n_heads;
-  const bool deep = variant == 3 || (variant == 0 && deep_wgs * split >= kPrefillDeepMinWorkgroups);
-  a.split = 1;
-  {  // the carry must hold one state image per workgroup of the launch
-    const int64_t wgs = deep ? deep_wgs * split : ceil_div(chunk_len, strip) * gy * n_heads;
-    const int64_t lanes = deep ? kPdWaves * 64 : kWgThreads;
-    const int64_t need = wgs * lanes * kCarryFloatsPerLane * 4;
-    if (carry_bytes >= 0 && need > carry_bytes) {
-      set_last_error("prefill launch: carry of %lld bytes needed, %lld provided", (long long)need, (long long)carry_bytes);
-      return HI_ERR_ARG;
-    }
+  const PrefillLaunch pl = prefill_launch_shape(G, chunk_len, n_heads, variant, last, sb.n > 0);
+  if (sa.n >= (1LL << 31) || sb.n >= (1LL << 31)) { set_last_error("prefill launch: more than 2^31 rows"); return HI_ERR_RANGE; }
+  if (carry_bytes >= 0 && pl.carry_bytes > carry_bytes) {     // the carry must hold every state image of the launch
+    set_last_error("prefill launch: carry of %lld bytes needed, %lld provided", (long long)pl.carry_bytes, (long long)carry_bytes);
+    return HI_ERR_ARG;
   }
-  if (deep) {
+  a.split = pl.split;
+  a.paired = pl.paired;
+  a.nbk = pl.nbk;
+  if (pl.deep) {
     static std::once_flag attr_once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(attr_once, [] {
@@ -1184,13 +1209,12 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
                                      kPdLdsBytes);
     });
     if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
-    a.split = split;
-    dim3 grid((unsigned)ceil_div(chunk_len, 2 * strip), (unsigned)(gy * n_heads), (unsigned)split);
+    dim3 grid((unsigned)(pl.nbk * pl.split), (unsigned)(gy * n_heads));
     hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
-    if (split > 1 && last) {
+    if (pl.merge) {
       hipError_t e1 = hipGetLastError();
       if (e1 != hipSuccess) { set_last_error("prefill launch: %s", hipGetErrorString(e1)); return HI_ERR_HIP; }
-      hipLaunchKernelGGL(prefill_merge_kernel, dim3(grid.x, grid.y), dim3(kPdWaves * 64), 0, (hipStream_t)stream, a);
+      hipLaunchKernelGGL(prefill_merge_kernel, dim3((unsigned)pl.nbk, grid.y, 4), dim3(kPdWaves * 64), 0, (hipStream_t)stream, a);
     }
   } else {
     dim3 grid((unsigned)ceil_div(chunk_len, strip), (unsigned)(gy * n_heads));

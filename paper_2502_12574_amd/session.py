@@ -12,7 +12,7 @@ from . import binding as hb
 class Session:
     def __init__(self, n_layers, n_kv_heads, gqa_group, max_context, chunk, mode=hb.HI_MODE_OFFLOAD, out_fp32=1,
                  device="cuda:0", gpu_kv_budget_heads=1, n_compute_units=0, resident_heads=0, streaming_heads=0,
-                 sink_tokens=0, recent_tokens=0, link_kv_bits=0):
+                 sink_tokens=0, recent_tokens=0, link_kv_bits=0, per_layer_cache=False):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the library has no CPU path")
         self.device = torch.device(device)
@@ -25,11 +25,23 @@ class Session:
                                        link_kv_bits=link_kv_bits)
         self.plan = hb.hi_offload_plan(self.problem)
         nbytes = self.plan.host_bytes_total
+        # per_layer_cache: one allocation per layer (hi_ctx_set_layer_cache) instead of one for the whole cache
+        self.kv_layers = None
+        if per_layer_cache:
+            per = nbytes // n_layers
+            if mode == hb.HI_MODE_OFFLOAD:
+                self.kv_layers = [torch.empty(per, dtype=torch.uint8, pin_memory=True) for _ in range(n_layers)]
+            else:
+                self.kv_layers = [torch.empty(per, dtype=torch.uint8, device=self.device) for _ in range(n_layers)]
+            self.kv = None
+            nbytes = 0
         if mode == hb.HI_MODE_OFFLOAD:
-            self.kv = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+            if not per_layer_cache:
+                self.kv = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
             self.staging = torch.empty(self.plan.hbm_staging_bytes, dtype=torch.uint8, device=self.device)
         else:
-            self.kv = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            if not per_layer_cache:
+                self.kv = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
             self.staging = None
             if self.plan.hbm_stream_bytes > 0:      # only the streaming heads' stores are used
                 self.staging = torch.empty(self.plan.hbm_staging_bytes, dtype=torch.uint8, device=self.device)
@@ -39,12 +51,21 @@ class Session:
         self.s_d2h = torch.cuda.Stream(self.device)
         self.ctx = hb.hi_ctx_create(self.problem, self.plan, mode, self.kv, self.staging, self.workspace,
                                     self.s_compute, self.s_h2d, self.s_d2h)
+        if self.kv_layers is not None:
+            for l, t in enumerate(self.kv_layers):
+                hb.hi_ctx_set_layer_cache(self.ctx, l, t)
         self.out_dtype = torch.float32 if out_fp32 else torch.bfloat16
 
     # [layer][retrieval kv_head][K|V][S_max][d] bf16 views of the cache (host or device); with 4-bit rows on the
     # link, [layer][retrieval kv_head][K|V][S_max][80] bytes
-    def cache_view(self) -> torch.Tensor:
+    def cache_view(self, layer=None) -> torch.Tensor:
         p = self.problem
+        if self.kv_layers is not None:          # one allocation per layer: the view of one layer, [1][kv_head]...
+            assert layer is not None, "a per-layer cache is viewed layer by layer"
+            raw = self.kv_layers[layer]
+            if p.link_kv_bits == 4:
+                return raw.view(1, p.n_kv_heads - p.streaming_heads, 2, p.max_context, self.plan.link_row_bytes)
+            return raw.view(torch.bfloat16).view(1, p.n_kv_heads - p.streaming_heads, 2, p.max_context, p.head_dim)
         if p.link_kv_bits == 4:
             return self.kv.view(p.n_layers, p.n_kv_heads - p.streaming_heads, 2, p.max_context,
                                 self.plan.link_row_bytes)

@@ -37,14 +37,14 @@ def test_struct_layouts_match_the_c_header(tmp_path):
 #include <stddef.h>
 #include "headinfer.h"
 int main(void){ printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(hi_problem), sizeof(hi_plan), sizeof(hi_stats),
-  offsetof(hi_problem, mfma_TFLOPs), offsetof(hi_plan, regime_decode), offsetof(hi_stats, decode_kernel_ms)); return 0; }
+  offsetof(hi_problem, mfma_TFLOPs), offsetof(hi_plan, regime_decode), offsetof(hi_stats, exposed_copy_ms)); return 0; }
 ''')
     exe = tmp_path / "sz"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
                    check=True)
     got = [int(x) for x in subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split()]
     want = [ctypes.sizeof(hb.hi_problem), ctypes.sizeof(hb.hi_plan), ctypes.sizeof(hb.hi_stats),
-            hb.hi_problem.mfma_TFLOPs.offset, hb.hi_plan.regime_decode.offset, hb.hi_stats.decode_kernel_ms.offset]
+            hb.hi_problem.mfma_TFLOPs.offset, hb.hi_plan.regime_decode.offset, hb.hi_stats.exposed_copy_ms.offset]
     assert got == want
 
 
@@ -158,8 +158,11 @@ def test_entry_points_reject_null_context_without_touching_the_gpu():
     plan = hb.hi_offload_plan(prob)
     st, _ = hb.hi_ctx_create(prob, plan, 7, 1, 1, 1, None, None, None, check=False)
     assert st == hb.HI_ERR_ARG                      # unknown mode
-    st, _ = hb.hi_ctx_create(prob, plan, hb.HI_MODE_OFFLOAD, None, 1, 1, None, None, None, check=False)
-    assert st == hb.HI_ERR_ARG                      # null cache
+    st, _ = hb.hi_ctx_create(prob, plan, hb.HI_MODE_OFFLOAD, 1, 1, None, None, None, None, check=False)
+    assert st == hb.HI_ERR_ARG                      # null workspace (a null cache means: one allocation per layer)
+    st, _ = hb.hi_ctx_create(prob, plan, hb.HI_MODE_OFFLOAD, 1, None, 1, None, None, None, check=False)
+    assert st == hb.HI_ERR_ARG                      # null staging buffer in offload mode
+    assert L.hi_ctx_set_layer_cache(None, 0, None) == hb.HI_ERR_ARG
     other = hb.hi_offload_plan(hb.make_problem(1, 1, 4, 8192, 512))
     st, _ = hb.hi_ctx_create(prob, other, hb.HI_MODE_OFFLOAD, 1, 1, 1, None, None, None, check=False)
     assert st == hb.HI_ERR_ARG and "plan" in hb.last_error()

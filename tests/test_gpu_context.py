@@ -1,0 +1,143 @@
+"""Context-level behaviour on the GPU: one cache allocation per layer, the closed state after a failure that
+followed an enqueue, and the copy / exposed-copy timings of hi_stats."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from paper_2502_12574_amd import binding as hb
+from paper_2502_12574_amd import driver, synth
+from paper_2502_12574_amd.session import Session
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _run_stack(mode, per_layer, seed=4321, L=3, H=2, G=4, S=700, C=256, nd=2):
+    with Session(L, H, G, S + nd, C, mode=mode, out_fp32=1, per_layer_cache=per_layer) as ss:
+        kept = {}
+        with torch.cuda.stream(ss.s_compute):
+            inp = driver.LayerInputs(seed, L, H, G, S, C, DEV)
+            driver.prefill(ss, inp, keep=lambda c, l, h, out: kept.__setitem__((c, l, h), out.clone()),
+                           last_hint=(0, 0, S))
+            dec = driver.decode(ss, inp, S, nd)
+        ss.sync()
+        caches = [ss.cache_view(l if per_layer else None)[0 if per_layer else l].cpu().clone() for l in range(L)]
+        pre = {k: v.cpu() for k, v in kept.items()}
+        dec = [d.cpu() for d in dec]
+    return pre, dec, caches
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_OFFLOAD, hb.HI_MODE_RESIDENT])
+def test_one_cache_allocation_per_layer(mode):
+    # Eq. 7-8: the cache is partitioned by layer and head; with hi_ctx_set_layer_cache each layer's rows live in an
+    # allocation of their own.  Same results, bit for bit, as one allocation for all layers, and both match the oracle.
+    seed, L, H, G, S, C, nd = 4321, 3, 2, 4, 700, 256, 2
+    pre_a, dec_a, cache_a = _run_stack(mode, True)
+    pre_b, dec_b, cache_b = _run_stack(mode, False)
+    for k in pre_b:
+        assert torch.equal(pre_a[k], pre_b[k]), k
+    for a, b in zip(dec_a, dec_b):
+        assert torch.equal(a, b)
+    for l in range(L):
+        assert torch.equal(cache_a[l][:, :, :S + nd], cache_b[l][:, :, :S + nd])
+        for h in range(H):
+            assert torch.equal(cache_a[l][h, 0, :S + nd], synth.draw_k(seed, l, h, 0, S + nd))
+            assert torch.equal(cache_a[l][h, 1, :S + nd], synth.draw_v(seed, l, h, 0, S + nd))
+    l, h = L - 1, H - 1                       # the last layer against the oracle
+    Q = np.stack([synth.to_f64(synth.draw_q(seed, l, h * G + g, 0, S + nd)) for g in range(G)])
+    K = synth.to_f64(synth.draw_k(seed, l, h, 0, S + nd))
+    V = synth.to_f64(synth.draw_v(seed, l, h, 0, S + nd))
+    ref = oa.attn_head(Q, K, V)
+    got = torch.cat([pre_a[(c, l, h)] for c in range((S + C - 1) // C)], dim=1).double().numpy()
+    assert np.abs(got - ref[:, :S]).max() <= 1e-2
+    for t in range(nd):
+        assert np.abs(dec_a[t][l, h].double().numpy() - ref[:, S + t]).max() <= 1e-2
+
+
+def test_a_layer_without_cache_is_refused_and_can_be_given_later():
+    prob = hb.make_problem(2, 1, 4, 512, 128, out_fp32=1)
+    plan = hb.hi_offload_plan(prob)
+    per = plan.host_bytes_total // 2
+    kv0 = torch.empty(per, dtype=torch.uint8, pin_memory=True)
+    stg = torch.empty(plan.hbm_staging_bytes, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device=DEV)
+    s = [torch.cuda.Stream(DEV) for _ in range(3)]
+    ctx = hb.hi_ctx_create(prob, plan, hb.HI_MODE_OFFLOAD, None, stg, ws, *s)
+    hb.hi_ctx_set_layer_cache(ctx, 0, kv0)
+    q = torch.zeros(4, 128, 128, dtype=torch.bfloat16, device=DEV)
+    k = torch.zeros(128, 128, dtype=torch.bfloat16, device=DEV)
+    out = torch.zeros(4, 128, 128, dtype=torch.float32, device=DEV)
+    assert hb.hi_prefill_head(ctx, 1, 0, q, k, k, 0, 128, out, check=False) == hb.HI_ERR_ARG      # layer 1 has no rows
+    assert hb.hi_prefill_head(ctx, 0, 0, q, k, k, 0, 128, out, 1, 0, 0, check=False) == hb.HI_ERR_ARG  # nor as a hint
+    assert hb.hi_ctx_set_layer_cache(ctx, 1, torch.empty(per, dtype=torch.uint8), check=False) == hb.HI_ERR_NOT_PINNED
+    assert hb.hi_ctx_set_layer_cache(ctx, 2, kv0, check=False) == hb.HI_ERR_ARG
+    kv1 = torch.empty(per, dtype=torch.uint8, pin_memory=True)
+    hb.hi_ctx_set_layer_cache(ctx, 1, kv1)
+    assert hb.hi_prefill_head(ctx, 1, 0, q, k, k, 0, 128, out) == hb.HI_OK
+    hb.hi_sync(ctx)
+    hb.hi_ctx_destroy(ctx)
+
+
+@pytest.mark.parametrize("phase", ["prefill", "decode"])
+def test_a_failure_after_the_checks_closes_the_context(phase):
+    # HI_FLAG_INJECT_FAILURE makes a unit call return HI_ERR_HIP at the point where its enqueues begin, the way a failed
+    # copy or launch would (nothing on the GPU is broken by it).  The ring's bookkeeping can no longer be trusted then:
+    # the context refuses every later unit call, still synchronises and destroys, and a new context over the same
+    # buffers works.
+    seed, G, S, C = 99, 4, 600, 200
+    with Session(1, 1, G, S, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1) as ss:
+        with torch.cuda.stream(ss.s_compute):
+            Q = torch.stack([synth.draw_q(seed, 0, g, 0, S, device=DEV) for g in range(G)])
+            K = synth.draw_k(seed, 0, 0, 0, S, device=DEV)
+            V = synth.draw_v(seed, 0, 0, 0, S, device=DEV)
+            out = torch.empty(G, C, 128, dtype=torch.float32, device=DEV)
+            outd = torch.empty(G, 128, dtype=torch.float32, device=DEV)
+            ss.prefill_head(0, 0, Q[:, :C].contiguous(), K[:C], V[:C], 0, out, (0, 0, C))
+            ss.sync()
+            before = ss.kv.clone()
+            hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_INJECT_FAILURE)
+            # refusals that come from the checks do not close the context
+            assert hb.hi_prefill_head(ss.ctx, 0, 0, Q[:, C:2 * C].contiguous(), K[C:2 * C], V[C:2 * C], S, C, out,
+                                      check=False) == hb.HI_ERR_RANGE
+            if phase == "prefill":
+                st = hb.hi_prefill_head(ss.ctx, 0, 0, Q[:, C:2 * C].contiguous(), K[C:2 * C], V[C:2 * C], C, C, out,
+                                        check=False)
+            else:
+                st = hb.hi_decode_head(ss.ctx, 0, 0, Q[:, C].contiguous(), K[C], V[C], C, outd, check=False)
+            assert st == hb.HI_ERR_HIP and "injected" in hb.last_error()
+            hb.hi_ctx_set_flags(ss.ctx, 0)
+            st = hb.hi_prefill_head(ss.ctx, 0, 0, Q[:, C:2 * C].contiguous(), K[C:2 * C], V[C:2 * C], C, C, out,
+                                    check=False)
+            assert st == hb.HI_ERR_HIP and "earlier call failed" in hb.last_error()
+            assert hb.hi_decode_head(ss.ctx, 0, 0, Q[:, C].contiguous(), K[C], V[C], C, outd, check=False) == hb.HI_ERR_HIP
+        ss.sync()
+        assert torch.equal(ss.kv, before)            # nothing was appended by the refused calls
+        saved = ss.kv.clone()
+    # a new context continues from the host cache
+    with Session(1, 1, G, S, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1) as s2:
+        s2.kv.copy_(saved)
+        with torch.cuda.stream(s2.s_compute):
+            out2 = torch.empty(G, C, 128, dtype=torch.float32, device=DEV)
+            s2.prefill_head(0, 0, Q[:, C:2 * C].contiguous(), K[C:2 * C], V[C:2 * C], C, out2)
+        s2.sync()
+        ref = oa.attn_head(synth.to_f64(Q[:, :2 * C].cpu()), synth.to_f64(K[:2 * C].cpu()), synth.to_f64(V[:2 * C].cpu()))
+        assert np.abs(out2.cpu().double().numpy() - ref[:, C:2 * C]).max() <= 1e-2
+
+
+def test_stats_time_the_copies_and_the_exposed_waits():
+    seed, H, G, S, C = 7, 2, 4, 4096, 1024
+    with Session(1, H, G, S, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0) as ss:
+        hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_TIME_KERNELS)
+        with torch.cuda.stream(ss.s_compute):
+            inp = driver.LayerInputs(seed, 1, H, G, S, C, DEV)
+            driver.prefill(ss, inp)
+        ss.sync()
+        st = ss.stats()
+        assert st.bytes_h2d == 512 * H * sum(range(0, S, C)) and st.n_h2d_copies > 0
+        assert st.prefill_kernel_ms > 0 and st.h2d_copy_ms > 0 and st.d2h_copy_ms > 0
+        assert 0 <= st.exposed_copy_ms < 1e3
+        # a copy cannot be faster than the link: 64 GB/s is 6.4e7 bytes per millisecond
+        assert st.bytes_h2d / st.h2d_copy_ms < 6.4e7 * 1.05
+        hb.hi_reset_stats(ss.ctx)
+        assert ss.stats().h2d_copy_ms == 0 and ss.stats().exposed_copy_ms == 0

@@ -126,15 +126,36 @@ def test_prefill_ragged_shapes(G, P, C):
                                    (4, 1000, 129), (1, 77, 200), (2, 130, 95), (8, 200, 70), (8, 0, 40),
                                    (4, 97, 700)])
 @pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
-@pytest.mark.parametrize("variant", ["deep", "narrow"])
+@pytest.mark.parametrize("variant", ["deep", "narrow", "paired"])
 def test_prefill_other_kernel_variants_ragged_shapes(G, P, C, mode, variant):
     # the 8-wave / 4-stage kernel is normally picked for long chunks and the 4-wave kernel for very short ones;
-    # force each of them on small ragged shapes
-    flag = hb.HI_FLAG_PREFILL_DEEP if variant == "deep" else hb.HI_FLAG_PREFILL_NARROW
+    # force each of them on small ragged shapes - and the 8-wave kernel with deep and shallow blocks of positions
+    # paired (two passes per workgroup, states merged), which is otherwise picked for long chunks only
+    flag = {"deep": hb.HI_FLAG_PREFILL_DEEP, "narrow": hb.HI_FLAG_PREFILL_NARROW,
+            "paired": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED}[variant]
     out, Q, K, V = one_unit(G, P, C, seed=700 + P + C, mode=mode, flags=flag)
     ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
     for g in range(G):
         check(out[g:g + 1], ref[g:g + 1], f"{variant} G={G} P={P} C={C} head {g}")
+
+
+@pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
+@pytest.mark.parametrize("G,P,C", [(4, 500, 1000), (1, 300, 1500), (2, 0, 777), (8, 129, 450), (4, 2100, 1300),
+                                   (4, 8000, 192), (2, 6500, 260), (1, 6000, 515), (4, 3000, 2048), (4, 0, 4096)])
+def test_prefill_paired_blocks_with_carried_states(G, P, C, mode):
+    # the balanced partition of the causal triangle, forced on shapes of a few blocks: odd and even block counts,
+    # every split factor, a clipped last block, and (offload mode: the past arrives in up to four staging slices) a
+    # last launch whose passes continue states carried from earlier launches
+    out, Q, K, V = one_unit(G, P, C, seed=6600 + P + C, mode=mode,
+                            flags=hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED)
+    ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)
+    for g in range(G):
+        check(out[g:g + 1], ref[g:g + 1], f"paired G={G} P={P} C={C} head {g}")
+    # and the same unit without pairing differs by rounding only (the probabilities are rounded to bf16 relative to
+    # a running reference that depends on the order in which a state meets its tiles)
+    out2, *_ = one_unit(G, P, C, seed=6600 + P + C, mode=mode,
+                        flags=hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_UNPAIRED)
+    assert (out - out2).abs().max() < 4e-3 * float(out2.abs().max())
 
 
 @pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
