@@ -286,6 +286,20 @@ hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, i
                       int32_t chunk_len, int32_t out_fp32, void* y_out_dev);
 
 /*
+ * hi_qkv_rope for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same operation, same kernels and the same results as hi_qkv_rope;
+ * the chunk's cos / sin table is written to an 8 MiB array built into the library's device image (one copy per GPU,
+ * held until the process ends) instead of workspace_dev.  chunk_len may be at most 16384 (HI_ERR_RANGE beyond, nothing
+ * enqueued).  The call allocates nothing and frees nothing.  All calls on one GPU share that GPU's array: calls that
+ * may overlap in time on one GPU (different streams, different host threads) race on it and must be ordered by the
+ * caller; calls on one stream are ordered by the stream.  Nothing needs clearing between calls: a call rewrites the
+ * table for every token it rotates.  Otherwise as hi_qkv_rope (arguments, layouts, errors).
+ */
+hi_status hi_qkv_rope_static(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model, int32_t n_q_heads,
+                             int32_t n_kv_heads, int32_t chunk_len, int64_t past_len, double rope_theta,
+                             int32_t out_fp32, void* q_out_dev, void* k_out_dev, void* v_out_dev);
+
+/*
  * 4-bit rows on the link (Appendix B and Section 6.3 describe 4-bit KV quantisation as a representation that shrinks
  * the cache about 4x and is converted back on the GPU; Section 3.3 finds offloaded decode bound by the link).  With
  * hi_problem.link_kv_bits = 4 the rows of an offloaded head are stored in the host cache, and cross the link, as

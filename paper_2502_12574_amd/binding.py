@@ -21,7 +21,7 @@ HI_FLAG_INJECT_FAILURE = 128
 
 EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_layer_cache", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
            "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_proj_workspace_bytes",
-           "hi_qkv_rope", "hi_out_proj", "hi_kv_quantize", "hi_kv_dequantize", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
+           "hi_qkv_rope", "hi_qkv_rope_static", "hi_out_proj", "hi_kv_quantize", "hi_kv_dequantize", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
 
 
 class hi_problem(C.Structure):
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
         L.hi_decode_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, vp, i32, i32, i32, i64]
         L.hi_proj_workspace_bytes.argtypes = [i32, C.POINTER(i64)]
         L.hi_qkv_rope.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp, vp]
+        L.hi_qkv_rope_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp]
         L.hi_out_proj.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
         L.hi_kv_quantize.argtypes = [vp, vp, i64, vp]
         L.hi_kv_dequantize.argtypes = [vp, vp, i64, vp]
@@ -233,6 +234,16 @@ def hi_qkv_rope(stream, x_dev, w_qkv_dev, d_model, n_q_heads, n_kv_heads, chunk_
                            _ptr(workspace_dev))
     if check and st != HI_OK:
         raise HiError(st, "hi_qkv_rope")
+    return st
+
+
+def hi_qkv_rope_static(stream, x_dev, w_qkv_dev, d_model, n_q_heads, n_kv_heads, chunk_len, past_len, rope_theta,
+                       out_fp32, q_out_dev, k_out_dev, v_out_dev, check: bool = True):
+    st = lib().hi_qkv_rope_static(_stream(stream), _ptr(x_dev), _ptr(w_qkv_dev), d_model, n_q_heads, n_kv_heads,
+                                  chunk_len, past_len, float(rope_theta), out_fp32, _ptr(q_out_dev), _ptr(k_out_dev),
+                                  _ptr(v_out_dev))
+    if check and st != HI_OK:
+        raise HiError(st, "hi_qkv_rope_static")
     return st
 
 

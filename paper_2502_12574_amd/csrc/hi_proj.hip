@@ -543,6 +543,47 @@ extern "C" hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_
                        out_fp32, q_out_dev, k_out_dev, v_out_dev, workspace_dev);
 }
 
+// ---- the variant for callers that cannot allocate: the chunk's rotary table lives in a file-scope device array.
+// Every GPU holds its own copy of the array at its own address; in host code the array's name is only a stand-in,
+// so the address is looked up once per device (with that device current) and only that pointer is handed to kernels.
+constexpr int kQkvStaticMaxChunk = 16384;
+constexpr int kQkvStaticMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[(size_t)kQkvStaticMaxChunk * 64 * sizeof(float2)];   // 8 MiB
+
+static hi_status qkv_static_scratch(void** out) {
+  static std::mutex mu;
+  static void* ptr_of_device[kQkvStaticMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { set_last_error("hipGetDevice: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+  if (dev < 0 || dev >= kQkvStaticMaxDevices) { set_last_error("device index %d out of range", dev); return HI_ERR_UNSUPPORTED; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr_of_device[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { set_last_error("hipGetSymbolAddress: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
+    ptr_of_device[dev] = p;
+  }
+  *out = ptr_of_device[dev];
+  return HI_OK;
+}
+
+extern "C" hi_status hi_qkv_rope_static(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model,
+                                        int32_t n_q_heads, int32_t n_kv_heads, int32_t chunk_len, int64_t past_len,
+                                        double rope_theta, int32_t out_fp32, void* q_out_dev, void* k_out_dev,
+                                        void* v_out_dev) {
+  if (chunk_len > kQkvStaticMaxChunk) {
+    set_last_error("qkv projection without a workspace: chunk_len %d exceeds the built-in table of %d tokens", chunk_len,
+                   kQkvStaticMaxChunk);
+    return HI_ERR_RANGE;
+  }
+  void* table = nullptr;
+  HI_PJ_TRY(qkv_static_scratch(&table));
+  // the table is rewritten for tokens [0, chunk_len) by every call that rotates: nothing to clear
+  return qkv_rope_impl(stream, x_dev, w_qkv_dev, d_model, n_q_heads, n_kv_heads, chunk_len, past_len, rope_theta,
+                       out_fp32, q_out_dev, k_out_dev, v_out_dev, table);
+}
+
 extern "C" hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, int32_t n_q_heads,
                                  int32_t d_model, int32_t chunk_len, int32_t out_fp32, void* y_out_dev) {
   if (!attn_dev || !w_o_dev || !y_out_dev) { set_last_error("output projection: null buffer"); return HI_ERR_ARG; }
