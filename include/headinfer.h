@@ -132,8 +132,10 @@ typedef struct hi_stats {
                                                  synchronises to read them */
   double h2d_copy_ms, d2h_copy_ms;   /* the same for the prefetch copies (on stream_h2d) and the write-backs (on
                                         stream_d2h): time the copy engines spent on them */
-  double exposed_copy_ms;            /* time stream_compute spent waiting for a staging slice to land: the part of the
-                                        transfers that no kernel covered (HIP events around each wait) */
+  double exposed_copy_ms;            /* time stream_compute spent between consecutive attention launches (from the same
+                                        events): the wait for the next staging slice - the part of the transfers that
+                                        no kernel covered - plus launch latency and the expansion of 4-bit slices; an
+                                        upper bound of the exposed transfer time */
 } hi_stats;
 
 typedef struct hi_ctx hi_ctx;

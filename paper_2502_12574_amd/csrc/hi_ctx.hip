@@ -230,11 +230,24 @@ hi_status retire_slice(hi_ctx* c, int slot) {
   return HI_OK;
 }
 
+constexpr float kIdleGapCapMs = 50.f;     // longer pauses are the caller's (between phases), not the pipeline's
+
 hi_status collect_spans(hi_ctx* c) {
+  const TimedSpan* prev_kernel = nullptr;
   for (auto& s : c->spans) {
     HI_HIP(hipEventSynchronize(s.stop));
     float ms = 0.f;
     HI_HIP(hipEventElapsedTime(&ms, s.start, s.stop));
+    if (s.kind <= 1) {
+      // what stream_compute did between two attention launches: launch latency, the wait for the next staging
+      // slice, the expansion of 4-bit slices.  Spans of one stream are in issue order.
+      if (prev_kernel) {
+        float gap = 0.f;
+        if (hipEventElapsedTime(&gap, prev_kernel->stop, s.start) == hipSuccess && gap > 0.f && gap < kIdleGapCapMs)
+          c->stats.exposed_copy_ms += gap;
+      }
+      prev_kernel = &s;
+    }
     switch (s.kind) {
       case 0: c->stats.prefill_kernel_ms += ms; break;
       case 1: c->stats.decode_kernel_ms += ms; break;
@@ -248,14 +261,9 @@ hi_status collect_spans(hi_ctx* c) {
   return HI_OK;
 }
 
-// the compute stream waits for a slice; with timing on, the wait is bracketed by two events of that stream: what
-// they measure is the part of the slice's transfer that no kernel covered
+// the compute stream waits for a slice
 hi_status wait_slice(hi_ctx* c, int slot) {
-  const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
-  TimedSpan sp;
-  if (timed) HI_TRY(span_begin(c, 4, &sp));
   HI_HIP(hipStreamWaitEvent(c->sc, c->ev_ready[slot], 0));
-  if (timed) HI_TRY(span_end(c, sp));
   return HI_OK;
 }
 

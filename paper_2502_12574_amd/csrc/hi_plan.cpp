@@ -101,7 +101,8 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   const int64_t budget_rows = (int64_t)(p->gpu_kv_budget_heads - p->resident_heads) * S;
   const int64_t budget_tokens = packed ? budget_rows * row / (row + link_row) : budget_rows;
   // (four slices: measured against eight, the larger copies and fewer launches win 1-3 % of prefill time and up to
-  // 14 % of offloaded decode time at a 128K context, and nothing is lost in overlap)
+  // 14 % of offloaded decode time at a 128K context, and nothing is lost in overlap; three or two slices are within
+  // 1.5 % of four either way at 128K and 1M contexts)
   // (4-bit rows: two slices - a slice is 3.2x fewer link bytes, and the larger copies matter more than the depth of
   // the ring: measured at a 128K context, decode 4.0 -> 3.5 ms per token and prefill 1 % faster; at 1M, 25.0 -> 24.5 ms,
   // and 24.2 ms with slices of up to 524288 rows)
