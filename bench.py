@@ -58,6 +58,14 @@ def prefill_traffic_per_launch(S, C):
     return None, "no counter run for this shape"
 
 
+_T0 = time.perf_counter()
+
+
+def note(msg):
+    """progress line of the work itself (stderr; stdout carries the one JSON line)"""
+    print(f"bench.py [{time.perf_counter() - _T0:6.1f} s] {msg}", file=sys.stderr, flush=True)
+
+
 def causal_flops_layer(S):
     return 4.0 * D * HQ * (S * (S + 1) / 2.0)
 
@@ -121,7 +129,8 @@ def run_stack(args):
     L, ss = max(1, args.layers), None
     while ss is None:
         try:
-            ss = Session(L, HKV, G, S + max(nd, 1), C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0, per_layer_cache=True)
+            ss = Session(L, HKV, G, S + max(nd, 1), C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0, per_layer_cache=True,
+                         progress=lambda m: print("bench.py: " + m, file=sys.stderr, flush=True))
         except RuntimeError as e:               # the box refuses to pin that much: fewer layers, figures stay per layer
             print(f"bench.py: {L} layers of pinned cache refused ({str(e)[:80]}); trying {L // 2}", file=sys.stderr, flush=True)
             torch.cuda.empty_cache()
@@ -222,11 +231,15 @@ def main():
     ap.add_argument("--resident-decode-tokens", type=int, default=64)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra-legs", action="store_true", help="skip transfer-only and resident-decode legs")
+    ap.add_argument("--no-next-legs", action="store_true", help="skip the streaming-heads, projection and 4-bit-link legs")
     ap.add_argument("--layers", type=int, default=1, help="layers run in Algorithm 1's order (chunk -> layer -> head); "
                     "every figure stays per layer")
     ap.add_argument("--heads-per-call", type=int, default=0, help="KV heads per call; 0 = what hi_offload_plan "
                     "recommends for the context (Section 4, adaptive head-wise offloading: 1 beyond 256K tokens)")
     ap.add_argument("--seed", type=int, default=20250216)
+    ap.add_argument("--resident-passes", type=int, default=2, help="passes of the compute-only (HBM-resident) prefill leg; "
+                    "the last one is timed")
+    ap.add_argument("--peaked-keys", action="store_true", help="one key row in ten scaled x4 (peaked softmax rows)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="run the timed steps without the library's HIP events "
                     "around kernels and copies (wall figures only; the roofline object is then empty)")
     ap.add_argument("--stack", action="store_true", help="the literal multi-layer configuration: --layers attention blocks "
@@ -250,18 +263,26 @@ def main():
     hpc = args.heads_per_call if args.heads_per_call > 0 else max(1, ss.plan.heads_per_group)
     t_gen = time.perf_counter()
     with torch.cuda.stream(ss.s_compute):
-        inp = driver.LayerInputs(args.seed, NL, HKV, G, S, C, dev)
+        inp = driver.LayerInputs(args.seed, NL, HKV, G, S, C, dev, peaked=args.peaked_keys)
         dec_rows = [inp.decode_rows(S + t) for t in range(max(nd, args.resident_decode_tokens))]
         out_buf = [torch.empty(HKV, G, C, D, dtype=ss.out_dtype, device=dev) for _ in range(NL)]
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
+    note(f"inputs drawn ({t_gen:.1f} s)")
+
+    # runs of minutes report their progress (the host is never more than two units ahead of the GPU)
+    n_chunks = (S + C - 1) // C
+    every = max(1, n_chunks // 8)
+    progress = (lambda c, l, h, out: note(f"chunk {c + 1} of {n_chunks} enqueued")
+                if h == HKV - 1 and l == NL - 1 and c % every == every - 1 else None) if S * NL >= (1 << 21) else None
 
     def step(timed):
         hb.hi_reset_stats(ss.ctx)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         with torch.cuda.stream(ss.s_compute):
-            driver.prefill(ss, inp, out_buf=out_buf, last_hint=(0, 0, S) if nd else None, heads_per_call=hpc)
+            driver.prefill(ss, inp, out_buf=out_buf, last_hint=(0, 0, S) if nd else None, heads_per_call=hpc,
+                           keep=progress)
         ss.sync()
         t1 = time.perf_counter()
         st_pre = ss.stats()                    # the prefill's own counters and event timings
@@ -272,6 +293,7 @@ def main():
         ss.sync()
         torch.cuda.synchronize()
         t2 = time.perf_counter()
+        note(f"step done: prefill {t1 - t0:.3f} s, {nd} decode tokens {t2 - t1b:.3f} s")
         return t1 - t0, t2 - t1b, st_pre, ss.stats()
 
     hb.hi_ctx_set_flags(ss.ctx, 0 if args.no_kernel_timing else hb.HI_FLAG_TIME_KERNELS)
@@ -309,6 +331,7 @@ def main():
             driver.prefill(ss, inp, out_buf=out_buf, heads_per_call=hpc)
         ss.sync()
         t_xfer = (time.perf_counter() - t0) / NL
+        note(f"transfer-only leg done ({t_xfer:.3f} s per layer)")
         hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_TIME_KERNELS)
         link_bytes = 512.0 * HKV * sum(range(0, S, C)) + 512.0 * HKV * S
         # compute-only: the same calls on one layer with K/V resident in HBM (no link, no ring; a unit's past is one
@@ -320,12 +343,15 @@ def main():
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             with torch.cuda.stream(ss_r.s_compute):
-                driver.prefill(ss_r, inp0, out_buf=out_buf[:1], heads_per_call=hpc)
+                driver.prefill(ss_r, inp0, out_buf=out_buf[:1], heads_per_call=hpc, keep=progress if NL == 1 else None)
             ss_r.sync()
             return time.perf_counter() - t0
 
-        resident_prefill()                        # warm-up; also fills the resident cache for the decode leg below
-        t_comp = resident_prefill()
+        # (the first pass also fills the resident cache for the decode leg below; with --resident-passes 1 it is the
+        # timed one - the kernels are warm from the steps above)
+        for _ in range(max(1, args.resident_passes)):
+            t_comp = resident_prefill()
+            note(f"compute-only pass done ({t_comp:.3f} s)")
         # hidden = 1 - max(0, T_pipelined - T_compute_only) / T_transfer_only; two more readings of the same thing ride
         # along: with the summed kernel time of the pipelined run in place of the resident run, and the time the
         # compute stream spent between attention launches (launch latency included) over the transfer time
@@ -372,6 +398,7 @@ def main():
                          "wall_GBps": 512.0 * HKV * S * nr / t_res / 1e9}}
         ss_r.close()
         del ss_r
+        note("resident decode leg done")
 
     traffic, traffic_src = prefill_traffic_per_launch(S, C)
     dec_link_GBps = 512.0 * HKV * (S + (nd - 1) / 2.0) / (decode_ms_tok * 1e-3) / 1e9 if nd else None
@@ -387,6 +414,7 @@ def main():
                                f"{HQ} Q / {HKV} KV heads, head_dim {D}, context {S}, head-wise chunked prefill "
                                f"chunk {C} + {nd} decode tokens, K/V offloaded to pinned host DRAM, 1-KV-head HBM "
                                f"budget", "context": S, "chunk": C, "decode_tokens": nd, "layers_timed": NL, "heads_per_call": hpc,
+                   "peaked_keys": bool(args.peaked_keys),
                    "seed": args.seed},
         "prefill_s_per_layer": prefill_s,
         "decode_ms_per_token_per_layer_offloaded": decode_ms_tok if nd else None,
@@ -405,7 +433,7 @@ def main():
     result.update(extra)
     ss.close()
     del ss
-    if not args.no_extra_legs:
+    if not args.no_extra_legs and not args.no_next_legs:
         # the rows built after the hot path met its bar: streaming heads (Appendix E: 4 of the 8 heads keep sink +
         # recent tokens in HBM) on the same layer, and the projections either side of the attention calls
         from paper_2502_12574_amd import layer_bench, proj_bench
@@ -415,6 +443,7 @@ def main():
         if nd:
             sp["decode_speedup_vs_all_retrieval"] = decode_ms_tok / sp["decode_ms_per_token"]
         result["streaming_heads_50pct"] = sp
+        note("streaming-heads leg done")
         result["projections"] = proj_bench.measure(C)
         # the same layer with 4-bit rows on the host link (every head offloaded): the link-bound decode should follow
         # the bytes per row, the prefill should not change
@@ -424,6 +453,7 @@ def main():
         if nd:
             lk["decode_speedup_vs_bf16_rows"] = decode_ms_tok / lk["decode_ms_per_token"]
         result["link_kv_4bit"] = lk
+        note("4-bit link leg done")
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(args.seed, S, C)
     print(json.dumps(result))

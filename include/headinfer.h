@@ -76,6 +76,15 @@ typedef struct hi_problem {
                                   bf16 rows (exact attention); 4 = 4-bit codes, 80 bytes per row of 128 channels (see
                                   "4-bit rows on the link" below; offload mode only).  Rows that stay in HBM (the chunk
                                   being processed, resident and streaming heads) are always bf16 */
+  const uint8_t* streaming_mask; /* HOST, optional, [n_layers][n_kv_heads]: 1 = streaming head, 0 = retrieval head, for
+                                  models whose split differs from layer to layer (Appendix E takes the roles from a
+                                  trained model; Table 14 runs at 50 % streaming heads overall).  When given it replaces
+                                  the "last streaming_heads heads of every layer" rule (streaming_heads is then ignored);
+                                  every layer keeps at least one retrieval head.  Read by hi_offload_plan and copied by
+                                  hi_ctx_create; the caller may free it afterwards.  With a mask, the cache holds the
+                                  retrieval heads of all layers back to back in (layer, head) order, a layer's
+                                  allocation (hi_ctx_set_layer_cache) its own retrieval heads in head order, and the
+                                  streaming stores follow (layer, head) order likewise */
 } hi_problem;
 
 /* Output of hi_offload_plan.  Sizes in bytes. */
@@ -258,6 +267,7 @@ hi_status hi_decode_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n
  *     position order without gaps (the store holds only what earlier calls left in it);
  *   - a head group must not mix streaming and retrieval heads (HI_ERR_ARG); a hint naming a streaming unit
  *     prefetches nothing.
+ * With hi_problem.streaming_mask the roles are given per (layer, head) instead; everything above holds head by head.
  */
 
 /*

@@ -31,7 +31,7 @@ class hi_problem(C.Structure):
                 ("n_compute_units", C.c_int32), ("resident_heads", C.c_int32), ("host_mem_limit_bytes", C.c_int64),
                 ("link_GBps", C.c_double), ("hbm_GBps", C.c_double), ("mfma_TFLOPs", C.c_double),
                 ("streaming_heads", C.c_int32), ("sink_tokens", C.c_int32), ("recent_tokens", C.c_int32),
-                ("link_kv_bits", C.c_int32)]
+                ("link_kv_bits", C.c_int32), ("streaming_mask", C.c_void_p)]
 
 
 class hi_plan(C.Structure):
@@ -133,10 +133,18 @@ def _stream(s):
 def make_problem(n_layers, n_kv_heads, gqa_group, max_context, chunk, head_dim=128, gpu_kv_budget_heads=1,
                  dtype_bytes=2, out_fp32=0, n_compute_units=0, host_mem_limit_bytes=0, link_GBps=0.0, hbm_GBps=0.0,
                  mfma_TFLOPs=0.0, resident_heads=0, streaming_heads=0, sink_tokens=0, recent_tokens=0,
-                 link_kv_bits=0) -> hi_problem:
-    return hi_problem(n_layers, n_kv_heads, gqa_group, head_dim, max_context, chunk, gpu_kv_budget_heads,
-                      dtype_bytes, out_fp32, n_compute_units, resident_heads, host_mem_limit_bytes, link_GBps, hbm_GBps,
-                      mfma_TFLOPs, streaming_heads, sink_tokens, recent_tokens, link_kv_bits)
+                 link_kv_bits=0, streaming_mask=None) -> hi_problem:
+    """streaming_mask: optional [n_layers][n_kv_heads] nested list / array of 0 and 1 (1 = streaming head)."""
+    p = hi_problem(n_layers, n_kv_heads, gqa_group, head_dim, max_context, chunk, gpu_kv_budget_heads,
+                   dtype_bytes, out_fp32, n_compute_units, resident_heads, host_mem_limit_bytes, link_GBps, hbm_GBps,
+                   mfma_TFLOPs, streaming_heads, sink_tokens, recent_tokens, link_kv_bits, None)
+    if streaming_mask is not None:
+        flat = [int(x) for row in streaming_mask for x in row]
+        assert len(flat) == n_layers * n_kv_heads
+        buf = (C.c_uint8 * len(flat))(*flat)
+        p._mask_keepalive = buf                       # the struct only holds the address
+        p.streaming_mask = C.addressof(buf)
+    return p
 
 
 def hi_offload_plan(problem: hi_problem, check: bool = True):

@@ -40,6 +40,10 @@ struct hi_ctx {
   hi_plan plan;
   int mode = HI_MODE_OFFLOAD;
   int flags = 0;
+  // Appendix E head roles, per (layer, head): index among the retrieval heads (layer-major order; -1: a streaming
+  // head) and among the streaming heads (-1: a retrieval head); the retrieval index of each layer's first one
+  std::vector<uint8_t> mask;
+  std::vector<int32_t> retr_idx, strm_idx, layer_retr0;
   std::vector<char*> kv_layer;   // per layer: host (offload) or device (resident) cache rows, null: not given yet
   bool failed = false;       // an error after work had been enqueued: the ring's bookkeeping cannot be trusted
   bool enqueuing = false;    // the running call has passed its checks and started to enqueue
@@ -86,8 +90,8 @@ namespace {
 
 // heads of a layer that keep their whole history (Appendix E: "retrieval heads"); the last streaming_heads heads
 // of each layer are streaming heads, which have no rows in the cache
-inline int n_retrieval(const hi_ctx* c) { return c->prob.n_kv_heads - c->prob.streaming_heads; }
-inline bool unit_streaming(const hi_ctx* c, int head) { return head >= n_retrieval(c); }
+inline bool unit_streaming(const hi_ctx* c, int layer, int head) { return c->strm_idx[layer * c->prob.n_kv_heads + head] >= 0; }
+inline int64_t retr_index(const hi_ctx* c, int layer, int head) { return c->retr_idx[layer * c->prob.n_kv_heads + head]; }
 
 // one K (or V) row in the host cache and on the link: bf16, or 4-bit codes with a scale and a zero per 32 channels
 inline int64_t link_row(const hi_ctx* c) { return c->plan.link_row_bytes; }
@@ -96,7 +100,7 @@ inline bool link_packed(const hi_ctx* c) { return c->prob.link_kv_bits == 4; }
 // rows of (layer, head) in the cache: each layer has its own base pointer, [kv_head][K|V][S_max][row bytes] behind it
 inline char* cache_plane(const hi_ctx* c, int layer, int head, int which /*0 K, 1 V*/) {
   const int64_t plane = c->prob.max_context * link_row(c);
-  return c->kv_layer[layer] + ((int64_t)head * 2 + which) * plane;
+  return c->kv_layer[layer] + ((retr_index(c, layer, head) - c->layer_retr0[layer]) * 2 + which) * plane;
 }
 
 // A ring slot holds one sequence slice of every head of a group: rows_of(nh) rows of K then of V per head, the
@@ -110,22 +114,22 @@ inline int64_t head_pitch(const hi_ctx* c, int nh) { return rows_of(c, nh) * 2 *
 // Algorithm 1, "if h in H_on": the unit's K/V live in HBM (the whole cache in resident mode; the first
 // resident_heads (layer, head) pairs, kept behind the ring in the staging buffer, in offload mode)
 inline bool unit_resident(const hi_ctx* c, int layer, int head) {
-  if (unit_streaming(c, head)) return false;
-  return c->mode == HI_MODE_RESIDENT || (int64_t)layer * n_retrieval(c) + head < c->prob.resident_heads;
+  if (unit_streaming(c, layer, head)) return false;
+  return c->mode == HI_MODE_RESIDENT || retr_index(c, layer, head) < c->prob.resident_heads;
 }
 inline char* res_plane(const hi_ctx* c, int layer, int head, int which) {
   if (c->mode == HI_MODE_RESIDENT) return cache_plane(c, layer, head, which);
   const int64_t plane = c->prob.max_context * kRowBytes;
-  return c->staging + c->plan.hbm_resident_offset + (((int64_t)layer * n_retrieval(c) + head) * 2 + which) * plane;
+  return c->staging + c->plan.hbm_resident_offset + (retr_index(c, layer, head) * 2 + which) * plane;
 }
 // 0 offloaded, 1 HBM-resident, 2 streaming: a head group is of one kind
 inline int unit_kind(const hi_ctx* c, int layer, int head) {
-  return unit_streaming(c, head) ? 2 : unit_resident(c, layer, head) ? 1 : 0;
+  return unit_streaming(c, layer, head) ? 2 : unit_resident(c, layer, head) ? 1 : 0;
 }
 // a streaming head's bounded store (K plane, then V plane, stream_rows rows each)
 inline int64_t stream_head_stride(const hi_ctx* c) { return 2 * c->plan.stream_rows * kRowBytes; }
 inline char* stream_plane(const hi_ctx* c, int layer, int head, int which) {
-  const int64_t t = (int64_t)layer * c->prob.streaming_heads + (head - n_retrieval(c));
+  const int64_t t = c->strm_idx[layer * c->prob.n_kv_heads + head];
   return c->staging + c->plan.hbm_stream_offset + t * stream_head_stride(c) + which * c->plan.stream_rows * kRowBytes;
 }
 
@@ -305,8 +309,12 @@ hi_status check_unit_args(const hi_ctx* c, int layer, int head, int nh, const vo
     set_last_error("prefetch hint out of range");
     return HI_ERR_ARG;
   }
-  if (unit_kind(c, layer, head) != unit_kind(c, layer, head + nh - 1) ||
-      (next_layer >= 0 && unit_kind(c, next_layer, next_head) != unit_kind(c, next_layer, next_head + next_nh - 1))) {
+  auto one_kind = [&](int l, int h0, int n) {
+    for (int j = 1; j < n; ++j)
+      if (unit_kind(c, l, h0 + j) != unit_kind(c, l, h0)) return false;
+    return true;
+  };
+  if (!one_kind(layer, head, nh) || (next_layer >= 0 && !one_kind(next_layer, next_head, next_nh))) {
     set_last_error("a head group must be all HBM-resident, all offloaded or all streaming");
     return HI_ERR_ARG;
   }
@@ -463,7 +471,7 @@ extern "C" hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* pla
   if (!out || !plan) { set_last_error("null argument"); return HI_ERR_ARG; }
   HI_TRY(validate_problem(problem));
   if (mode != HI_MODE_OFFLOAD && mode != HI_MODE_RESIDENT) { set_last_error("unknown mode"); return HI_ERR_ARG; }
-  if (!hbm_workspace || ((mode == HI_MODE_OFFLOAD || problem->streaming_heads > 0) && !hbm_staging)) { set_last_error("null buffer"); return HI_ERR_ARG; }
+  if (!hbm_workspace || ((mode == HI_MODE_OFFLOAD || count_streaming(*problem) > 0) && !hbm_staging)) { set_last_error("null buffer"); return HI_ERR_ARG; }
   if (problem->link_kv_bits == 4 && mode != HI_MODE_OFFLOAD) {
     set_last_error("link_kv_bits = 4 describes the host link: offload mode only");
     return HI_ERR_UNSUPPORTED;
@@ -480,11 +488,24 @@ extern "C" hi_status hi_ctx_create(const hi_problem* problem, const hi_plan* pla
   c->prob = *problem;
   c->plan = *plan;
   c->mode = mode;
-  {  // one pointer for the whole cache: layer l starts l * (bytes of a layer) behind it
-    const int64_t layer_bytes = plan->host_bytes_total / problem->n_layers;
-    c->kv_layer.assign(problem->n_layers, nullptr);
+  {  // head roles, and one pointer for the whole cache: the retrieval heads of all layers back to back
+    const int L = problem->n_layers, H = problem->n_kv_heads;
+    if (problem->streaming_mask) c->mask.assign(problem->streaming_mask, problem->streaming_mask + (size_t)L * H);
+    c->prob.streaming_mask = nullptr;          // the caller's table is not kept
+    c->retr_idx.assign((size_t)L * H, -1);
+    c->strm_idx.assign((size_t)L * H, -1);
+    c->layer_retr0.assign(L, 0);
+    int32_t nr = 0, ns = 0;
+    for (int l = 0; l < L; ++l) {
+      c->layer_retr0[l] = nr;
+      for (int h = 0; h < H; ++h) {
+        if (head_is_streaming(*problem, c->mask.empty() ? nullptr : c->mask.data(), l, h)) c->strm_idx[(size_t)l * H + h] = ns++;
+        else c->retr_idx[(size_t)l * H + h] = nr++;
+      }
+    }
+    c->kv_layer.assign(L, nullptr);
     if (kv_cache)
-      for (int l = 0; l < problem->n_layers; ++l) c->kv_layer[l] = (char*)kv_cache + l * layer_bytes;
+      for (int l = 0; l < L; ++l) c->kv_layer[l] = (char*)kv_cache + c->layer_retr0[l] * plan->host_bytes_per_head;
   }
   c->staging = (char*)hbm_staging;
   c->ws = (char*)hbm_workspace;
@@ -630,7 +651,7 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
 
   // Everything that can be refused is refused here, before the first enqueue: the state images of the chosen
   // kernel must fit the carry, the encoded rows the write-back buffer.
-  if (!unit_streaming(c, kv_head)) {
+  if (!unit_streaming(c, layer, kv_head)) {
     const PrefillLaunch shape = prefill_launch_shape(G, chunk_len, nh, pf_variant(c), 1, 1);
     if (shape.carry_bytes > c->plan.ws_partials_offset) {
       set_last_error("prefill: the workspace holds %lld bytes of attention state, %lld needed",
@@ -650,7 +671,7 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
   }
 
   hi_ctx::Unit next = hinted_unit(c, next_layer, next_kv_head, next_nh, next_past_len);
-  if (unit_streaming(c, kv_head)) {
+  if (unit_streaming(c, layer, kv_head)) {
     // Appendix E: attention over what the bounded store holds of the past plus the chunk, then the chunk's rows
     // enter the store; nothing crosses the link
     char* sk = stream_plane(c, layer, kv_head, 0);
@@ -750,7 +771,7 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
   }
 
   hi_ctx::Unit next = hinted_unit(c, next_layer, next_kv_head, next_nh, next_past_len);
-  if (unit_streaming(c, kv_head)) {
+  if (unit_streaming(c, layer, kv_head)) {
     // Appendix E: the store holds the sink tokens and the n_recent tokens before this one; the oldest of those
     // has just left the window: it takes no part, and the token's row replaces it
     const int64_t n_sink = c->prob.sink_tokens, n_recent = c->prob.recent_tokens;

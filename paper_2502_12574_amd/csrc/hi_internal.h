@@ -94,6 +94,19 @@ inline int64_t decode_part_head_stride(int64_t max_context, int64_t slice_tokens
 
 hi_status validate_problem(const hi_problem* p);
 
+// Appendix E head roles: is (layer, head) a streaming head?  (the mask if given, else the last streaming_heads heads)
+inline bool head_is_streaming(const hi_problem& p, const uint8_t* mask, int layer, int head) {
+  if (mask) return mask[(int64_t)layer * p.n_kv_heads + head] != 0;
+  return head >= p.n_kv_heads - p.streaming_heads;
+}
+// streaming heads of all layers
+inline int64_t count_streaming(const hi_problem& p) {
+  if (!p.streaming_mask) return (int64_t)p.n_layers * p.streaming_heads;
+  int64_t n = 0;
+  for (int64_t i = 0; i < (int64_t)p.n_layers * p.n_kv_heads; ++i) n += p.streaming_mask[i] != 0;
+  return n;
+}
+
 // ---- kernel launchers (defined in the .hip files) ------------------------------------------------------
 struct PrefillSegment {
   const void* k;      // device, [n][128] bf16 (first head of a group)

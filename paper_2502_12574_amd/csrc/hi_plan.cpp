@@ -26,22 +26,34 @@ hi_status validate_problem(const hi_problem* p) {
     return HI_ERR_ARG;
   }
   if (p->chunk > p->max_context) { set_last_error("chunk %d exceeds max_context", p->chunk); return HI_ERR_ARG; }
-  if (p->streaming_heads < 0 || p->streaming_heads >= p->n_kv_heads) {
+  if (!p->streaming_mask && (p->streaming_heads < 0 || p->streaming_heads >= p->n_kv_heads)) {
     set_last_error("streaming_heads must be in [0, n_kv_heads)");
     return HI_ERR_ARG;
   }
+  if (p->streaming_mask) {
+    for (int l = 0; l < p->n_layers; ++l) {
+      int n = 0;
+      for (int h = 0; h < p->n_kv_heads; ++h) {
+        const uint8_t m = p->streaming_mask[(int64_t)l * p->n_kv_heads + h];
+        if (m > 1) { set_last_error("streaming_mask entries must be 0 or 1"); return HI_ERR_ARG; }
+        n += m;
+      }
+      if (n >= p->n_kv_heads) { set_last_error("layer %d has no retrieval head", l); return HI_ERR_ARG; }
+    }
+  }
+  const int64_t n_streaming = count_streaming(*p);
   if (p->link_kv_bits != 0 && p->link_kv_bits != 16 && p->link_kv_bits != 4) {
     set_last_error("link_kv_bits must be 0, 16 (bf16 rows) or 4");
     return HI_ERR_ARG;
   }
-  if (p->streaming_heads > 0 && (p->sink_tokens < 0 || p->recent_tokens < 1 ||
+  if (n_streaming > 0 && (p->sink_tokens < 0 || p->recent_tokens < 1 ||
                                  (int64_t)p->sink_tokens + p->recent_tokens > kStreamMaxRows)) {
     set_last_error("streaming heads need sink_tokens >= 0, recent_tokens >= 1 and at most %lld rows in all",
                    (long long)kStreamMaxRows);
     return HI_ERR_ARG;
   }
   if (p->resident_heads < 0 ||
-      (int64_t)p->resident_heads > (int64_t)p->n_layers * (p->n_kv_heads - p->streaming_heads)) {
+      (int64_t)p->resident_heads > (int64_t)p->n_layers * p->n_kv_heads - n_streaming) {
     set_last_error("resident_heads out of range");
     return HI_ERR_ARG;
   }
@@ -78,7 +90,8 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
 
   // Eq. 11 and Eq. 4
   pl.host_bytes_per_head = S * link_row;
-  pl.host_bytes_total = (int64_t)p->n_layers * (p->n_kv_heads - p->streaming_heads) * pl.host_bytes_per_head;
+  const int64_t n_streaming = count_streaming(*p);
+  pl.host_bytes_total = ((int64_t)p->n_layers * p->n_kv_heads - n_streaming) * pl.host_bytes_per_head;
   if (p->host_mem_limit_bytes > 0 && pl.host_bytes_total > p->host_mem_limit_bytes) {
     set_last_error("host cache of %lld bytes exceeds the limit", (long long)pl.host_bytes_total);
     return HI_ERR_HOST_MEM;
@@ -123,7 +136,18 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   // per-call overheads dominate and as many heads as the slice can hold (64 rows each) go into one call; up to 256K
   // two heads per call still gain a few per cent; beyond, one head per call (the finest granularity) is as fast.
   {
-    const int n_retrieval = p->n_kv_heads - p->streaming_heads;   // a group never mixes the two kinds of head
+    // a group never mixes the two kinds of head (with a mask: the layer with the fewest retrieval heads decides)
+    int n_retrieval = p->n_kv_heads - p->streaming_heads, n_stream_layer = p->streaming_heads;
+    if (p->streaming_mask) {
+      n_retrieval = p->n_kv_heads;
+      n_stream_layer = 0;
+      for (int l = 0; l < p->n_layers; ++l) {
+        int n = 0;
+        for (int h = 0; h < p->n_kv_heads; ++h) n += p->streaming_mask[(int64_t)l * p->n_kv_heads + h];
+        if (p->n_kv_heads - n < n_retrieval) n_retrieval = p->n_kv_heads - n;
+        if (n > n_stream_layer) n_stream_layer = n;
+      }
+    }
     int hpg = 1;
     if (S <= 16 * 1024 + p->chunk) {
       while (hpg * 2 <= n_retrieval && (int64_t)hpg * 2 * 64 <= slice) hpg *= 2;
@@ -131,14 +155,14 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
       if (n_retrieval >= 2 && 2 * 64 <= slice) hpg = 2;
     }
     pl.heads_per_group = hpg;
-    pl.n_groups = (int32_t)(ceil_div(n_retrieval, hpg) + ceil_div(p->streaming_heads, hpg));
+    pl.n_groups = (int32_t)(ceil_div(n_retrieval, hpg) + ceil_div(n_stream_layer, hpg));
   }
   pl.hbm_resident_offset = n_slices * slice * row;
   pl.hbm_resident_bytes = (int64_t)p->resident_heads * S * row;
   // Appendix E: the streaming heads' bounded stores, small and outside the whole-head budget
-  pl.stream_rows = p->streaming_heads > 0 ? (int64_t)p->sink_tokens + p->recent_tokens : 0;
+  pl.stream_rows = n_streaming > 0 ? (int64_t)p->sink_tokens + p->recent_tokens : 0;
   pl.hbm_stream_offset = pl.hbm_resident_offset + pl.hbm_resident_bytes;
-  pl.hbm_stream_bytes = (int64_t)p->n_layers * p->streaming_heads * pl.stream_rows * row;
+  pl.hbm_stream_bytes = n_streaming * pl.stream_rows * row;
   pl.hbm_packed_offset = pl.hbm_stream_offset + pl.hbm_stream_bytes;
   pl.hbm_packed_bytes = packed ? n_slices * slice * link_row : 0;
   pl.hbm_staging_bytes = pl.hbm_packed_offset + pl.hbm_packed_bytes;
@@ -152,7 +176,7 @@ extern "C" hi_status hi_offload_plan(const hi_problem* p, hi_plan* out) {
   const int64_t partial_bytes = decode_part_head_stride(S, slice, pl.n_split_decode, G) * 4 * p->n_kv_heads;
   pl.ws_partials_offset = round_up(carry_bytes, 256);
   pl.ws_writeback_offset = pl.ws_partials_offset + round_up(partial_bytes, 256);
-  pl.ws_writeback_bytes = packed ? 2 * round_up((int64_t)(p->n_kv_heads - p->streaming_heads) * C * link_row, 256) : 0;
+  pl.ws_writeback_bytes = packed ? 2 * round_up((int64_t)(p->streaming_mask ? p->n_kv_heads : p->n_kv_heads - p->streaming_heads) * C * link_row, 256) : 0;
   pl.workspace_bytes = pl.ws_writeback_offset + pl.ws_writeback_bytes;
 
   // Section 5: T ~ max(T_comp, T_mem), evaluated for the deepest unit

@@ -12,7 +12,7 @@ from . import binding as hb
 class Session:
     def __init__(self, n_layers, n_kv_heads, gqa_group, max_context, chunk, mode=hb.HI_MODE_OFFLOAD, out_fp32=1,
                  device="cuda:0", gpu_kv_budget_heads=1, n_compute_units=0, resident_heads=0, streaming_heads=0,
-                 sink_tokens=0, recent_tokens=0, link_kv_bits=0, per_layer_cache=False):
+                 sink_tokens=0, recent_tokens=0, link_kv_bits=0, per_layer_cache=False, progress=None, streaming_mask=None):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the library has no CPU path")
         self.device = torch.device(device)
@@ -22,17 +22,28 @@ class Session:
                                        gpu_kv_budget_heads=gpu_kv_budget_heads, n_compute_units=n_compute_units,
                                        resident_heads=resident_heads, streaming_heads=streaming_heads,
                                        sink_tokens=sink_tokens, recent_tokens=recent_tokens,
-                                       link_kv_bits=link_kv_bits)
+                                       link_kv_bits=link_kv_bits, streaming_mask=streaming_mask)
+        # retrieval heads of each layer (the heads that have rows in the cache), in head order
+        if streaming_mask is not None:
+            self.retrieval = [[h for h in range(n_kv_heads) if not streaming_mask[l][h]] for l in range(n_layers)]
+        else:
+            self.retrieval = [list(range(n_kv_heads - streaming_heads)) for _ in range(n_layers)]
         self.plan = hb.hi_offload_plan(self.problem)
         nbytes = self.plan.host_bytes_total
         # per_layer_cache: one allocation per layer (hi_ctx_set_layer_cache) instead of one for the whole cache
         self.kv_layers = None
         if per_layer_cache:
-            per = nbytes // n_layers
+            per_head = self.plan.host_bytes_per_head
+            per = per_head * len(self.retrieval[0])
             if mode == hb.HI_MODE_OFFLOAD:
-                self.kv_layers = [torch.empty(per, dtype=torch.uint8, pin_memory=True) for _ in range(n_layers)]
+                self.kv_layers = []
+                for l in range(n_layers):
+                    self.kv_layers.append(torch.empty(per_head * len(self.retrieval[l]), dtype=torch.uint8, pin_memory=True))
+                    if progress is not None:
+                        progress(f"pinned the cache of layer {l + 1} of {n_layers} ({per / 2**30:.1f} GiB)")
             else:
-                self.kv_layers = [torch.empty(per, dtype=torch.uint8, device=self.device) for _ in range(n_layers)]
+                self.kv_layers = [torch.empty(per_head * len(self.retrieval[l]), dtype=torch.uint8, device=self.device)
+                                  for l in range(n_layers)]
             self.kv = None
             nbytes = 0
         if mode == hb.HI_MODE_OFFLOAD:
@@ -71,6 +82,20 @@ class Session:
                                 self.plan.link_row_bytes)
         return self.kv.view(torch.bfloat16).view(p.n_layers, p.n_kv_heads - p.streaming_heads, 2, p.max_context,
                                                  p.head_dim)
+
+    def head_cache_view(self, layer, head) -> torch.Tensor:
+        """[K|V][S_max][d] bf16 (or [K|V][S_max][80] bytes) rows of one retrieval head, whatever the head roles."""
+        p = self.problem
+        j = self.retrieval[layer].index(head)
+        per_head = self.plan.host_bytes_per_head
+        if self.kv_layers is not None:
+            raw = self.kv_layers[layer][j * per_head:(j + 1) * per_head]
+        else:
+            first = sum(len(self.retrieval[l]) for l in range(layer)) + j
+            raw = self.kv[first * per_head:(first + 1) * per_head]
+        if p.link_kv_bits == 4:
+            return raw.view(2, p.max_context, self.plan.link_row_bytes)
+        return raw.view(torch.bfloat16).view(2, p.max_context, p.head_dim)
 
     # [layer][streaming head][K|V][stream_rows][d] bf16 view of the streaming heads' bounded stores
     def stream_view(self) -> torch.Tensor:
