@@ -255,6 +255,18 @@ hi_status hi_decode_group(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n
                           int32_t next_layer, int32_t next_kv_head, int32_t next_n_heads, int64_t next_past_len);
 
 /*
+ * A decode step over n_heads (<= 64) consecutive HBM-RESIDENT KV heads whose histories differ in length - a batch of
+ * sequences of different lengths served as more KV heads (the paper runs batch 1; Section 3.2 notes the head-wise
+ * partition extends to the batch dimension): head j has past_lens[j] rows (HOST array, read before the call returns),
+ * its token's row is appended at row past_lens[j] and attends over rows 0..past_lens[j].  One split-KV launch over
+ * all heads (a head with fewer rows than partitions leaves neutral partials), one combine launch.  Buffers as in
+ * hi_decode_group.  HI_ERR_UNSUPPORTED for offloaded or streaming heads (the heads of an offloaded group share
+ * staging slices of one length: call those one by one, each at its own past_len).
+ */
+hi_status hi_decode_group_ragged(hi_ctx* ctx, int32_t layer, int32_t kv_head, int32_t n_heads, const void* q_dev,
+                                 const void* k_new_dev, const void* v_new_dev, const int64_t* past_lens, void* out_dev);
+
+/*
  * Streaming heads (Appendix E, "Efficient Management of KV cache": retrieval heads retain all tokens and are
  * offloaded, streaming heads retain only recent tokens and stay on the GPU).  With hi_problem.streaming_heads > 0
  * the same four calls serve the last streaming_heads KV heads of a layer, with these differences:

@@ -20,7 +20,7 @@ HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_PAIRED, HI_FLAG_PREFILL_DEEP, HI_FLAG_PR
 HI_FLAG_INJECT_FAILURE = 128
 
 EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_layer_cache", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
-           "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_proj_workspace_bytes",
+           "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_decode_group_ragged", "hi_proj_workspace_bytes",
            "hi_qkv_rope", "hi_qkv_rope_static", "hi_out_proj", "hi_kv_quantize", "hi_kv_dequantize", "hi_sync", "hi_get_stats", "hi_reset_stats", "hi_status_string", "hi_last_error")
 
 
@@ -88,6 +88,7 @@ def lib() -> C.CDLL:
         L.hi_decode_head.argtypes = [vp, i32, i32, vp, vp, vp, i64, vp, i32, i32, i64]
         L.hi_prefill_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, i32, vp, i32, i32, i32, i64]
         L.hi_decode_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, vp, i32, i32, i32, i64]
+        L.hi_decode_group_ragged.argtypes = [vp, i32, i32, i32, vp, vp, vp, C.POINTER(i64), vp]
         L.hi_proj_workspace_bytes.argtypes = [i32, C.POINTER(i64)]
         L.hi_qkv_rope.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp, vp]
         L.hi_qkv_rope_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp]
@@ -224,6 +225,16 @@ def hi_decode_group(ctx, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, p
                                _ptr(out_dev), next_layer, next_kv_head, next_n_heads, next_past_len)
     if check and st != HI_OK:
         raise HiError(st, "hi_decode_group")
+    return st
+
+
+def hi_decode_group_ragged(ctx, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, past_lens, out_dev,
+                           check: bool = True):
+    lens = (C.c_int64 * n_heads)(*[int(x) for x in past_lens])
+    st = lib().hi_decode_group_ragged(ctx, layer, kv_head, n_heads, _ptr(q_dev), _ptr(k_new_dev), _ptr(v_new_dev), lens,
+                                      _ptr(out_dev))
+    if check and st != HI_OK:
+        raise HiError(st, "hi_decode_group_ragged")
     return st
 
 

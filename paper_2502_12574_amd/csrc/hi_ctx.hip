@@ -876,6 +876,55 @@ extern "C" hi_status hi_decode_group(hi_ctx* c, int32_t layer, int32_t kv_head, 
   });
 }
 
+// One token of n_heads HBM-resident KV heads whose histories differ in length (a batch of sequences served as more KV
+// heads): one split-KV launch over all of them, each head reading its own number of rows, one combine launch.
+extern "C" hi_status hi_decode_group_ragged(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t n_heads, const void* q_dev,
+                                            const void* k_new_dev, const void* v_new_dev, const int64_t* past_lens,
+                                            void* out_dev) {
+  if (!past_lens) { set_last_error("past_lens is null"); return HI_ERR_ARG; }
+  if (n_heads < 1 || n_heads > kDecodeMaxRagged) { set_last_error("a ragged call takes 1 to %d heads", kDecodeMaxRagged); return HI_ERR_ARG; }
+  int64_t longest = 0;
+  for (int j = 0; j < n_heads; ++j) {
+    if (past_lens[j] < 0) { set_last_error("negative past_len"); return HI_ERR_ARG; }
+    if (past_lens[j] > longest) longest = past_lens[j];
+  }
+  HI_TRY(check_unit_args(c, layer, kv_head, n_heads, q_dev, k_new_dev, v_new_dev, longest, 1, out_dev, -1, 0, 1, 0));
+  if (unit_kind(c, layer, kv_head) != 1) {
+    set_last_error("heads of different lengths in one call: HBM-resident heads only (offloaded heads share staging slices "
+                   "of one length; call them one by one)");
+    return HI_ERR_UNSUPPORTED;
+  }
+  const int G = c->prob.gqa_group;
+  const int64_t part_stride = decode_part_head_stride(c->prob.max_context, c->slice_tokens, c->plan.n_split_decode, G);
+  const int64_t part_cap = part_stride / (G * kPartialFloats);
+  int n_split = c->plan.n_split_decode / n_heads > 0 ? c->plan.n_split_decode / n_heads : 1;
+  const int64_t need = ceil_div(longest, 64);
+  if (need < n_split) n_split = (int)need;
+  if (n_split > part_cap) { set_last_error("decode: the partial workspace cannot hold %d partitions", n_split); return HI_ERR_UNSUPPORTED; }
+  return guarded(c, [&]() -> hi_status {
+    c->enqueuing = true;
+    if (c->flags & HI_FLAG_SKIP_KERNELS) { set_last_error("a ragged call has no copies to time"); return HI_ERR_UNSUPPORTED; }
+    DecodeLens lens = {};
+    for (int j = 0; j < n_heads; ++j) lens.n[j] = past_lens[j];
+    float* partials = (float*)(c->ws + c->plan.ws_partials_offset);
+    const int64_t plane2 = 2 * c->prob.max_context * kRowBytes;
+    const bool timed = (c->flags & HI_FLAG_TIME_KERNELS) != 0;
+    if (longest > 0) {
+      TimedSpan sp;
+      if (timed) HI_TRY(span_begin(c, 1, &sp));
+      HI_TRY(launch_decode_partial(c->sc, q_dev, G, res_plane(c, layer, kv_head, 0), res_plane(c, layer, kv_head, 1), longest,
+                                   n_split, partials, 0, n_heads, plane2, part_stride, -1, &lens));
+      if (timed) HI_TRY(span_end(c, sp));
+      c->stats.n_decode_kernels += 1;
+    }
+    HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, longest > 0 ? n_split : 0, out_dev,
+                                 c->prob.out_fp32, res_plane(c, layer, kv_head, 0), res_plane(c, layer, kv_head, 1), n_heads,
+                                 part_stride, plane2, &lens));
+    c->stats.n_combine_kernels += 1;
+    return HI_OK;
+  });
+}
+
 extern "C" hi_status hi_prefill_head(hi_ctx* c, int32_t layer, int32_t kv_head, const void* q_dev,
                                      const void* k_new_dev, const void* v_new_dev, int64_t past_len,
                                      int32_t chunk_len, void* out_dev, int32_t next_layer, int32_t next_kv_head,

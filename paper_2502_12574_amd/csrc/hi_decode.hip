@@ -37,12 +37,17 @@ __device__ __forceinline__ void dec_issue_block(const char* __restrict__ k, cons
   }
 }
 
+// RAGGED: the heads of the launch have their own numbers of rows (sequences of different lengths served as more KV
+// heads); a head with fewer 16-row blocks than the grid has wavefronts leaves neutral partials.
+template <bool RAGGED>
 __global__ __launch_bounds__(256) void decode_partial_kernel(const uint16_t* __restrict__ q, int G,
                                                              const char* __restrict__ k, const char* __restrict__ v,
                                                              int64_t n, float* __restrict__ partials, int part0,
                                                              float c, int64_t kv_head_stride,
-                                                             int64_t part_head_stride, int64_t skip_row) {
+                                                             int64_t part_head_stride, int64_t skip_row,
+                                                             DecodeLens lens) {
   // group launches: blockIdx.y is the head
+  if (RAGGED) n = lens.n[blockIdx.y];
   q += (int64_t)blockIdx.y * G * kHeadDim;
   k += blockIdx.y * kv_head_stride;
   v += blockIdx.y * kv_head_stride;
@@ -208,7 +213,8 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const uint16_t* __r
                                                              void* __restrict__ out, int out_fp32, float c,
                                                              uint16_t* __restrict__ k_append,
                                                              uint16_t* __restrict__ v_append,
-                                                             int64_t part_head_stride, int64_t append_head_stride) {
+                                                             int64_t part_head_stride, int64_t append_head_stride,
+                                                             int ragged, DecodeLens lens) {
   // group launches: blockIdx.z is the head
   q += (int64_t)blockIdx.z * G * kHeadDim;
   k_new += blockIdx.z * kHeadDim;
@@ -216,8 +222,10 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const uint16_t* __r
   partials += blockIdx.z * part_head_stride;
   out = (char*)out + (int64_t)blockIdx.z * G * kHeadDim * (out_fp32 ? 4 : 2);
   if (k_append != nullptr) {
-    k_append = (uint16_t*)((char*)k_append + blockIdx.z * append_head_stride);
-    v_append = (uint16_t*)((char*)v_append + blockIdx.z * append_head_stride);
+    // (ragged: k_append / v_append point at row 0 of the first head; each head appends at its own length)
+    const int64_t row_off = ragged ? lens.n[blockIdx.z] * kRowBytes : 0;
+    k_append = (uint16_t*)((char*)k_append + blockIdx.z * append_head_stride + row_off);
+    v_append = (uint16_t*)((char*)v_append + blockIdx.z * append_head_stride + row_off);
   }
   __shared__ float red[4];
   __shared__ float red_o[kCombLanes][kCombDims + 1];
@@ -278,18 +286,27 @@ static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   //
 
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
                                 int n_split, void* partials, int part0, int n_heads, int64_t kv_head_stride,
-                                int64_t part_head_stride, int64_t skip_row) {
-  if (n <= 0 || n_split <= 0 || n_heads < 1) { set_last_error("decode partial: empty launch"); return HI_ERR_ARG; }
+                                int64_t part_head_stride, int64_t skip_row, const DecodeLens* lens) {
+  if (n <= 0 || n_split <= 0 || n_heads < 1 || (lens && n_heads > kDecodeMaxRagged)) { set_last_error("decode partial: empty launch"); return HI_ERR_ARG; }
   static std::once_flag attr_once;      // contexts on different host threads may get here together
   static hipError_t attr_err = hipSuccess;
   std::call_once(attr_once, [] {
-    attr_err = hipFuncSetAttribute((const void*)decode_partial_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+    attr_err = hipFuncSetAttribute((const void*)decode_partial_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    kDecLdsBytes);
+    if (attr_err == hipSuccess)
+      attr_err = hipFuncSetAttribute((const void*)decode_partial_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     kDecLdsBytes);
   });
   if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
-  hipLaunchKernelGGL(decode_partial_kernel, dim3(n_split, n_heads), dim3(256), kDecLdsBytes, (hipStream_t)stream,
-                     (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e,
-                     kv_head_stride, part_head_stride, skip_row);
+  static const DecodeLens no_lens = {};
+  if (lens)
+    hipLaunchKernelGGL(decode_partial_kernel<true>, dim3(n_split, n_heads), dim3(256), kDecLdsBytes, (hipStream_t)stream,
+                       (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e,
+                       kv_head_stride, part_head_stride, skip_row, *lens);
+  else
+    hipLaunchKernelGGL(decode_partial_kernel<false>, dim3(n_split, n_heads), dim3(256), kDecLdsBytes, (hipStream_t)stream,
+                       (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e,
+                       kv_head_stride, part_head_stride, skip_row, no_lens);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("decode_partial launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
   return HI_OK;
@@ -297,11 +314,14 @@ hi_status launch_decode_partial(void* stream, const void* q, int G, const void* 
 
 hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
                                 const void* partials, int n_part, void* out, int out_fp32, void* k_append,
-                                void* v_append, int n_heads, int64_t part_head_stride, int64_t append_head_stride) {
+                                void* v_append, int n_heads, int64_t part_head_stride, int64_t append_head_stride,
+                                const DecodeLens* lens) {
+  static const DecodeLens no_lens = {};
+  if (lens && n_heads > kDecodeMaxRagged) { set_last_error("decode combine: too many heads of their own length"); return HI_ERR_ARG; }
   hipLaunchKernelGGL(decode_combine_kernel, dim3(G, kHeadDim / kCombDims, n_heads), dim3(256), 0, (hipStream_t)stream,
                      (const uint16_t*)q, G, (const uint16_t*)k_new, (const uint16_t*)v_new, (const float*)partials,
                      n_part, out, out_fp32, kScaleLog2e, (uint16_t*)k_append, (uint16_t*)v_append, part_head_stride,
-                     append_head_stride);
+                     append_head_stride, lens ? 1 : 0, lens ? *lens : no_lens);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("decode_combine launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
   return HI_OK;

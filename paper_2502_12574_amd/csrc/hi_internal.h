@@ -126,20 +126,26 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
                          const PrefillSegment& b, int first, int last, void* carry, void* out, int out_fp32,
                          int variant, int n_heads = 1, int64_t carry_bytes = -1);
 
+// rows per head of a decode launch whose heads differ in length (passed to the kernels by value)
+constexpr int kDecodeMaxRagged = 64;
+struct DecodeLens { int64_t n[kDecodeMaxRagged]; };
+
 // Split-KV decode over rows [0, n) of one slice: writes n_split partials starting at partial index part0.
 // n_heads > 1: q is [n_heads][G][128], the heads' K (V) rows kv_head_stride bytes apart, their partials
 // part_head_stride floats apart.
 // skip_row >= 0: that row takes no part (the row of a streaming head's store that the token replaces).
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
                                 int n_split, void* partials, int part0, int n_heads = 1, int64_t kv_head_stride = 0,
-                                int64_t part_head_stride = 0, int64_t skip_row = -1);
+                                int64_t part_head_stride = 0, int64_t skip_row = -1, const DecodeLens* lens = nullptr);
+// lens != null: head h has lens->n[h] rows instead of n (n = the largest of them), and launch_decode_combine appends
+// head h's row at row lens->n[h] behind k_append / v_append (which then point at row 0 of the first head)
 // Merge n_part partials with the token's own row and write out[G][128]; if k_append/v_append are not null the
 // token's K/V row is also copied there (device rows of an HBM-resident cache; heads append_head_stride bytes
 // apart).  n_heads > 1: q and out are [n_heads][G][128], k_new / v_new [n_heads][128].
 hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
                                 const void* partials, int n_part, void* out, int out_fp32, void* k_append,
                                 void* v_append, int n_heads = 1, int64_t part_head_stride = 0,
-                                int64_t append_head_stride = 0);
+                                int64_t append_head_stride = 0, const DecodeLens* lens = nullptr);
 
 // Streaming heads (Appendix E): a head that keeps n_sink initial and n_recent recent tokens in an HBM store of
 // n_sink + n_recent rows (sink token j at row j; token j >= n_sink at row n_sink + (j - n_sink) mod n_recent).

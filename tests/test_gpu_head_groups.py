@@ -173,3 +173,62 @@ def test_a_batch_of_ragged_sequences_is_more_heads(mode):
             ref = oa.attn_head(synth.to_f64(Q[h].cpu()), synth.to_f64(K[h].cpu()), synth.to_f64(V[h].cpu()))
             check(torch.cat(pre[h], dim=1), ref[:, :S], f"sequence {b} head {j} prefill")
             check(torch.stack(dec[h], dim=1), ref[:, S:], f"sequence {b} head {j} decode")
+
+
+def test_one_decode_launch_over_heads_of_different_lengths():
+    """A batch of sequences of different lengths in HBM-resident heads: hi_decode_group_ragged serves all heads of all
+    sequences in one split-KV launch and one combine launch, each head reading its own number of rows and appending
+    its token's row at its own position.  Every head matches the oracle and the per-sequence calls."""
+    Hs, G, nd, seed, dev = 2, 4, 3, 6500, "cuda:0"
+    lens = [5000, 0, 45, 1333, 64]                         # rows already cached per sequence (one has none yet)
+    B = len(lens)
+    H = B * Hs
+    S_max = max(lens) + nd
+    with Session(1, H, G, S_max, 64, mode=hb.HI_MODE_RESIDENT, out_fp32=1) as ss, \
+            Session(1, H, G, S_max, 64, mode=hb.HI_MODE_RESIDENT, out_fp32=1) as ref_ss:
+        Q, K, V = {}, {}, {}
+        with torch.cuda.stream(ss.s_compute):
+            for h in range(H):
+                n = lens[h // Hs] + nd
+                Q[h] = torch.stack([synth.draw_q(seed, 0, h * G + g, 0, n, device=dev) for g in range(G)])
+                K[h] = synth.draw_k(seed, 0, h, 0, n, device=dev)
+                V[h] = synth.draw_v(seed, 0, h, 0, n, device=dev)
+                for s_ in (ss, ref_ss):
+                    cv = s_.cache_view()
+                    cv[0, h, 0, :lens[h // Hs]].copy_(K[h][:lens[h // Hs]])
+                    cv[0, h, 1, :lens[h // Hs]].copy_(V[h][:lens[h // Hs]])
+            torch.cuda.synchronize()
+            got, sep = [], []
+            for t in range(nd):
+                past = [lens[h // Hs] + t for h in range(H)]
+                q = torch.stack([Q[h][:, past[h]] for h in range(H)]).contiguous()
+                k = torch.stack([K[h][past[h]] for h in range(H)]).contiguous()
+                v = torch.stack([V[h][past[h]] for h in range(H)]).contiguous()
+                out = torch.empty(H, G, 128, dtype=torch.float32, device=dev)
+                hb.hi_decode_group_ragged(ss.ctx, 0, 0, H, q, k, v, past, out)
+                got.append(out)
+                out2 = torch.empty(H, G, 128, dtype=torch.float32, device=dev)
+                with torch.cuda.stream(ref_ss.s_compute):
+                    for b in range(B):
+                        ref_ss.decode_group(0, b * Hs, Hs, q[b * Hs:(b + 1) * Hs], k[b * Hs:(b + 1) * Hs],
+                                            v[b * Hs:(b + 1) * Hs], lens[b] + t, out2[b * Hs:(b + 1) * Hs])
+                sep.append(out2)
+        ss.sync()
+        ref_ss.sync()
+        torch.cuda.synchronize()
+        for h in range(H):
+            n = lens[h // Hs]
+            qf, kf, vf = synth.to_f64(Q[h].cpu()), synth.to_f64(K[h].cpu()), synth.to_f64(V[h].cpu())
+            for t in range(nd):
+                want = np.stack([oa.attn_rows(qf[g][n + t][None], kf, vf, np.array([n + t]))[0] for g in range(G)])
+                check(got[t][h], want, f"ragged decode head {h} token {t}")
+                assert (got[t][h] - sep[t][h]).abs().max() < 1e-3     # other partitions: bf16 rounding of the weights differs
+            # the token rows were appended at each head's own position; nothing beyond was touched
+            cv = ss.cache_view()[0, h].cpu()
+            assert torch.equal(cv[0, :n + nd], K[h].cpu()) and torch.equal(cv[1, :n + nd], V[h].cpu())
+    # offloaded heads share staging slices of one length: refused before anything is enqueued
+    with Session(1, 2, G, 1024, 64, mode=hb.HI_MODE_OFFLOAD, out_fp32=1) as so:
+        z = torch.zeros(2, G, 128, dtype=torch.bfloat16, device=dev)
+        o = torch.zeros(2, G, 128, dtype=torch.float32, device=dev)
+        assert hb.hi_decode_group_ragged(so.ctx, 0, 0, 2, z, z[:, 0], z[:, 0], [5, 9], o, check=False) == hb.HI_ERR_UNSUPPORTED
+        assert hb.hi_decode_group_ragged(so.ctx, 0, 0, 2, z, z[:, 0], z[:, 0], [5, -1], o, check=False) == hb.HI_ERR_ARG
