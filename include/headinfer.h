@@ -44,6 +44,7 @@ enum { HI_REGIME_COMPUTE = 0, HI_REGIME_LINK = 1, HI_REGIME_HBM = 2 };
  * the deepest workgroups at least a few tiles. Do not change the variant between the calls of one (chunk, head) unit. */
 enum { HI_FLAG_SKIP_KERNELS = 1, HI_FLAG_SKIP_COPIES = 2, HI_FLAG_TIME_KERNELS = 4, HI_FLAG_PREFILL_NARROW = 8,
        HI_FLAG_PREFILL_PAIRED = 16, HI_FLAG_PREFILL_DEEP = 32, HI_FLAG_PREFILL_UNPAIRED = 64,
+       HI_FLAG_PREFILL_MFMA32 = 256 /* the DEEP kernel in its 32x32x16 MFMA form (by default it uses 16x16x32) */,
        HI_FLAG_INJECT_FAILURE = 128 /* test hook: the next unit call fails with HI_ERR_HIP right after its checks, as a
                                        failed launch or copy would; no GPU work is skipped or broken by it */ };
 

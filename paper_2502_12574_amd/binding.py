@@ -18,6 +18,7 @@ HI_REGIME_COMPUTE, HI_REGIME_LINK, HI_REGIME_HBM = 0, 1, 2
 HI_FLAG_SKIP_KERNELS, HI_FLAG_SKIP_COPIES, HI_FLAG_TIME_KERNELS = 1, 2, 4
 HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_PAIRED, HI_FLAG_PREFILL_DEEP, HI_FLAG_PREFILL_UNPAIRED = 8, 16, 32, 64
 HI_FLAG_INJECT_FAILURE = 128
+HI_FLAG_PREFILL_MFMA32 = 256
 
 EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_layer_cache", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
            "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_decode_group_ragged", "hi_proj_workspace_bytes",

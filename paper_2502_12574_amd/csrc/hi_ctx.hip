@@ -289,7 +289,8 @@ hi_status pace_end(hi_ctx* c) {
 
 int pf_variant(const hi_ctx* c) {
   return ((c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_DEEP) ? 3 : 0) |
-         ((c->flags & HI_FLAG_PREFILL_PAIRED) ? 4 : 0) | ((c->flags & HI_FLAG_PREFILL_UNPAIRED) ? 8 : 0);
+         ((c->flags & HI_FLAG_PREFILL_PAIRED) ? 4 : 0) | ((c->flags & HI_FLAG_PREFILL_UNPAIRED) ? 8 : 0) |
+         ((c->flags & HI_FLAG_PREFILL_MFMA32) ? 16 : 0);
 }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -576,7 +577,7 @@ extern "C" hi_status hi_ctx_set_layer_cache(hi_ctx* c, int32_t layer, void* kv_l
 extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
   if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS | HI_FLAG_PREFILL_NARROW |
                       HI_FLAG_PREFILL_PAIRED | HI_FLAG_PREFILL_DEEP | HI_FLAG_PREFILL_UNPAIRED |
-                      HI_FLAG_INJECT_FAILURE))) { set_last_error("bad flags"); return HI_ERR_ARG; }
+                      HI_FLAG_INJECT_FAILURE | HI_FLAG_PREFILL_MFMA32))) { set_last_error("bad flags"); return HI_ERR_ARG; }
   c->flags = flags;
   return HI_OK;
 }

@@ -10,7 +10,8 @@ constexpr int kHeadDim = 128;
 constexpr int kRowBytes = kHeadDim * 2;          // one K (or V) row of one head, bf16
 constexpr int kLinkRowBytes4 = kHeadDim / 2 + 4 * (kHeadDim / 32);   // a row as 4-bit codes + bf16 scale/zero per 32 channels
 constexpr int kWgThreads = 256;                  // 4 wavefronts of 64
-constexpr int kCarryFloatsPerLane = 66;          // 64 O^T accumulators + running max + running sum
+constexpr int kCarryFloatsPerLane = 68;          // 64 O^T accumulators + running maxima + row-sum shares (one of each
+                                                 // in the 32x32x16 kernels, two in the 16x16x32 kernel)
 constexpr int kPartialFloats = kHeadDim + 2;     // O[128], m, l of one (partition, query head)
 
 void set_last_error(const char* fmt, ...);
@@ -37,7 +38,8 @@ inline int prefill_split(int G, int64_t chunk_len, int n_heads = 1) {
 }
 // What one launch of a prefill unit looks like (host side; the kernels derive the rest from these numbers).
 // variant: low two bits 0 = pick the kernel by chunk length, 1 = 4-wave kernel, 3 = 8-wave kernel; + 4: pair deep and
-// shallow blocks in every last launch that has two blocks, + 8: never pair (measurement).
+// shallow blocks in every last launch that has two blocks, + 8: never pair (measurement); + 16: the 8-wave kernel in
+// its 32x32x16 MFMA form instead of the 16x16x32 one.
 constexpr int kPdLanes = 512;                   // lanes of an 8-wave workgroup
 constexpr int kPrefillPairMinTiles = 4;         // pair when it saves the deepest workgroup at least this many tiles
 struct PrefillLaunch {

@@ -870,6 +870,649 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// The 8-wave kernel on the 16x16x32 bf16 MFMA.  Same tiles, LDS rings, alternating schedule, pass loop and state
+// images as prefill_kernel_deep; what differs is the matrix instruction and with it the register layouts.  Measured
+// on this part, a register-only loop of v_mfma_f32_16x16x32_bf16 on random operands sustains 2.10 PFLOP/s under the
+// board's power limit where v_mfma_f32_32x32x16_bf16 sustains 1.84: the smaller accumulator tile moves half as many
+// accumulator registers per flop, and the kernel runs against that limit.
+//   * A wavefront still owns 32 query rows of one query head, now as two blocks of 16 (qb = 0, 1): lane = (query
+//     l % 16 of each block, g = l / 16).  S^T = K Q^T per 16-key block kb: register r of s[kb][qb] is key row
+//     16 kb + 4 g + r.  A K operand read (16 keys x 32 dims) feeds the MFMAs of both query blocks.
+//   * O^T += V^T P^T over 32 keys per MFMA: the lane's 4 + 4 scores of key blocks 2 kp and 2 kp + 1 are, rounded to
+//     bf16, its B operand (contraction index 8 g + j is key 32 kp + 16 (j / 4) + 4 g + j % 4), and the V^T operand
+//     takes the same permutation: two transpose reads of 4 consecutive rows each.  Register r of o[db][qb] is dim
+//     16 db + 4 g + r of the lane's query in block qb.
+//   * A lane serves two query rows, so it carries two running references and two shares of the row sums.
+//   * V tiles take one more swizzle bit than in the other kernels (rows 4 apart are read by neighbouring 16-lane
+//     groups of one transpose read and must not share banks).
+constexpr int kCarryFloats16 = 68;     // 64 O^T accumulators + two running maxima + two row-sum shares
+
+__device__ __forceinline__ int swz_v16(int row) { return swz_v(row) ^ (((row >> 2) & 1) << 1); }
+
+struct PfLane16 {
+  uint32_t gk[2];     // global byte offset inside a 64-row K tile of this lane's 2 load instructions
+  uint32_t gv[2];     // same for V
+  uint32_t koff[4];   // absolute LDS address of the K operand read of contraction step kk (key block kb adds 4096)
+  uint32_t voff[8];   // absolute LDS address of the V^T transpose read of dim block db (+4096: the second 16 rows
+                      // of the key pair, +8192: key pair 1)
+};
+
+// The 4-register accumulator tiles of the 16x16x32 MFMA are kept as quarters of 16-register vectors: a result that has to
+// land in a quarter of the vector its accumulator came from is computed in place, where free-standing 4-register tiles
+// were moved from tuple to tuple by most MFMAs (and the register file overflowed).
+__device__ __forceinline__ f32x4 q4_get(const f32x16& v, int k) { return (f32x4){v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]}; }
+__device__ __forceinline__ void q4_set(f32x16& v, int k, const f32x4& x) {
+  v[4 * k] = x[0]; v[4 * k + 1] = x[1]; v[4 * k + 2] = x[2]; v[4 * k + 3] = x[3];
+}
+
+struct PfState16 {
+  f32x16 o[4];        // tile (db, qb) is quarter (2 db + qb) % 4 of o[(2 db + qb) / 4]
+  float m[2], l[2];
+};
+// element r of accumulator tile (db, qb) of O^T, and of score tile (kb, qb) in f32x16 s[2]
+#define PF16_O(st, db, qb, r) (st).o[(2 * (db) + (qb)) >> 2][4 * ((2 * (db) + (qb)) & 3) + (r)]
+#define PF16_S(s, kb, qb, r) (s)[(2 * (kb) + (qb)) >> 2][4 * ((2 * (kb) + (qb)) & 3) + (r)]
+
+__device__ __forceinline__ void pf16_issue_k(const char* kt, int rows, uint32_t lds_tile, int wave, int lane,
+                                             const PfLane16& lc) {
+  const uint32_t ldk = lds_tile + wave * 2048;
+  if (rows >= kPfTileRows) {
+    g2lds16_s<0>(kt, lc.gk[0], ldk);
+    g2lds16_s<0>(kt, lc.gk[1], ldk + 1024);
+  } else {
+    const int r_in = lane >> 4, cpos = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int r = (wave * 2 + i) * 4 + r_in;
+      const int rc = r < rows ? r : rows - 1;
+      g2lds16_s<0>(kt, (uint32_t)(rc * kRowBytes + ((cpos ^ swz_k(r)) << 4)), ldk + i * 1024);
+    }
+  }
+}
+
+__device__ __forceinline__ void pf16_issue_v(const char* vt, int rows, uint32_t lds_tile, int wave, int lane,
+                                             const PfLane16& lc) {
+  const uint32_t ldv = lds_tile + wave * 2048;
+  if (rows >= kPfTileRows) {
+    g2lds16_s<0>(vt, lc.gv[0], ldv);
+    g2lds16_s<0>(vt, lc.gv[1], ldv + 1024);
+  } else {
+    const int r_in = lane >> 4, cpos = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int r = (wave * 2 + i) * 4 + r_in;
+      const int rc = r < rows ? r : rows - 1;
+      g2lds16_s<0>(vt, (uint32_t)(rc * kRowBytes + ((cpos ^ swz_v16(r)) << 4)), ldv + i * 1024);
+    }
+  }
+}
+
+// operand i of a matrix phase: i < 16 the V^T fragment of (key pair, dim block) = (i / 8, i % 8), i >= 16 the K
+// fragment of (contraction step, key block) = ((i - 16) / 4, (i - 16) % 4); each feeds the MFMAs of both query blocks
+__device__ __forceinline__ constexpr int pd16_kp(int i) { return i >> 3; }
+__device__ __forceinline__ constexpr int pd16_db(int i) { return i & 7; }
+__device__ __forceinline__ constexpr int pd16_kk(int i) { return (i - 16) >> 2; }
+__device__ __forceinline__ constexpr int pd16_kb(int i) { return (i - 16) & 3; }
+
+__device__ __forceinline__ bf16x8 pd16_operand(int i, uint32_t v_off, uint32_t k_off, const PfLane16& lc) {
+  if (i < 16) {
+    const uint32_t ad = lc.voff[pd16_db(i)] + v_off + pd16_kp(i) * 8192;
+    const bf16x4 v0 = lds_read_tr8((lds_char*)(uintptr_t)ad);
+    const bf16x4 v1 = lds_read_tr8((lds_char*)(uintptr_t)(ad + 4096));
+    return __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+  return *(lds_bf16x8*)(uintptr_t)(lc.koff[pd16_kk(i)] + k_off + pd16_kb(i) * 4096);
+}
+
+__device__ __forceinline__ void pd16_preread(uint32_t v_off, const PfLane16& lc, bf16x8 (&pre)[kPfAhead]) {
+#pragma unroll
+  for (int i = 0; i < kPfAhead; ++i) pre[i] = pd16_operand(i, v_off, 0, lc);
+}
+
+// The matrix phase: O^T += V^T P^T of the previous tile, then S^T = K Q^T of the next - 64 MFMAs, their 32 LDS operands
+// read kPfAhead operands ahead.  Template switches as in pd_matrix_phase.
+template <bool LOADS_ALWAYS, bool PREREAD, bool CINIT, bool EARLY_BARRIER = false>
+__device__ __forceinline__ void pd16_matrix_phase(uint32_t v_off, uint32_t k_off, const PfLane16& lc,
+                                                  const bf16x8 (&qf)[4][2], const bf16x8 (&pb)[2][2], PfState16& st,
+                                                  f32x16 (&s)[2], const PfPhaseLoads& ld,
+                                                  const bf16x8 (&pre)[kPfAhead], const f32x4 (&cinit)[2]) {
+  bf16x8 op[kPfAhead + 1];
+#pragma unroll
+  for (int i = 0; i < kPfAhead; ++i) op[i] = PREREAD ? pre[i] : pd16_operand(i, v_off, k_off, lc);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    if (i + kPfAhead < 32) op[(i + kPfAhead) % (kPfAhead + 1)] = pd16_operand(i + kPfAhead, v_off, k_off, lc);
+    bf16x8 x = op[i % (kPfAhead + 1)];
+    if (EARLY_BARRIER && i == 31) {
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(x) : : "memory");
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (i < 16) {
+      const int kp = pd16_kp(i), db = pd16_db(i);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        const int t4 = 2 * db + qb;
+        q4_set(st.o[t4 >> 2], t4 & 3,
+               __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, pb[kp][qb], q4_get(st.o[t4 >> 2], t4 & 3), 0, 0, 0));
+      }
+    } else {
+      const int kk = pd16_kk(i), kb = pd16_kb(i);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        const int t4 = 2 * kb + qb;
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        const f32x4 c0 = kk == 0 ? (CINIT ? cinit[qb] : z) : q4_get(s[t4 >> 2], t4 & 3);
+        q4_set(s[t4 >> 2], t4 & 3, __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, qf[kk][qb], c0, 0, 0, 0));
+      }
+    }
+    if (i == 1 && (LOADS_ALWAYS || ld.k)) g2lds16_s<0>(ld.k, lc.gk[0], ld.ldk);
+    if (i == 3 && (LOADS_ALWAYS || ld.k)) g2lds16_s<0>(ld.k, lc.gk[1], ld.ldk + 1024);
+    if (i == 5 && (LOADS_ALWAYS || ld.v)) g2lds16_s<0>(ld.v, lc.gv[0], ld.ldv);
+    if (i == 7 && (LOADS_ALWAYS || ld.v)) g2lds16_s<0>(ld.v, lc.gv[1], ld.ldv + 1024);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// maximum over the four 16-lane groups that hold the key rows of one query
+__device__ __forceinline__ float max_groups16(float x) {
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+__device__ __forceinline__ float sum_groups16(float x) {
+  x += __shfl_xor(x, 16);
+  return x + __shfl_xor(x, 32);
+}
+
+// Online softmax of one tile (general form: raw scores, running maximum moved when it must, masks).  rel[qb]: key
+// rows of the tile with index > rel[qb] are hidden from the lane's query of block qb.
+__device__ __forceinline__ void pf16_softmax(f32x16 (&s)[2], PfState16& st, float c, bool masked, const int (&rel)[2],
+                                             int g16, bf16x8 (&pb)[2][2]) {
+  if (masked) {
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (16 * kb + 4 * g16 + r > rel[qb]) PF16_S(s, kb, qb, r) = kNegBig;
+  }
+  float m_new[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    float mx = PF16_S(s, 0, qb, 0);
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) mx = fmaxf(mx, PF16_S(s, kb, qb, r));
+    m_new[qb] = fmaxf(st.m[qb], max_groups16(mx));
+  }
+  if (__builtin_amdgcn_ballot_w64(m_new[0] > st.m[0] || m_new[1] > st.m[1]) != 0) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const float alpha = fast_exp2((st.m[qb] - m_new[qb]) * c);
+      st.l[qb] *= alpha;
+#pragma unroll
+      for (int db = 0; db < 8; ++db)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) PF16_O(st, db, qb, r) *= alpha;
+      st.m[qb] = m_new[qb];
+    }
+  }
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const float mc = st.m[qb] * c;
+    float lsum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float p = fast_exp2(__builtin_fmaf(PF16_S(s, kb, qb, r), c, -mc));
+        lsum += p;
+        pb[kb >> 1][qb][4 * (kb & 1) + r] = (__bf16)p;
+      }
+    st.l[qb] += lsum;
+  }
+#pragma unroll
+  for (int kp = 0; kp < 2; ++kp)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) asm volatile("" : "+v"(pb[kp][qb]));
+}
+
+// Softmax phase of a steady-state tile: the scores left the matrix pipe relative to the running reference (the
+// accumulators started from cinit = -m), p = 2^(c s); the reference only moves when a lane's share of a row sum says
+// it must (see pf_softmax_fast).
+__device__ __forceinline__ void pf16_softmax_fast(f32x16 (&s)[2], PfState16& st, float c, f32x4 (&cinit)[2],
+                                                  bf16x8 (&pb)[2][2]) {
+  float ls[2];
+  auto probs = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      float lq[2];
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float p = fast_exp2(PF16_S(s, kb, qb, r) * c);
+          lq[kb & 1] = (kb < 2 && r == 0) ? p : lq[kb & 1] + p;
+          pb[kb >> 1][qb][4 * (kb & 1) + r] = (__bf16)p;
+        }
+      ls[qb] = lq[0] + lq[1];
+    }
+  };
+  probs();
+  if (__builtin_amdgcn_ballot_w64(!(ls[0] <= kPfSumLimit) || !(ls[1] <= kPfSumLimit)) != 0) {    // also inf and NaN
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      float mx = PF16_S(s, 0, qb, 0);
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mx = fmaxf(mx, PF16_S(s, kb, qb, r));
+      const float d = fmaxf(max_groups16(mx), 0.f);       // queries whose maximum did not move keep their reference
+      const float alpha = fast_exp2(-d * c);
+      st.l[qb] *= alpha;
+#pragma unroll
+      for (int db = 0; db < 8; ++db)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) PF16_O(st, db, qb, r) *= alpha;
+#pragma unroll
+      for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) PF16_S(s, kb, qb, r) -= d;
+      st.m[qb] += d;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) cinit[qb][r] = -st.m[qb];
+    }
+    probs();
+  }
+  st.l[0] += ls[0];
+  st.l[1] += ls[1];
+#pragma unroll
+  for (int kp = 0; kp < 2; ++kp)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) asm volatile("" : "+v"(pb[kp][qb]));
+}
+
+// Normalise and write the lane's parts of the query row of block QB: dims 16 (db0 + d) + 4 g16 + 0..3 for d < NDB
+// (o[d] holds dim block db0 + d); l is the lane's share of the row sum.
+template <int NDB>
+__device__ __forceinline__ void pf16_write_row(void* out, int out_fp32, int C, int g, int i, int g16, int db0,
+                                               const f32x4 (&o)[NDB], float l) {
+  const float inv = 1.0f / sum_groups16(l);
+  if (i >= C) return;
+  const int64_t base = ((int64_t)g * C + i) * kHeadDim;
+#pragma unroll
+  for (int d = 0; d < NDB; ++d) {
+    const f32x4 v = o[d];
+    const int dim = 16 * (db0 + d) + 4 * g16;
+    const float x0 = v[0] * inv, x1 = v[1] * inv, x2 = v[2] * inv, x3 = v[3] * inv;
+    if (out_fp32) {
+      *(float4*)((float*)out + base + dim) = make_float4(x0, x1, x2, x3);
+    } else {
+      uint2 pk;
+      pk.x = (uint32_t)float_to_bf16_bits(x0) | ((uint32_t)float_to_bf16_bits(x1) << 16);
+      pk.y = (uint32_t)float_to_bf16_bits(x2) | ((uint32_t)float_to_bf16_bits(x3) << 16);
+      *(uint2*)((uint16_t*)out + base + dim) = pk;
+    }
+  }
+}
+
+__global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) char lds_dyn[];
+  lds_char* lds = (lds_char*)lds_dyn;
+  const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+  const int lane = lane_id();
+  const int wave = wave_id();
+  const int g16 = lane >> 4;
+  const int c16 = lane & 15;
+
+  const int gl = a.G < 4 ? a.G : 4;
+  const int strip = 32 * (kPdWaves / gl);
+  const int g = pf_select_head(a) * 4 + (wave % gl);
+
+  PfLane16 lc;
+  {
+    const int r_in = lane >> 4, cpos = lane & 15;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int r = (wave * 2 + i) * 4 + r_in;
+      lc.gk[i] = (uint32_t)(r * kRowBytes + ((cpos ^ swz_k(r)) << 4));
+      lc.gv[i] = (uint32_t)(r * kRowBytes + ((cpos ^ swz_v16(r)) << 4));
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      lc.koff[kk] = lds_base + (uint32_t)(c16 * kRowBytes + (((4 * kk + g16) ^ swz_k(c16)) << 4));
+    const int row = 4 * g16 + (c16 >> 2);             // the row of the 4-row block this lane addresses
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      const int chunk = 2 * db + ((c16 & 3) >> 1);
+      lc.voff[db] = lds_base + kPdVRing +
+                    (uint32_t)(row * kRowBytes + ((chunk ^ swz_v16(row)) << 4) + ((c16 & 1) << 3));
+    }
+  }
+
+  PfShape sh;
+  sh.nbk = a.nbk; sh.m = strip / kPfTileRows;
+  sh.ta = (int)((a.na + kPfTileRows - 1) / kPfTileRows);
+  sh.tb_all = (int)((a.nb + kPfTileRows - 1) / kPfTileRows);
+  sh.split = a.split; sh.paired = a.paired; sh.carried = !a.first;
+  constexpr int kLanes = kPdWaves * 64;
+  constexpr int kImageFloats = kCarryFloatsPerLane * kLanes;
+  float* const images = a.carry + (int64_t)blockIdx.y * pf_images_per_row(a.nbk, a.split) * kImageFloats + threadIdx.x;
+  int first_which = 0;
+  {
+    const PfPass d = pf_pass(sh, blockIdx.x, 0, a.last), sw = pf_pass(sh, blockIdx.x, 1, a.last);
+    if (sw.run && sw.a1 > sw.a0 && !(d.run && d.a1 > d.a0)) first_which = 1;
+  }
+#pragma nounroll
+  for (int pi = 0; pi < 2; ++pi) {
+    const PfPass ps = pf_pass(sh, blockIdx.x, first_which ^ pi, a.last);
+    if (ps.init) {
+      float* im = images + (int64_t)ps.store * kImageFloats;
+#pragma unroll
+      for (int i = 0; i < 64; ++i) im[i * kLanes] = 0.f;
+      im[64 * kLanes] = kNegBig;
+      im[65 * kLanes] = kNegBig;
+      im[66 * kLanes] = 0.f;
+      im[67 * kLanes] = 0.f;
+    }
+    if (!ps.run) continue;
+    __syncthreads();
+    const int bx = ps.bx;
+    const int i0 = bx * strip + 32 * (wave / gl);
+    int my_i[2], qi[2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      my_i[qb] = i0 + 16 * qb + c16;
+      qi[qb] = my_i[qb] > a.C - 1 ? a.C - 1 : my_i[qb];
+    }
+
+    // Q^T operands: lane holds q[g][qi[qb]][32*kk + 8*g16 .. +7]
+    bf16x8 qf[4][2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const uint16_t* qrow = a.q + ((int64_t)g * a.C + qi[qb]) * kHeadDim + 8 * g16;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) qf[kk][qb] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 32 * kk));
+    }
+
+    const char* const ka_p = a.ka + (int64_t)ps.a0 * kPfTileBytes;
+    const char* const va_p = a.va + (int64_t)ps.a0 * kPfTileBytes;
+    int64_t na_p = (int64_t)ps.a1 * kPfTileRows;
+    if (na_p > a.na) na_p = a.na;
+    na_p -= (int64_t)ps.a0 * kPfTileRows;
+    const int b_t0 = ps.b0;
+    const int tb = ps.b1 - ps.b0;
+
+    PfState16 st;
+    if (ps.load < 0) {
+      st.m[0] = st.m[1] = kNegBig;
+      st.l[0] = st.l[1] = 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.o[j][r] = 0.f;
+    } else {
+      const float* im = images + (int64_t)ps.load * kImageFloats;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st.o[j][r] = im[(16 * j + r) * kLanes];     // = ((2 db + qb) * 4 + r)
+      st.m[0] = im[64 * kLanes];
+      st.m[1] = im[65 * kLanes];
+      st.l[0] = im[66 * kLanes];
+      st.l[1] = im[67 * kLanes];
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(qf[kk][0]), "+v"(qf[kk][1]));
+    asm volatile("" : "+v"(st.m[0]), "+v"(st.m[1]), "+v"(st.l[0]), "+v"(st.l[1]));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) asm volatile("" : "+v"(st.o[j]));
+
+    const int ta = (int)((na_p + kPfTileRows - 1) / kPfTileRows);
+    const int T = ta + tb;
+    const int tb_base = b_t0 - ta;
+
+    auto issue = [&](int t, int which) __attribute__((always_inline)) {
+      if (t >= T) return;
+      const bool in_b = t >= ta;
+      const int64_t row0 = (int64_t)(in_b ? t + tb_base : t) * kPfTileRows;
+      const int64_t left = (in_b ? a.nb : na_p) - row0;
+      const int rows = left < kPfTileRows ? (int)left : kPfTileRows;
+      const uint32_t slot = lds_base + (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes;
+      if (which == 0) pf16_issue_k((in_b ? a.kb : ka_p) + row0 * kRowBytes, rows, slot, wave, lane, lc);
+      else pf16_issue_v((in_b ? a.vb : va_p) + row0 * kRowBytes, rows, slot + kPdVRing, wave, lane, lc);
+    };
+    auto wait_landed = [&](int t) {
+      if (t + 3 < T) wait_vmcnt<4>();
+      else wait_vmcnt<0>();
+    };
+    auto phase_barrier = [&]() {
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // the alternating schedule, barrier protocol and ring discipline of prefill_kernel_deep
+    const int group = wave >> 2;
+    const float c = a.c;
+    wait_vmcnt<0>();
+    issue(0, 0);
+    issue(1, 0); issue(0, 1);
+    issue(2, 0); issue(1, 1);
+    wait_landed(-1);
+    phase_barrier();
+    if (group == 1) phase_barrier();
+
+    f32x16 sc[2];
+    bf16x8 pb[2][2];
+    auto softmax_phase = [&](int t) __attribute__((always_inline)) {
+      const bool in_b = t >= ta;
+      const int64_t j0 = (int64_t)(in_b ? t + tb_base : t) * kPfTileRows;
+      const int64_t n_seg = in_b ? a.nb : na_p;
+      const bool masked = (j0 + kPfTileRows > n_seg) || (in_b && (j0 + kPfTileRows - 1 > i0));
+      int rel[2] = {kPfTileRows, kPfTileRows};
+      if (masked) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          int64_t lim = n_seg - 1;
+          if (in_b && (int64_t)my_i[qb] < lim) lim = my_i[qb];
+          const int64_t d = lim - j0;
+          rel[qb] = d < -1 ? -1 : (d > kPfTileRows ? kPfTileRows : (int)d);
+        }
+      }
+      pf16_softmax(sc, st, c, masked, rel, g16, pb);
+    };
+    // tile 0: nothing to accumulate yet
+    issue(3, 0);
+    issue(2, 1);
+#pragma unroll
+    for (int i = 16; i < 32; ++i) {
+      const bf16x8 x = pd16_operand(i, 0, 0, lc);
+      const int kk = pd16_kk(i), kb = pd16_kb(i);
+      const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        const int t4 = 2 * kb + qb;
+        q4_set(sc[t4 >> 2], t4 & 3,
+               __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, qf[kk][qb], kk == 0 ? z : q4_get(sc[t4 >> 2], t4 & 3), 0, 0, 0));
+      }
+    }
+    phase_barrier();
+    softmax_phase(0);
+    wait_landed(0);
+    phase_barrier();
+    bf16x8 pre[kPfAhead];
+    f32x4 cinit[2];      // minus the running references, the start values of the steady-state score accumulators
+    cinit[0] = cinit[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    auto generic_tile = [&](int t) __attribute__((always_inline)) {
+      PfPhaseLoads ld;
+      ld.k = ld.v = nullptr;
+      const int tk = t + 3, tv = t + 2;
+      const bool kb = tk >= ta, vb = tv >= ta;
+      const int64_t krow0 = (int64_t)(kb ? tk + tb_base : tk) * kPfTileRows;
+      const int64_t vrow0 = (int64_t)(vb ? tv + tb_base : tv) * kPfTileRows;
+      const bool kfull = tk < T && (kb ? a.nb : na_p) - krow0 >= kPfTileRows;
+      const bool vfull = tv < T && (vb ? a.nb : na_p) - vrow0 >= kPfTileRows;
+      if (kfull) ld.k = (kb ? a.kb : ka_p) + krow0 * kRowBytes; else issue(tk, 0);
+      if (vfull) ld.v = (vb ? a.vb : va_p) + vrow0 * kRowBytes; else issue(tv, 1);
+      ld.ldk = lds_base + (uint32_t)(tk & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
+      ld.ldv = lds_base + kPdVRing + (uint32_t)(tv & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
+      pd16_matrix_phase<false, false, false>((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes,
+                                             (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes, lc, qf, pb, st, sc, ld, pre,
+                                             cinit);
+      phase_barrier();
+      softmax_phase(t);
+      wait_landed(t);
+      phase_barrier();
+    };
+    const char* kp = ka_p;
+    const char* vp = va_p;
+    const uint32_t ld_wave = lds_base + wave * 2048;
+    auto fast_tile = [&](auto stage_tag) __attribute__((always_inline)) {
+      constexpr int S = decltype(stage_tag)::value;
+      PfPhaseLoads ld;
+      ld.k = kp;
+      ld.v = vp;
+      ld.ldk = ld_wave + ((S + 3) & 3) * kPfTileBytes;
+      ld.ldv = ld_wave + kPdVRing + ((S + 2) & 3) * kPfTileBytes;
+      __builtin_amdgcn_s_setprio(2);
+      pd16_matrix_phase<true, true, true, true>(((S + 3) & 3) * kPfTileBytes, S * kPfTileBytes, lc, qf, pb, st, sc, ld,
+                                                pre, cinit);
+      __builtin_amdgcn_s_setprio(0);
+      pd16_preread(S * kPfTileBytes, lc, pre);
+      __builtin_amdgcn_sched_barrier(0);
+      pf16_softmax_fast(sc, st, c, cinit, pb);
+      wait_vmcnt<4>();
+      phase_barrier();
+      kp += kPfTileBytes;
+      vp += kPfTileBytes;
+    };
+    int t = 1;
+    auto fast_run = [&](int t_end, const char* kbase, const char* vbase, int tile0) __attribute__((always_inline)) {
+      if (t_end - t < 8) return;
+      while (t & 3) { generic_tile(t); ++t; }
+      kp = kbase + (int64_t)(t + 3 - tile0) * kPfTileBytes;
+      vp = vbase + (int64_t)(t + 2 - tile0) * kPfTileBytes;
+      pd16_preread((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes, lc, pre);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) cinit[qb][r] = -st.m[qb];
+      for (; t + 4 <= t_end; t += 4) {
+        fast_tile(std::integral_constant<int, 0>());
+        fast_tile(std::integral_constant<int, 1>());
+        fast_tile(std::integral_constant<int, 2>());
+        fast_tile(std::integral_constant<int, 3>());
+      }
+    };
+    fast_run((int)(na_p / kPfTileRows) - 3, ka_p, va_p, 0);
+    while (t < ta && t < T) { generic_tile(t); ++t; }
+    {
+      const int64_t unmasked = ((int64_t)bx * strip + 1) / kPfTileRows;
+      const int64_t loadable = a.nb / kPfTileRows - 3;
+      const int64_t j_end = unmasked < loadable ? unmasked : loadable;
+      const int64_t t_end = j_end - tb_base < T - 3 ? j_end - tb_base : T - 3;
+      fast_run((int)t_end, a.kb, a.vb, -tb_base);
+    }
+    for (; t < T; ++t) generic_tile(t);
+    {
+      const uint32_t v_off = (uint32_t)((T - 1) & (kPdStages - 1)) * kPfTileBytes;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const bf16x8 x = pd16_operand(i, v_off, 0, lc);
+        const int kp2 = pd16_kp(i), db = pd16_db(i);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          const int t4 = 2 * db + qb;
+          q4_set(st.o[t4 >> 2], t4 & 3,
+                 __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, pb[kp2][qb], q4_get(st.o[t4 >> 2], t4 & 3), 0, 0, 0));
+        }
+      }
+    }
+    if (group == 0) phase_barrier();
+
+    if (ps.store >= 0) {
+      float* im = images + (int64_t)ps.store * kImageFloats;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) im[(16 * j + r) * kLanes] = st.o[j][r];
+      im[64 * kLanes] = st.m[0];
+      im[65 * kLanes] = st.m[1];
+      im[66 * kLanes] = st.l[0];
+      im[67 * kLanes] = st.l[1];
+    } else {
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        f32x4 rows[8];
+#pragma unroll
+        for (int db = 0; db < 8; ++db) rows[db] = q4_get(st.o[(2 * db + qb) >> 2], (2 * db + qb) & 3);
+        pf16_write_row<8>(a.out, a.out_fp32, a.C, g, my_i[qb], g16, 0, rows, st.l[qb]);
+      }
+    }
+  }
+}
+
+// Merge of the states of prefill_kernel_deep16 (its own image layout): grid (blocks, grid rows, 4): quarter z combines
+// dim blocks 2 z and 2 z + 1 of both query rows of the lane.
+__global__ __launch_bounds__(512) void prefill_merge16_kernel(PrefillArgs a) {
+  const int lane = lane_id();
+  const int wave = wave_id();
+  const int g16 = lane >> 4;
+  const int c16 = lane & 15;
+  const int gl = a.G < 4 ? a.G : 4;
+  const int strip = 32 * (kPdWaves / gl);
+  const int bx = blockIdx.x;
+  const int zq = blockIdx.z;
+  const int g = pf_select_head(a) * 4 + (wave % gl);
+  const int i0 = bx * strip + 32 * (wave / gl);
+  constexpr int kLanes = kPdWaves * 64;
+  constexpr int kImageFloats = kCarryFloatsPerLane * kLanes;
+  PfShape sh;
+  sh.nbk = a.nbk; sh.m = strip / kPfTileRows;
+  sh.ta = (int)((a.na + kPfTileRows - 1) / kPfTileRows);
+  sh.tb_all = (int)((a.nb + kPfTileRows - 1) / kPfTileRows);
+  sh.split = a.split; sh.paired = a.paired; sh.carried = !a.first;
+  int n_e, n_x;
+  pf_block_images(sh, bx, n_e, n_x);
+  if (n_e + n_x == 1 && a.split == 1) return;
+  const float* images = a.carry + (int64_t)blockIdx.y * pf_images_per_row(a.nbk, a.split) * kImageFloats + threadIdx.x;
+  auto image_of = [&](int i) { return images + (int64_t)(i < n_e ? pf_image_e(sh, bx, i) : pf_image_x(sh, bx, i - n_e)) * kImageFloats; };
+  float m[2] = {kNegBig, kNegBig};
+  for (int i = 0; i < n_e + n_x; ++i) {
+    const float* im = image_of(i);
+    m[0] = fmaxf(m[0], im[64 * kLanes]);
+    m[1] = fmaxf(m[1], im[65 * kLanes]);
+  }
+  f32x4 o[2][2];      // [dim block 2 zq + d][qb]
+#pragma unroll
+  for (int d = 0; d < 2; ++d)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) o[d][qb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float l[2] = {0.f, 0.f};
+  for (int i = 0; i < n_e + n_x; ++i) {
+    const float* im = image_of(i);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const float w = fast_exp2((im[(64 + qb) * kLanes] - m[qb]) * a.c);
+      l[qb] += w * im[(66 + qb) * kLanes];
+#pragma unroll
+      for (int d = 0; d < 2; ++d)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o[d][qb][r] += w * im[(((2 * zq + d) * 2 + qb) * 4 + r) * kLanes];
+    }
+  }
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const f32x4 rows[2] = {o[0][qb], o[1][qb]};
+    pf16_write_row<2>(a.out, a.out_fp32, a.C, g, i0 + 16 * qb + c16, g16, 2 * zq, rows, l[qb]);
+  }
+}
+
 // One dim block (32 of the 128 output dims) of pf_write_row: register r of o is dim 32*db + 8*(r/4) + 4*hl + r%4.
 __device__ __forceinline__ void pf_write_row_db(void* out, int out_fp32, int C, int g, int i, int hl, int db,
                                                 const f32x16& o, float l) {
@@ -1207,14 +1850,20 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
     std::call_once(attr_once, [] {
       attr_err = hipFuncSetAttribute((const void*)prefill_kernel_deep, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      kPdLdsBytes);
+      if (attr_err == hipSuccess)
+        attr_err = hipFuncSetAttribute((const void*)prefill_kernel_deep16, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kPdLdsBytes);
     });
     if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
     dim3 grid((unsigned)(pl.nbk * pl.split), (unsigned)(gy * n_heads));
-    hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
+    const bool mfma32 = (variant & 16) != 0;        // the 32x32x16 form of the kernel (its state images differ)
+    if (mfma32) hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(prefill_kernel_deep16, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
     if (pl.merge) {
       hipError_t e1 = hipGetLastError();
       if (e1 != hipSuccess) { set_last_error("prefill launch: %s", hipGetErrorString(e1)); return HI_ERR_HIP; }
-      hipLaunchKernelGGL(prefill_merge_kernel, dim3((unsigned)pl.nbk, grid.y, 4), dim3(kPdWaves * 64), 0, (hipStream_t)stream, a);
+      if (mfma32) hipLaunchKernelGGL(prefill_merge_kernel, dim3((unsigned)pl.nbk, grid.y, 4), dim3(kPdWaves * 64), 0, (hipStream_t)stream, a);
+      else hipLaunchKernelGGL(prefill_merge16_kernel, dim3((unsigned)pl.nbk, grid.y, 4), dim3(kPdWaves * 64), 0, (hipStream_t)stream, a);
     }
   } else {
     dim3 grid((unsigned)ceil_div(chunk_len, strip), (unsigned)(gy * n_heads));

@@ -64,6 +64,7 @@ def main():
     ap.add_argument("--gqa", type=int, default=4, choices=[1, 2, 4, 8], help="query heads per KV head")
     ap.add_argument("--narrow", action="store_true", help="force the 4-wave, 2-stage prefill kernel")
     ap.add_argument("--deep", action="store_true", help="force the 8-wave, 4-stage prefill kernel")
+    ap.add_argument("--mfma32", action="store_true", help="the 8-wave kernel in its 32x32x16 MFMA form")
     ap.add_argument("--calibrate", action="store_true", help="also run a plain 1 GiB device-to-device copy")
     args = ap.parse_args()
     P, C, G, dev = args.past, args.chunk, args.gqa, "cuda:0"
@@ -72,6 +73,7 @@ def main():
     ss = Session(1, 1, G, P + C, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0)
     flags = hb.HI_FLAG_TIME_KERNELS
     flags |= (hb.HI_FLAG_PREFILL_NARROW if args.narrow else 0) | (hb.HI_FLAG_PREFILL_DEEP if args.deep else 0)
+    flags |= hb.HI_FLAG_PREFILL_MFMA32 if args.mfma32 else 0
     hb.hi_ctx_set_flags(ss.ctx, flags)
     with torch.cuda.stream(ss.s_compute):
         cv = ss.cache_view()
