@@ -207,7 +207,7 @@ def run_stack(args):
         "peak_staging_bytes": max(st.peak_staging_bytes, sd.peak_staging_bytes), "one_head_bytes": ss.plan.host_bytes_per_head,
         "bytes_h2d_prefill": st.bytes_h2d, "bytes_d2h_prefill": st.bytes_d2h,
         "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS, "traffic": None, "kernel": "prefill_kernel_deep",
+                     "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS, "traffic": None, "kernel": "prefill_kernel_deep16",
                      "launches_per_step": st.n_prefill_kernels, "avg_launch_ms": st.prefill_kernel_ms / max(st.n_prefill_kernels, 1),
                      "wall_TFLOPs": flops / (t_pre / L) / 1e12,
                      "note": "wall time includes the projections of every chunk and layer (about 1.2 % of a layer)"},
@@ -425,7 +425,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS,
                      "traffic": traffic, "traffic_source": traffic_src,
-                     "kernel": "prefill_kernel_deep",
+                     "kernel": "prefill_kernel_deep16",
                      "launches_per_step": n_pre_k / K, "avg_launch_ms": kern_pre_ms / max(n_pre_k, 1),
                      "flops_per_launch": flops * NL / (n_pre_k / K),
                      "wall_TFLOPs": flops / prefill_s / 1e12},

@@ -971,8 +971,9 @@ __device__ __forceinline__ void pd16_preread(uint32_t v_off, const PfLane16& lc,
 }
 
 // The matrix phase: O^T += V^T P^T of the previous tile, then S^T = K Q^T of the next - 64 MFMAs, their 32 LDS operands
-// read kPfAhead operands ahead.  Template switches as in pd_matrix_phase.
-template <bool LOADS_ALWAYS, bool PREREAD, bool CINIT, bool EARLY_BARRIER = false>
+// read kPfAhead operands ahead.  LOADS: 0 = the phase issues the global loads that ld names (either may be null),
+// 1 = both unconditionally.  Other switches as in pd_matrix_phase.
+template <int LOADS, bool PREREAD, bool CINIT, bool EARLY_BARRIER = false>
 __device__ __forceinline__ void pd16_matrix_phase(uint32_t v_off, uint32_t k_off, const PfLane16& lc,
                                                   const bf16x8 (&qf)[4][2], const bf16x8 (&pb)[2][2], PfState16& st,
                                                   f32x16 (&s)[2], const PfPhaseLoads& ld,
@@ -1008,10 +1009,10 @@ __device__ __forceinline__ void pd16_matrix_phase(uint32_t v_off, uint32_t k_off
         q4_set(s[t4 >> 2], t4 & 3, __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, qf[kk][qb], c0, 0, 0, 0));
       }
     }
-    if (i == 1 && (LOADS_ALWAYS || ld.k)) g2lds16_s<0>(ld.k, lc.gk[0], ld.ldk);
-    if (i == 3 && (LOADS_ALWAYS || ld.k)) g2lds16_s<0>(ld.k, lc.gk[1], ld.ldk + 1024);
-    if (i == 5 && (LOADS_ALWAYS || ld.v)) g2lds16_s<0>(ld.v, lc.gv[0], ld.ldv);
-    if (i == 7 && (LOADS_ALWAYS || ld.v)) g2lds16_s<0>(ld.v, lc.gv[1], ld.ldv + 1024);
+    if (i == 1 && (LOADS == 1 || ld.k)) g2lds16_s<0>(ld.k, lc.gk[0], ld.ldk);
+    if (i == 3 && (LOADS == 1 || ld.k)) g2lds16_s<0>(ld.k, lc.gk[1], ld.ldk + 1024);
+    if (i == 5 && (LOADS == 1 || ld.v)) g2lds16_s<0>(ld.v, lc.gv[0], ld.ldv);
+    if (i == 7 && (LOADS == 1 || ld.v)) g2lds16_s<0>(ld.v, lc.gv[1], ld.ldv + 1024);
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -1083,9 +1084,14 @@ __device__ __forceinline__ void pf16_softmax(f32x16 (&s)[2], PfState16& st, floa
 
 // Softmax phase of a steady-state tile: the scores left the matrix pipe relative to the running reference (the
 // accumulators started from cinit = -m), p = 2^(c s); the reference only moves when a lane's share of a row sum says
-// it must (see pf_softmax_fast).
+// it must (see pf_softmax_fast).  The scores are scaled in place first, so that the 32 multiplications and the 32
+// exponentials are independent instructions (with a shared temporary they formed one dependent chain).
 __device__ __forceinline__ void pf16_softmax_fast(f32x16 (&s)[2], PfState16& st, float c, f32x4 (&cinit)[2],
                                                   bf16x8 (&pb)[2][2]) {
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[j][r] *= c;
   float ls[2];
   auto probs = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -1095,7 +1101,7 @@ __device__ __forceinline__ void pf16_softmax_fast(f32x16 (&s)[2], PfState16& st,
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float p = fast_exp2(PF16_S(s, kb, qb, r) * c);
+          const float p = fast_exp2(PF16_S(s, kb, qb, r));
           lq[kb & 1] = (kb < 2 && r == 0) ? p : lq[kb & 1] + p;
           pb[kb >> 1][qb][4 * (kb & 1) + r] = (__bf16)p;
         }
@@ -1104,6 +1110,7 @@ __device__ __forceinline__ void pf16_softmax_fast(f32x16 (&s)[2], PfState16& st,
   };
   probs();
   if (__builtin_amdgcn_ballot_w64(!(ls[0] <= kPfSumLimit) || !(ls[1] <= kPfSumLimit)) != 0) {    // also inf and NaN
+    const float inv_c = 1.0f / c;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       float mx = PF16_S(s, 0, qb, 0);
@@ -1111,8 +1118,11 @@ __device__ __forceinline__ void pf16_softmax_fast(f32x16 (&s)[2], PfState16& st,
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
         for (int r = 0; r < 4; ++r) mx = fmaxf(mx, PF16_S(s, kb, qb, r));
-      const float d = fmaxf(max_groups16(mx), 0.f);       // queries whose maximum did not move keep their reference
-      const float alpha = fast_exp2(-d * c);
+      // queries whose maximum did not move keep their reference; the step is taken in score units (the reference
+      // is kept in them) and applied here as the exponent it becomes
+      const float d = fmaxf(max_groups16(mx), 0.f) * inv_c;
+      const float dc = d * c;
+      const float alpha = fast_exp2(-dc);
       st.l[qb] *= alpha;
 #pragma unroll
       for (int db = 0; db < 8; ++db)
@@ -1121,7 +1131,7 @@ __device__ __forceinline__ void pf16_softmax_fast(f32x16 (&s)[2], PfState16& st,
 #pragma unroll
       for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) PF16_S(s, kb, qb, r) -= d;
+        for (int r = 0; r < 4; ++r) PF16_S(s, kb, qb, r) -= dc;
       st.m[qb] += d;
 #pragma unroll
       for (int r = 0; r < 4; ++r) cinit[qb][r] = -st.m[qb];
@@ -1361,7 +1371,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
       if (vfull) ld.v = (vb ? a.vb : va_p) + vrow0 * kRowBytes; else issue(tv, 1);
       ld.ldk = lds_base + (uint32_t)(tk & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
       ld.ldv = lds_base + kPdVRing + (uint32_t)(tv & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
-      pd16_matrix_phase<false, false, false>((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes,
+      pd16_matrix_phase<0, false, false>((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes,
                                              (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes, lc, qf, pb, st, sc, ld, pre,
                                              cinit);
       phase_barrier();
@@ -1380,8 +1390,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
       ld.ldk = ld_wave + ((S + 3) & 3) * kPfTileBytes;
       ld.ldv = ld_wave + kPdVRing + ((S + 2) & 3) * kPfTileBytes;
       __builtin_amdgcn_s_setprio(2);
-      pd16_matrix_phase<true, true, true, true>(((S + 3) & 3) * kPfTileBytes, S * kPfTileBytes, lc, qf, pb, st, sc, ld,
-                                                pre, cinit);
+      pd16_matrix_phase<1, true, true, true>(((S + 3) & 3) * kPfTileBytes, S * kPfTileBytes, lc, qf, pb, st, sc, ld,
+                                             pre, cinit);
       __builtin_amdgcn_s_setprio(0);
       pd16_preread(S * kPfTileBytes, lc, pre);
       __builtin_amdgcn_sched_barrier(0);

@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--narrow", action="store_true", help="force the 4-wave, 2-stage prefill kernel")
     ap.add_argument("--deep", action="store_true", help="force the 8-wave, 4-stage prefill kernel")
     ap.add_argument("--mfma32", action="store_true", help="the 8-wave kernel in its 32x32x16 MFMA form")
+    ap.add_argument("--zeros", action="store_true",
+                    help="all-zero Q, K, V: the same instruction stream with no switching in the multipliers, i.e. the "
+                         "kernel's schedule without the board's power limit")
     ap.add_argument("--calibrate", action="store_true", help="also run a plain 1 GiB device-to-device copy")
     args = ap.parse_args()
     P, C, G, dev = args.past, args.chunk, args.gqa, "cuda:0"
@@ -85,6 +88,8 @@ def main():
         Q = torch.stack([synth.draw_q(1, 0, g, P, C, device=dev) for g in range(G)])
         K = synth.draw_k(1, 0, 0, P, C, device=dev)
         V = synth.draw_v(1, 0, 0, P, C, device=dev)
+        if args.zeros:
+            cv.zero_(); Q.zero_(); K.zero_(); V.zero_()
         out = torch.empty(G, C, 128, dtype=torch.bfloat16, device=dev)
         outd = torch.empty(G, 128, dtype=torch.bfloat16, device=dev)
         if args.calibrate:
