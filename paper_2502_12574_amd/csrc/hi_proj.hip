@@ -76,6 +76,11 @@ __device__ __forceinline__ void pj_tile_of(const ProjArgs& p, int j, int& ta, in
   }
 }
 
+// One rotary pair (x, y) -> (x cos - y sin, y cos + x sin), with the roundings spelled out so that every epilogue
+// (and the one-token kernel's caller-visible contract: bf16 output = fp32 output rounded) produces the same bits.
+__device__ __forceinline__ float pj_rot_lo(float x, float y, float c, float sn) { return __builtin_fmaf(x, c, -(y * sn)); }
+__device__ __forceinline__ float pj_rot_hi(float x, float y, float c, float sn) { return __builtin_fmaf(y, c, x * sn); }
+
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 __device__ __forceinline__ uint32_t pj_pack2(float x, float y) {
   const bf16x2 v = {(__bf16)x, (__bf16)y};      // round to nearest even
@@ -94,7 +99,9 @@ __device__ __forceinline__ void pj_store_rows_bf16(char* dst, const float (&o)[8
   if (ok) *(uint4*)(dst + (16 * rp + 8 * hl) * 2) = make_uint4(s0[0], s1[0], s0[1], s1[1]);
 }
 
-template <int MODE>
+// WIDE: bf16 output in whole runs of 128 features with a 16-byte aligned row pitch (decided by the launcher for the
+// whole launch, so that each kernel holds one epilogue only and the accumulators never meet a control-flow join)
+template <int MODE, bool WIDE>
 __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
   extern __shared__ __attribute__((aligned(1024))) char lds_dyn[];
   const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_char*)lds_dyn;
@@ -236,23 +243,11 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
       step(t + 1, S1(), std::true_type(), std::true_type());
     }
     step(t, S0(), std::true_type(), std::false_type());
-    step(t + 1, S1(), std::false_type(), std::false_type());
 
-    // nobody reads LDS after the last barrier: the next tile's first two steps start loading under the epilogue
+    // ---- where this wavefront's results go.  Register r of block (ia, ib): A-row 128 wa + 32 ia + 8 (r / 4) + 4 hl
+    // + r % 4 (an output feature), B-row 128 wb + 32 ib + l (a token): a lane owns one token and, with its partner in
+    // the other half-wave, runs of 8 consecutive features.
     const int my_ta = ta, my_tb = tb;
-    cur_j = tile_index(s + n_li);
-    if (cur_j >= 0) {
-      pj_tile_of(p, cur_j, ta, tb);
-      set_offsets(ta, tb);
-#pragma unroll
-      for (int u = 0; u < 16; ++u) issue_one(0, 0, u);
-#pragma unroll
-      for (int u = 0; u < 16; ++u) issue_one(1, 1, u);
-    }
-
-    // ---- epilogue.  Register r of block (ia, ib): A-row 128 wa + 32 ia + 8 (r / 4) + 4 hl + r % 4 (an output
-    // feature), B-row 128 wb + 32 ib + l (a token): a lane owns one token and, with its partner in the other
-    // half-wave, runs of 8 consecutive features.
     char* base = nullptr;        // where feature 0 of this wavefront's 128 A-rows goes, for token 0
     int64_t row_bytes = 0;       // bytes from one token's output row to the next
     bool rotate = false;
@@ -274,59 +269,124 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
       row_bytes = p.y_stride * esz;
       n_valid = p.a_rows - n0 < 128 ? (p.a_rows - n0 > 0 ? p.a_rows - n0 : 0) : 128;
     }
-    // 16-byte stores need whole groups of 8 features and an aligned row pitch
-    const bool wide_ok = !p.out_fp32 && n_valid == 128 && (row_bytes & 15) == 0;
-    int hl_slow = hl;            // opaque per tile: keeps the element-wise path's offsets from being hoisted out of the
-    asm volatile("" : "+v"(hl_slow));   // tile loop, where they would sit in registers (or scratch) for nothing
+    const int m0 = my_tb * kPjTile + wb * 128 + l;                    // this lane's token in token block 0
+
+    // The rotary table, (cos, sin) of 8 pairs of the lane's token per group (token block ib, pair half ip) of the
+    // epilogue, is fetched two groups ahead (each buffer is refilled as soon as its group is rotated): a lone
+    // wavefront per SIMD has nobody to hide a load's latency behind (fetched where it is used, the 32 load-wait rounds
+    // of a tile took a fifth of its time).  The loads are unconditional and their addresses are a wave-uniform base, one lane
+    // offset and immediates: the table of C tokens is [16 groups of 4 pairs][C][4] (cos, sin), 32 bytes per (group,
+    // token), and holds a token block's worth of slack behind its last row, so that lanes past the end of a ragged
+    // chunk still read inside it.  A wavefront that has no table reads the first bytes of the weights instead and,
+    // like a V head, keeps its unrotated values.
+    const bool have_table = MODE == kPjQkv && p.rope != nullptr;
+    const char* tab_base = have_table ? (const char*)p.rope : p.a;
+    const uint32_t group_bytes = have_table ? (uint32_t)p.b_rows * 32u : 0u;
+    const uint32_t tab_lane = have_table ? (uint32_t)m0 * 32u + (uint32_t)hl * group_bytes : 0u;
+    float4 tab0[8], tab1[8];     // the buffers of pair half 0 and 1 (two arrays: every index is a compile-time constant)
+    auto tab_load = [&](int ib, int ip, float4 (&dst)[8]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int ib = 0; ib < 4; ++ib) {
-      const int m = my_tb * kPjTile + wb * 128 + ib * 32 + l;          // token of this lane
-      const bool tok_ok = m < p.b_rows;
-      char* row = base + (int64_t)(tok_ok ? m : 0) * row_bytes;
+      for (int rq = 0; rq < 4; ++rq) {
+        // pairs i0 .. i0 + 3 with i0 = 32 ip + 8 rq + 4 hl: group i0 / 4 = 8 ip + 2 rq + hl
+        const char* src = tab_base + (size_t)(8 * ip + 2 * rq) * group_bytes;       // wave-uniform
+        const float4* cs = (const float4*)(src + tab_lane + ib * 1024);
+        dst[2 * rq] = cs[0];
+        dst[2 * rq + 1] = cs[1];
+      }
+    };
+    step(t + 1, S1(), std::false_type(), std::false_type());
+
+    // nobody reads LDS after the last barrier: the next tile's first two steps start loading under the epilogue
+    cur_j = tile_index(s + n_li);
+    if (cur_j >= 0) {
+      pj_tile_of(p, cur_j, ta, tb);
+      set_offsets(ta, tb);
 #pragma unroll
-      for (int ip = 0; ip < 2; ++ip) {                                // blocks ip and ip + 2 hold the rotary pairs
-        float lo[16], hi[16];
+      for (int u = 0; u < 16; ++u) issue_one(0, 0, u);
+#pragma unroll
+      for (int u = 0; u < 16; ++u) issue_one(1, 1, u);
+    }
+
+    if (MODE == kPjQkv) { tab_load(0, 0, tab0); tab_load(0, 1, tab1); }
+    if (WIDE) {
+      // bf16 output of whole heads / whole 128-feature runs: straight-line code, 16-byte stores
+      auto group = [&](int ib, int ip, float4 (&tb8)[8], char* row, bool tok_ok) __attribute__((always_inline)) {
+        if (MODE == kPjQkv) __builtin_amdgcn_sched_barrier(0);    // one group at a time: nothing of the next is computed early
+        float lo[16], hi[16];                     // blocks ip and ip + 2 hold the rotary pairs
 #pragma unroll
         for (int r = 0; r < 16; ++r) { lo[r] = acc[ip][ib][r]; hi[r] = acc[ip + 2][ib][r]; }
-        if (MODE == kPjQkv && rotate) {
+        if (MODE == kPjQkv) {
 #pragma unroll
           for (int rq = 0; rq < 4; ++rq) {
-            const int i0 = ip * 32 + 8 * rq + 4 * hl;                  // dims i0 .. i0+3 and 64 + i0 .. 64 + i0+3
-            // table layout [16 groups of 4 pairs][token][4]: consecutive lanes (tokens) read consecutive 32 bytes
-            const float4* cs = (const float4*)(p.rope + ((int64_t)(i0 >> 2) * p.b_rows + (tok_ok ? m : 0)) * 4);
-            const float4 c01 = cs[0], c23 = cs[1];                     // (cos, sin) of two pairs each
+            const float4 c01 = tb8[2 * rq], c23 = tb8[2 * rq + 1];                   // (cos, sin) of two pairs each
             const float cv[4] = {c01.x, c01.z, c23.x, c23.z}, sv[4] = {c01.y, c01.w, c23.y, c23.w};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               const float x = lo[4 * rq + e], y = hi[4 * rq + e];
-              lo[4 * rq + e] = x * cv[e] - y * sv[e];
-              hi[4 * rq + e] = y * cv[e] + x * sv[e];
+              const float xr = pj_rot_lo(x, y, cv[e], sv[e]), yr = pj_rot_hi(x, y, cv[e], sv[e]);
+              lo[4 * rq + e] = rotate ? xr : x;           // selects, not a branch: V heads keep their values bit for bit
+              hi[4 * rq + e] = rotate ? yr : y;
             }
           }
+          if (ib + 1 < 4) tab_load(ib + 1, ip, tb8);      // the buffer this group has just used: two groups ahead
         }
-        if (wide_ok) {
 #pragma unroll
-          for (int rp = 0; rp < 2; ++rp) {
-            const float l8[8] = {lo[8 * rp], lo[8 * rp + 1], lo[8 * rp + 2], lo[8 * rp + 3],
-                                 lo[8 * rp + 4], lo[8 * rp + 5], lo[8 * rp + 6], lo[8 * rp + 7]};
-            const float h8[8] = {hi[8 * rp], hi[8 * rp + 1], hi[8 * rp + 2], hi[8 * rp + 3],
-                                 hi[8 * rp + 4], hi[8 * rp + 5], hi[8 * rp + 6], hi[8 * rp + 7]};
-            pj_store_rows_bf16(row + 32 * ip * 2, l8, rp, hl, tok_ok);
-            pj_store_rows_bf16(row + 32 * (ip + 2) * 2, h8, rp, hl, tok_ok);
-          }
-        } else if (tok_ok) {
-#pragma unroll
-          for (int half = 0; half < 2; ++half)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int f = 32 * (ip + 2 * half) + 8 * (r >> 2) + 4 * hl_slow + (r & 3);
-              const float x = half ? hi[r] : lo[r];
-              if (f >= n_valid) continue;
-              if (p.out_fp32) *(float*)(row + f * 4) = x;
-              else *(uint16_t*)(row + f * 2) = float_to_bf16_bits(x);
-            }
+        for (int rp = 0; rp < 2; ++rp) {
+          const float l8[8] = {lo[8 * rp], lo[8 * rp + 1], lo[8 * rp + 2], lo[8 * rp + 3],
+                               lo[8 * rp + 4], lo[8 * rp + 5], lo[8 * rp + 6], lo[8 * rp + 7]};
+          const float h8[8] = {hi[8 * rp], hi[8 * rp + 1], hi[8 * rp + 2], hi[8 * rp + 3],
+                               hi[8 * rp + 4], hi[8 * rp + 5], hi[8 * rp + 6], hi[8 * rp + 7]};
+          pj_store_rows_bf16(row + 32 * ip * 2, l8, rp, hl, tok_ok);
+          pj_store_rows_bf16(row + 32 * (ip + 2) * 2, h8, rp, hl, tok_ok);
         }
+      };
+#pragma unroll
+      for (int ib = 0; ib < 4; ++ib) {
+        const int m = m0 + ib * 32;
+        const bool tok_ok = m < p.b_rows && n_valid > 0;              // n_valid is 128 or, for a head past the last, 0
+        char* row = base + (int64_t)m * row_bytes;                    // only stored to when tok_ok
+        group(ib, 0, tab0, row, tok_ok);
+        group(ib, 1, tab1, row, tok_ok);
       }
+    } else {
+      // fp32 output, a ragged last run of features or an odd row pitch: element by element
+      int hl_slow = hl;            // opaque per tile: keeps this path's offsets from being hoisted out of the tile loop,
+      asm volatile("" : "+v"(hl_slow));   // where they would sit in registers (or scratch) for nothing
+      auto group = [&](int ib, int ip, float4 (&tb8)[8], char* row, bool tok_ok) __attribute__((always_inline)) {
+        if (MODE == kPjQkv && ib > 0) tab_load(ib, ip, tb8);          // token block 0 was fetched above
+        if (!tok_ok) return;
+#pragma unroll
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int f = 32 * (ip + 2 * half) + 8 * (r >> 2) + 4 * hl_slow + (r & 3);
+            float x = half ? acc[ip + 2][ib][r] : acc[ip][ib][r];
+            if (MODE == kPjQkv && rotate) {
+              const float4 cq = tb8[2 * (r >> 2) + ((r & 3) >> 1)];
+              const float c = (r & 1) ? cq.z : cq.x, sn = (r & 1) ? cq.w : cq.y;
+              const float other = half ? acc[ip][ib][r] : acc[ip + 2][ib][r];
+              x = half ? pj_rot_hi(other, x, c, sn) : pj_rot_lo(x, other, c, sn);
+            }
+            if (f >= n_valid) continue;
+            if (p.out_fp32) *(float*)(row + f * 4) = x;
+            else *(uint16_t*)(row + f * 2) = float_to_bf16_bits(x);
+          }
+      };
+#pragma unroll
+      for (int ib = 0; ib < 4; ++ib) {
+        const int m = m0 + ib * 32;
+        char* row = base + (int64_t)m * row_bytes;
+        group(ib, 0, tab0, row, m < p.b_rows);
+        group(ib, 1, tab1, row, m < p.b_rows);
+      }
+    }
+    // The next tile's load offsets are formed again here rather than kept across the epilogue: kept, they are spilled
+    // and reloaded, and the waits the compiler then puts before their first uses inside the contraction loop count
+    // memory operations it cannot see - they would drain the operand loads that are meant to stay in flight.
+    if (cur_j >= 0) {
+      int ta2 = ta, tb2 = tb;
+      asm volatile("" : "+v"(ta2), "+v"(tb2));
+      set_offsets(ta2, tb2);
     }
   }
 }
@@ -442,9 +502,10 @@ static hi_status pj_launch(void* stream, ProjArgs& p, int mode) {
   static std::once_flag attr_once;      // the projections are stateless: any host thread may get here first
   static hipError_t attr_err = hipSuccess;
   std::call_once(attr_once, [] {
-    attr_err = hipFuncSetAttribute((const void*)proj_gemm_kernel<kPjQkv>, hipFuncAttributeMaxDynamicSharedMemorySize, kPjLdsBytes);
-    if (attr_err == hipSuccess)
-      attr_err = hipFuncSetAttribute((const void*)proj_gemm_kernel<kPjOut>, hipFuncAttributeMaxDynamicSharedMemorySize, kPjLdsBytes);
+    const void* kernels[4] = {(const void*)proj_gemm_kernel<kPjQkv, true>, (const void*)proj_gemm_kernel<kPjQkv, false>,
+                              (const void*)proj_gemm_kernel<kPjOut, true>, (const void*)proj_gemm_kernel<kPjOut, false>};
+    for (int i = 0; i < 4 && attr_err == hipSuccess; ++i)
+      attr_err = hipFuncSetAttribute(kernels[i], hipFuncAttributeMaxDynamicSharedMemorySize, kPjLdsBytes);
   });
   if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
   p.a_tiles = (int)ceil_div(p.a_rows, kPjTile);
@@ -454,8 +515,13 @@ static hi_status pj_launch(void* stream, ProjArgs& p, int mode) {
   const int per = (total + 7) / 8;
   // persistent workgroups: at most 32 per XCD (one per compute unit), each looping over its share of the tiles
   dim3 grid((unsigned)(8 * (per < kPjWgsPerXcd ? per : kPjWgsPerXcd)));
-  if (mode == kPjQkv) hipLaunchKernelGGL(proj_gemm_kernel<kPjQkv>, grid, dim3(kPjWaves * 64), kPjLdsBytes, (hipStream_t)stream, p);
-  else hipLaunchKernelGGL(proj_gemm_kernel<kPjOut>, grid, dim3(kPjWaves * 64), kPjLdsBytes, (hipStream_t)stream, p);
+  // 16-byte stores need bf16 output, whole runs of 128 features per wavefront and an aligned row pitch
+  const bool wide = !p.out_fp32 && p.a_rows % 128 == 0 && (mode == kPjQkv || (p.y_stride * 2) % 16 == 0);
+  const dim3 block(kPjWaves * 64);
+  if (mode == kPjQkv && wide) hipLaunchKernelGGL((proj_gemm_kernel<kPjQkv, true>), grid, block, kPjLdsBytes, (hipStream_t)stream, p);
+  else if (mode == kPjQkv) hipLaunchKernelGGL((proj_gemm_kernel<kPjQkv, false>), grid, block, kPjLdsBytes, (hipStream_t)stream, p);
+  else if (wide) hipLaunchKernelGGL((proj_gemm_kernel<kPjOut, true>), grid, block, kPjLdsBytes, (hipStream_t)stream, p);
+  else hipLaunchKernelGGL((proj_gemm_kernel<kPjOut, false>), grid, block, kPjLdsBytes, (hipStream_t)stream, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("projection launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
   return HI_OK;
@@ -475,7 +541,8 @@ using namespace hi;
 
 extern "C" hi_status hi_proj_workspace_bytes(int32_t chunk, int64_t* bytes) {
   if (chunk < 1 || !bytes) { set_last_error("projection workspace: bad argument"); return HI_ERR_ARG; }
-  *bytes = (int64_t)chunk * 64 * sizeof(float2);
+  // the table of the chunk plus a token block's worth of slack (see the epilogue of proj_gemm_kernel)
+  *bytes = (int64_t)chunk * 64 * sizeof(float2) + kPjTile * 32;
   return HI_OK;
 }
 
