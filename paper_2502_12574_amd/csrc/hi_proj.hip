@@ -434,6 +434,7 @@ __device__ __forceinline__ float gemv_dot8(uint4 a, uint4 b) {
   return s;
 }
 
+constexpr int kGemvChunks = 8;
 __global__ __launch_bounds__(256) void proj_gemv_kernel(GemvArgs g) {
   const int lane = lane_id();
   const int wave_global = blockIdx.x * 4 + wave_id();
@@ -446,10 +447,12 @@ __global__ __launch_bounds__(256) void proj_gemv_kernel(GemvArgs g) {
     const uint16_t* wa = g.w + (int64_t)ra * g.K;
     const uint16_t* wb = g.w + (int64_t)rb * g.K;
     float sa = 0.f, sb = 0.f;
-    for (int k0 = lane * 8; k0 < g.K; k0 += 4 * 512) {
-      uint4 a[4], b[4], xv[4];
+    // 8 x 512 contraction elements per round: both rows of a Llama-3-8B pair (4096 each) are in flight at once,
+    // 16 loads of 16 bytes per lane, instead of two dependent rounds of 8
+    for (int k0 = lane * 8; k0 < g.K; k0 += kGemvChunks * 512) {
+      uint4 a[kGemvChunks], b[kGemvChunks], xv[kGemvChunks];
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < kGemvChunks; ++c) {
         const int k = k0 + c * 512;
         const int kc = k < g.K ? k : 0;                  // in bounds; the product is dropped below
         a[c] = gemv_load_stream(wa + kc);                // the weights are read once: non-temporal
@@ -457,7 +460,7 @@ __global__ __launch_bounds__(256) void proj_gemv_kernel(GemvArgs g) {
         xv[c] = *(const uint4*)(g.x + kc);
       }
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
+      for (int c = 0; c < kGemvChunks; ++c)
         if (k0 + c * 512 < g.K) { sa += gemv_dot8(a[c], xv[c]); sb += gemv_dot8(b[c], xv[c]); }
     }
 #pragma unroll
