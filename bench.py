@@ -61,6 +61,13 @@ def prefill_traffic_per_launch(S, C):
 _T0 = time.perf_counter()
 
 
+EXTRA_FLAGS = 0      # kernel-selection flags of the command line, added to every flag word set below
+
+
+def set_flags(ss, flags):
+    hb.hi_ctx_set_flags(ss.ctx, flags | EXTRA_FLAGS)
+
+
 def note(msg):
     """progress line of the work itself (stderr; stdout carries the one JSON line)"""
     print(f"bench.py [{time.perf_counter() - _T0:6.1f} s] {msg}", file=sys.stderr, flush=True)
@@ -147,7 +154,7 @@ def run_stack(args):
     xs = [synth.draw_hidden(args.seed, 0, p, min(C, S - p), d_model, device=dev) for p in starts]
     xbuf = [torch.empty(C, d_model, dtype=torch.bfloat16, device=dev) for _ in range(2)]
     first = blocks[0].calls[0]
-    hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_TIME_KERNELS)
+    set_flags(ss, hb.HI_FLAG_TIME_KERNELS)
     hb.hi_reset_stats(ss.ctx)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -207,7 +214,7 @@ def run_stack(args):
         "peak_staging_bytes": max(st.peak_staging_bytes, sd.peak_staging_bytes), "one_head_bytes": ss.plan.host_bytes_per_head,
         "bytes_h2d_prefill": st.bytes_h2d, "bytes_d2h_prefill": st.bytes_d2h,
         "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS, "traffic": None, "kernel": "prefill_kernel_deep16",
+                     "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS, "traffic": None, "kernel": "prefill_kernel_deep" if EXTRA_FLAGS & hb.HI_FLAG_PREFILL_MFMA32 else "prefill_kernel_deep16",
                      "launches_per_step": st.n_prefill_kernels, "avg_launch_ms": st.prefill_kernel_ms / max(st.n_prefill_kernels, 1),
                      "wall_TFLOPs": flops / (t_pre / L) / 1e12,
                      "note": "wall time includes the projections of every chunk and layer (about 1.2 % of a layer)"},
@@ -239,6 +246,7 @@ def main():
     ap.add_argument("--seed", type=int, default=20250216)
     ap.add_argument("--resident-passes", type=int, default=2, help="passes of the compute-only (HBM-resident) prefill leg; "
                     "the last one is timed")
+    ap.add_argument("--mfma32", action="store_true", help="the 8-wave prefill kernel in its 32x32x16 MFMA form (A/B runs)")
     ap.add_argument("--peaked-keys", action="store_true", help="one key row in ten scaled x4 (peaked softmax rows)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="run the timed steps without the library's HIP events "
                     "around kernels and copies (wall figures only; the roofline object is then empty)")
@@ -249,6 +257,8 @@ def main():
         print("bench.py: this build runs on ONE GPU (one process, no collectives); --gpus must be 1. KV heads are "
               "independent, so N GPUs would each own n_kv_heads/N heads and their own host link.", file=sys.stderr)
         sys.exit(2)
+    global EXTRA_FLAGS
+    EXTRA_FLAGS = hb.HI_FLAG_PREFILL_MFMA32 if args.mfma32 else 0
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
@@ -296,7 +306,7 @@ def main():
         note(f"step done: prefill {t1 - t0:.3f} s, {nd} decode tokens {t2 - t1b:.3f} s")
         return t1 - t0, t2 - t1b, st_pre, ss.stats()
 
-    hb.hi_ctx_set_flags(ss.ctx, 0 if args.no_kernel_timing else hb.HI_FLAG_TIME_KERNELS)
+    set_flags(ss, 0 if args.no_kernel_timing else hb.HI_FLAG_TIME_KERNELS)
     for _ in range(args.warmup):
         step(False)
     pre_s, dec_s, kern_pre_ms, kern_dec_ms, n_pre_k, n_dec_k = [], [], 0.0, 0.0, 0, 0
@@ -324,7 +334,7 @@ def main():
     extra = {}
     if not args.no_extra_legs:
         # transfer-only: the same copy sequence with the kernels disabled
-        hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_SKIP_KERNELS)
+        set_flags(ss, hb.HI_FLAG_SKIP_KERNELS)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         with torch.cuda.stream(ss.s_compute):
@@ -332,7 +342,7 @@ def main():
         ss.sync()
         t_xfer = (time.perf_counter() - t0) / NL
         note(f"transfer-only leg done ({t_xfer:.3f} s per layer)")
-        hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_TIME_KERNELS)
+        set_flags(ss, hb.HI_FLAG_TIME_KERNELS)
         link_bytes = 512.0 * HKV * sum(range(0, S, C)) + 512.0 * HKV * S
         # compute-only: the same calls on one layer with K/V resident in HBM (no link, no ring; a unit's past is one
         # contiguous segment there, so it takes one launch instead of one per staging slice)
@@ -367,7 +377,7 @@ def main():
                             "d2h_copy_engine_s": copy_ms["d2h"] / K * 1e-3 / NL,
                             "link_bytes": link_bytes, "transfer_only_GBps": link_bytes / t_xfer / 1e9}
         # HBM-resident decode over the cache the resident prefill has just filled
-        hb.hi_ctx_set_flags(ss_r.ctx, hb.HI_FLAG_TIME_KERNELS)
+        set_flags(ss_r, hb.HI_FLAG_TIME_KERNELS)
         nr = args.resident_decode_tokens
         # all KV heads of the layer in one call per token (head groups; with everything in HBM nothing speaks
         # against the largest group)
@@ -425,7 +435,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS,
                      "traffic": traffic, "traffic_source": traffic_src,
-                     "kernel": "prefill_kernel_deep16",
+                     "kernel": "prefill_kernel_deep" if EXTRA_FLAGS & hb.HI_FLAG_PREFILL_MFMA32 else "prefill_kernel_deep16",
                      "launches_per_step": n_pre_k / K, "avg_launch_ms": kern_pre_ms / max(n_pre_k, 1),
                      "flops_per_launch": flops * NL / (n_pre_k / K),
                      "wall_TFLOPs": flops / prefill_s / 1e12},
