@@ -39,7 +39,15 @@ def draw_case(rng):
     n_sink = rng.choice([0, 1, 5, 64, 130])
     n_recent = rng.choice([1, 2, 33, 64, 100, 257, 5000])
     group = rng.choice([1, 1, 2])
-    return dict(G=G, H=H, T=T, R=R, mode=mode, C=C, S=S, nd=nd, n_sink=n_sink, n_recent=n_recent, group=group)
+    # which prefill kernel: the launcher's choice, or one of the forced forms (these shapes are far below the sizes
+    # at which the launcher picks the 8-wave kernels by itself)
+    flags = rng.choice([0, 0, hb.HI_FLAG_PREFILL_DEEP, hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED,
+                        hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_UNPAIRED,
+                        hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_MFMA32,
+                        hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_MFMA32,
+                        hb.HI_FLAG_PREFILL_NARROW])
+    return dict(G=G, H=H, T=T, R=R, mode=mode, C=C, S=S, nd=nd, n_sink=n_sink, n_recent=n_recent, group=group,
+                flags=flags)
 
 
 @pytest.mark.parametrize("case_id", range(int(os.environ.get("HI_TEST_RANDOM_CASES", "24"))))
@@ -62,6 +70,7 @@ def test_random_shape(case_id):
         h += nh
     with Session(1, H, G, max_ctx, C, mode=c["mode"], out_fp32=1, gpu_kv_budget_heads=R + 1, resident_heads=R,
                  streaming_heads=T, sink_tokens=n_sink if T else 0, recent_tokens=n_recent if T else 0) as ss:
+        hb.hi_ctx_set_flags(ss.ctx, c["flags"])
         ss.kv.view(torch.int16).fill_(0x7FC1)
         if ss.staging is not None:
             ss.staging.view(torch.int16).fill_(0x7FC1)
