@@ -62,6 +62,7 @@ _T0 = time.perf_counter()
 
 
 EXTRA_FLAGS = 0      # kernel-selection flags of the command line, added to every flag word set below
+Q_PRESCALED = True   # the queries carry the softmax scale (hi_problem.q_prescaled), as the Q projection emits them
 
 
 def set_flags(ss, flags):
@@ -88,7 +89,8 @@ def cpu_baseline(seed, S, C, seconds_target=15.0):
     V = synth.to_f64(synth.draw_v(seed, 0, 0, 0, S))
     rows = 64
     pos = np.linspace(S - C, S - 1, rows).astype(np.int64)
-    q = synth.to_f64(synth.draw_q(seed, 0, 0, 0, S)[pos])
+    qs = hb.HI_Q_PRESCALE if Q_PRESCALED else 1.0          # the oracle takes the q of Eq. 3: the drawn query / the constant
+    q = synth.to_f64(synth.draw_q(seed, 0, 0, 0, S, scale=qs)[pos]) / qs
     t0 = time.perf_counter()
     oa.attn_rows(q, K, V, pos)
     dt = time.perf_counter() - t0
@@ -106,7 +108,7 @@ def cpu_baseline(seed, S, C, seconds_target=15.0):
     decode_ms = sec_per_pair * HQ * S * 1e3
     # the small configuration in full: 4 query heads over one KV head, 2048 tokens, then 16 decode rows
     n1, nd1 = 2048, 16
-    Q1 = np.stack([synth.to_f64(synth.draw_q(seed, 0, g, 0, n1 + nd1)) for g in range(4)])
+    Q1 = np.stack([synth.to_f64(synth.draw_q(seed, 0, g, 0, n1 + nd1, scale=qs)) / qs for g in range(4)])
     K1 = synth.to_f64(synth.draw_k(seed, 0, 0, 0, n1 + nd1))
     V1 = synth.to_f64(synth.draw_v(seed, 0, 0, 0, n1 + nd1))
     t0 = time.perf_counter()
@@ -137,6 +139,7 @@ def run_stack(args):
     while ss is None:
         try:
             ss = Session(L, HKV, G, S + max(nd, 1), C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0, per_layer_cache=True,
+                         q_prescaled=Q_PRESCALED,
                          progress=lambda m: print("bench.py: " + m, file=sys.stderr, flush=True))
         except RuntimeError as e:               # the box refuses to pin that much: fewer layers, figures stay per layer
             print(f"bench.py: {L} layers of pinned cache refused ({str(e)[:80]}); trying {L // 2}", file=sys.stderr, flush=True)
@@ -207,7 +210,7 @@ def run_stack(args):
                                f"layer's output from hi_out_proj; {ss.plan.host_bytes_total / 2**30:.0f} GiB of K/V in "
                                f"pinned host DRAM (one allocation per layer), 1-KV-head HBM budget",
                    "context": S, "chunk": C, "decode_tokens": nd, "layers_timed": L, "layers_asked": args.layers,
-                   "seed": args.seed},
+                   "q_prescaled": Q_PRESCALED, "seed": args.seed},
         "prefill_s_total": t_pre, "prefill_s_per_layer": t_pre / L,
         "decode_ms_per_token_per_layer_offloaded": dec_ms if nd else None,
         "decode_link": {"achieved_GBps": 512.0 * HKV * S / (dec_ms * 1e-3) / 1e9 if nd else None, "peak_GBps": PEAK_LINK_GBPS},
@@ -246,6 +249,8 @@ def main():
     ap.add_argument("--seed", type=int, default=20250216)
     ap.add_argument("--resident-passes", type=int, default=2, help="passes of the compute-only (HBM-resident) prefill leg; "
                     "the last one is timed")
+    ap.add_argument("--no-q-prescale", action="store_true", help="hand the attention calls plain queries (the q of Eq. 3) "
+                    "instead of queries that carry the softmax scale; one more multiplication per score in the kernels")
     ap.add_argument("--mfma32", action="store_true", help="the 8-wave prefill kernel in its 32x32x16 MFMA form (A/B runs)")
     ap.add_argument("--peaked-keys", action="store_true", help="one key row in ten scaled x4 (peaked softmax rows)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="run the timed steps without the library's HIP events "
@@ -257,7 +262,8 @@ def main():
         print("bench.py: this build runs on ONE GPU (one process, no collectives); --gpus must be 1. KV heads are "
               "independent, so N GPUs would each own n_kv_heads/N heads and their own host link.", file=sys.stderr)
         sys.exit(2)
-    global EXTRA_FLAGS
+    global EXTRA_FLAGS, Q_PRESCALED
+    Q_PRESCALED = not args.no_q_prescale
     EXTRA_FLAGS = hb.HI_FLAG_PREFILL_MFMA32 if args.mfma32 else 0
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
@@ -269,11 +275,12 @@ def main():
     S, C, nd = args.context, args.chunk, args.decode_tokens
     S_max = S + max(nd, args.resident_decode_tokens)
     NL = max(1, args.layers)
-    ss = Session(NL, HKV, G, S_max, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0)
+    ss = Session(NL, HKV, G, S_max, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0, q_prescaled=Q_PRESCALED)
     hpc = args.heads_per_call if args.heads_per_call > 0 else max(1, ss.plan.heads_per_group)
     t_gen = time.perf_counter()
     with torch.cuda.stream(ss.s_compute):
-        inp = driver.LayerInputs(args.seed, NL, HKV, G, S, C, dev, peaked=args.peaked_keys)
+        inp = driver.LayerInputs(args.seed, NL, HKV, G, S, C, dev, peaked=args.peaked_keys,
+                                 q_scale=hb.HI_Q_PRESCALE if Q_PRESCALED else 1.0)
         dec_rows = [inp.decode_rows(S + t) for t in range(max(nd, args.resident_decode_tokens))]
         out_buf = [torch.empty(HKV, G, C, D, dtype=ss.out_dtype, device=dev) for _ in range(NL)]
     torch.cuda.synchronize()
@@ -346,7 +353,7 @@ def main():
         link_bytes = 512.0 * HKV * sum(range(0, S, C)) + 512.0 * HKV * S
         # compute-only: the same calls on one layer with K/V resident in HBM (no link, no ring; a unit's past is one
         # contiguous segment there, so it takes one launch instead of one per staging slice)
-        ss_r = Session(1, HKV, G, S_max, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0)
+        ss_r = Session(1, HKV, G, S_max, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0, q_prescaled=Q_PRESCALED)
         inp0 = inp.single_layer(0)
 
         def resident_prefill():
@@ -423,8 +430,9 @@ def main():
         "config": {"workload": f"one Llama-3-8B-shaped attention layer of the 32-layer 1M-token configuration: "
                                f"{HQ} Q / {HKV} KV heads, head_dim {D}, context {S}, head-wise chunked prefill "
                                f"chunk {C} + {nd} decode tokens, K/V offloaded to pinned host DRAM, 1-KV-head HBM "
-                               f"budget", "context": S, "chunk": C, "decode_tokens": nd, "layers_timed": NL, "heads_per_call": hpc,
-                   "peaked_keys": bool(args.peaked_keys),
+                               f"budget" + ("; queries carry the softmax scale, as the Q projection emits them" if Q_PRESCALED else ""),
+                   "context": S, "chunk": C, "decode_tokens": nd, "layers_timed": NL, "heads_per_call": hpc,
+                   "peaked_keys": bool(args.peaked_keys), "q_prescaled": Q_PRESCALED,
                    "seed": args.seed},
         "prefill_s_per_layer": prefill_s,
         "decode_ms_per_token_per_layer_offloaded": decode_ms_tok if nd else None,

@@ -86,7 +86,15 @@ typedef struct hi_problem {
                                   retrieval heads of all layers back to back in (layer, head) order, a layer's
                                   allocation (hi_ctx_set_layer_cache) its own retrieval heads in head order, and the
                                   streaming stores follow (layer, head) order likewise */
+  int32_t q_prescaled;         /* 0: the queries handed to the attention calls are the q of Eq. 3 and a weight is
+                                  exp(q.k / sqrt(head_dim) - max); 1: they are HI_Q_PRESCALE times that q (folded into
+                                  the query projection, as hi_qkv_rope does with q_scale = HI_Q_PRESCALE: one rounding
+                                  to bf16 either way) and a weight is 2^(q.k - max) - the same function of the model's
+                                  q, one multiplication per score less in the attention kernels */
 } hi_problem;
+
+/* log2(e) / sqrt(128): the factor between the q of Eq. 3 and a pre-scaled query (hi_problem.q_prescaled) */
+#define HI_Q_PRESCALE 0.12751743082459868f
 
 /* Output of hi_offload_plan.  Sizes in bytes. */
 typedef struct hi_plan {
@@ -297,6 +305,8 @@ hi_status hi_decode_group_ragged(hi_ctx* ctx, int32_t layer, int32_t kv_head, in
  *   [n_kv_heads][chunk_len][128] - exactly the q_dev / k_new_dev / v_new_dev of hi_prefill_group over all heads
  *   (bf16, or fp32 with out_fp32 = 1 for checking).  workspace_dev: DEVICE, hi_proj_workspace_bytes(chunk_len)
  *   bytes (the chunk's cos / sin table, computed in double precision); may be null when rope_theta = 0.
+ *   q_scale: factor applied to the query heads after the rotation, in fp32, before the one rounding of the output
+ *   (> 0; 1 = none; HI_Q_PRESCALE for a context with hi_problem.q_prescaled = 1).
  * hi_out_proj: Y [chunk_len][d_model] = Concat_h(attn[h]) W_o^T for the head-major attention output
  *   attn [n_q_heads][chunk_len][128] (the out_dev of the attention calls) and W_o [d_model][n_q_heads * 128].
  * d_model must be a multiple of 128; every operand must be smaller than 4 GiB; all pointers 16-byte aligned.
@@ -306,7 +316,7 @@ hi_status hi_decode_group_ragged(hi_ctx* ctx, int32_t layer, int32_t kv_head, in
 hi_status hi_proj_workspace_bytes(int32_t chunk_len, int64_t* bytes);
 hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model, int32_t n_q_heads,
                       int32_t n_kv_heads, int32_t chunk_len, int64_t past_len, double rope_theta, int32_t out_fp32,
-                      void* q_out_dev, void* k_out_dev, void* v_out_dev, void* workspace_dev);
+                      void* q_out_dev, void* k_out_dev, void* v_out_dev, void* workspace_dev, float q_scale);
 hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, int32_t n_q_heads, int32_t d_model,
                       int32_t chunk_len, int32_t out_fp32, void* y_out_dev);
 
@@ -322,7 +332,7 @@ hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, i
  */
 hi_status hi_qkv_rope_static(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model, int32_t n_q_heads,
                              int32_t n_kv_heads, int32_t chunk_len, int64_t past_len, double rope_theta,
-                             int32_t out_fp32, void* q_out_dev, void* k_out_dev, void* v_out_dev);
+                             int32_t out_fp32, void* q_out_dev, void* k_out_dev, void* v_out_dev, float q_scale);
 
 /*
  * 4-bit rows on the link (Appendix B and Section 6.3 describe 4-bit KV quantisation as a representation that shrinks

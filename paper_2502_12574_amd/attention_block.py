@@ -58,7 +58,9 @@ class AttentionBlock:
         if self.kv_done[self.turn] is not None:
             s.wait_event(self.kv_done[self.turn])
         with torch.cuda.stream(s):
-            hb.hi_qkv_rope(s, x, self.w_qkv, self.D, self.Hq, self.Hkv, n, past_len, self.theta, 0, q, k, v, self.ws)
+            # the softmax scale rides on the queries when the Session's attention calls expect it there
+            hb.hi_qkv_rope(s, x, self.w_qkv, self.D, self.Hq, self.Hkv, n, past_len, self.theta, 0, q, k, v, self.ws,
+                           q_scale=hb.HI_Q_PRESCALE if ss.problem.q_prescaled else 1.0)
             for i, (h0, nh) in enumerate(self.calls):
                 hint = (self.layer, self.calls[i + 1][0], self.calls[i + 1][1], past_len) if i + 1 < len(self.calls) else nxt
                 if n == 1:

@@ -19,6 +19,7 @@ HI_FLAG_SKIP_KERNELS, HI_FLAG_SKIP_COPIES, HI_FLAG_TIME_KERNELS = 1, 2, 4
 HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_PAIRED, HI_FLAG_PREFILL_DEEP, HI_FLAG_PREFILL_UNPAIRED = 8, 16, 32, 64
 HI_FLAG_INJECT_FAILURE = 128
 HI_FLAG_PREFILL_MFMA32 = 256
+HI_Q_PRESCALE = 0.12751743082459868      # log2(e) / sqrt(128): a pre-scaled query is this times the q of Eq. 3
 
 EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_layer_cache", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",
            "hi_prefill_head", "hi_decode_head", "hi_prefill_group", "hi_decode_group", "hi_decode_group_ragged", "hi_proj_workspace_bytes",
@@ -32,7 +33,7 @@ class hi_problem(C.Structure):
                 ("n_compute_units", C.c_int32), ("resident_heads", C.c_int32), ("host_mem_limit_bytes", C.c_int64),
                 ("link_GBps", C.c_double), ("hbm_GBps", C.c_double), ("mfma_TFLOPs", C.c_double),
                 ("streaming_heads", C.c_int32), ("sink_tokens", C.c_int32), ("recent_tokens", C.c_int32),
-                ("link_kv_bits", C.c_int32), ("streaming_mask", C.c_void_p)]
+                ("link_kv_bits", C.c_int32), ("streaming_mask", C.c_void_p), ("q_prescaled", C.c_int32)]
 
 
 class hi_plan(C.Structure):
@@ -91,8 +92,8 @@ def lib() -> C.CDLL:
         L.hi_decode_group.argtypes = [vp, i32, i32, i32, vp, vp, vp, i64, vp, i32, i32, i32, i64]
         L.hi_decode_group_ragged.argtypes = [vp, i32, i32, i32, vp, vp, vp, C.POINTER(i64), vp]
         L.hi_proj_workspace_bytes.argtypes = [i32, C.POINTER(i64)]
-        L.hi_qkv_rope.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp, vp]
-        L.hi_qkv_rope_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp]
+        L.hi_qkv_rope.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp, vp, C.c_float]
+        L.hi_qkv_rope_static.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, C.c_double, i32, vp, vp, vp, C.c_float]
         L.hi_out_proj.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp]
         L.hi_kv_quantize.argtypes = [vp, vp, i64, vp]
         L.hi_kv_dequantize.argtypes = [vp, vp, i64, vp]
@@ -135,11 +136,12 @@ def _stream(s):
 def make_problem(n_layers, n_kv_heads, gqa_group, max_context, chunk, head_dim=128, gpu_kv_budget_heads=1,
                  dtype_bytes=2, out_fp32=0, n_compute_units=0, host_mem_limit_bytes=0, link_GBps=0.0, hbm_GBps=0.0,
                  mfma_TFLOPs=0.0, resident_heads=0, streaming_heads=0, sink_tokens=0, recent_tokens=0,
-                 link_kv_bits=0, streaming_mask=None) -> hi_problem:
-    """streaming_mask: optional [n_layers][n_kv_heads] nested list / array of 0 and 1 (1 = streaming head)."""
+                 link_kv_bits=0, streaming_mask=None, q_prescaled=0) -> hi_problem:
+    """streaming_mask: optional [n_layers][n_kv_heads] nested list / array of 0 and 1 (1 = streaming head).
+    q_prescaled: 1 = the queries handed to the attention calls already carry HI_Q_PRESCALE."""
     p = hi_problem(n_layers, n_kv_heads, gqa_group, head_dim, max_context, chunk, gpu_kv_budget_heads,
                    dtype_bytes, out_fp32, n_compute_units, resident_heads, host_mem_limit_bytes, link_GBps, hbm_GBps,
-                   mfma_TFLOPs, streaming_heads, sink_tokens, recent_tokens, link_kv_bits, None)
+                   mfma_TFLOPs, streaming_heads, sink_tokens, recent_tokens, link_kv_bits, None, int(q_prescaled))
     if streaming_mask is not None:
         flat = [int(x) for row in streaming_mask for x in row]
         assert len(flat) == n_layers * n_kv_heads
@@ -248,20 +250,20 @@ def hi_proj_workspace_bytes(chunk_len: int) -> int:
 
 
 def hi_qkv_rope(stream, x_dev, w_qkv_dev, d_model, n_q_heads, n_kv_heads, chunk_len, past_len, rope_theta, out_fp32,
-                q_out_dev, k_out_dev, v_out_dev, workspace_dev, check: bool = True):
+                q_out_dev, k_out_dev, v_out_dev, workspace_dev, q_scale: float = 1.0, check: bool = True):
     st = lib().hi_qkv_rope(_stream(stream), _ptr(x_dev), _ptr(w_qkv_dev), d_model, n_q_heads, n_kv_heads, chunk_len,
                            past_len, float(rope_theta), out_fp32, _ptr(q_out_dev), _ptr(k_out_dev), _ptr(v_out_dev),
-                           _ptr(workspace_dev))
+                           _ptr(workspace_dev), float(q_scale))
     if check and st != HI_OK:
         raise HiError(st, "hi_qkv_rope")
     return st
 
 
 def hi_qkv_rope_static(stream, x_dev, w_qkv_dev, d_model, n_q_heads, n_kv_heads, chunk_len, past_len, rope_theta,
-                       out_fp32, q_out_dev, k_out_dev, v_out_dev, check: bool = True):
+                       out_fp32, q_out_dev, k_out_dev, v_out_dev, q_scale: float = 1.0, check: bool = True):
     st = lib().hi_qkv_rope_static(_stream(stream), _ptr(x_dev), _ptr(w_qkv_dev), d_model, n_q_heads, n_kv_heads,
                                   chunk_len, past_len, float(rope_theta), out_fp32, _ptr(q_out_dev), _ptr(k_out_dev),
-                                  _ptr(v_out_dev))
+                                  _ptr(v_out_dev), float(q_scale))
     if check and st != HI_OK:
         raise HiError(st, "hi_qkv_rope_static")
     return st

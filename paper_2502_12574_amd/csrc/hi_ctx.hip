@@ -290,8 +290,10 @@ hi_status pace_end(hi_ctx* c) {
 int pf_variant(const hi_ctx* c) {
   return ((c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_DEEP) ? 3 : 0) |
          ((c->flags & HI_FLAG_PREFILL_PAIRED) ? 4 : 0) | ((c->flags & HI_FLAG_PREFILL_UNPAIRED) ? 8 : 0) |
-         ((c->flags & HI_FLAG_PREFILL_MFMA32) ? 16 : 0);
+         ((c->flags & HI_FLAG_PREFILL_MFMA32) ? 16 : 0) | (c->prob.q_prescaled ? 32 : 0);
 }
+
+bool q_pre(const hi_ctx* c) { return c->prob.q_prescaled != 0; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -682,7 +684,8 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
       TimedSpan sp;
       if (timed) HI_TRY(span_begin(c, 0, &sp));
       HI_TRY(launch_prefill_window(c->sc, q_dev, G, chunk_len, sk, sv, stream_head_stride(c), k_new_dev, v_new_dev,
-                                   past_len, c->prob.sink_tokens, c->prob.recent_tokens, out_dev, c->prob.out_fp32, nh));
+                                   past_len, c->prob.sink_tokens, c->prob.recent_tokens, out_dev, c->prob.out_fp32, nh,
+                                   q_pre(c)));
       if (timed) HI_TRY(span_end(c, sp));
       c->stats.n_prefill_kernels += 1;
     }
@@ -745,7 +748,8 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
     if (part0 + np > part_cap) { set_last_error("decode: partial workspace exhausted"); return HI_ERR_UNSUPPORTED; }
     TimedSpan sp;
     if (timed) HI_TRY(span_begin(c, 1, &sp));
-    HI_TRY(launch_decode_partial(c->sc, q_dev, G, k, v, rows, np, partials, part0, nh, kv_stride, part_stride, skip_row));
+    HI_TRY(launch_decode_partial(c->sc, q_dev, G, k, v, rows, np, partials, part0, q_pre(c), nh, kv_stride, part_stride,
+                                 skip_row));
     if (timed) HI_TRY(span_end(c, sp));
     c->stats.n_decode_kernels += 1;
     return HI_OK;
@@ -798,7 +802,8 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
       HI_TRY(partial(sk, sv, n_store, n_part, 0, stream_head_stride(c), skip));
     }
     HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32,
-                                 sk + slot * kRowBytes, sv + slot * kRowBytes, nh, part_stride, stream_head_stride(c)));
+                                 sk + slot * kRowBytes, sv + slot * kRowBytes, q_pre(c), nh, part_stride,
+                                 stream_head_stride(c)));
     c->stats.n_combine_kernels += 1;
     return HI_OK;
   }
@@ -813,7 +818,7 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
       }
       HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32,
                                    res_plane(c, layer, kv_head, 0) + past_len * kRowBytes,
-                                   res_plane(c, layer, kv_head, 1) + past_len * kRowBytes, nh, part_stride,
+                                   res_plane(c, layer, kv_head, 1) + past_len * kRowBytes, q_pre(c), nh, part_stride,
                                    plane2));
       c->stats.n_combine_kernels += 1;
       return HI_OK;
@@ -843,7 +848,7 @@ static hi_status decode_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t 
   }
   if (run) {
     HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, n_part, out_dev, c->prob.out_fp32,
-                                 nullptr, nullptr, nh, part_stride, 0));
+                                 nullptr, nullptr, q_pre(c), nh, part_stride, 0));
     c->stats.n_combine_kernels += 1;
   }
   cur.valid = false;
@@ -914,13 +919,13 @@ extern "C" hi_status hi_decode_group_ragged(hi_ctx* c, int32_t layer, int32_t kv
       TimedSpan sp;
       if (timed) HI_TRY(span_begin(c, 1, &sp));
       HI_TRY(launch_decode_partial(c->sc, q_dev, G, res_plane(c, layer, kv_head, 0), res_plane(c, layer, kv_head, 1), longest,
-                                   n_split, partials, 0, n_heads, plane2, part_stride, -1, &lens));
+                                   n_split, partials, 0, q_pre(c), n_heads, plane2, part_stride, -1, &lens));
       if (timed) HI_TRY(span_end(c, sp));
       c->stats.n_decode_kernels += 1;
     }
     HI_TRY(launch_decode_combine(c->sc, q_dev, G, k_new_dev, v_new_dev, partials, longest > 0 ? n_split : 0, out_dev,
-                                 c->prob.out_fp32, res_plane(c, layer, kv_head, 0), res_plane(c, layer, kv_head, 1), n_heads,
-                                 part_stride, plane2, &lens));
+                                 c->prob.out_fp32, res_plane(c, layer, kv_head, 0), res_plane(c, layer, kv_head, 1), q_pre(c),
+                                 n_heads, part_stride, plane2, &lens));
     c->stats.n_combine_kernels += 1;
     return HI_OK;
   });

@@ -282,11 +282,11 @@ __global__ __launch_bounds__(256) void decode_combine_kernel(const uint16_t* __r
   }
 }
 
-static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   // log2(e) / sqrt(128)
 
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
-                                int n_split, void* partials, int part0, int n_heads, int64_t kv_head_stride,
-                                int64_t part_head_stride, int64_t skip_row, const DecodeLens* lens) {
+                                int n_split, void* partials, int part0, bool q_prescaled, int n_heads,
+                                int64_t kv_head_stride, int64_t part_head_stride, int64_t skip_row,
+                                const DecodeLens* lens) {
   if (n <= 0 || n_split <= 0 || n_heads < 1 || (lens && n_heads > kDecodeMaxRagged)) { set_last_error("decode partial: empty launch"); return HI_ERR_ARG; }
   static std::once_flag attr_once;      // contexts on different host threads may get here together
   static hipError_t attr_err = hipSuccess;
@@ -301,11 +301,11 @@ hi_status launch_decode_partial(void* stream, const void* q, int G, const void* 
   static const DecodeLens no_lens = {};
   if (lens)
     hipLaunchKernelGGL(decode_partial_kernel<true>, dim3(n_split, n_heads), dim3(256), kDecLdsBytes, (hipStream_t)stream,
-                       (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e,
+                       (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, softmax_scale_log2(q_prescaled),
                        kv_head_stride, part_head_stride, skip_row, *lens);
   else
     hipLaunchKernelGGL(decode_partial_kernel<false>, dim3(n_split, n_heads), dim3(256), kDecLdsBytes, (hipStream_t)stream,
-                       (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, kScaleLog2e,
+                       (const uint16_t*)q, G, (const char*)k, (const char*)v, n, (float*)partials, part0, softmax_scale_log2(q_prescaled),
                        kv_head_stride, part_head_stride, skip_row, no_lens);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("decode_partial launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }
@@ -314,13 +314,13 @@ hi_status launch_decode_partial(void* stream, const void* q, int G, const void* 
 
 hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
                                 const void* partials, int n_part, void* out, int out_fp32, void* k_append,
-                                void* v_append, int n_heads, int64_t part_head_stride, int64_t append_head_stride,
-                                const DecodeLens* lens) {
+                                void* v_append, bool q_prescaled, int n_heads, int64_t part_head_stride,
+                                int64_t append_head_stride, const DecodeLens* lens) {
   static const DecodeLens no_lens = {};
   if (lens && n_heads > kDecodeMaxRagged) { set_last_error("decode combine: too many heads of their own length"); return HI_ERR_ARG; }
   hipLaunchKernelGGL(decode_combine_kernel, dim3(G, kHeadDim / kCombDims, n_heads), dim3(256), 0, (hipStream_t)stream,
                      (const uint16_t*)q, G, (const uint16_t*)k_new, (const uint16_t*)v_new, (const float*)partials,
-                     n_part, out, out_fp32, kScaleLog2e, (uint16_t*)k_append, (uint16_t*)v_append, part_head_stride,
+                     n_part, out, out_fp32, softmax_scale_log2(q_prescaled), (uint16_t*)k_append, (uint16_t*)v_append, part_head_stride,
                      append_head_stride, lens ? 1 : 0, lens ? *lens : no_lens);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { set_last_error("decode_combine launch: %s", hipGetErrorString(e)); return HI_ERR_HIP; }

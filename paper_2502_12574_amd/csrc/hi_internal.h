@@ -120,13 +120,18 @@ struct PrefillSegment {
 
 // One launch of the prefill kernel over up to two KV segments.  first: start from an empty softmax state
 // instead of loading the carry; last: normalise and write `out` instead of storing the carry.
-// variant: as at prefill_launch_shape; every launch of one unit must use the same variant (the carry layouts differ).
+// variant: as at prefill_launch_shape (+ 32: the queries are pre-scaled, see softmax_scale_log2); every launch of one
+// unit must use the same variant (the carry layouts differ).
 // carry_bytes: size of the carry buffer (checked against what the launch will use; -1: not checked).
 // n_heads > 1: one launch over a group of KV heads; q is [n_heads][G][chunk_len][128], out likewise, the causal
 // segment's rows [n_heads][chunk_len][128], the other segment's heads head_stride bytes apart.
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& a,
                          const PrefillSegment& b, int first, int last, void* carry, void* out, int out_fp32,
                          int variant, int n_heads = 1, int64_t carry_bytes = -1);
+
+// The factor between a query-key dot product and the base-2 exponent of its softmax weight: log2(e) / sqrt(128) for
+// the q of Eq. 3, 1 for queries that already carry that factor (hi_problem.q_prescaled).
+inline float softmax_scale_log2(bool q_prescaled) { return q_prescaled ? 1.0f : 1.4426950408889634f / 11.313708498984761f; }
 
 // rows per head of a decode launch whose heads differ in length (passed to the kernels by value)
 constexpr int kDecodeMaxRagged = 64;
@@ -137,7 +142,8 @@ struct DecodeLens { int64_t n[kDecodeMaxRagged]; };
 // part_head_stride floats apart.
 // skip_row >= 0: that row takes no part (the row of a streaming head's store that the token replaces).
 hi_status launch_decode_partial(void* stream, const void* q, int G, const void* k, const void* v, int64_t n,
-                                int n_split, void* partials, int part0, int n_heads = 1, int64_t kv_head_stride = 0,
+                                int n_split, void* partials, int part0, bool q_prescaled, int n_heads = 1,
+                                int64_t kv_head_stride = 0,
                                 int64_t part_head_stride = 0, int64_t skip_row = -1, const DecodeLens* lens = nullptr);
 // lens != null: head h has lens->n[h] rows instead of n (n = the largest of them), and launch_decode_combine appends
 // head h's row at row lens->n[h] behind k_append / v_append (which then point at row 0 of the first head)
@@ -146,7 +152,7 @@ hi_status launch_decode_partial(void* stream, const void* q, int G, const void* 
 // apart).  n_heads > 1: q and out are [n_heads][G][128], k_new / v_new [n_heads][128].
 hi_status launch_decode_combine(void* stream, const void* q, int G, const void* k_new, const void* v_new,
                                 const void* partials, int n_part, void* out, int out_fp32, void* k_append,
-                                void* v_append, int n_heads = 1, int64_t part_head_stride = 0,
+                                void* v_append, bool q_prescaled, int n_heads = 1, int64_t part_head_stride = 0,
                                 int64_t append_head_stride = 0, const DecodeLens* lens = nullptr);
 
 // Streaming heads (Appendix E): a head that keeps n_sink initial and n_recent recent tokens in an HBM store of
@@ -157,7 +163,8 @@ constexpr int64_t kStreamMaxRows = 1 << 22;
 // store, the chunk's own rows from k_new / v_new.  Layouts of q, k_new, v_new, out as in launch_prefill.
 hi_status launch_prefill_window(void* stream, const void* q, int G, int chunk_len, const void* store_k,
                                 const void* store_v, int64_t store_head_stride, const void* k_new, const void* v_new,
-                                int64_t past_len, int n_sink, int n_recent, void* out, int out_fp32, int n_heads);
+                                int64_t past_len, int n_sink, int n_recent, void* out, int out_fp32, int n_heads,
+                                bool q_prescaled);
 // The chunk's rows enter the store (run it after the chunk's attention, on the same stream).
 hi_status launch_stream_store_update(void* stream, const void* k_new, const void* v_new, int chunk_len,
                                      int64_t past_len, int n_sink, int n_recent, void* store_k, void* store_v,

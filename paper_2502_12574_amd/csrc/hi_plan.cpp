@@ -21,7 +21,8 @@ hi_status validate_problem(const hi_problem* p) {
   if (!p) { set_last_error("problem is null"); return HI_ERR_ARG; }
   if (p->n_layers < 1 || p->n_kv_heads < 1 || p->max_context < 1 || p->chunk < 1 ||
       p->gpu_kv_budget_heads < 1 || p->n_compute_units < 0 || p->host_mem_limit_bytes < 0 ||
-      p->link_GBps < 0 || p->hbm_GBps < 0 || p->mfma_TFLOPs < 0 || (p->out_fp32 != 0 && p->out_fp32 != 1)) {
+      p->link_GBps < 0 || p->hbm_GBps < 0 || p->mfma_TFLOPs < 0 || (p->out_fp32 != 0 && p->out_fp32 != 1) ||
+      (p->q_prescaled != 0 && p->q_prescaled != 1)) {
     set_last_error("problem field out of range");
     return HI_ERR_ARG;
   }

@@ -1086,12 +1086,16 @@ __device__ __forceinline__ void pf16_softmax(f32x16 (&s)[2], PfState16& st, floa
 // accumulators started from cinit = -m), p = 2^(c s); the reference only moves when a lane's share of a row sum says
 // it must (see pf_softmax_fast).  The scores are scaled in place first, so that the 32 multiplications and the 32
 // exponentials are independent instructions (with a shared temporary they formed one dependent chain).
+// PRESCALED: the queries carry the softmax scale already (c is 1): the scores are exponents as they leave the matrix pipe.
+template <bool PRESCALED>
 __device__ __forceinline__ void pf16_softmax_fast(f32x16 (&s)[2], PfState16& st, float c, f32x4 (&cinit)[2],
                                                   bf16x8 (&pb)[2][2]) {
+  if (!PRESCALED) {
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s[j][r] *= c;
+      for (int r = 0; r < 16; ++r) s[j][r] *= c;
+  }
   float ls[2];
   auto probs = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -1170,6 +1174,7 @@ __device__ __forceinline__ void pf16_write_row(void* out, int out_fp32, int C, i
   }
 }
 
+template <bool PRESCALED>
 __global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char lds_dyn[];
   lds_char* lds = (lds_char*)lds_dyn;
@@ -1395,7 +1400,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
       __builtin_amdgcn_s_setprio(0);
       pd16_preread(S * kPfTileBytes, lc, pre);
       __builtin_amdgcn_sched_barrier(0);
-      pf16_softmax_fast(sc, st, c, cinit, pb);
+      pf16_softmax_fast<PRESCALED>(sc, st, c, cinit, pb);
       wait_vmcnt<4>();
       phase_barrier();
       kp += kPfTileBytes;
@@ -1824,12 +1829,11 @@ __global__ __launch_bounds__(256) void stream_store_update_kernel(const char* __
   *(uint4*)d = *(const uint4*)src;
 }
 
-static const float kScaleLog2e = 1.4426950408889634f / 11.313708498984761f;   // log2(e) / sqrt(128)
 
 hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, const PrefillSegment& sa,
                          const PrefillSegment& sb, int first, int last, void* carry, void* out, int out_fp32,
                          int variant, int n_heads, int64_t carry_bytes) {
-  if (n_heads < 1 || variant == 2) { set_last_error("prefill launch: head group or variant"); return HI_ERR_UNSUPPORTED; }
+  if (n_heads < 1 || (variant & 3) == 2) { set_last_error("prefill launch: head group or variant"); return HI_ERR_UNSUPPORTED; }
   if (chunk_len < 1 || !(G == 1 || G == 2 || G == 4 || G == 8)) { set_last_error("prefill launch: bad shape"); return HI_ERR_ARG; }
   if (sa.causal || (sb.n > 0 && !sb.causal)) { set_last_error("prefill launch: segment order"); return HI_ERR_ARG; }
   if (sa.n + sb.n <= 0) { set_last_error("prefill launch: no rows"); return HI_ERR_ARG; }
@@ -1840,7 +1844,8 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   a.carry = (float*)carry;
   a.out = out;
   a.G = G; a.C = chunk_len; a.first = first; a.last = last; a.out_fp32 = out_fp32;
-  a.c = kScaleLog2e;
+  const bool q_prescaled = (variant & 32) != 0;
+  a.c = softmax_scale_log2(q_prescaled);
   const int strip = prefill_strip(G);
   const int gy = prefill_grid_y(G);
   a.gy = gy;
@@ -1861,14 +1866,18 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
       attr_err = hipFuncSetAttribute((const void*)prefill_kernel_deep, hipFuncAttributeMaxDynamicSharedMemorySize,
                                      kPdLdsBytes);
       if (attr_err == hipSuccess)
-        attr_err = hipFuncSetAttribute((const void*)prefill_kernel_deep16, hipFuncAttributeMaxDynamicSharedMemorySize,
+        attr_err = hipFuncSetAttribute((const void*)prefill_kernel_deep16<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kPdLdsBytes);
+      if (attr_err == hipSuccess)
+        attr_err = hipFuncSetAttribute((const void*)prefill_kernel_deep16<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        kPdLdsBytes);
     });
     if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
     dim3 grid((unsigned)(pl.nbk * pl.split), (unsigned)(gy * n_heads));
     const bool mfma32 = (variant & 16) != 0;        // the 32x32x16 form of the kernel (its state images differ)
     if (mfma32) hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL(prefill_kernel_deep16, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
+    else if (q_prescaled) hipLaunchKernelGGL(prefill_kernel_deep16<true>, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(prefill_kernel_deep16<false>, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
     if (pl.merge) {
       hipError_t e1 = hipGetLastError();
       if (e1 != hipSuccess) { set_last_error("prefill launch: %s", hipGetErrorString(e1)); return HI_ERR_HIP; }
@@ -1886,7 +1895,8 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
 
 hi_status launch_prefill_window(void* stream, const void* q, int G, int chunk_len, const void* store_k,
                                 const void* store_v, int64_t store_head_stride, const void* k_new, const void* v_new,
-                                int64_t past_len, int n_sink, int n_recent, void* out, int out_fp32, int n_heads) {
+                                int64_t past_len, int n_sink, int n_recent, void* out, int out_fp32, int n_heads,
+                                bool q_prescaled) {
   if (n_heads < 1 || chunk_len < 1 || !(G == 1 || G == 2 || G == 4 || G == 8) || past_len < 0 || n_sink < 0 ||
       n_recent < 1 || (int64_t)n_sink + n_recent > kStreamMaxRows) {
     set_last_error("windowed prefill launch: bad shape");
@@ -1899,7 +1909,7 @@ hi_status launch_prefill_window(void* stream, const void* q, int G, int chunk_le
   a.out = out;
   a.G = G; a.C = chunk_len; a.out_fp32 = out_fp32;
   a.gy = prefill_grid_y(G);
-  a.c = kScaleLog2e;
+  a.c = softmax_scale_log2(q_prescaled);
   a.n_sink = n_sink; a.n_recent = n_recent;
   const int64_t P = past_len;
   const int64_t t0 = P - n_recent + 1 > n_sink ? P - n_recent + 1 : n_sink;

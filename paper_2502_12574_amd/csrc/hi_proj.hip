@@ -54,6 +54,7 @@ struct ProjArgs {
   void* q_out; void* k_out; void* v_out;   // [Hq][C][128], [Hkv][C][128], [Hkv][C][128]
   int n_q_heads, n_kv_heads;
   const float2* rope;                 // [16][C][4] (cos, sin) of pair 4 g + e at the chunk's token t: [g][t][e]; null: no rotation
+  float q_scale;                      // kPjQkv: factor on the query heads' outputs (after the rotation, before rounding)
   // kPjOut: A = W_o [D][Hq * 128], B = attention output [Hq][C][128]
   void* y; int64_t y_stride;          // [C][y_stride] elements
 };
@@ -251,6 +252,7 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
     char* base = nullptr;        // where feature 0 of this wavefront's 128 A-rows goes, for token 0
     int64_t row_bytes = 0;       // bytes from one token's output row to the next
     bool rotate = false;
+    float osc = 1.0f;            // factor on this wavefront's outputs (the query heads' q_scale; 1 is exact)
     int n_valid = 128;           // valid A-rows of the wavefront
     const int esz = p.out_fp32 ? 4 : 2;
     if (MODE == kPjQkv) {
@@ -261,6 +263,7 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
       else { base = (char*)p.v_out; hh = head - p.n_q_heads - p.n_kv_heads; }
       if (head >= p.n_q_heads + 2 * p.n_kv_heads) n_valid = 0;
       rotate = p.rope != nullptr && head < p.n_q_heads + p.n_kv_heads;
+      if (head < p.n_q_heads) osc = p.q_scale;
       base += (int64_t)hh * p.b_rows * kHeadDim * esz;
       row_bytes = (int64_t)kHeadDim * esz;
     } else {
@@ -324,8 +327,8 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
             for (int e = 0; e < 4; ++e) {
               const float x = lo[4 * rq + e], y = hi[4 * rq + e];
               const float xr = pj_rot_lo(x, y, cv[e], sv[e]), yr = pj_rot_hi(x, y, cv[e], sv[e]);
-              lo[4 * rq + e] = rotate ? xr : x;           // selects, not a branch: V heads keep their values bit for bit
-              hi[4 * rq + e] = rotate ? yr : y;
+              lo[4 * rq + e] = (rotate ? xr : x) * osc;   // selects, not a branch: V heads keep their values bit for bit
+              hi[4 * rq + e] = (rotate ? yr : y) * osc;
             }
           }
           if (ib + 1 < 4) tab_load(ib + 1, ip, tb8);      // the buffer this group has just used: two groups ahead
@@ -367,6 +370,7 @@ __global__ __launch_bounds__(256, 1) void proj_gemm_kernel(ProjArgs p) {
               const float other = half ? acc[ip][ib][r] : acc[ip + 2][ib][r];
               x = half ? pj_rot_hi(other, x, c, sn) : pj_rot_lo(x, other, c, sn);
             }
+            if (MODE == kPjQkv) x *= osc;
             if (f >= n_valid) continue;
             if (p.out_fp32) *(float*)(row + f * 4) = x;
             else *(uint16_t*)(row + f * 2) = float_to_bf16_bits(x);
@@ -414,6 +418,7 @@ struct GemvArgs {
   int mode, out_fp32;
   void* q_out; void* k_out; void* v_out; int n_q_heads, n_kv_heads;   // kPjQkv
   int64_t position; double log2_theta;                                // rotation angle position * 2^(-i/64 * log2_theta); < 0: none
+  float q_scale;                                                      // kPjQkv: factor on the query heads' outputs
   void* y;                                                            // kPjOut
 };
 
@@ -481,6 +486,7 @@ __global__ __launch_bounds__(256) void proj_gemv_kernel(GemvArgs g) {
         lo = sa * c - sb * s;
         hi = sb * c + sa * s;
       }
+      if (head < g.n_q_heads) { lo *= g.q_scale; hi *= g.q_scale; }
       const int64_t at = (int64_t)hh * kHeadDim + i;
       if (g.out_fp32) { ((float*)base)[at] = lo; ((float*)base)[at + 64] = hi; }
       else { ((uint16_t*)base)[at] = float_to_bf16_bits(lo); ((uint16_t*)base)[at + 64] = float_to_bf16_bits(hi); }
@@ -553,7 +559,7 @@ extern "C" hi_status hi_proj_workspace_bytes(int32_t chunk, int64_t* bytes) {
 static hi_status qkv_rope_impl(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model,
                                int32_t n_q_heads, int32_t n_kv_heads, int32_t chunk_len, int64_t past_len,
                                double rope_theta, int32_t out_fp32, void* q_out_dev, void* k_out_dev,
-                               void* v_out_dev, void* workspace_dev) {
+                               void* v_out_dev, void* workspace_dev, float q_scale) {
   if (!x_dev || !w_qkv_dev || !q_out_dev || !k_out_dev || !v_out_dev || (rope_theta > 0 && chunk_len > 1 && !workspace_dev)) {
     set_last_error("qkv projection: null buffer");
     return HI_ERR_ARG;
@@ -563,7 +569,8 @@ static hi_status qkv_rope_impl(void* stream, const void* x_dev, const void* w_qk
     set_last_error("qkv projection: buffers must be 16-byte aligned");
     return HI_ERR_ARG;
   }
-  if (n_q_heads < 1 || n_kv_heads < 1 || chunk_len < 1 || past_len < 0 || rope_theta < 0 || (out_fp32 != 0 && out_fp32 != 1)) {
+  if (n_q_heads < 1 || n_kv_heads < 1 || chunk_len < 1 || past_len < 0 || rope_theta < 0 || (out_fp32 != 0 && out_fp32 != 1) ||
+      !(q_scale > 0.0f) || !(q_scale < 3.0e38f)) {
     set_last_error("qkv projection: bad shape");
     return HI_ERR_ARG;
   }
@@ -582,6 +589,7 @@ static hi_status qkv_rope_impl(void* stream, const void* x_dev, const void* w_qk
     g.n_q_heads = n_q_heads; g.n_kv_heads = n_kv_heads;
     g.position = past_len;
     g.log2_theta = rope_theta > 0 ? log2(rope_theta) : -1.0;
+    g.q_scale = q_scale;
     return gemv_launch(stream, g);
   }
   ProjArgs p = {};
@@ -593,6 +601,7 @@ static hi_status qkv_rope_impl(void* stream, const void* x_dev, const void* w_qk
   p.q_out = q_out_dev; p.k_out = k_out_dev; p.v_out = v_out_dev;
   p.n_q_heads = n_q_heads; p.n_kv_heads = n_kv_heads;
   p.rope = nullptr;
+  p.q_scale = q_scale;
   if (rope_theta > 0) {
     RopeFreqs f;
     for (int i = 0; i < 64; ++i) f.inv[i] = pow(rope_theta, -(double)i / 64.0);
@@ -608,9 +617,9 @@ static hi_status qkv_rope_impl(void* stream, const void* x_dev, const void* w_qk
 extern "C" hi_status hi_qkv_rope(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model,
                                  int32_t n_q_heads, int32_t n_kv_heads, int32_t chunk_len, int64_t past_len,
                                  double rope_theta, int32_t out_fp32, void* q_out_dev, void* k_out_dev,
-                                 void* v_out_dev, void* workspace_dev) {
+                                 void* v_out_dev, void* workspace_dev, float q_scale) {
   return qkv_rope_impl(stream, x_dev, w_qkv_dev, d_model, n_q_heads, n_kv_heads, chunk_len, past_len, rope_theta,
-                       out_fp32, q_out_dev, k_out_dev, v_out_dev, workspace_dev);
+                       out_fp32, q_out_dev, k_out_dev, v_out_dev, workspace_dev, q_scale);
 }
 
 // ---- the variant for callers that cannot allocate: the chunk's rotary table lives in a file-scope device array.
@@ -641,7 +650,7 @@ static hi_status qkv_static_scratch(void** out) {
 extern "C" hi_status hi_qkv_rope_static(void* stream, const void* x_dev, const void* w_qkv_dev, int32_t d_model,
                                         int32_t n_q_heads, int32_t n_kv_heads, int32_t chunk_len, int64_t past_len,
                                         double rope_theta, int32_t out_fp32, void* q_out_dev, void* k_out_dev,
-                                        void* v_out_dev) {
+                                        void* v_out_dev, float q_scale) {
   if (chunk_len > kQkvStaticMaxChunk) {
     set_last_error("qkv projection without a workspace: chunk_len %d exceeds the built-in table of %d tokens", chunk_len,
                    kQkvStaticMaxChunk);
@@ -651,7 +660,7 @@ extern "C" hi_status hi_qkv_rope_static(void* stream, const void* x_dev, const v
   HI_PJ_TRY(qkv_static_scratch(&table));
   // the table is rewritten for tokens [0, chunk_len) by every call that rotates: nothing to clear
   return qkv_rope_impl(stream, x_dev, w_qkv_dev, d_model, n_q_heads, n_kv_heads, chunk_len, past_len, rope_theta,
-                       out_fp32, q_out_dev, k_out_dev, v_out_dev, table);
+                       out_fp32, q_out_dev, k_out_dev, v_out_dev, table, q_scale);
 }
 
 extern "C" hi_status hi_out_proj(void* stream, const void* attn_dev, const void* w_o_dev, int32_t n_q_heads,

@@ -18,16 +18,17 @@ class LayerInputs:
     layer stacked: q[chunk][layer] is [H][G][C][d], k/v[chunk][layer] is [H][C][d] (the last chunk may be short), so
     q[chunk][layer][kv_head] is the [G][C][d] operand of a one-head call and a slice of heads that of a group call."""
 
-    def __init__(self, seed, n_layers, n_kv_heads, G, S, C, device, peaked=False, first_layer=0):
+    def __init__(self, seed, n_layers, n_kv_heads, G, S, C, device, peaked=False, first_layer=0, q_scale=1.0):
+        """q_scale: constant folded into the queries (binding.HI_Q_PRESCALE for a Session with q_prescaled)."""
         self.seed, self.L, self.H, self.G, self.S, self.C = seed, n_layers, n_kv_heads, G, S, C
-        self.device, self.peaked, self.first_layer = device, peaked, first_layer
+        self.device, self.peaked, self.first_layer, self.q_scale = device, peaked, first_layer, q_scale
         self.q, self.k, self.v = [], [], []
         for p in range(0, S, C):
             n = min(C, S - p)
             ql, kl, vl = [], [], []
             for l in range(n_layers):
                 lay = first_layer + l
-                ql.append(torch.stack([torch.stack([synth.draw_q(seed, lay, h * G + g, p, n, device=device)
+                ql.append(torch.stack([torch.stack([synth.draw_q(seed, lay, h * G + g, p, n, device=device, scale=q_scale)
                                                     for g in range(G)]) for h in range(n_kv_heads)]))
                 kl.append(torch.stack([synth.draw_k(seed, lay, h, p, n, device=device, peaked=peaked)
                                        for h in range(n_kv_heads)]))
@@ -51,7 +52,8 @@ class LayerInputs:
     def decode_rows(self, pos):
         """q [L][H][G][d], k, v [L][H][d] of the token at absolute position pos (lists over layers of stacked heads)."""
         dev, G = self.device, self.G
-        q = [torch.stack([torch.stack([synth.draw_q(self.seed, self.first_layer + l, h * G + g, pos, 1, device=dev)[0]
+        q = [torch.stack([torch.stack([synth.draw_q(self.seed, self.first_layer + l, h * G + g, pos, 1, device=dev,
+                                                    scale=self.q_scale)[0]
                                        for g in range(G)]) for h in range(self.H)]) for l in range(self.L)]
         k = [torch.stack([synth.draw_k(self.seed, self.first_layer + l, h, pos, 1, device=dev, peaked=self.peaked)[0]
                           for h in range(self.H)]) for l in range(self.L)]

@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--narrow", action="store_true", help="force the 4-wave, 2-stage prefill kernel")
     ap.add_argument("--deep", action="store_true", help="force the 8-wave, 4-stage prefill kernel")
     ap.add_argument("--mfma32", action="store_true", help="the 8-wave kernel in its 32x32x16 MFMA form")
+    ap.add_argument("--q-prescaled", action="store_true",
+                    help="queries that carry the softmax scale (hi_problem.q_prescaled): no multiplication per score")
     ap.add_argument("--zeros", action="store_true",
                     help="all-zero Q, K, V: the same instruction stream with no switching in the multipliers, i.e. the "
                          "kernel's schedule without the board's power limit")
@@ -73,7 +75,8 @@ def main():
     P, C, G, dev = args.past, args.chunk, args.gqa, "cuda:0"
     if args.what == "kvq":
         return kvq(args.rows, args.reps, args.calibrate, dev)
-    ss = Session(1, 1, G, P + C, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0)
+    ss = Session(1, 1, G, P + C, C, mode=hb.HI_MODE_RESIDENT, out_fp32=0, q_prescaled=args.q_prescaled)
+    qs = hb.HI_Q_PRESCALE if args.q_prescaled else 1.0
     flags = hb.HI_FLAG_TIME_KERNELS
     flags |= (hb.HI_FLAG_PREFILL_NARROW if args.narrow else 0) | (hb.HI_FLAG_PREFILL_DEEP if args.deep else 0)
     flags |= hb.HI_FLAG_PREFILL_MFMA32 if args.mfma32 else 0
@@ -85,7 +88,7 @@ def main():
             b = min(P, a + step)
             cv[0, 0, 0, a:b] = synth.draw_k(1, 0, 0, a, b - a, device=dev)
             cv[0, 0, 1, a:b] = synth.draw_v(1, 0, 0, a, b - a, device=dev)
-        Q = torch.stack([synth.draw_q(1, 0, g, P, C, device=dev) for g in range(G)])
+        Q = torch.stack([synth.draw_q(1, 0, g, P, C, device=dev, scale=qs) for g in range(G)])
         K = synth.draw_k(1, 0, 0, P, C, device=dev)
         V = synth.draw_v(1, 0, 0, P, C, device=dev)
         if args.zeros:

@@ -12,7 +12,8 @@ from . import binding as hb
 class Session:
     def __init__(self, n_layers, n_kv_heads, gqa_group, max_context, chunk, mode=hb.HI_MODE_OFFLOAD, out_fp32=1,
                  device="cuda:0", gpu_kv_budget_heads=1, n_compute_units=0, resident_heads=0, streaming_heads=0,
-                 sink_tokens=0, recent_tokens=0, link_kv_bits=0, per_layer_cache=False, progress=None, streaming_mask=None):
+                 sink_tokens=0, recent_tokens=0, link_kv_bits=0, per_layer_cache=False, progress=None, streaming_mask=None,
+                 q_prescaled=False):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the library has no CPU path")
         self.device = torch.device(device)
@@ -22,7 +23,8 @@ class Session:
                                        gpu_kv_budget_heads=gpu_kv_budget_heads, n_compute_units=n_compute_units,
                                        resident_heads=resident_heads, streaming_heads=streaming_heads,
                                        sink_tokens=sink_tokens, recent_tokens=recent_tokens,
-                                       link_kv_bits=link_kv_bits, streaming_mask=streaming_mask)
+                                       link_kv_bits=link_kv_bits, streaming_mask=streaming_mask,
+                                       q_prescaled=int(bool(q_prescaled)))
         # retrieval heads of each layer (the heads that have rows in the cache), in head order
         if streaming_mask is not None:
             self.retrieval = [[h for h in range(n_kv_heads) if not streaming_mask[l][h]] for l in range(n_layers)]

@@ -124,8 +124,13 @@ def draw_keys_peaked(seed: int, layer: int, head: int, tok_start: int, n_tok: in
     return (k.to(torch.float32) * scale[:, None]).to(torch.bfloat16)
 
 
-def draw_q(seed, layer, q_head, tok_start, n_tok, head_dim=128, device="cpu"):
-    return draw(seed, TENSOR_Q, layer, q_head, tok_start, n_tok, head_dim, device)
+def draw_q(seed, layer, q_head, tok_start, n_tok, head_dim=128, device="cpu", scale=1.0):
+    """scale != 1: the drawn rows times `scale`, multiplied in fp32 and rounded to bf16 (queries as a projection
+    that folds a constant into them would emit them)."""
+    q = draw(seed, TENSOR_Q, layer, q_head, tok_start, n_tok, head_dim, device)
+    if scale == 1.0:
+        return q
+    return (q.to(torch.float32) * torch.tensor(scale, dtype=torch.float32, device=q.device)).to(torch.bfloat16)
 
 
 def draw_k(seed, layer, kv_head, tok_start, n_tok, head_dim=128, device="cpu", peaked=False):

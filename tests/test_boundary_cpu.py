@@ -134,6 +134,7 @@ def test_plan_rejects_bad_problems():
         (dict(chunk=0), hb.HI_ERR_ARG),
         (dict(chunk=5000), hb.HI_ERR_ARG),
         (dict(gpu_kv_budget_heads=0), hb.HI_ERR_ARG),
+        (dict(q_prescaled=2), hb.HI_ERR_ARG),
         (dict(max_context=100, chunk=50), hb.HI_ERR_HBM_BUDGET),
         (dict(host_mem_limit_bytes=1 << 20), hb.HI_ERR_HOST_MEM),
     ]

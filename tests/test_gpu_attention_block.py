@@ -21,8 +21,11 @@ def bf16_round(a):
     return synth.to_f64(torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16))
 
 
+@pytest.mark.parametrize("pre", [False, True])
 @pytest.mark.parametrize("mode,T", [(hb.HI_MODE_OFFLOAD, 0), (hb.HI_MODE_OFFLOAD, 2), (hb.HI_MODE_RESIDENT, 1)])
-def test_attention_block_prefill_and_decode(mode, T):
+def test_attention_block_prefill_and_decode(mode, T, pre):
+    """pre: the block folds the softmax scale into the query projection (Session q_prescaled) - the oracle chain then
+    rounds the scaled queries to bf16, as the projection does, and attends with them divided by the constant again."""
     D, Hkv, G, C, S, nd, theta, seed = 512, 4, 2, 256, 600, 4, 500000.0, 9400 + T
     Hq, n_sink, n_recent = Hkv * G, 6, 150
     n_tok = S + nd
@@ -31,7 +34,7 @@ def test_attention_block_prefill_and_decode(mode, T):
     Wo = synth.draw_weight(seed, synth.TENSOR_WO, 0, D, Hq * 128, device=DEV)
     Y = torch.full((n_tok, D), float("nan"), dtype=torch.bfloat16, device=DEV)
     with Session(1, Hkv, G, 1024, C, mode=mode, out_fp32=0, streaming_heads=T, sink_tokens=n_sink,
-                 recent_tokens=n_recent) as ss:
+                 recent_tokens=n_recent, q_prescaled=pre) as ss:
         blk = AttentionBlock(ss, 0, W, Wo, theta)
         for p in range(0, S, C):
             n = min(C, S - p)
@@ -46,7 +49,11 @@ def test_attention_block_prefill_and_decode(mode, T):
     Wf = synth.to_f64(W.cpu())
     Q, K, V = op.qkv_rope(synth.to_f64(X.cpu()), Wf[:Hq * 128], Wf[Hq * 128:(Hq + Hkv) * 128], Wf[(Hq + Hkv) * 128:],
                           np.arange(n_tok), 128, theta)
-    Q, K, V = bf16_round(Q), bf16_round(K), bf16_round(V)
+    if pre:
+        Q = bf16_round(Q * hb.HI_Q_PRESCALE) / hb.HI_Q_PRESCALE
+    else:
+        Q = bf16_round(Q)
+    K, V = bf16_round(K), bf16_round(V)
     A = np.empty((Hq, n_tok, 128))
     for h in range(Hkv):
         if h >= Hkv - T:

@@ -150,12 +150,14 @@ def test_config3_decode_1m_offloaded_and_resident():
 def test_config4_layer_1m_prefill_tail_sampled_rows():
     """One layer of the 1M-token configuration (chunk 16384) in the benchmark's launch configuration.  The cache is
     pre-filled up to the last two chunks, which then run through the library (every unit streams ~1M past rows
-    through the staging ring in 8 slices); sampled rows against the oracle, then two decode steps."""
+    through the staging ring in 8 slices); sampled rows against the oracle, then two decode steps.  As in the
+    benchmark, the queries carry the softmax scale (hi_problem.q_prescaled); the oracle gets them divided by it."""
     seed, S, C, H, G, nd = 20250216, 1 << 20, 16384, 8, 4, 2
+    QS = hb.HI_Q_PRESCALE
     checked = (2,)
     P0 = S - 2 * C
     rng = np.random.default_rng(4)
-    ss = Session(1, H, G, S + nd, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1)
+    ss = Session(1, H, G, S + nd, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, q_prescaled=True)
     fill_host_cache(ss, seed, 0, range(H), P0)
     pos = np.array(sorted({P0, P0 + 1, P0 + 63, P0 + 64, S - C - 1, S - C, S - C + 1, S - 1, S - 2} |
                           set(int(x) for x in rng.integers(P0, S, 24))), dtype=np.int64)
@@ -163,7 +165,7 @@ def test_config4_layer_1m_prefill_tail_sampled_rows():
     with torch.cuda.stream(ss.s_compute):
         for ci, p in enumerate((P0, P0 + C)):
             for h in range(H):
-                q = torch.stack([synth.draw_q(seed, 0, h * G + g, p, C, device=DEV) for g in range(G)])
+                q = torch.stack([synth.draw_q(seed, 0, h * G + g, p, C, device=DEV, scale=QS) for g in range(G)])
                 k = synth.draw_k(seed, 0, h, p, C, device=DEV)
                 v = synth.draw_v(seed, 0, h, p, C, device=DEV)
                 out = torch.empty(G, C, 128, dtype=torch.float32, device=DEV)
@@ -172,7 +174,7 @@ def test_config4_layer_1m_prefill_tail_sampled_rows():
                 if h in checked:
                     sel = [int(x - p) for x in pos if p <= x < p + C]
                     kept[(ci, h)] = out.index_select(1, torch.tensor(sel, device=DEV))
-        inp = driver.LayerInputs(seed, 1, H, G, 64, 64, DEV)
+        inp = driver.LayerInputs(seed, 1, H, G, 64, 64, DEV, q_scale=QS)
         rows = [inp.decode_rows(S + t) for t in range(nd)]
         dec = driver.decode(ss, inp, S, nd, rows=rows)
     ss.sync()
@@ -181,12 +183,12 @@ def test_config4_layer_1m_prefill_tail_sampled_rows():
         K = cpu_f64(synth.TENSOR_K, seed, 0, h, S + nd)
         V = cpu_f64(synth.TENSOR_V, seed, 0, h, S + nd)
         for g in range(G):
-            qrows = synth.to_f64(torch.cat([synth.draw_q(seed, 0, h * G + g, int(p), 1) for p in pos]))
+            qrows = synth.to_f64(torch.cat([synth.draw_q(seed, 0, h * G + g, int(p), 1, scale=QS) for p in pos])) / QS
             ref = oa.attn_rows(qrows, K, V, pos)
             got = torch.cat([kept[(0, h)][g], kept[(1, h)][g]])
             print("config 4 head", h, g, check_rows(got, ref, f"cfg4 kv head {h} q head {g}"))
         for t in range(nd):
-            q = np.stack([synth.to_f64(synth.draw_q(seed, 0, h * G + g, S + t, 1))[0] for g in range(G)])
+            q = np.stack([synth.to_f64(synth.draw_q(seed, 0, h * G + g, S + t, 1, scale=QS))[0] for g in range(G)]) / QS
             ref = oa.attn_rows(q, K, V, np.full(G, S + t))
             for g in range(G):
                 check_rows(dec[t][0, h, g:g + 1], ref[g:g + 1], f"cfg4 decode head {h} step {t} q {g}")

@@ -46,8 +46,9 @@ def draw_case(rng):
                         hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_MFMA32,
                         hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_MFMA32,
                         hb.HI_FLAG_PREFILL_NARROW])
+    pre = rng.choice([False, False, True])       # queries that carry the softmax scale (hi_problem.q_prescaled)
     return dict(G=G, H=H, T=T, R=R, mode=mode, C=C, S=S, nd=nd, n_sink=n_sink, n_recent=n_recent, group=group,
-                flags=flags)
+                flags=flags, pre=pre)
 
 
 @pytest.mark.parametrize("case_id", range(int(os.environ.get("HI_TEST_RANDOM_CASES", "24"))))
@@ -69,7 +70,8 @@ def test_random_shape(case_id):
         calls.append((h, nh))
         h += nh
     with Session(1, H, G, max_ctx, C, mode=c["mode"], out_fp32=1, gpu_kv_budget_heads=R + 1, resident_heads=R,
-                 streaming_heads=T, sink_tokens=n_sink if T else 0, recent_tokens=n_recent if T else 0) as ss:
+                 streaming_heads=T, sink_tokens=n_sink if T else 0, recent_tokens=n_recent if T else 0,
+                 q_prescaled=c["pre"]) as ss:
         hb.hi_ctx_set_flags(ss.ctx, c["flags"])
         ss.kv.view(torch.int16).fill_(0x7FC1)
         if ss.staging is not None:
@@ -77,7 +79,9 @@ def test_random_shape(case_id):
         pre = {h: [] for h in range(H)}
         dec = {h: [] for h in range(H)}
         with torch.cuda.stream(ss.s_compute):
-            Q = {h: torch.stack([synth.draw_q(seed, 0, h * G + g, 0, n_tok, device=dev) for g in range(G)]) for h in range(H)}
+            qs = hb.HI_Q_PRESCALE if c["pre"] else 1.0
+            Q = {h: torch.stack([synth.draw_q(seed, 0, h * G + g, 0, n_tok, device=dev, scale=qs) for g in range(G)])
+                 for h in range(H)}
             K = {h: synth.draw_k(seed, 0, h, 0, n_tok, device=dev) for h in range(H)}
             V = {h: synth.draw_v(seed, 0, h, 0, n_tok, device=dev) for h in range(H)}
             p = 0
@@ -104,7 +108,7 @@ def test_random_shape(case_id):
                         dec[h].append(out[i])
         ss.sync()
     for h in range(H):
-        q, k, v = synth.to_f64(Q[h].cpu()), synth.to_f64(K[h].cpu()), synth.to_f64(V[h].cpu())
+        q, k, v = synth.to_f64(Q[h].cpu()) / qs, synth.to_f64(K[h].cpu()), synth.to_f64(V[h].cpu())
         ref = os_.attn_head_streaming(q, k, v, 0, n_sink, n_recent) if h >= n_ret else oa.attn_head(q, k, v)
         got = torch.cat(pre[h], dim=1).cpu()
         for g in range(G):
