@@ -871,11 +871,12 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// The 8-wave kernel on the 16x16x32 bf16 MFMA.  Same tiles, LDS rings, alternating schedule, pass loop and state
-// images as prefill_kernel_deep; what differs is the matrix instruction and with it the register layouts.  Measured
-// on this part, a register-only loop of v_mfma_f32_16x16x32_bf16 on random operands sustains 2.10 PFLOP/s under the
-// board's power limit where v_mfma_f32_32x32x16_bf16 sustains 1.84: the smaller accumulator tile moves half as many
-// accumulator registers per flop, and the kernel runs against that limit.
+// The 8-wave kernel on the 16x16x32 bf16 MFMA.  Same tiles, LDS rings, alternating schedule, barrier protocol, pass
+// loop and work partition as prefill_kernel_deep; what differs is the matrix instruction and with it the register
+// layouts (and so the layout of a state image, which has a merge kernel of its own).  Measured on this part, a
+// register-only loop of v_mfma_f32_16x16x32_bf16 on random operands sustains 2.10 PFLOP/s under the board's power limit
+// where v_mfma_f32_32x32x16_bf16 sustains 1.84: less energy per flop, and the kernel runs against that limit.
+// PRESCALED: the queries carry the softmax scale (a.c is 1), and the steady-state softmax has no multiplication.
 //   * A wavefront still owns 32 query rows of one query head, now as two blocks of 16 (qb = 0, 1): lane = (query
 //     l % 16 of each block, g = l / 16).  S^T = K Q^T per 16-key block kb: register r of s[kb][qb] is key row
 //     16 kb + 4 g + r.  A K operand read (16 keys x 32 dims) feeds the MFMAs of both query blocks.
