@@ -6,6 +6,7 @@ import os
 import re
 import subprocess
 
+import numpy as np
 import pytest
 
 from oracle import memory_model as mm
@@ -216,3 +217,16 @@ def test_plan_four_bit_link_rows():
     for bits in (1, 8, -4, 3):
         st, _ = hb.hi_offload_plan(hb.make_problem(**base, link_kv_bits=bits), check=False)
         assert st == hb.HI_ERR_ARG, bits
+
+
+def test_prescale_constant_turns_the_softmax_of_eq3_into_powers_of_two():
+    """HI_Q_PRESCALE is the constant with which exp(q.k / sqrt(d_k)) = 2^(q'.k) for q' = HI_Q_PRESCALE q: checked
+    against the oracle's softmax weights (Eq. 3), and the header's value against the binding's."""
+    from oracle import attention as oa
+    rng = np.random.default_rng(5)
+    q, K = rng.standard_normal(128), rng.standard_normal((37, 128))
+    w = oa.softmax_weights(q, K, 37)
+    e = np.exp2(K @ (hb.HI_Q_PRESCALE * q))
+    assert np.abs(w - e / e.sum()).max() < 1e-14
+    header = open(os.path.join(ROOT, "include", "headinfer.h")).read()
+    assert "#define HI_Q_PRESCALE %.17gf" % hb.HI_Q_PRESCALE in header
