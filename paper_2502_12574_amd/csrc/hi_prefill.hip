@@ -887,7 +887,7 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep(PrefillArgs a) {
 //   * A lane serves two query rows, so it carries two running references and two shares of the row sums.
 //   * V tiles take one more swizzle bit than in the other kernels (rows 4 apart are read by neighbouring 16-lane
 //     groups of one transpose read and must not share banks).
-constexpr int kCarryFloats16 = 68;     // 64 O^T accumulators + two running maxima + two row-sum shares
+static_assert(kCarryFloatsPerLane >= 68, "a state image holds 64 O^T accumulators, two running maxima and two row-sum shares per lane");
 
 __device__ __forceinline__ int swz_v16(int row) { return swz_v(row) ^ (((row >> 2) & 1) << 1); }
 
