@@ -458,7 +458,7 @@ def main():
         # recent tokens in HBM) on the same layer, and the projections either side of the attention calls
         from paper_2502_12574_amd import layer_bench, proj_bench
         torch.cuda.empty_cache()
-        sp = layer_bench.run(S, C, HKV // 2, 128, 512, 8, HKV // 2, heads_per_call=hpc)
+        sp = layer_bench.run(S, C, HKV // 2, 128, 512, 8, HKV // 2, heads_per_call=hpc, q_prescaled=Q_PRESCALED)
         sp["prefill_speedup_vs_all_retrieval"] = prefill_s / sp["prefill_s"]
         if nd:
             sp["decode_speedup_vs_all_retrieval"] = decode_ms_tok / sp["decode_ms_per_token"]
@@ -468,7 +468,7 @@ def main():
         # the same layer with 4-bit rows on the host link (every head offloaded): the link-bound decode should follow
         # the bytes per row, the prefill should not change
         torch.cuda.empty_cache()
-        lk = layer_bench.run(S, C, 0, 0, 0, 8, 1, link_kv_bits=4, heads_per_call=hpc)
+        lk = layer_bench.run(S, C, 0, 0, 0, 8, 1, link_kv_bits=4, heads_per_call=hpc, q_prescaled=Q_PRESCALED)
         lk["prefill_speedup_vs_bf16_rows"] = prefill_s / lk["prefill_s"]
         if nd:
             lk["decode_speedup_vs_bf16_rows"] = decode_ms_tok / lk["decode_ms_per_token"]

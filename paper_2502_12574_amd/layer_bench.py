@@ -28,16 +28,16 @@ H, G, D = 8, 4, 128
 
 
 def run(S, C, T=0, n_sink=0, n_recent=0, n_dec=8, stream_group=1, link_kv_bits=0, heads_per_call=1, resident_heads=0,
-        mode=hb.HI_MODE_OFFLOAD, decode_only=False):
+        mode=hb.HI_MODE_OFFLOAD, decode_only=False, q_prescaled=False):
     """One layer: T streaming heads (the last T), the others retrieval heads called heads_per_call at a time."""
     dev = "cuda:0"
     with Session(1, H, G, S + n_dec, C, mode=mode, out_fp32=0, streaming_heads=T, sink_tokens=n_sink,
                  recent_tokens=n_recent, link_kv_bits=link_kv_bits, gpu_kv_budget_heads=resident_heads + 1,
-                 resident_heads=resident_heads) as ss:
+                 resident_heads=resident_heads, q_prescaled=q_prescaled) as ss:
         if mode == hb.HI_MODE_OFFLOAD and heads_per_call * 64 > ss.plan.slice_tokens:
             return None                 # a staging slice cannot hold 64 rows of every head of the group
         gen = torch.Generator(device=dev).manual_seed(1)
-        q = torch.randn(H, G, C, D, device=dev, generator=gen).to(torch.bfloat16)
+        q = (torch.randn(H, G, C, D, device=dev, generator=gen) * (hb.HI_Q_PRESCALE if q_prescaled else 1.0)).to(torch.bfloat16)
         k = torch.randn(H, C, D, device=dev, generator=gen).to(torch.bfloat16)
         v = torch.randn(H, C, D, device=dev, generator=gen).to(torch.bfloat16)
         out = torch.empty(H, G, C, D, dtype=torch.bfloat16, device=dev)
@@ -138,6 +138,7 @@ def main():
     ap.add_argument("--resident-heads", default="0")
     ap.add_argument("--resident", action="store_true")
     ap.add_argument("--decode-only", action="store_true")
+    ap.add_argument("--q-prescaled", action="store_true", help="queries that carry the softmax scale")
     a = ap.parse_args()
     if not torch.cuda.is_available():
         raise SystemExit("a GPU is required")
@@ -150,7 +151,8 @@ def main():
                 for hpc in ints(a.heads_per_call):
                     for rh in ints(a.resident_heads):
                         r = run(S, min(S, a.chunk), T, a.sink if T else 0, a.recent if T else 0, a.decode_tokens,
-                                max(1, a.stream_group), 0 if bits == 16 else bits, hpc, rh, mode, a.decode_only)
+                                max(1, a.stream_group), 0 if bits == 16 else bits, hpc, rh, mode, a.decode_only,
+                                a.q_prescaled)
                         if r is None:
                             print(json.dumps(dict(context=S, heads_per_call=hpc, skipped="slice too short")), flush=True)
                             continue
