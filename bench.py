@@ -37,8 +37,14 @@ PEAK_LINK_GBPS = 64.0         # PCIe Gen5 x16, one direction
 # holds it, where it is stored next to the hash of the kernel source it was measured on: a changed kernel or another
 # shape gives null instead of a stale number.  The resident decode launch reads each K/V byte once (measured).
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "prefill_kernel_deep_unit_resident_pmc.md")
-KERNEL_SOURCE = os.path.join(ROOT, "paper_2502_12574_amd", "csrc", "hi_prefill.hip")
+KERNEL_SOURCES = [os.path.join(ROOT, "paper_2502_12574_amd", "csrc", f) for f in ("hi_prefill.hip", "hi_prefill_wide.inc")]
 DECODE_TRAFFIC_PER_ROW = 512.0
+
+
+def prefill_kernel_name():
+    if EXTRA_FLAGS & hb.HI_FLAG_PREFILL_MFMA32:
+        return "prefill_kernel_deep"
+    return "prefill_kernel_deep16" if EXTRA_FLAGS & hb.HI_FLAG_PREFILL_8WAVE else "prefill_kernel_wide"
 
 
 def prefill_traffic_per_launch(S, C):
@@ -47,7 +53,7 @@ def prefill_traffic_per_launch(S, C):
     import re
     try:
         # fingerprint of the code, not of the text: // comments and white space do not count
-        code = re.sub(r"//[^\n]*", "", open(KERNEL_SOURCE, encoding="utf-8").read())
+        code = re.sub(r"//[^\n]*", "", "".join(open(f, encoding="utf-8").read() for f in KERNEL_SOURCES))
         sha = hashlib.sha256(re.sub(r"\s+", " ", code).encode()).hexdigest()[:16]
         for line in open(TRAFFIC_PROFILE):
             m = re.match(r"\s*bench-traffic: context=(\d+) chunk=(\d+) source_sha256=(\w+) bytes_per_launch=(\d+)", line)
@@ -219,7 +225,7 @@ def run_stack(args):
         "peak_staging_bytes": max(st.peak_staging_bytes, sd.peak_staging_bytes), "one_head_bytes": ss.plan.host_bytes_per_head,
         "bytes_h2d_prefill": st.bytes_h2d, "bytes_d2h_prefill": st.bytes_d2h,
         "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS, "traffic": None, "kernel": "prefill_kernel_deep" if EXTRA_FLAGS & hb.HI_FLAG_PREFILL_MFMA32 else "prefill_kernel_deep16",
+                     "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS, "traffic": None, "kernel": prefill_kernel_name(),
                      "launches_per_step": st.n_prefill_kernels, "avg_launch_ms": st.prefill_kernel_ms / max(st.n_prefill_kernels, 1),
                      "wall_TFLOPs": flops / (t_pre / L) / 1e12,
                      "note": "wall time includes the projections of every chunk and layer (about 1.2 % of a layer)"},
@@ -254,6 +260,7 @@ def main():
     ap.add_argument("--no-q-prescale", action="store_true", help="hand the attention calls plain queries (the q of Eq. 3) "
                     "instead of queries that carry the softmax scale; one more multiplication per score in the kernels")
     ap.add_argument("--mfma32", action="store_true", help="the 8-wave prefill kernel in its 32x32x16 MFMA form (A/B runs)")
+    ap.add_argument("--eight-wave", action="store_true", help="the 16x16x32 prefill kernel with 8 wavefronts of 32 query rows (A/B runs)")
     ap.add_argument("--peaked-keys", action="store_true", help="one key row in ten scaled x4 (peaked softmax rows)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="run the timed steps without the library's HIP events "
                     "around kernels and copies (wall figures only; the roofline object is then empty)")
@@ -266,7 +273,7 @@ def main():
         sys.exit(2)
     global EXTRA_FLAGS, Q_PRESCALED
     Q_PRESCALED = not args.no_q_prescale
-    EXTRA_FLAGS = hb.HI_FLAG_PREFILL_MFMA32 if args.mfma32 else 0
+    EXTRA_FLAGS = (hb.HI_FLAG_PREFILL_MFMA32 if args.mfma32 else 0) | (hb.HI_FLAG_PREFILL_8WAVE if args.eight_wave else 0)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)
@@ -445,7 +452,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": flops / kern_s / 1e12, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / kern_s / 1e12 / PEAK_MFMA_TFLOPS,
                      "traffic": traffic, "traffic_source": traffic_src,
-                     "kernel": "prefill_kernel_deep" if EXTRA_FLAGS & hb.HI_FLAG_PREFILL_MFMA32 else "prefill_kernel_deep16",
+                     "kernel": prefill_kernel_name(),
                      "launches_per_step": n_pre_k / K, "avg_launch_ms": kern_pre_ms / max(n_pre_k, 1),
                      "flops_per_launch": flops * NL / (n_pre_k / K),
                      "wall_TFLOPs": flops / prefill_s / 1e12},

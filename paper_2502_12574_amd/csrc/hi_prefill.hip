@@ -1529,6 +1529,8 @@ __global__ __launch_bounds__(512) void prefill_merge16_kernel(PrefillArgs a) {
   }
 }
 
+#include "hi_prefill_wide.inc"
+
 // One dim block (32 of the 128 output dims) of pf_write_row: register r of o is dim 32*db + 8*(r/4) + 4*hl + r%4.
 __device__ __forceinline__ void pf_write_row_db(void* out, int out_fp32, int C, int g, int i, int hl, int db,
                                                 const f32x16& o, float l) {
@@ -1872,11 +1874,20 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
       if (attr_err == hipSuccess)
         attr_err = hipFuncSetAttribute((const void*)prefill_kernel_deep16<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        kPdLdsBytes);
+      if (attr_err == hipSuccess)
+        attr_err = hipFuncSetAttribute((const void*)prefill_kernel_wide<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kPdLdsBytes);
+      if (attr_err == hipSuccess)
+        attr_err = hipFuncSetAttribute((const void*)prefill_kernel_wide<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kPdLdsBytes);
     });
     if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
     dim3 grid((unsigned)(pl.nbk * pl.split), (unsigned)(gy * n_heads));
     const bool mfma32 = (variant & 16) != 0;        // the 32x32x16 form of the kernel (its state images differ)
+    const bool wide = !mfma32 && (variant & 64) == 0;   // the 4-wave, 64-rows-per-wavefront form of the 16x16x32 kernel
     if (mfma32) hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
+    else if (wide && q_prescaled) hipLaunchKernelGGL(prefill_kernel_wide<true>, grid, dim3(kPwWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
+    else if (wide) hipLaunchKernelGGL(prefill_kernel_wide<false>, grid, dim3(kPwWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
     else if (q_prescaled) hipLaunchKernelGGL(prefill_kernel_deep16<true>, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
     else hipLaunchKernelGGL(prefill_kernel_deep16<false>, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
     if (pl.merge) {

@@ -43,6 +43,8 @@ def draw_case(rng):
     # at which the launcher picks the 8-wave kernels by itself)
     flags = rng.choice([0, 0, hb.HI_FLAG_PREFILL_DEEP, hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED,
                         hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_UNPAIRED,
+                        hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_8WAVE,
+                        hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_8WAVE,
                         hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_MFMA32,
                         hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_MFMA32,
                         hb.HI_FLAG_PREFILL_NARROW])
