@@ -291,7 +291,7 @@ int pf_variant(const hi_ctx* c) {
   return ((c->flags & HI_FLAG_PREFILL_NARROW) ? 1 : (c->flags & HI_FLAG_PREFILL_DEEP) ? 3 : 0) |
          ((c->flags & HI_FLAG_PREFILL_PAIRED) ? 4 : 0) | ((c->flags & HI_FLAG_PREFILL_UNPAIRED) ? 8 : 0) |
          ((c->flags & HI_FLAG_PREFILL_MFMA32) ? 16 : 0) | (c->prob.q_prescaled ? 32 : 0) |
-         ((c->flags & HI_FLAG_PREFILL_8WAVE) ? 64 : 0);
+         ((c->flags & HI_FLAG_PREFILL_8WAVE) ? 64 : 0) | ((c->flags & HI_FLAG_PREFILL_WIDE) ? 128 : 0);
 }
 
 bool q_pre(const hi_ctx* c) { return c->prob.q_prescaled != 0; }
@@ -580,7 +580,7 @@ extern "C" hi_status hi_ctx_set_layer_cache(hi_ctx* c, int32_t layer, void* kv_l
 extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
   if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS | HI_FLAG_PREFILL_NARROW |
                       HI_FLAG_PREFILL_PAIRED | HI_FLAG_PREFILL_DEEP | HI_FLAG_PREFILL_UNPAIRED |
-                      HI_FLAG_INJECT_FAILURE | HI_FLAG_PREFILL_MFMA32 | HI_FLAG_PREFILL_8WAVE))) { set_last_error("bad flags"); return HI_ERR_ARG; }
+                      HI_FLAG_INJECT_FAILURE | HI_FLAG_PREFILL_MFMA32 | HI_FLAG_PREFILL_8WAVE | HI_FLAG_PREFILL_WIDE))) { set_last_error("bad flags"); return HI_ERR_ARG; }
   c->flags = flags;
   return HI_OK;
 }

@@ -39,8 +39,10 @@ inline int prefill_split(int G, int64_t chunk_len, int n_heads = 1) {
 // What one launch of a prefill unit looks like (host side; the kernels derive the rest from these numbers).
 // variant: low two bits 0 = pick the kernel by chunk length, 1 = 4-wave kernel, 3 = 8-wave kernel; + 4: pair deep and
 // shallow blocks in every last launch that has two blocks, + 8: never pair (measurement); + 16: the 8-wave kernel in
-// its 32x32x16 MFMA form instead of the 16x16x32 one; + 64: the 16x16x32 kernel with 8 wavefronts of 32 query rows
-// (prefill_kernel_deep16) instead of 4 wavefronts of 64 (prefill_kernel_wide).
+// its 32x32x16 MFMA form instead of the 16x16x32 one; + 64 / + 128: the 16x16x32 kernel with 8 wavefronts of 32 query rows
+// (prefill_kernel_deep16) / with 4 wavefronts of 64 (prefill_kernel_wide) whatever the launch's length (by default the
+// second for launches of kPrefillWideMinTiles tiles and more).
+constexpr int kPrefillWideMinTiles = 1024;
 constexpr int kPdLanes = 512;                   // lanes of an 8-wave workgroup
 constexpr int kPrefillPairMinTiles = 4;         // pair when it saves the deepest workgroup at least this many tiles
 struct PrefillLaunch {

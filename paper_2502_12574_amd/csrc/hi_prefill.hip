@@ -1884,7 +1884,10 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
     if (attr_err != hipSuccess) { set_last_error("hipFuncSetAttribute: %s", hipGetErrorString(attr_err)); return HI_ERR_HIP; }
     dim3 grid((unsigned)(pl.nbk * pl.split), (unsigned)(gy * n_heads));
     const bool mfma32 = (variant & 16) != 0;        // the 32x32x16 form of the kernel (its state images differ)
-    const bool wide = !mfma32 && (variant & 64) == 0;   // the 4-wave, 64-rows-per-wavefront form of the 16x16x32 kernel
+    // the 4-wave, 64-rows-per-wavefront form of the 16x16x32 kernel: for launches long enough to pay for its slow
+    // straight-line tiles (it gains about 3 % per steady-state tile and loses about 20 tiles' worth at the ends)
+    const bool wide = !mfma32 && ((variant & 128) != 0 ||
+                                  ((variant & 64) == 0 && (sa.n + sb.n) / kPfTileRows >= kPrefillWideMinTiles));
     if (mfma32) hipLaunchKernelGGL(prefill_kernel_deep, grid, dim3(kPdWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
     else if (wide && q_prescaled) hipLaunchKernelGGL(prefill_kernel_wide<true>, grid, dim3(kPwWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);
     else if (wide) hipLaunchKernelGGL(prefill_kernel_wide<false>, grid, dim3(kPwWaves * 64), kPdLdsBytes, (hipStream_t)stream, a);

@@ -66,6 +66,7 @@ def main():
     ap.add_argument("--deep", action="store_true", help="force the 8-wave, 4-stage prefill kernel")
     ap.add_argument("--mfma32", action="store_true", help="the 8-wave kernel in its 32x32x16 MFMA form")
     ap.add_argument("--eight-wave", action="store_true", help="the 16x16x32 kernel with 8 wavefronts of 32 query rows")
+    ap.add_argument("--wide", action="store_true", help="the 16x16x32 kernel with 4 wavefronts of 64 query rows")
     ap.add_argument("--q-prescaled", action="store_true",
                     help="queries that carry the softmax scale (hi_problem.q_prescaled): no multiplication per score")
     ap.add_argument("--zeros", action="store_true",
@@ -82,6 +83,7 @@ def main():
     flags |= (hb.HI_FLAG_PREFILL_NARROW if args.narrow else 0) | (hb.HI_FLAG_PREFILL_DEEP if args.deep else 0)
     flags |= hb.HI_FLAG_PREFILL_MFMA32 if args.mfma32 else 0
     flags |= hb.HI_FLAG_PREFILL_8WAVE if args.eight_wave else 0
+    flags |= hb.HI_FLAG_PREFILL_WIDE if args.wide else 0
     hb.hi_ctx_set_flags(ss.ctx, flags)
     with torch.cuda.stream(ss.s_compute):
         cv = ss.cache_view()

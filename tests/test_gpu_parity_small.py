@@ -126,15 +126,15 @@ def test_prefill_ragged_shapes(G, P, C):
                                    (4, 1000, 129), (1, 77, 200), (2, 130, 95), (8, 200, 70), (8, 0, 40),
                                    (4, 97, 700)])
 @pytest.mark.parametrize("mode", [hb.HI_MODE_RESIDENT, hb.HI_MODE_OFFLOAD])
-@pytest.mark.parametrize("variant", ["deep", "narrow", "paired", "deep8", "paired8", "deep32", "paired32"])
+@pytest.mark.parametrize("variant", ["deep", "narrow", "paired", "wide", "pairedwide", "deep32", "paired32"])
 def test_prefill_other_kernel_variants_ragged_shapes(G, P, C, mode, variant):
     # the 8-wave / 4-stage kernel is normally picked for long chunks and the 4-wave kernel for very short ones;
     # force each of them on small ragged shapes - and the 8-wave kernel with deep and shallow blocks of positions
     # paired (two passes per workgroup, states merged), which is otherwise picked for long chunks only
     flag = {"deep": hb.HI_FLAG_PREFILL_DEEP, "narrow": hb.HI_FLAG_PREFILL_NARROW,
             "paired": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED,
-            "deep8": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_8WAVE,
-            "paired8": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_8WAVE,
+            "wide": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_WIDE,
+            "pairedwide": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_WIDE,
             "deep32": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_MFMA32,
             "paired32": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_MFMA32}[variant]
     out, Q, K, V = one_unit(G, P, C, seed=700 + P + C, mode=mode, flags=flag)
@@ -229,7 +229,7 @@ def test_prefill_group_first_chunk(n_heads, G, P, C, mode):
 
 
 @pytest.mark.parametrize("shape", ["rising", "falling", "spikes", "overflow"])
-@pytest.mark.parametrize("variant", ["deep", "deep8", "deep32", "narrow"])
+@pytest.mark.parametrize("variant", ["deep", "wide", "deep32", "narrow"])
 def test_prefill_running_reference_moves(shape, variant):
     # key magnitudes that keep moving the rows' running maxima: rising along the sequence (the steady-state loop of
     # the 8-wave kernel must rescale in place again and again), falling (later probabilities underflow against an
@@ -248,7 +248,7 @@ def test_prefill_running_reference_moves(shape, variant):
     else:
         sc = torch.ones(P + C)
         sc[torch.tensor([700, 1501, 2302, 3103, 3904])] = 8.0
-    flag = {"deep": hb.HI_FLAG_PREFILL_DEEP, "deep8": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_8WAVE,
+    flag = {"deep": hb.HI_FLAG_PREFILL_DEEP, "wide": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_WIDE,
             "deep32": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_MFMA32, "narrow": hb.HI_FLAG_PREFILL_NARROW}[variant]
     out, Q, K, V = one_unit(G, P, C, seed=5200, flags=flag, k_row_scale=sc)
     ref = oa.attn_head(synth.to_f64(Q), synth.to_f64(K), synth.to_f64(V), past_len=P)

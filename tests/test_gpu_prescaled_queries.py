@@ -57,8 +57,8 @@ def test_chunked_prefill_and_decode(mode):
         check(torch.stack(dec)[:, g], ref[g, S:], f"decode head {g}")
 
 
-FORMS = {"default": 0, "deep": hb.HI_FLAG_PREFILL_DEEP, "deep8": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_8WAVE,
-         "paired8": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_8WAVE, "deep32": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_MFMA32,
+FORMS = {"default": 0, "deep": hb.HI_FLAG_PREFILL_DEEP, "wide": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_WIDE,
+         "pairedwide": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_WIDE, "deep32": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_MFMA32,
          "paired": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED, "narrow": hb.HI_FLAG_PREFILL_NARROW}
 
 

@@ -44,7 +44,8 @@ def draw_case(rng):
     flags = rng.choice([0, 0, hb.HI_FLAG_PREFILL_DEEP, hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED,
                         hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_UNPAIRED,
                         hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_8WAVE,
-                        hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_8WAVE,
+                        hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_WIDE, hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_WIDE,
+                        hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_WIDE,
                         hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_MFMA32,
                         hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_PAIRED | hb.HI_FLAG_PREFILL_MFMA32,
                         hb.HI_FLAG_PREFILL_NARROW])
