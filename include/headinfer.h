@@ -47,7 +47,7 @@ enum { HI_FLAG_SKIP_KERNELS = 1, HI_FLAG_SKIP_COPIES = 2, HI_FLAG_TIME_KERNELS =
        HI_FLAG_PREFILL_MFMA32 = 256 /* the DEEP kernel in its 32x32x16 MFMA form (by default it uses 16x16x32) */,
        HI_FLAG_PREFILL_8WAVE = 512, HI_FLAG_PREFILL_WIDE = 1024 /* the 16x16x32 DEEP kernel has two forms: 8 wavefronts of
           32 query rows, and 4 wavefronts of 64 (half the LDS operand reads per MFMA, but slow first and last tiles); by
-          default each launch takes the second when it sweeps at least 1024 K/V tiles; these flags force one (their
+          default each launch takes the second when it sweeps at least 640 K/V tiles; these flags force one (their
           state images are the same, so a unit's launches may mix them) */,
        HI_FLAG_INJECT_FAILURE = 128 /* test hook: the next unit call fails with HI_ERR_HIP right after its checks, as a
                                        failed launch or copy would; no GPU work is skipped or broken by it */ };

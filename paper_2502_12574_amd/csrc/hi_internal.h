@@ -42,7 +42,7 @@ inline int prefill_split(int G, int64_t chunk_len, int n_heads = 1) {
 // its 32x32x16 MFMA form instead of the 16x16x32 one; + 64 / + 128: the 16x16x32 kernel with 8 wavefronts of 32 query rows
 // (prefill_kernel_deep16) / with 4 wavefronts of 64 (prefill_kernel_wide) whatever the launch's length (by default the
 // second for launches of kPrefillWideMinTiles tiles and more).
-constexpr int kPrefillWideMinTiles = 1024;
+constexpr int kPrefillWideMinTiles = 640;
 constexpr int kPdLanes = 512;                   // lanes of an 8-wave workgroup
 constexpr int kPrefillPairMinTiles = 4;         // pair when it saves the deepest workgroup at least this many tiles
 struct PrefillLaunch {
