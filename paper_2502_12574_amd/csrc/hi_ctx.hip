@@ -581,6 +581,10 @@ extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
   if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS | HI_FLAG_PREFILL_NARROW |
                       HI_FLAG_PREFILL_PAIRED | HI_FLAG_PREFILL_DEEP | HI_FLAG_PREFILL_UNPAIRED |
                       HI_FLAG_INJECT_FAILURE | HI_FLAG_PREFILL_MFMA32 | HI_FLAG_PREFILL_8WAVE | HI_FLAG_PREFILL_WIDE))) { set_last_error("bad flags"); return HI_ERR_ARG; }
+  if ((flags & HI_FLAG_PREFILL_8WAVE) && (flags & HI_FLAG_PREFILL_WIDE)) {
+    set_last_error("HI_FLAG_PREFILL_8WAVE and HI_FLAG_PREFILL_WIDE exclude each other");
+    return HI_ERR_ARG;
+  }
   c->flags = flags;
   return HI_OK;
 }

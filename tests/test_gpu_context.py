@@ -125,6 +125,14 @@ def test_a_failure_after_the_checks_closes_the_context(phase):
         assert np.abs(out2.cpu().double().numpy() - ref[:, C:2 * C]).max() <= 1e-2
 
 
+def test_flag_words_that_make_no_sense_are_refused():
+    with Session(1, 1, 4, 256, 128, mode=hb.HI_MODE_RESIDENT) as ss:
+        both = hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_8WAVE | hb.HI_FLAG_PREFILL_WIDE
+        assert hb.hi_ctx_set_flags(ss.ctx, both, check=False) == hb.HI_ERR_ARG and "exclude" in hb.last_error()
+        assert hb.hi_ctx_set_flags(ss.ctx, 1 << 20, check=False) == hb.HI_ERR_ARG
+        assert hb.hi_ctx_set_flags(ss.ctx, hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_WIDE, check=False) == hb.HI_OK
+
+
 def test_stats_time_the_copies_and_the_exposed_waits():
     seed, H, G, S, C = 7, 2, 4, 4096, 1024
     with Session(1, H, G, S, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=0) as ss:
