@@ -261,6 +261,7 @@ def main():
                     "instead of queries that carry the softmax scale; one more multiplication per score in the kernels")
     ap.add_argument("--mfma32", action="store_true", help="the 8-wave prefill kernel in its 32x32x16 MFMA form (A/B runs)")
     ap.add_argument("--eight-wave", action="store_true", help="the 16x16x32 prefill kernel with 8 wavefronts of 32 query rows in every launch (A/B runs)")
+    ap.add_argument("--single-slices", action="store_true", help="one attention launch per staging slice (A/B runs)")
     ap.add_argument("--wide", action="store_true", help="the 16x16x32 prefill kernel with 4 wavefronts of 64 query rows in every launch (A/B runs)")
     ap.add_argument("--peaked-keys", action="store_true", help="one key row in ten scaled x4 (peaked softmax rows)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="run the timed steps without the library's HIP events "
@@ -274,7 +275,7 @@ def main():
         sys.exit(2)
     global EXTRA_FLAGS, Q_PRESCALED
     Q_PRESCALED = not args.no_q_prescale
-    EXTRA_FLAGS = (hb.HI_FLAG_PREFILL_MFMA32 if args.mfma32 else 0) | (hb.HI_FLAG_PREFILL_8WAVE if args.eight_wave else 0) | (hb.HI_FLAG_PREFILL_WIDE if args.wide else 0)
+    EXTRA_FLAGS = (hb.HI_FLAG_PREFILL_MFMA32 if args.mfma32 else 0) | (hb.HI_FLAG_PREFILL_8WAVE if args.eight_wave else 0) | (hb.HI_FLAG_PREFILL_WIDE if args.wide else 0) | (hb.HI_FLAG_PREFILL_SINGLE_SLICES if args.single_slices else 0)
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
         sys.exit(2)

@@ -49,6 +49,8 @@ enum { HI_FLAG_SKIP_KERNELS = 1, HI_FLAG_SKIP_COPIES = 2, HI_FLAG_TIME_KERNELS =
           32 query rows, and 4 wavefronts of 64 (half the LDS operand reads per MFMA, but slow first and last tiles); by
           default each launch takes the second when it sweeps at least 640 K/V tiles; these flags force one (their
           state images are the same, so a unit's launches may mix them) */,
+       HI_FLAG_PREFILL_SINGLE_SLICES = 2048 /* one attention launch per staging slice, also where the library would hand
+          two short slices to one launch (measurement) */,
        HI_FLAG_INJECT_FAILURE = 128 /* test hook: the next unit call fails with HI_ERR_HIP right after its checks, as a
                                        failed launch or copy would; no GPU work is skipped or broken by it */ };
 

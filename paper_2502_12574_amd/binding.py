@@ -19,7 +19,7 @@ HI_FLAG_SKIP_KERNELS, HI_FLAG_SKIP_COPIES, HI_FLAG_TIME_KERNELS = 1, 2, 4
 HI_FLAG_PREFILL_NARROW, HI_FLAG_PREFILL_PAIRED, HI_FLAG_PREFILL_DEEP, HI_FLAG_PREFILL_UNPAIRED = 8, 16, 32, 64
 HI_FLAG_INJECT_FAILURE = 128
 HI_FLAG_PREFILL_MFMA32 = 256
-HI_FLAG_PREFILL_8WAVE, HI_FLAG_PREFILL_WIDE = 512, 1024
+HI_FLAG_PREFILL_8WAVE, HI_FLAG_PREFILL_WIDE, HI_FLAG_PREFILL_SINGLE_SLICES = 512, 1024, 2048
 HI_Q_PRESCALE = 0.12751743082459868      # log2(e) / sqrt(128): a pre-scaled query is this times the q of Eq. 3
 
 EXPORTS = ("hi_offload_plan", "hi_ctx_create", "hi_ctx_destroy", "hi_ctx_set_layer_cache", "hi_ctx_set_flags", "hi_ctx_set_run_ahead",

@@ -580,7 +580,8 @@ extern "C" hi_status hi_ctx_set_layer_cache(hi_ctx* c, int32_t layer, void* kv_l
 extern "C" hi_status hi_ctx_set_flags(hi_ctx* c, int32_t flags) {
   if (!c || (flags & ~(HI_FLAG_SKIP_KERNELS | HI_FLAG_SKIP_COPIES | HI_FLAG_TIME_KERNELS | HI_FLAG_PREFILL_NARROW |
                       HI_FLAG_PREFILL_PAIRED | HI_FLAG_PREFILL_DEEP | HI_FLAG_PREFILL_UNPAIRED |
-                      HI_FLAG_INJECT_FAILURE | HI_FLAG_PREFILL_MFMA32 | HI_FLAG_PREFILL_8WAVE | HI_FLAG_PREFILL_WIDE))) { set_last_error("bad flags"); return HI_ERR_ARG; }
+                      HI_FLAG_INJECT_FAILURE | HI_FLAG_PREFILL_MFMA32 | HI_FLAG_PREFILL_8WAVE | HI_FLAG_PREFILL_WIDE |
+                      HI_FLAG_PREFILL_SINGLE_SLICES))) { set_last_error("bad flags"); return HI_ERR_ARG; }
   if ((flags & HI_FLAG_PREFILL_8WAVE) && (flags & HI_FLAG_PREFILL_WIDE)) {
     set_last_error("HI_FLAG_PREFILL_8WAVE and HI_FLAG_PREFILL_WIDE exclude each other");
     return HI_ERR_ARG;
@@ -712,19 +713,40 @@ static hi_status prefill_impl(hi_ctx* c, int32_t layer, int32_t kv_head, int32_t
   const int64_t ns = cur.n_slices;
   const int64_t st = rows_of(c, nh);
   if (ns == 0 && run) HI_TRY(launch(PrefillSegment{nullptr, nullptr, 0, 0}, diag, 1, 1));
-  for (int64_t i = 0; i < ns; ++i) {
+  // Short slices go to the kernel two at a time (one launch over two ring slots, the second slot's rows addressed as
+  // a jump inside the past segment): a launch costs a round trip of the softmax state through HBM, a ring to fill
+  // and a tail to drain, about 30 us, which is 7 % of a launch over one 16 384-row slice of two heads.  Two slots are
+  // half the ring, so the copies of the next pair still run under the kernel of this one.
+  const PrefillLaunch shape = prefill_launch_shape(G, chunk_len, nh, pf_variant(c), 1, 1);
+  const bool pairs = shape.deep && !(pf_variant(c) & 16) && c->n_slots >= 4 && st / 64 < kPrefillWideMinTiles &&
+                     !(c->flags & HI_FLAG_PREFILL_SINGLE_SLICES);
+  for (int64_t i = 0; i < ns;) {
     HI_TRY(top_up(c, cur, next));          // guarantees slice i has been fetched
     const int slot = (int)((cur.first_seq + i) % c->n_slots);
+    const int slot2 = (int)((cur.first_seq + i + 1) % c->n_slots);
     int64_t rows = past_len - i * st;
     if (rows > st) rows = st;
+    int64_t rows2 = past_len - (i + 1) * st;
+    if (rows2 > st) rows2 = st;
+    const int64_t jump = (slot_k(c, slot2) - slot_k(c, slot)) - st * kRowBytes;
+    const bool two = pairs && i + 1 < ns && cur.issued >= i + 2 &&
+                     (slot_v(c, slot2, nh) - slot_v(c, slot, nh)) - st * kRowBytes == jump;
     HI_TRY(wait_slice(c, slot));
+    if (two) HI_TRY(wait_slice(c, slot2));
     if (run) {
       HI_TRY(expand_slice(c, slot, rows, nh));
-      const bool is_last = (i == ns - 1);
-      PrefillSegment seg{slot_k(c, slot), slot_v(c, slot, nh), rows, 0, head_pitch(c, nh)};
+      if (two) HI_TRY(expand_slice(c, slot2, rows2, nh));
+      const bool is_last = (i + (two ? 2 : 1) == ns);
+      PrefillSegment seg{slot_k(c, slot), slot_v(c, slot, nh), rows + (two ? rows2 : 0), 0, head_pitch(c, nh)};
+      if (two) {
+        seg.jump_rows = st;
+        seg.jump_bytes = jump;
+      }
       HI_TRY(launch(seg, is_last ? diag : PrefillSegment{nullptr, nullptr, 0, 1}, i == 0, is_last));
     }
     HI_TRY(retire_slice(c, slot));
+    if (two) HI_TRY(retire_slice(c, slot2));
+    i += two ? 2 : 1;
   }
   cur.valid = false;
   hi_ctx::Unit none;

@@ -119,6 +119,11 @@ struct PrefillSegment {
   int64_t n;          // rows
   int causal;         // 1: rows are the chunk's own (row j visible to query i iff j <= i)
   int64_t head_stride = 0;   // bytes from one head's K (V) rows to the next head's, for launches over a head group
+  // A past segment may consist of two pieces (two staging slots in one launch): rows [0, jump_rows) start at k / v,
+  // the rows after them jump_bytes further on than they would in one piece.  jump_rows is a multiple of 64; 0: one
+  // piece.  Only the 16x16x32 8-wave and 4-wave kernels take such a segment.
+  int64_t jump_rows = 0;
+  int64_t jump_bytes = 0;
 };
 
 // One launch of the prefill kernel over up to two KV segments.  first: start from an empty softmax state

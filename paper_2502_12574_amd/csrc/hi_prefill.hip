@@ -49,6 +49,8 @@ struct PrefillArgs {
   int64_t a_head_stride;  // bytes between the heads' rows in the past segment
   int paired;             // 8-wave kernel: deep and shallow blocks of the causal triangle share their tiles
   int nbk;                // 8-wave kernel: blocks of positions per head
+  int a_jump_tile;        // the past segment's tiles from this one on lie a_jump_bytes further on (0: one piece)
+  int64_t a_jump_bytes;
 };
 
 // Group launches: point the arguments at this workgroup's head; returns blockIdx.y within the head.
@@ -1255,8 +1257,13 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
       for (int kk = 0; kk < 4; ++kk) qf[kk][qb] = __builtin_bit_cast(bf16x8, *(const uint4*)(qrow + 32 * kk));
     }
 
-    const char* const ka_p = a.ka + (int64_t)ps.a0 * kPfTileBytes;
-    const char* const va_p = a.va + (int64_t)ps.a0 * kPfTileBytes;
+    // a past segment in two pieces: the pass's tiles from jr on lie a.a_jump_bytes further on
+    int jr = a.a_jump_tile > 0 ? a.a_jump_tile - ps.a0 : 0x7fffffff;
+    const int64_t jump0 = jr <= 0 ? a.a_jump_bytes : 0;        // the whole pass is behind the jump
+    if (jr <= 0) jr = 0x7fffffff;
+    const char* const ka_p = a.ka + (int64_t)ps.a0 * kPfTileBytes + jump0;
+    const char* const va_p = a.va + (int64_t)ps.a0 * kPfTileBytes + jump0;
+    auto a_jump = [&](int t) { return t >= jr ? a.a_jump_bytes : (int64_t)0; };
     int64_t na_p = (int64_t)ps.a1 * kPfTileRows;
     if (na_p > a.na) na_p = a.na;
     na_p -= (int64_t)ps.a0 * kPfTileRows;
@@ -1299,8 +1306,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
       const int64_t left = (in_b ? a.nb : na_p) - row0;
       const int rows = left < kPfTileRows ? (int)left : kPfTileRows;
       const uint32_t slot = lds_base + (uint32_t)(t & (kPdStages - 1)) * kPfTileBytes;
-      if (which == 0) pf16_issue_k((in_b ? a.kb : ka_p) + row0 * kRowBytes, rows, slot, wave, lane, lc);
-      else pf16_issue_v((in_b ? a.vb : va_p) + row0 * kRowBytes, rows, slot + kPdVRing, wave, lane, lc);
+      if (which == 0) pf16_issue_k((in_b ? a.kb : ka_p + a_jump(t)) + row0 * kRowBytes, rows, slot, wave, lane, lc);
+      else pf16_issue_v((in_b ? a.vb : va_p + a_jump(t)) + row0 * kRowBytes, rows, slot + kPdVRing, wave, lane, lc);
     };
     auto wait_landed = [&](int t) {
       if (t + 3 < T) wait_vmcnt<4>();
@@ -1373,8 +1380,8 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
       const int64_t vrow0 = (int64_t)(vb ? tv + tb_base : tv) * kPfTileRows;
       const bool kfull = tk < T && (kb ? a.nb : na_p) - krow0 >= kPfTileRows;
       const bool vfull = tv < T && (vb ? a.nb : na_p) - vrow0 >= kPfTileRows;
-      if (kfull) ld.k = (kb ? a.kb : ka_p) + krow0 * kRowBytes; else issue(tk, 0);
-      if (vfull) ld.v = (vb ? a.vb : va_p) + vrow0 * kRowBytes; else issue(tv, 1);
+      if (kfull) ld.k = (kb ? a.kb : ka_p + a_jump(tk)) + krow0 * kRowBytes; else issue(tk, 0);
+      if (vfull) ld.v = (vb ? a.vb : va_p + a_jump(tv)) + vrow0 * kRowBytes; else issue(tv, 1);
       ld.ldk = lds_base + (uint32_t)(tk & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
       ld.ldv = lds_base + kPdVRing + (uint32_t)(tv & (kPdStages - 1)) * kPfTileBytes + wave * 2048;
       pd16_matrix_phase<0, false, false>((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes,
@@ -1408,9 +1415,10 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
       vp += kPfTileBytes;
     };
     int t = 1;
-    auto fast_run = [&](int t_end, const char* kbase, const char* vbase, int tile0) __attribute__((always_inline)) {
-      if (t_end - t < 8) return;
-      while (t & 3) { generic_tile(t); ++t; }
+    // t_min: the run may not start before this tile (the tiles up to it go through the general routine first)
+    auto fast_run = [&](int t_end, const char* kbase, const char* vbase, int tile0, int t_min) __attribute__((always_inline)) {
+      if (t_end - (t > t_min ? t : t_min) < 8) return;
+      while ((t & 3) || t < t_min) { generic_tile(t); ++t; }
       kp = kbase + (int64_t)(t + 3 - tile0) * kPfTileBytes;
       vp = vbase + (int64_t)(t + 2 - tile0) * kPfTileBytes;
       pd16_preread((uint32_t)((t - 1) & (kPdStages - 1)) * kPfTileBytes, lc, pre);
@@ -1425,14 +1433,26 @@ __global__ __launch_bounds__(512, 2) void prefill_kernel_deep16(PrefillArgs a) {
         fast_tile(std::integral_constant<int, 3>());
       }
     };
-    fast_run((int)(na_p / kPfTileRows) - 3, ka_p, va_p, 0);
+    {
+      // steady-state tiles load K(t+3) and V(t+2) through running pointers: a run stays on one side of a jump (one
+      // call site for both sides: every copy of the loop the compiler has to fit costs the others registers)
+      const int a_end = (int)(na_p / kPfTileRows) - 3;
+      const int pieces = jr < ta ? 2 : 1;
+#pragma nounroll
+      for (int piece = 0; piece < pieces; ++piece) {
+        const int64_t off = piece ? a.a_jump_bytes : 0;
+        int end = a_end;
+        if (piece == 0 && pieces == 2 && jr - 3 < end) end = jr - 3;
+        fast_run(end, ka_p + off, va_p + off, 0, piece ? jr - 2 : 0);
+      }
+    }
     while (t < ta && t < T) { generic_tile(t); ++t; }
     {
       const int64_t unmasked = ((int64_t)bx * strip + 1) / kPfTileRows;
       const int64_t loadable = a.nb / kPfTileRows - 3;
       const int64_t j_end = unmasked < loadable ? unmasked : loadable;
       const int64_t t_end = j_end - tb_base < T - 3 ? j_end - tb_base : T - 3;
-      fast_run((int)t_end, a.kb, a.vb, -tb_base);
+      fast_run((int)t_end, a.kb, a.vb, -tb_base, 0);
     }
     for (; t < T; ++t) generic_tile(t);
     {
@@ -1852,6 +1872,12 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   const int strip = prefill_strip(G);
   const int gy = prefill_grid_y(G);
   a.gy = gy;
+  a.a_jump_tile = (int)(sa.jump_rows / kPfTileRows);
+  a.a_jump_bytes = sa.jump_bytes;
+  if (sa.jump_rows != 0 && (sa.jump_rows % kPfTileRows != 0 || sa.jump_rows < 0 || sa.jump_rows >= sa.n)) {
+    set_last_error("prefill launch: a past segment in two pieces breaks at a multiple of 64 rows inside it");
+    return HI_ERR_ARG;
+  }
   a.a_head_stride = sa.head_stride;
   const PrefillLaunch pl = prefill_launch_shape(G, chunk_len, n_heads, variant, last, sb.n > 0);
   if (sa.n >= (1LL << 31) || sb.n >= (1LL << 31)) { set_last_error("prefill launch: more than 2^31 rows"); return HI_ERR_RANGE; }
@@ -1862,6 +1888,10 @@ hi_status launch_prefill(void* stream, const void* q, int G, int chunk_len, cons
   a.split = pl.split;
   a.paired = pl.paired;
   a.nbk = pl.nbk;
+  if (sa.jump_rows != 0 && !(pl.deep && (variant & 16) == 0)) {
+    set_last_error("prefill launch: this kernel takes its past segment in one piece");
+    return HI_ERR_UNSUPPORTED;
+  }
   if (pl.deep) {
     static std::once_flag attr_once;
     static hipError_t attr_err = hipSuccess;
