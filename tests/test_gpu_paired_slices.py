@@ -19,10 +19,10 @@ FORMS = {"eight-wave": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_8WAVE,
          "wide, balanced triangle": hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_WIDE | hb.HI_FLAG_PREFILL_PAIRED}
 
 
-def run(flags, seed, H, G, S, C, pre):
+def run(flags, seed, H, G, S, C, pre, link_kv_bits=0):
     qs = hb.HI_Q_PRESCALE if pre else 1.0
     outs = {h: [] for h in range(H)}
-    with Session(1, H, G, S, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, q_prescaled=pre) as ss:
+    with Session(1, H, G, S, C, mode=hb.HI_MODE_OFFLOAD, out_fp32=1, q_prescaled=pre, link_kv_bits=link_kv_bits) as ss:
         hb.hi_ctx_set_flags(ss.ctx, flags)
         st = ss.plan.slice_tokens
         with torch.cuda.stream(ss.s_compute):
@@ -70,3 +70,16 @@ def test_the_other_kernels_take_one_slice_per_launch():
     f = hb.HI_FLAG_PREFILL_DEEP | hb.HI_FLAG_PREFILL_MFMA32
     _, _, _, _, launches, st = run(f, seed, H, G, S, C, False)
     assert launches == H * sum(max(1, -(-p // st)) for p in range(0, S, C))
+
+
+@pytest.mark.parametrize("form", ["eight-wave", "wide"])
+def test_a_ring_of_two_slots_is_not_paired(form):
+    """With 4-bit rows on the link the plan's ring has two (larger) slots: a pair would be the whole ring and nothing
+    could land under the kernel, so the library launches once per slice."""
+    seed, H, G, S, C = 41002, 2, 4, 6144, 512
+    got, _, _, _, launches, st = run(FORMS[form], seed, H, G, S, C, True, link_kv_bits=4)
+    one, _, _, _, launches_single, _ = run(FORMS[form] | hb.HI_FLAG_PREFILL_SINGLE_SLICES, seed, H, G, S, C, True,
+                                           link_kv_bits=4)
+    assert launches == launches_single
+    for h in range(H):
+        assert torch.isfinite(got[h]).all() and torch.equal(got[h], one[h])
